@@ -1,0 +1,210 @@
+/*
+ * lychee.h -- C ABI of the LycheeCluster decode hot path for AMD MI355X (gfx950).
+ *
+ * The library implements, as hand-written HIP kernels, the decode-time path of
+ * the LycheeCluster method: a hierarchical index over variable-length KV chunks
+ * (Section 4.1, 4.3), retrieval with the triangle-inequality score bound
+ * (Eq. 2; Algorithm 1 steps 1-2), exact attention over the retrieved chunks
+ * (Eq. 1; Algorithm 1 step 3) and the lazy index update for streamed tokens
+ * (Section 4.4; Algorithm 1 step 4).
+ *
+ * Conventions
+ *   - Plain C.  Every call returns an int: LC_OK (0) or a negative LC_ERR_*.
+ *     Nothing throws.  Host-side argument errors are detected before any GPU
+ *     work is enqueued and leave all buffers untouched.
+ *   - Pointers are DEVICE pointers unless marked "host".  The library never
+ *     allocates or frees device memory: the caller provides the index buffer
+ *     and a workspace, sized by lc_index_bytes() / lc_workspace_bytes().
+ *   - All GPU work is enqueued on the caller's stream (a hipStream_t passed as
+ *     void*, NULL = the default stream) and is asynchronous.  Calls on the same
+ *     index must be stream-ordered; two calls that overlap on one index race.
+ *   - Shapes: B sequences, H_q query heads, H_kv KV heads, G = H_q / H_kv
+ *     (1 <= G <= 8), head dimension d = 128.  Query head hq uses KV head hq / G.
+ *   - q, k, v are bfloat16; K and V caches are bfloat16 [B][H_kv][tokens][d]
+ *     addressed through element strides {sequence, head, token} with d
+ *     contiguous; outputs are float32.
+ *   - Levels: level 0 = chunks, level L-1 = top.  `fanout` F is the average
+ *     number of children: level l+1 has ceil(N_l / F) nodes.
+ *   - A chunk id is the chunk's position in its sequence's boundary list.
+ */
+#ifndef LYCHEE_H
+#define LYCHEE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LC_MAX_LEVELS 6
+#define LC_MAX_GROUP 8
+#define LC_HEAD_DIM 128
+
+enum {
+    LC_OK = 0,
+    LC_ERR_INVALID_ARG = -1,          /* null pointer, negative size, unknown enum value   */
+    LC_ERR_BAD_SHAPE = -2,            /* d != 128, H_q not a multiple of H_kv, G > 8, ...  */
+    LC_ERR_WORKSPACE_TOO_SMALL = -3,  /* index buffer or workspace smaller than required   */
+    LC_ERR_CAPACITY = -4,             /* max_chunks / max_tokens / id capacity exceeded    */
+    LC_ERR_HIP = -5,                  /* a HIP runtime call failed (see lc_last_hip_error) */
+    LC_ERR_BAD_BLOB = -6              /* lc_index_import: malformed or mismatching blob    */
+};
+
+/* How a node's (center, radius) is stored.
+ * TOKEN_BALL: a chunk's center is its mean key and its radius covers the chunk's
+ *   token keys, so Eq. 2 bounds every token logit beneath a node.
+ * PAPER_UNIT: the literal representative of Section 4.1: the mean key projected
+ *   onto the unit sphere, radius 0; internal centers are spherical centroids. */
+enum { LC_GEOMETRY_TOKEN_BALL = 0, LC_GEOMETRY_PAPER_UNIT = 1 };
+
+/* EXACT: the selection equals a flat scan over all chunks; subtrees are pruned
+ *   only when Eq. 2 proves they cannot reach the cutoff.
+ * BEAM: Algorithm 1's top-k per level (beam[l] nodes kept at level l). */
+enum { LC_POLICY_EXACT = 0, LC_POLICY_BEAM = 1 };
+
+typedef struct lc_config {
+    int32_t levels;                 /* L >= 1, counts the chunk level (paper: 3)            */
+    int32_t fanout;                 /* F >= 1                                               */
+    int32_t kmeans_iters;           /* spherical k-means iterations (Appendix B: 10)        */
+    int32_t geometry;               /* LC_GEOMETRY_*                                        */
+    int32_t policy;                 /* LC_POLICY_*                                          */
+    int32_t beam[LC_MAX_LEVELS];    /* BEAM: nodes kept per level; <= 0 means no limit.
+                                       beam[0] limits the number of chunks returned.        */
+    int32_t sink_tokens;            /* leading chunks covering this many tokens are always
+                                       attended, never scored, not charged to the budget    */
+    int32_t max_chunks;             /* capacity: closed chunks per sequence                 */
+    int32_t max_tokens;             /* capacity: tokens per sequence (rows of K and V)      */
+    int32_t decode_splits;          /* split-K factor of the attention kernel; 0 = auto     */
+} lc_config;
+
+typedef struct lc_index lc_index;   /* opaque host-side handle */
+
+/* Fill *cfg with defaults: levels 3, fanout 16, kmeans_iters 10, TOKEN_BALL,
+ * EXACT, no beam limits, sink 0, capacities 0 (the caller must set them). */
+void lc_config_default(lc_config* cfg /* host */);
+
+/* Text for an error code (static storage). */
+const char* lc_strerror(int code);
+
+/* The last hipError_t seen by a failing call on this thread, as text. */
+const char* lc_last_hip_error(void);
+
+/* Bytes of device memory an index needs for B sequences (pure host function;
+ * 0 on invalid arguments). */
+size_t lc_index_bytes(const lc_config* cfg /* host */, int B, int H_kv, int d);
+
+/* Bytes of workspace sufficient for lc_build_index, lc_retrieve,
+ * lc_sparse_decode and lc_append on such an index (pure host function; 0 on
+ * invalid arguments).  The workspace holds no state between calls. */
+size_t lc_workspace_bytes(const lc_config* cfg /* host */, int B, int H_q, int H_kv, int d);
+
+/*
+ * lc_build_index -- index construction at prefill (Section 4.3).
+ * Per (sequence, KV head): mean-pools the keys of every chunk (representative
+ * key, Section 4.1), then builds levels-1 rounds of spherical k-means
+ * (inner-product similarity, cfg->kmeans_iters iterations, k = ceil(N/F),
+ * centroid c starts at point floor(c*N/k), ties to the lower id, an empty
+ * cluster keeps its centroid) over the unit directions of the level below; each
+ * node stores a center and a radius covering all descendant chunks' balls.
+ *
+ *   out           host: receives the new handle (destroy with lc_index_destroy)
+ *   K             bf16 key cache, k_strides = {sequence, head, token} in elements
+ *   seq_lens      host int32[B]: tokens written per sequence (<= cfg->max_tokens)
+ *   chunk_bounds  host int32: per sequence, chunk_counts[b]+1 ascending boundaries
+ *                 starting at 0 and ending <= seq_lens[b], concatenated over b;
+ *                 tokens after the last boundary form the open tail (attended,
+ *                 not indexed).  Boundaries are shared by all heads.
+ *   chunk_counts  host int32[B]: closed chunks per sequence (<= cfg->max_chunks)
+ *   index_buf     device buffer of >= lc_index_bytes() bytes, 256-byte aligned,
+ *                 owned by the caller, must outlive the handle
+ *   ws            device workspace of >= lc_workspace_bytes() bytes
+ */
+int lc_build_index(lc_index** out, const lc_config* cfg,
+                   const void* K, const int64_t k_strides[3],
+                   const int32_t* seq_lens, const int32_t* chunk_bounds, const int32_t* chunk_counts,
+                   int B, int H_kv, int d,
+                   void* index_buf, size_t index_bytes, void* ws, size_t ws_bytes, void* stream);
+
+/* Change the retrieval policy of an existing index (host state only). */
+int lc_set_policy(lc_index* idx, int policy, const int32_t* beam /* host, LC_MAX_LEVELS, may be NULL */,
+                  int sink_tokens);
+
+/*
+ * lc_retrieve -- hierarchical retrieval for one decode step (Eq. 2, Algorithm 1
+ * steps 1-2).  Per (sequence, KV head) every node u gets the group score
+ *   s(u) = max over the G query heads of (q_g . mu_u + |q_g| r_u) / sqrt(d);
+ * chunks are ordered by (score descending, id ascending) and the longest prefix
+ * whose token total is <= budget is returned, ids ascending.  EXACT prunes a
+ * subtree only if its bound is below a proven lower bound of the cutoff, so the
+ * result equals the flat scan; BEAM keeps beam[l] nodes per level.
+ *
+ *   q          bf16 [B][H_q][d]
+ *   chunk_ids  int32 [B][H_kv][cap]  (entries past counts[] are unspecified)
+ *   counts     int32 [B][H_kv]
+ *   scores     optional float32 [B][H_kv][cfg.max_chunks]: chunk scores; -inf for
+ *              chunks that were pruned or pinned.  May be NULL.
+ *   cap        ids capacity per (sequence, head); must be >= min(chunks, budget +
+ *              sink chunks) for every sequence, else LC_ERR_CAPACITY
+ */
+int lc_retrieve(const lc_index* idx, const void* q, int H_q, int budget,
+                int32_t* chunk_ids, int32_t* counts, float* scores, int cap,
+                void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * lc_sparse_decode -- exact attention over the retrieved chunks (Eq. 1 restricted
+ * to the active set; Algorithm 1 step 3), as a split-K flash-decode followed by a
+ * log-sum-exp merge.  The active set of (b, h) is the listed chunks plus the open
+ * tail.  Logits q.k/sqrt(d), bf16 inputs, float32 accumulation.
+ *
+ *   chunk_ids, counts, cap   as produced by lc_retrieve (ids ascending, distinct)
+ *   out        float32 [B][H_q][d]; an empty active set gives 0
+ *   lse        optional float32 [B][H_q]: ln sum exp(logit); -inf if empty
+ */
+int lc_sparse_decode(const lc_index* idx, const void* q, const void* K, const void* V,
+                     const int64_t kv_strides[3],
+                     const int32_t* chunk_ids, const int32_t* counts, int cap, int H_q,
+                     float* out, float* lse, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * lc_append -- lazy update for one streamed token per sequence (Section 4.4,
+ * Algorithm 1 step 4).  Writes k_new/v_new at row T_b of K and V and advances
+ * T_b.  Where close_chunk[b] != 0 the open tail (including the new token) becomes
+ * chunk M_b: it is attached to the level-1 node of nearest direction (largest
+ * inner product of unit directions, ties to the lower id); that node and its
+ * ancestors take the count-weighted moving average of the new center, and their
+ * radii grow monotonically (by the centroid shift, and to cover the new chunk).
+ *
+ *   k_new, v_new   bf16 [B][H_kv][d]
+ *   close_chunk    host uint8[B] (the caller's boundary decision); NULL = none
+ * Returns LC_ERR_CAPACITY (nothing enqueued) if a sequence is at max_tokens, or
+ * would exceed max_chunks.
+ */
+int lc_append(lc_index* idx, void* K, void* V, const int64_t kv_strides[3],
+              const void* k_new, const void* v_new, const uint8_t* close_chunk,
+              void* ws, size_t ws_bytes, void* stream);
+
+/* Host-side view of the index state: tokens, closed chunks and level sizes of
+ * sequence b (n_per_level: host int32[LC_MAX_LEVELS], may be NULL). */
+int lc_index_info(const lc_index* idx, int b, int32_t* T, int32_t* M, int32_t* n_per_level);
+
+/*
+ * Export / import of the stored index as a flat little-endian host blob, so that
+ * a CPU reference and the GPU can run on the identical stored values.
+ *   int32 header[16] = {magic 'LCIX', version 1, B, H_kv, d, L, F, geometry, 0...}
+ *   per sequence b:    int32 T_b, M_b, N_1..N_{L-1};  int32 bounds[M_b+1]
+ *   per (b, h, level): float32 center[N_l][d], float32 radius[N_l],
+ *                      int32 parent[N_l], int32 ntok[N_l], int32 nchunk[N_l]
+ * lc_index_export synchronises the stream.  With blob == NULL it only stores the
+ * required size in *bytes.
+ */
+int lc_index_export(const lc_index* idx, void* blob /* host */, size_t* bytes /* host, in/out */, void* stream);
+int lc_index_import(lc_index** out, const lc_config* cfg, const void* blob /* host */, size_t blob_bytes,
+                    void* index_buf, size_t index_bytes, void* stream);
+
+void lc_index_destroy(lc_index* idx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LYCHEE_H */

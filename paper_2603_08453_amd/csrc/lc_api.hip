@@ -1,0 +1,546 @@
+// C ABI of liblychee: argument validation, buffer layout, handle management.
+// All checks that do not need the GPU happen before the first HIP call.
+#include <string.h>
+
+#include <new>
+#include <string>
+
+#include "lc_internal.h"
+
+namespace {
+
+thread_local hipError_t g_last_hip = hipSuccess;
+
+inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+bool config_ok(const lc_config* c) {
+    if (!c) return false;
+    if (c->levels < 1 || c->levels > LC_MAX_LEVELS) return false;
+    if (c->fanout < 1) return false;
+    if (c->kmeans_iters < 0) return false;
+    if (c->geometry != LC_GEOMETRY_TOKEN_BALL && c->geometry != LC_GEOMETRY_PAPER_UNIT) return false;
+    if (c->policy != LC_POLICY_EXACT && c->policy != LC_POLICY_BEAM) return false;
+    if (c->sink_tokens < 0) return false;
+    if (c->max_chunks < 1 || c->max_tokens < 1) return false;
+    if (c->max_chunks > c->max_tokens) return false;
+    if (c->max_tokens > (1 << 30)) return false;
+    if (c->decode_splits < 0 || c->decode_splits > 1024) return false;
+    return true;
+}
+
+void level_caps(const lc_config* c, int* cap) {
+    cap[0] = c->max_chunks;
+    for (int l = 1; l < LC_MAX_LEVELS; ++l) {
+        cap[l] = l < c->levels ? (cap[l - 1] + c->fanout - 1) / c->fanout : 0;
+        if (l < c->levels && cap[l] < 1) cap[l] = 1;
+    }
+}
+
+struct Carver {
+    char* base;
+    size_t off;
+    template <typename T>
+    T* take(size_t count) {
+        off = align_up(off);
+        T* p = base ? reinterpret_cast<T*>(base + off) : nullptr;
+        off += count * sizeof(T);
+        return p;
+    }
+};
+
+}  // namespace
+
+void lc_set_hip_error(hipError_t e) { g_last_hip = e; }
+
+size_t lc_layout_index(const lc_config* cfg, int B, int H, int d, void* base, LcDev* dev) {
+    LcDev tmp;
+    LcDev* D = dev ? dev : &tmp;
+    memset(D, 0, sizeof(LcDev));
+    D->B = B; D->H = H; D->d = d; D->L = cfg->levels; D->F = cfg->fanout;
+    level_caps(cfg, D->cap);
+    Carver c{static_cast<char*>(base), 0};
+    const size_t BH = (size_t)B * H;
+    D->state = c.take<int>(BH * 4);
+    D->sync = c.take<int>(BH * 4);
+    D->nlev = c.take<int>((size_t)B * LC_MAX_LEVELS);
+    D->bounds = c.take<int>((size_t)B * (D->cap[0] + 1));
+    for (int l = 0; l < cfg->levels; ++l) {
+        const size_t n = BH * D->cap[l];
+        D->center[l] = c.take<float>(n * d);
+        D->radius[l] = c.take<float>(n);
+        D->parent[l] = c.take<int>(n);
+        D->ntok[l] = c.take<int>(n);
+        D->nchunk[l] = c.take<int>(n);
+    }
+    return align_up(c.off);
+}
+
+int lc_auto_splits(const lc_config* cfg, int B, int H) {
+    if (cfg->decode_splits > 0) return cfg->decode_splits;
+    // aim for ~1024 workgroups over the 256 compute units
+    int s = (1024 + B * H - 1) / (B * H);
+    if (s < 1) s = 1;
+    if (s > 64) s = 64;
+    return s;
+}
+
+size_t lc_layout_ws(const lc_config* cfg, int B, int H_q, int H, int d, int splits, void* base, LcWs* ws) {
+    LcWs tmp;
+    LcWs* W = ws ? ws : &tmp;
+    int cap[LC_MAX_LEVELS];
+    level_caps(cfg, cap);
+    const int cap1 = cfg->levels > 1 ? cap[1] : 1;
+    const size_t BH = (size_t)B * H;
+    Carver c{static_cast<char*>(base), 0};
+    W->keys = c.take<uint32_t>(BH * cap[0]);
+    W->kept1 = c.take<uint8_t>(BH * cap1);
+    W->scores = c.take<float>(BH * cap[0]);
+    W->part_acc = c.take<float>((size_t)B * H_q * splits * d);
+    W->part_ml = c.take<float>((size_t)B * H_q * splits * 2);
+    W->dirs = c.take<float>(BH * cap[0] * d);
+    W->cent_a = c.take<float>(BH * cap1 * d);
+    W->cent_b = c.take<float>(BH * cap1 * d);
+    W->labels = c.take<int>(BH * cap[0]);
+    W->anc = c.take<int>(BH * cap[0]);
+    W->total = align_up(c.off);
+    return W->total;
+}
+
+extern "C" {
+
+void lc_config_default(lc_config* cfg) {
+    if (!cfg) return;
+    memset(cfg, 0, sizeof(*cfg));
+    cfg->levels = 3;
+    cfg->fanout = 16;
+    cfg->kmeans_iters = 10;
+    cfg->geometry = LC_GEOMETRY_TOKEN_BALL;
+    cfg->policy = LC_POLICY_EXACT;
+}
+
+const char* lc_strerror(int code) {
+    switch (code) {
+        case LC_OK: return "ok";
+        case LC_ERR_INVALID_ARG: return "invalid argument";
+        case LC_ERR_BAD_SHAPE: return "unsupported shape (need d = 128, H_q a multiple of H_kv, group size <= 8, strides multiple of 8)";
+        case LC_ERR_WORKSPACE_TOO_SMALL: return "index buffer or workspace too small";
+        case LC_ERR_CAPACITY: return "capacity exceeded";
+        case LC_ERR_HIP: return "HIP runtime error";
+        case LC_ERR_BAD_BLOB: return "malformed index blob";
+    }
+    return "unknown error";
+}
+
+const char* lc_last_hip_error(void) { return hipGetErrorString(g_last_hip); }
+
+size_t lc_index_bytes(const lc_config* cfg, int B, int H_kv, int d) {
+    if (!config_ok(cfg) || B < 1 || H_kv < 1 || d != LC_HEAD_DIM) return 0;
+    return lc_layout_index(cfg, B, H_kv, d, nullptr, nullptr);
+}
+
+size_t lc_workspace_bytes(const lc_config* cfg, int B, int H_q, int H_kv, int d) {
+    if (!config_ok(cfg) || B < 1 || H_kv < 1 || H_q < H_kv || H_q % H_kv != 0 || d != LC_HEAD_DIM) return 0;
+    if (H_q / H_kv > LC_MAX_GROUP) return 0;
+    return lc_layout_ws(cfg, B, H_q, H_kv, d, lc_auto_splits(cfg, B, H_kv), nullptr, nullptr);
+}
+
+}  // extern "C"
+
+namespace {
+
+int check_shape(int B, int H_kv, int d) {
+    if (B < 1 || H_kv < 1) return LC_ERR_INVALID_ARG;
+    if (d != LC_HEAD_DIM) return LC_ERR_BAD_SHAPE;
+    return LC_OK;
+}
+
+int check_strides(const int64_t s[3]) {
+    if (!s) return LC_ERR_INVALID_ARG;
+    for (int i = 0; i < 3; ++i)
+        if (s[i] < 0 || s[i] % 8 != 0) return LC_ERR_BAD_SHAPE;
+    if (s[2] < LC_HEAD_DIM) return LC_ERR_BAD_SHAPE;
+    return LC_OK;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+lc_index* new_handle(const lc_config* cfg, int B, int H, int d, void* buf, size_t bytes) {
+    lc_index* h = new (std::nothrow) lc_index();
+    if (!h) return nullptr;
+    h->cfg = *cfg;
+    h->B = B; h->H_kv = H; h->d = d;
+    h->device = 0;
+    h->buf = buf;
+    h->bytes = bytes;
+    lc_layout_index(cfg, B, H, d, buf, &h->dev);
+    h->T.assign(B, 0);
+    h->M.assign(B, 0);
+    h->N.assign((size_t)B * LC_MAX_LEVELS, 0);
+    return h;
+}
+
+void fill_level_counts(lc_index* h) {
+    for (int b = 0; b < h->B; ++b) {
+        int n = h->M[b];
+        h->N[(size_t)b * LC_MAX_LEVELS + 0] = n;
+        for (int l = 1; l < h->cfg.levels; ++l) {
+            n = (n + h->cfg.fanout - 1) / h->cfg.fanout;
+            if (n < 1) n = 1;
+            h->N[(size_t)b * LC_MAX_LEVELS + l] = n;
+        }
+    }
+}
+
+// state, nlev, bounds, sync -> device (synchronous small copies from host staging vectors)
+int upload_state(lc_index* h, const int32_t* bounds_concat, hipStream_t stream) {
+    const int B = h->B, H = h->H_kv;
+    std::vector<int> state((size_t)B * H * 4, 0), nlev((size_t)B * LC_MAX_LEVELS, 0);
+    for (int b = 0; b < B; ++b) {
+        for (int hh = 0; hh < H; ++hh) {
+            state[((size_t)b * H + hh) * 4 + 0] = h->T[b];
+            state[((size_t)b * H + hh) * 4 + 1] = h->M[b];
+        }
+        for (int l = 0; l < LC_MAX_LEVELS; ++l) nlev[(size_t)b * LC_MAX_LEVELS + l] = h->N[(size_t)b * LC_MAX_LEVELS + l];
+    }
+    LC_HIP_CHECK(hipMemcpyAsync(h->dev.state, state.data(), state.size() * sizeof(int), hipMemcpyHostToDevice, stream));
+    LC_HIP_CHECK(hipMemcpyAsync(h->dev.nlev, nlev.data(), nlev.size() * sizeof(int), hipMemcpyHostToDevice, stream));
+    std::vector<int> zeros((size_t)B * H * 4, 0);
+    LC_HIP_CHECK(hipMemcpyAsync(h->dev.sync, zeros.data(), zeros.size() * sizeof(int), hipMemcpyHostToDevice, stream));
+    size_t off = 0;
+    for (int b = 0; b < B; ++b) {
+        const size_t n = (size_t)h->M[b] + 1;
+        LC_HIP_CHECK(hipMemcpyAsync(h->dev.bounds + (size_t)b * (h->dev.cap[0] + 1), bounds_concat + off,
+                                    n * sizeof(int), hipMemcpyHostToDevice, stream));
+        off += n;
+    }
+    // the staging vectors die at return: make sure the copies are done
+    LC_HIP_CHECK(hipStreamSynchronize(stream));
+    return LC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int lc_build_index(lc_index** out, const lc_config* cfg, const void* K, const int64_t k_strides[3],
+                   const int32_t* seq_lens, const int32_t* chunk_bounds, const int32_t* chunk_counts,
+                   int B, int H_kv, int d, void* index_buf, size_t index_bytes, void* ws, size_t ws_bytes,
+                   void* stream) {
+    if (!out || !cfg || !K || !seq_lens || !chunk_bounds || !chunk_counts || !index_buf || !ws)
+        return LC_ERR_INVALID_ARG;
+    if (!config_ok(cfg)) return LC_ERR_INVALID_ARG;
+    int rc = check_shape(B, H_kv, d);
+    if (rc) return rc;
+    rc = check_strides(k_strides);
+    if (rc) return rc;
+    if (!aligned16(K) || (reinterpret_cast<uintptr_t>(index_buf) & 255u) || (reinterpret_cast<uintptr_t>(ws) & 255u))
+        return LC_ERR_INVALID_ARG;
+    size_t off = 0;
+    for (int b = 0; b < B; ++b) {
+        const int M = chunk_counts[b], T = seq_lens[b];
+        if (M < 0 || T < 0) return LC_ERR_INVALID_ARG;
+        if (M > cfg->max_chunks || T > cfg->max_tokens) return LC_ERR_CAPACITY;
+        const int32_t* bd = chunk_bounds + off;
+        if (bd[0] != 0) return LC_ERR_INVALID_ARG;
+        for (int j = 0; j < M; ++j)
+            if (bd[j + 1] <= bd[j]) return LC_ERR_INVALID_ARG;
+        if (bd[M] > T) return LC_ERR_INVALID_ARG;
+        off += (size_t)M + 1;
+    }
+    if (index_bytes < lc_layout_index(cfg, B, H_kv, d, nullptr, nullptr)) return LC_ERR_WORKSPACE_TOO_SMALL;
+    // the build does not depend on the number of query heads: size with G = 1
+    LcWs w;
+    if (ws_bytes < lc_layout_ws(cfg, B, H_kv, H_kv, d, 1, nullptr, nullptr)) return LC_ERR_WORKSPACE_TOO_SMALL;
+    lc_layout_ws(cfg, B, H_kv, H_kv, d, 1, ws, &w);
+
+    lc_index* h = new_handle(cfg, B, H_kv, d, index_buf, index_bytes);
+    if (!h) return LC_ERR_INVALID_ARG;
+    int max_M = 0;
+    for (int b = 0; b < B; ++b) {
+        h->T[b] = seq_lens[b];
+        h->M[b] = chunk_counts[b];
+        if (h->M[b] > max_M) max_M = h->M[b];
+    }
+    fill_level_counts(h);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    rc = upload_state(h, chunk_bounds, s);
+    if (rc == LC_OK) rc = lc_launch_build(h, w, K, k_strides, max_M, s);
+    if (rc != LC_OK) {
+        delete h;
+        return rc;
+    }
+    *out = h;
+    return LC_OK;
+}
+
+int lc_set_policy(lc_index* idx, int policy, const int32_t* beam, int sink_tokens) {
+    if (!idx) return LC_ERR_INVALID_ARG;
+    if (policy != LC_POLICY_EXACT && policy != LC_POLICY_BEAM) return LC_ERR_INVALID_ARG;
+    if (sink_tokens < 0) return LC_ERR_INVALID_ARG;
+    idx->cfg.policy = policy;
+    idx->cfg.sink_tokens = sink_tokens;
+    for (int l = 0; l < LC_MAX_LEVELS; ++l) idx->cfg.beam[l] = beam ? beam[l] : 0;
+    return LC_OK;
+}
+
+int lc_index_info(const lc_index* idx, int b, int32_t* T, int32_t* M, int32_t* n_per_level) {
+    if (!idx || b < 0 || b >= idx->B) return LC_ERR_INVALID_ARG;
+    if (T) *T = idx->T[b];
+    if (M) *M = idx->M[b];
+    if (n_per_level)
+        for (int l = 0; l < LC_MAX_LEVELS; ++l)
+            n_per_level[l] = l < idx->cfg.levels ? idx->N[(size_t)b * LC_MAX_LEVELS + l] : 0;
+    return LC_OK;
+}
+
+static int common_decode_checks(const lc_index* idx, const void* q, int H_q, int cap) {
+    if (!idx || !q) return LC_ERR_INVALID_ARG;
+    if (H_q < idx->H_kv || H_q % idx->H_kv != 0) return LC_ERR_BAD_SHAPE;
+    if (H_q / idx->H_kv > LC_MAX_GROUP) return LC_ERR_BAD_SHAPE;
+    if (cap < 1) return LC_ERR_INVALID_ARG;
+    if (!aligned16(q)) return LC_ERR_INVALID_ARG;
+    return LC_OK;
+}
+
+int lc_retrieve(const lc_index* idx, const void* q, int H_q, int budget, int32_t* chunk_ids, int32_t* counts,
+                float* scores, int cap, void* ws, size_t ws_bytes, void* stream) {
+    int rc = common_decode_checks(idx, q, H_q, cap);
+    if (rc) return rc;
+    if (!chunk_ids || !counts || !ws) return LC_ERR_INVALID_ARG;
+    if (budget < 0) return LC_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(ws) & 255u) return LC_ERR_INVALID_ARG;
+    const int splits = lc_auto_splits(&idx->cfg, idx->B, idx->H_kv);
+    if (ws_bytes < lc_layout_ws(&idx->cfg, idx->B, H_q, idx->H_kv, idx->d, splits, nullptr, nullptr))
+        return LC_ERR_WORKSPACE_TOO_SMALL;
+    int max_M = 0, max_upper = 0;
+    for (int b = 0; b < idx->B; ++b) {
+        const int M = idx->M[b];
+        if (M > max_M) max_M = M;
+        // every chunk holds >= 1 token: at most `budget` chunks fit, plus the pinned ones
+        long long need = (long long)budget + idx->cfg.sink_tokens;
+        if (need > M) need = M;
+        if (cap < need) return LC_ERR_CAPACITY;
+        int up = 0;
+        for (int l = 1; l < idx->cfg.levels; ++l) up += idx->N[(size_t)b * LC_MAX_LEVELS + l];
+        if (up > max_upper) max_upper = up;
+    }
+    if (max_upper > 8192) return LC_ERR_CAPACITY;       // internal nodes of one (sequence, head) live in LDS
+    LcWs w;
+    lc_layout_ws(&idx->cfg, idx->B, H_q, idx->H_kv, idx->d, splits, ws, &w);
+    return lc_launch_retrieve(idx, w, q, H_q / idx->H_kv, budget, chunk_ids, counts, scores, cap, max_M, max_upper,
+                              static_cast<hipStream_t>(stream));
+}
+
+int lc_sparse_decode(const lc_index* idx, const void* q, const void* K, const void* V, const int64_t kv_strides[3],
+                     const int32_t* chunk_ids, const int32_t* counts, int cap, int H_q, float* out, float* lse,
+                     void* ws, size_t ws_bytes, void* stream) {
+    int rc = common_decode_checks(idx, q, H_q, cap);
+    if (rc) return rc;
+    if (!K || !V || !chunk_ids || !counts || !out || !ws) return LC_ERR_INVALID_ARG;
+    rc = check_strides(kv_strides);
+    if (rc) return rc;
+    if (!aligned16(K) || !aligned16(V) || (reinterpret_cast<uintptr_t>(ws) & 255u)) return LC_ERR_INVALID_ARG;
+    const int splits = lc_auto_splits(&idx->cfg, idx->B, idx->H_kv);
+    if (ws_bytes < lc_layout_ws(&idx->cfg, idx->B, H_q, idx->H_kv, idx->d, splits, nullptr, nullptr))
+        return LC_ERR_WORKSPACE_TOO_SMALL;
+    int max_M = 0;
+    for (int b = 0; b < idx->B; ++b)
+        if (idx->M[b] > max_M) max_M = idx->M[b];
+    int eff_cap = cap < max_M ? cap : max_M;
+    if (eff_cap < 1) eff_cap = 1;
+    if (eff_cap > 16000) return LC_ERR_CAPACITY;        // the run table of one (sequence, head) lives in LDS
+    LcWs w;
+    lc_layout_ws(&idx->cfg, idx->B, H_q, idx->H_kv, idx->d, splits, ws, &w);
+    return lc_launch_decode(idx, w, q, K, V, kv_strides, chunk_ids, counts, cap, H_q / idx->H_kv, splits, out, lse,
+                            static_cast<hipStream_t>(stream));
+}
+
+int lc_append(lc_index* idx, void* K, void* V, const int64_t kv_strides[3], const void* k_new, const void* v_new,
+              const uint8_t* close_chunk, void* ws, size_t ws_bytes, void* stream) {
+    (void)ws; (void)ws_bytes;
+    if (!idx || !K || !V || !k_new || !v_new) return LC_ERR_INVALID_ARG;
+    int rc = check_strides(kv_strides);
+    if (rc) return rc;
+    if (!aligned16(K) || !aligned16(V) || !aligned16(k_new) || !aligned16(v_new)) return LC_ERR_INVALID_ARG;
+    if (idx->B > 1024) return LC_ERR_CAPACITY;
+    for (int b = 0; b < idx->B; ++b) {
+        if (idx->T[b] + 1 > idx->cfg.max_tokens) return LC_ERR_CAPACITY;
+        if (close_chunk && close_chunk[b] && idx->M[b] + 1 > idx->cfg.max_chunks) return LC_ERR_CAPACITY;
+    }
+    rc = lc_launch_append(idx, K, V, kv_strides, k_new, v_new, close_chunk, 0u, static_cast<hipStream_t>(stream));
+    if (rc != LC_OK) return rc;
+    for (int b = 0; b < idx->B; ++b) {
+        idx->T[b] += 1;
+        if (close_chunk && close_chunk[b]) {
+            idx->M[b] += 1;
+            idx->N[(size_t)b * LC_MAX_LEVELS + 0] = idx->M[b];
+        }
+    }
+    return LC_OK;
+}
+
+// ---------------------------------------------------------------------------------
+// export / import
+// ---------------------------------------------------------------------------------
+static const int32_t kMagic = 0x5849434C;    // 'L','C','I','X'
+
+static size_t blob_size(const lc_index* idx) {
+    size_t n = 16 * 4;
+    const int L = idx->cfg.levels;
+    for (int b = 0; b < idx->B; ++b) {
+        n += (size_t)(2 + (L - 1)) * 4 + ((size_t)idx->M[b] + 1) * 4;
+        for (int l = 0; l < L; ++l) {
+            const size_t nl = idx->N[(size_t)b * LC_MAX_LEVELS + l];
+            n += (size_t)idx->H_kv * nl * ((size_t)idx->d * 4 + 16);
+        }
+    }
+    return n;
+}
+
+int lc_index_export(const lc_index* idx, void* blob, size_t* bytes, void* stream) {
+    if (!idx || !bytes) return LC_ERR_INVALID_ARG;
+    const size_t need = blob_size(idx);
+    if (!blob) { *bytes = need; return LC_OK; }
+    if (*bytes < need) { *bytes = need; return LC_ERR_WORKSPACE_TOO_SMALL; }
+    *bytes = need;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    LC_HIP_CHECK(hipStreamSynchronize(s));
+    char* p = static_cast<char*>(blob);
+    int32_t hdr[16] = {kMagic, 1, idx->B, idx->H_kv, idx->d, idx->cfg.levels, idx->cfg.fanout, idx->cfg.geometry};
+    memcpy(p, hdr, sizeof(hdr));
+    p += sizeof(hdr);
+    const int L = idx->cfg.levels;
+    const LcDev& D = idx->dev;
+    for (int b = 0; b < idx->B; ++b) {
+        int32_t rec[2 + LC_MAX_LEVELS];
+        rec[0] = idx->T[b];
+        rec[1] = idx->M[b];
+        for (int l = 1; l < L; ++l) rec[1 + l] = idx->N[(size_t)b * LC_MAX_LEVELS + l];
+        memcpy(p, rec, (size_t)(2 + (L - 1)) * 4);
+        p += (size_t)(2 + (L - 1)) * 4;
+        const size_t nb = ((size_t)idx->M[b] + 1) * 4;
+        LC_HIP_CHECK(hipMemcpy(p, D.bounds + (size_t)b * (D.cap[0] + 1), nb, hipMemcpyDeviceToHost));
+        p += nb;
+    }
+    for (int b = 0; b < idx->B; ++b)
+        for (int h = 0; h < idx->H_kv; ++h)
+            for (int l = 0; l < L; ++l) {
+                const size_t nl = idx->N[(size_t)b * LC_MAX_LEVELS + l];
+                const size_t base = ((size_t)b * idx->H_kv + h) * D.cap[l];
+                if (nl == 0) continue;
+                LC_HIP_CHECK(hipMemcpy(p, D.center[l] + base * idx->d, nl * idx->d * 4, hipMemcpyDeviceToHost));
+                p += nl * idx->d * 4;
+                LC_HIP_CHECK(hipMemcpy(p, D.radius[l] + base, nl * 4, hipMemcpyDeviceToHost)); p += nl * 4;
+                LC_HIP_CHECK(hipMemcpy(p, D.parent[l] + base, nl * 4, hipMemcpyDeviceToHost)); p += nl * 4;
+                LC_HIP_CHECK(hipMemcpy(p, D.ntok[l] + base, nl * 4, hipMemcpyDeviceToHost)); p += nl * 4;
+                LC_HIP_CHECK(hipMemcpy(p, D.nchunk[l] + base, nl * 4, hipMemcpyDeviceToHost)); p += nl * 4;
+            }
+    return LC_OK;
+}
+
+int lc_index_import(lc_index** out, const lc_config* cfg, const void* blob, size_t blob_bytes, void* index_buf,
+                    size_t index_bytes, void* stream) {
+    if (!out || !cfg || !blob || !index_buf) return LC_ERR_INVALID_ARG;
+    if (!config_ok(cfg)) return LC_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(index_buf) & 255u) return LC_ERR_INVALID_ARG;
+    if (blob_bytes < 64) return LC_ERR_BAD_BLOB;
+    const char* p = static_cast<const char*>(blob);
+    const char* end = p + blob_bytes;
+    int32_t hdr[16];
+    memcpy(hdr, p, sizeof(hdr));
+    p += sizeof(hdr);
+    if (hdr[0] != kMagic || hdr[1] != 1) return LC_ERR_BAD_BLOB;
+    const int B = hdr[2], H = hdr[3], d = hdr[4], L = hdr[5], F = hdr[6], geo = hdr[7];
+    if (B < 1 || H < 1) return LC_ERR_BAD_BLOB;
+    if (d != LC_HEAD_DIM) return LC_ERR_BAD_SHAPE;
+    if (L != cfg->levels || F != cfg->fanout || geo != cfg->geometry) return LC_ERR_BAD_BLOB;
+    if (index_bytes < lc_layout_index(cfg, B, H, d, nullptr, nullptr)) return LC_ERR_WORKSPACE_TOO_SMALL;
+
+    lc_index* h = new_handle(cfg, B, H, d, index_buf, index_bytes);
+    if (!h) return LC_ERR_INVALID_ARG;
+    std::vector<int32_t> bounds_concat;
+    int rc = LC_OK;
+    for (int b = 0; b < B && rc == LC_OK; ++b) {
+        const size_t rec_bytes = (size_t)(2 + (L - 1)) * 4;
+        if (p + rec_bytes > end) { rc = LC_ERR_BAD_BLOB; break; }
+        int32_t rec[2 + LC_MAX_LEVELS];
+        memcpy(rec, p, rec_bytes);
+        p += rec_bytes;
+        const int T = rec[0], M = rec[1];
+        if (M < 0 || T < 0) { rc = LC_ERR_BAD_BLOB; break; }
+        if (M > cfg->max_chunks || T > cfg->max_tokens) { rc = LC_ERR_CAPACITY; break; }
+        h->T[b] = T;
+        h->M[b] = M;
+        h->N[(size_t)b * LC_MAX_LEVELS] = M;
+        for (int l = 1; l < L; ++l) {
+            const int n = rec[1 + l];
+            if (n < 1 || n > h->dev.cap[l]) { rc = LC_ERR_BAD_BLOB; break; }
+            h->N[(size_t)b * LC_MAX_LEVELS + l] = n;
+        }
+        if (rc != LC_OK) break;
+        const size_t nb = ((size_t)M + 1) * 4;
+        if (p + nb > end) { rc = LC_ERR_BAD_BLOB; break; }
+        const size_t at = bounds_concat.size();
+        bounds_concat.resize(at + M + 1);
+        memcpy(bounds_concat.data() + at, p, nb);
+        p += nb;
+        const int32_t* bd = bounds_concat.data() + at;
+        if (bd[0] != 0 || bd[M] > T) { rc = LC_ERR_BAD_BLOB; break; }
+        for (int j = 0; j < M; ++j)
+            if (bd[j + 1] <= bd[j]) { rc = LC_ERR_BAD_BLOB; break; }
+    }
+    if (rc == LC_OK) {
+        // validate the node records before touching the GPU
+        const char* r = p;
+        for (int b = 0; b < B && rc == LC_OK; ++b)
+            for (int hh = 0; hh < H && rc == LC_OK; ++hh)
+                for (int l = 0; l < L; ++l) {
+                    const size_t nl = h->N[(size_t)b * LC_MAX_LEVELS + l];
+                    const size_t sz = nl * ((size_t)d * 4 + 16);
+                    if (r + sz > end) { rc = LC_ERR_BAD_BLOB; break; }
+                    const int32_t* par = reinterpret_cast<const int32_t*>(r + nl * (size_t)d * 4 + nl * 4);
+                    if (l + 1 < L) {
+                        const int up = h->N[(size_t)b * LC_MAX_LEVELS + l + 1];
+                        for (size_t n = 0; n < nl; ++n) {
+                            int32_t pv;
+                            memcpy(&pv, par + n, 4);
+                            if (pv < 0 || pv >= up) { rc = LC_ERR_BAD_BLOB; break; }
+                        }
+                    }
+                    r += sz;
+                }
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (rc == LC_OK) rc = upload_state(h, bounds_concat.data(), s);
+    if (rc == LC_OK) {
+        const LcDev& D = h->dev;
+        for (int b = 0; b < B && rc == LC_OK; ++b)
+            for (int hh = 0; hh < H && rc == LC_OK; ++hh)
+                for (int l = 0; l < L && rc == LC_OK; ++l) {
+                    const size_t nl = h->N[(size_t)b * LC_MAX_LEVELS + l];
+                    if (nl == 0) continue;
+                    const size_t base = ((size_t)b * H + hh) * D.cap[l];
+                    hipError_t e = hipMemcpy(D.center[l] + base * d, p, nl * d * 4, hipMemcpyHostToDevice);
+                    p += nl * d * 4;
+                    if (e == hipSuccess) e = hipMemcpy(D.radius[l] + base, p, nl * 4, hipMemcpyHostToDevice);
+                    p += nl * 4;
+                    if (e == hipSuccess) e = hipMemcpy(D.parent[l] + base, p, nl * 4, hipMemcpyHostToDevice);
+                    p += nl * 4;
+                    if (e == hipSuccess) e = hipMemcpy(D.ntok[l] + base, p, nl * 4, hipMemcpyHostToDevice);
+                    p += nl * 4;
+                    if (e == hipSuccess) e = hipMemcpy(D.nchunk[l] + base, p, nl * 4, hipMemcpyHostToDevice);
+                    p += nl * 4;
+                    if (e != hipSuccess) { lc_set_hip_error(e); rc = LC_ERR_HIP; }
+                }
+    }
+    if (rc != LC_OK) {
+        delete h;
+        return rc;
+    }
+    *out = h;
+    return LC_OK;
+}
+
+void lc_index_destroy(lc_index* idx) { delete idx; }
+
+}  // extern "C"

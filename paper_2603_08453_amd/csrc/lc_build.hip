@@ -1,0 +1,521 @@
+// Index construction (prefill side) and the lazy update for streamed tokens.
+//
+// Build, per (sequence, KV head):
+//   lc_pool_kernel    chunk representative = mean-pooled keys; covering radius; unit direction
+//   lc_kmeans_*       spherical k-means on unit directions: strided init, then
+//                     `iters` x (assign by largest inner product, normalised-sum update)
+//   lc_anc_kernel     chunk -> ancestor at the new level
+//   lc_node_kernel    node center, radius over all descendant chunks' balls, counts, direction
+// Append: lc_append_kernel writes the token's k, v; on a chunk close it pools the
+// open tail, finds the level-1 node of nearest direction and updates the path to the top.
+//
+// Every reduction runs in a fixed order, so results are reproducible run to run.
+#include "lc_device.h"
+#include "lc_internal.h"
+
+#define LC_BT 256                 // threads per block
+#define LC_BG (LC_BT / 16)        // 16-lane groups per block
+#define LC_RADIUS_PAD 4e-6f       // stored radii are inflated by this relative amount so that
+                                  // float32 rounding in the distance never leaves a member outside
+
+__device__ __forceinline__ float lc_pad_radius(float r) { return r > 0.f ? r * (1.0f + LC_RADIUS_PAD) : r; }
+
+// ---------------------------------------------------------------------------------
+// pooling of rows [lo, hi) of one (sequence, head) key cache; block-wide.
+// On return every lane holds, for its 8 columns [8 sub, 8 sub + 8), the stored center
+// `mu`, and all threads hold the stored radius.  sh: LC_BG * 128 + LC_BG floats.
+// ---------------------------------------------------------------------------------
+__device__ __forceinline__ void lc_pool_rows(const uint16_t* __restrict__ Kbh, long long ks_tok, int lo, int hi,
+                                             int geometry, float* sh, float (&mu)[8], float* radius) {
+    const int tid = threadIdx.x, sub = tid & 15, grp = tid >> 4;
+    float sum[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) sum[i] = 0.f;
+    for (int r = lo + grp; r < hi; r += LC_BG) {
+        const uint4 v = *reinterpret_cast<const uint4*>(Kbh + (long long)r * ks_tok + 8 * sub);
+        float f[8];
+        lc_unpack8(v, f);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) sum[i] += f[i];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 8; ++i) sh[grp * LC_D + 8 * sub + i] = sum[i];
+    __syncthreads();
+    const float inv_n = 1.0f / (float)(hi - lo);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        float s = 0.f;
+        for (int g = 0; g < LC_BG; ++g) s += sh[g * LC_D + 8 * sub + i];
+        mu[i] = s * inv_n;
+    }
+    if (geometry == LC_GEOMETRY_PAPER_UNIT) {
+        float n2 = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) n2 = fmaf(mu[i], mu[i], n2);
+        n2 = lc_sum16(n2);
+        if (n2 > 0.f) {
+            const float inv = 1.0f / sqrtf(n2);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) mu[i] *= inv;
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) mu[i] = (sub == 0 && i == 0) ? 1.f : 0.f;
+        }
+        *radius = 0.f;
+        __syncthreads();
+        return;
+    }
+    float far2 = 0.f;
+    for (int r = lo + grp; r < hi; r += LC_BG) {
+        const uint4 v = *reinterpret_cast<const uint4*>(Kbh + (long long)r * ks_tok + 8 * sub);
+        float f[8];
+        lc_unpack8(v, f);
+        float d2 = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { const float t = f[i] - mu[i]; d2 = fmaf(t, t, d2); }
+        d2 = lc_sum16(d2);
+        far2 = fmaxf(far2, d2);
+    }
+    __syncthreads();
+    if (sub == 0) sh[grp] = far2;
+    __syncthreads();
+    float mx = 0.f;
+    for (int g = 0; g < LC_BG; ++g) mx = fmaxf(mx, sh[g]);
+    *radius = lc_pad_radius(sqrtf(mx));
+    __syncthreads();
+}
+
+// unit direction of the 8-column fragments (zero vector -> e_0)
+__device__ __forceinline__ void lc_unit_frag(const float (&v)[8], int sub, float (&u)[8]) {
+    float n2 = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) n2 = fmaf(v[i], v[i], n2);
+    n2 = lc_sum16(n2);
+    if (n2 > 0.f) {
+        const float inv = 1.0f / sqrtf(n2);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) u[i] = v[i] * inv;
+    } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) u[i] = (sub == 0 && i == 0) ? 1.f : 0.f;
+    }
+}
+
+__device__ __forceinline__ void lc_store8(float* p, const float (&v)[8]) {
+    *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    *reinterpret_cast<float4*>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
+}
+__device__ __forceinline__ void lc_load8(const float* p, float (&v)[8]) {
+    const float4 a = *reinterpret_cast<const float4*>(p);
+    const float4 b = *reinterpret_cast<const float4*>(p + 4);
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+    v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+
+// ---------------------------------------------------------------------------------
+// level 0: one block per chunk
+// ---------------------------------------------------------------------------------
+__global__ void __launch_bounds__(LC_BT)
+lc_pool_kernel(LcDev ix, const uint16_t* K, long long ks_seq, long long ks_head, long long ks_tok,
+               int geometry, float* dirs) {
+    __shared__ float sh[LC_BG * LC_D + LC_BG];
+    const int j = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int bh = b * ix.H + h;
+    const int M = ix.state[bh * 4 + 1];
+    if (j >= M) return;
+    const int* bnd = ix.bounds + (size_t)b * (ix.cap[0] + 1);
+    const int lo = bnd[j], hi = bnd[j + 1];
+    const int sub = threadIdx.x & 15;
+    float mu[8], radius;
+    lc_pool_rows(K + b * ks_seq + h * ks_head, ks_tok, lo, hi, geometry, sh, mu, &radius);
+    const size_t n = (size_t)bh * ix.cap[0] + j;
+    if (threadIdx.x < 16) {
+        lc_store8(ix.center[0] + n * LC_D + 8 * sub, mu);
+        float u[8];
+        lc_unit_frag(mu, sub, u);
+        lc_store8(dirs + n * LC_D + 8 * sub, u);
+        if (sub == 0) {
+            ix.radius[0][n] = radius;
+            ix.parent[0][n] = -1;
+            ix.ntok[0][n] = hi - lo;
+            ix.nchunk[0][n] = 1;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// spherical k-means
+// ---------------------------------------------------------------------------------
+// Number of points / clusters of sequence b when clustering level `l` into level l+1.
+__device__ __forceinline__ int lc_level_count(const LcDev& ix, int b, int bh, int l) {
+    return l == 0 ? ix.state[bh * 4 + 1] : ix.nlev[b * LC_MAX_LEVELS + l];
+}
+
+// centroid c starts at point floor(c * N / k)
+__global__ void __launch_bounds__(LC_D)
+lc_kmeans_init_kernel(LcDev ix, int l, const float* pts, int pts_cap, float* cent, int cent_cap) {
+    const int c = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int bh = b * ix.H + h;
+    const int N = lc_level_count(ix, b, bh, l);
+    const int k = ix.nlev[b * LC_MAX_LEVELS + l + 1];
+    if (c >= k) return;
+    float v = (threadIdx.x == 0) ? 1.f : 0.f;
+    if (N > 0) {
+        const long long src = ((long long)c * N) / k;
+        v = pts[((size_t)bh * pts_cap + src) * LC_D + threadIdx.x];
+    }
+    cent[((size_t)bh * cent_cap + c) * LC_D + threadIdx.x] = v;
+}
+
+// label(i) = argmax_c <x_i, m_c>, ties to the lower c.  One 16-lane group per point.
+__global__ void __launch_bounds__(LC_BT)
+lc_kmeans_assign_kernel(LcDev ix, int l, const float* pts, int pts_cap, const float* cent, int cent_cap) {
+    const int h = blockIdx.y, b = blockIdx.z;
+    const int bh = b * ix.H + h;
+    const int sub = threadIdx.x & 15, grp = threadIdx.x >> 4;
+    const int N = lc_level_count(ix, b, bh, l);
+    const int k = ix.nlev[b * LC_MAX_LEVELS + l + 1];
+    const int i = blockIdx.x * LC_BG + grp;
+    if (i >= N) return;
+    float x[8];
+    lc_load8(pts + ((size_t)bh * pts_cap + i) * LC_D + 8 * sub, x);
+    const float* cb = cent + (size_t)bh * cent_cap * LC_D;
+    float best = LC_NEG_INF;
+    int arg = 0;
+    for (int c = 0; c < k; ++c) {
+        float m[8];
+        lc_load8(cb + (size_t)c * LC_D + 8 * sub, m);
+        float p = 0.f;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) p = fmaf(x[t], m[t], p);
+        p = lc_sum16(p);
+        if (p > best) { best = p; arg = c; }
+    }
+    if (sub == 0) ix.parent[l][(size_t)bh * ix.cap[l] + i] = arg;
+}
+
+// m_c = normalise(sum of members); a cluster without members (or with a zero sum) keeps m_c.
+__global__ void __launch_bounds__(LC_BT)
+lc_kmeans_update_kernel(LcDev ix, int l, const float* pts, int pts_cap, float* cent, int cent_cap) {
+    __shared__ float sh[LC_BG * LC_D];
+    const int c = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int bh = b * ix.H + h;
+    const int sub = threadIdx.x & 15, grp = threadIdx.x >> 4;
+    const int N = lc_level_count(ix, b, bh, l);
+    const int k = ix.nlev[b * LC_MAX_LEVELS + l + 1];
+    if (c >= k) return;
+    const int* lab = ix.parent[l] + (size_t)bh * ix.cap[l];
+    float sum[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) sum[t] = 0.f;
+    for (int i = grp; i < N; i += LC_BG) {
+        if (lab[i] == c) {
+            float x[8];
+            lc_load8(pts + ((size_t)bh * pts_cap + i) * LC_D + 8 * sub, x);
+#pragma unroll
+            for (int t = 0; t < 8; ++t) sum[t] += x[t];
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < 8; ++t) sh[grp * LC_D + 8 * sub + t] = sum[t];
+    __syncthreads();
+    if (threadIdx.x < 16) {
+        float s[8];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            float a = 0.f;
+            for (int g = 0; g < LC_BG; ++g) a += sh[g * LC_D + 8 * sub + t];
+            s[t] = a;
+        }
+        float n2 = 0.f;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) n2 = fmaf(s[t], s[t], n2);
+        n2 = lc_sum16(n2);
+        if (n2 > 0.f) {
+            const float inv = 1.0f / sqrtf(n2);
+#pragma unroll
+            for (int t = 0; t < 8; ++t) s[t] *= inv;
+            lc_store8(cent + ((size_t)bh * cent_cap + c) * LC_D + 8 * sub, s);
+        }
+    }
+}
+
+// anc[j] <- label of anc[j] at the level just clustered (anc starts as identity)
+__global__ void lc_anc_kernel(LcDev ix, int l, int* anc) {
+    const int h = blockIdx.y, b = blockIdx.z;
+    const int bh = b * ix.H + h;
+    const int M = ix.state[bh * 4 + 1];
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= M) return;
+    int* a = anc + (size_t)bh * ix.cap[0];
+    const int cur = (l == 0) ? j : a[j];
+    a[j] = ix.parent[l][(size_t)bh * ix.cap[l] + cur];
+}
+
+// node u of level l+1: center, radius over all descendant chunks, counts, direction
+__global__ void __launch_bounds__(LC_BT)
+lc_node_kernel(LcDev ix, int l, const int* anc, const float* cent, int cent_cap, int geometry,
+               float* next_pts, int next_cap) {
+    __shared__ float sh[LC_BG * LC_D + LC_BG];
+    __shared__ int shi[2 * LC_BG];
+    const int u = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int bh = b * ix.H + h;
+    const int sub = threadIdx.x & 15, grp = threadIdx.x >> 4;
+    const int k = ix.nlev[b * LC_MAX_LEVELS + l + 1];
+    if (u >= k) return;
+    const int M = ix.state[bh * 4 + 1];
+    const int* a = anc + (size_t)bh * ix.cap[0];
+    const size_t cb = (size_t)bh * ix.cap[0];
+    float sum[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) sum[t] = 0.f;
+    int cnt = 0, tok = 0;
+    for (int j = grp; j < M; j += LC_BG) {
+        if (a[j] == u) {
+            float c[8];
+            lc_load8(ix.center[0] + (cb + j) * LC_D + 8 * sub, c);
+#pragma unroll
+            for (int t = 0; t < 8; ++t) sum[t] += c[t];
+            cnt += 1;
+            tok += ix.ntok[0][cb + j];
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < 8; ++t) sh[grp * LC_D + 8 * sub + t] = sum[t];
+    if (sub == 0) { shi[grp] = cnt; shi[LC_BG + grp] = tok; }
+    __syncthreads();
+    int nch = 0, ntk = 0;
+    for (int g = 0; g < LC_BG; ++g) { nch += shi[g]; ntk += shi[LC_BG + g]; }
+    float mu[8];
+    if (nch > 0 && geometry == LC_GEOMETRY_TOKEN_BALL) {
+        const float inv = 1.0f / (float)nch;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            float s = 0.f;
+            for (int g = 0; g < LC_BG; ++g) s += sh[g * LC_D + 8 * sub + t];
+            mu[t] = s * inv;
+        }
+    } else {
+        lc_load8(cent + ((size_t)bh * cent_cap + u) * LC_D + 8 * sub, mu);
+    }
+    __syncthreads();
+    float far = LC_NEG_INF;
+    for (int j = grp; j < M; j += LC_BG) {
+        if (a[j] == u) {
+            float c[8];
+            lc_load8(ix.center[0] + (cb + j) * LC_D + 8 * sub, c);
+            float d2 = 0.f;
+#pragma unroll
+            for (int t = 0; t < 8; ++t) { const float e = c[t] - mu[t]; d2 = fmaf(e, e, d2); }
+            d2 = lc_sum16(d2);
+            far = fmaxf(far, lc_pad_radius(sqrtf(d2)) + ix.radius[0][cb + j]);
+        }
+    }
+    if (sub == 0) sh[grp] = far;
+    __syncthreads();
+    float R = LC_NEG_INF;
+    for (int g = 0; g < LC_BG; ++g) R = fmaxf(R, sh[g]);
+    const size_t n = (size_t)bh * ix.cap[l + 1] + u;
+    if (threadIdx.x < 16) {
+        lc_store8(ix.center[l + 1] + n * LC_D + 8 * sub, mu);
+        float d[8];
+        lc_unit_frag(mu, sub, d);
+        lc_store8(next_pts + ((size_t)bh * next_cap + u) * LC_D + 8 * sub, d);
+        if (sub == 0) {
+            ix.radius[l + 1][n] = nch > 0 ? lc_pad_radius(R) : LC_NEG_INF;
+            ix.parent[l + 1][n] = -1;
+            ix.ntok[l + 1][n] = ntk;
+            ix.nchunk[l + 1][n] = nch;
+        }
+    }
+}
+
+int lc_launch_build(const lc_index* idx, const LcWs& ws, const void* Kp, const int64_t ks[3],
+                    int max_M, hipStream_t stream) {
+    const LcDev& ix = idx->dev;
+    const uint16_t* K = static_cast<const uint16_t*>(Kp);
+    const int geometry = idx->cfg.geometry;
+    const int B = ix.B, H = ix.H, L = ix.L;
+    if (max_M > 0) {
+        hipLaunchKernelGGL(lc_pool_kernel, dim3(max_M, H, B), dim3(LC_BT), 0, stream, ix, K,
+                           (long long)ks[0], (long long)ks[1], (long long)ks[2], geometry, ws.dirs);
+        LC_HIP_CHECK(hipGetLastError());
+    }
+    // per-level maxima over the batch (host mirror)
+    float* pts = ws.dirs;
+    int pts_cap = ix.cap[0];
+    float* other = ws.cent_b;
+    int other_cap = ix.cap[1];
+    for (int l = 0; l + 1 < L; ++l) {
+        int maxN = 0, maxK = 0;
+        for (int b = 0; b < B; ++b) {
+            maxN = idx->N[b * LC_MAX_LEVELS + l] > maxN ? idx->N[b * LC_MAX_LEVELS + l] : maxN;
+            maxK = idx->N[b * LC_MAX_LEVELS + l + 1] > maxK ? idx->N[b * LC_MAX_LEVELS + l + 1] : maxK;
+        }
+        const int cent_cap = ix.cap[1];
+        hipLaunchKernelGGL(lc_kmeans_init_kernel, dim3(maxK, H, B), dim3(LC_D), 0, stream, ix, l,
+                           (const float*)pts, pts_cap, ws.cent_a, cent_cap);
+        LC_HIP_CHECK(hipGetLastError());
+        if (maxN > 0) {
+            for (int it = 0; it < idx->cfg.kmeans_iters; ++it) {
+                hipLaunchKernelGGL(lc_kmeans_assign_kernel, dim3((maxN + LC_BG - 1) / LC_BG, H, B), dim3(LC_BT), 0,
+                                   stream, ix, l, (const float*)pts, pts_cap, (const float*)ws.cent_a, cent_cap);
+                hipLaunchKernelGGL(lc_kmeans_update_kernel, dim3(maxK, H, B), dim3(LC_BT), 0, stream, ix, l,
+                                   (const float*)pts, pts_cap, ws.cent_a, cent_cap);
+            }
+            LC_HIP_CHECK(hipGetLastError());
+            if (max_M > 0) {
+                hipLaunchKernelGGL(lc_anc_kernel, dim3((max_M + 255) / 256, H, B), dim3(256), 0, stream, ix, l, ws.anc);
+                LC_HIP_CHECK(hipGetLastError());
+            }
+        }
+        hipLaunchKernelGGL(lc_node_kernel, dim3(maxK, H, B), dim3(LC_BT), 0, stream, ix, l, (const int*)ws.anc,
+                           (const float*)ws.cent_a, cent_cap, geometry, other, other_cap);
+        LC_HIP_CHECK(hipGetLastError());
+        float* t = pts; pts = other; other = t;
+        const int tc = pts_cap; pts_cap = other_cap; other_cap = tc;
+    }
+    return LC_OK;
+}
+
+// ---------------------------------------------------------------------------------
+// lazy update
+// ---------------------------------------------------------------------------------
+struct LcCloseBits { uint32_t w[32]; };       // one bit per sequence (B <= 1024)
+
+__global__ void __launch_bounds__(LC_BT)
+lc_append_kernel(LcDev ix, uint16_t* K, uint16_t* V, long long ks_seq, long long ks_head, long long ks_tok,
+                 const uint16_t* k_new, const uint16_t* v_new, LcCloseBits close, int geometry) {
+    __shared__ float sh[LC_BG * LC_D + LC_BG];
+    __shared__ float best_sim[LC_BG];
+    __shared__ int best_arg[LC_BG];
+    const int h = blockIdx.x, b = blockIdx.y;
+    const int bh = b * ix.H + h;
+    const int tid = threadIdx.x, sub = tid & 15, grp = tid >> 4;
+    const int T = ix.state[bh * 4 + 0];
+    const int M = ix.state[bh * 4 + 1];
+    uint16_t* Kbh = K + b * ks_seq + h * ks_head;
+    uint16_t* Vbh = V + b * ks_seq + h * ks_head;
+    if (tid < 16) {
+        *reinterpret_cast<uint4*>(Kbh + (long long)T * ks_tok + 8 * sub) =
+            *reinterpret_cast<const uint4*>(k_new + (size_t)bh * LC_D + 8 * sub);
+    } else if (tid < 32) {
+        *reinterpret_cast<uint4*>(Vbh + (long long)T * ks_tok + 8 * sub) =
+            *reinterpret_cast<const uint4*>(v_new + (size_t)bh * LC_D + 8 * sub);
+    }
+    const bool do_close = (close.w[b >> 5] >> (b & 31)) & 1u;
+    if (!do_close) {
+        if (tid == 0) ix.state[bh * 4 + 0] = T + 1;
+        return;
+    }
+    __threadfence_block();
+    __syncthreads();
+
+    int* bnd = ix.bounds + (size_t)b * (ix.cap[0] + 1);
+    const int lo = bnd[M], hi = T + 1;
+    float mu_x[8], r_x;
+    lc_pool_rows(Kbh, ks_tok, lo, hi, geometry, sh, mu_x, &r_x);
+    const int n_x = hi - lo;
+    int p = -1;
+    if (ix.L > 1) {
+        float xh[8];
+        lc_unit_frag(mu_x, sub, xh);
+        const float xh0 = __shfl(xh[0], (tid & 48), 64);        // first component, from the group's lane 0
+        const int n1 = ix.nlev[b * LC_MAX_LEVELS + 1];
+        const size_t b1 = (size_t)bh * ix.cap[1];
+        float bs = LC_NEG_INF;
+        int ba = 0x7fffffff;
+        for (int c = grp; c < n1; c += LC_BG) {
+            float m[8];
+            lc_load8(ix.center[1] + (b1 + c) * LC_D + 8 * sub, m);
+            float dot = 0.f, n2 = 0.f;
+#pragma unroll
+            for (int t = 0; t < 8; ++t) { dot = fmaf(xh[t], m[t], dot); n2 = fmaf(m[t], m[t], n2); }
+            dot = lc_sum16(dot);
+            n2 = lc_sum16(n2);
+            const float sim = n2 > 0.f ? dot / sqrtf(n2) : xh0;
+            if (sim > bs) { bs = sim; ba = c; }
+        }
+        if (sub == 0) { best_sim[grp] = bs; best_arg[grp] = ba; }
+        __syncthreads();
+        float s = LC_NEG_INF;
+        p = 0x7fffffff;
+        for (int g = 0; g < LC_BG; ++g) {
+            const float sg = best_sim[g];
+            const int ag = best_arg[g];
+            if (sg > s || (sg == s && ag < p)) { s = sg; p = ag; }
+        }
+        // path to the top: moving-average centers, monotone radii
+        if (tid < 16) {
+            int a = p;
+            for (int l = 1; l < ix.L; ++l) {
+                const size_t n = (size_t)bh * ix.cap[l] + a;
+                const int n_a = ix.nchunk[l][n];
+                float mu_a[8], nw[8];
+                lc_load8(ix.center[l] + n * LC_D + 8 * sub, mu_a);
+                const float inv = 1.0f / (float)(n_a + 1);
+#pragma unroll
+                for (int t = 0; t < 8; ++t) nw[t] = fmaf((float)n_a, mu_a[t], mu_x[t]) * inv;
+                if (geometry == LC_GEOMETRY_PAPER_UNIT) {
+                    float un[8];
+                    lc_unit_frag(nw, sub, un);
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) nw[t] = un[t];
+                }
+                float sh2 = 0.f, re2 = 0.f;
+#pragma unroll
+                for (int t = 0; t < 8; ++t) {
+                    const float e = nw[t] - mu_a[t];
+                    const float f = mu_x[t] - nw[t];
+                    sh2 = fmaf(e, e, sh2);
+                    re2 = fmaf(f, f, re2);
+                }
+                sh2 = lc_sum16(sh2);
+                re2 = lc_sum16(re2);
+                const float R_old = ix.radius[l][n];
+                const float grown = R_old + lc_pad_radius(sqrtf(sh2));
+                const float reach = lc_pad_radius(sqrtf(re2)) + r_x;
+                const int next = ix.parent[l][n];
+                lc_store8(ix.center[l] + n * LC_D + 8 * sub, nw);
+                if (sub == 0) {
+                    ix.radius[l][n] = lc_pad_radius(fmaxf(grown, reach));
+                    ix.ntok[l][n] += n_x;
+                    ix.nchunk[l][n] = n_a + 1;
+                }
+                a = next;
+            }
+        }
+    }
+    const size_t n0 = (size_t)bh * ix.cap[0] + M;
+    if (tid < 16) {
+        lc_store8(ix.center[0] + n0 * LC_D + 8 * sub, mu_x);
+        if (sub == 0) {
+            ix.radius[0][n0] = r_x;
+            ix.parent[0][n0] = p;
+            ix.ntok[0][n0] = n_x;
+            ix.nchunk[0][n0] = 1;
+            if (h == 0) bnd[M + 1] = hi;
+            ix.state[bh * 4 + 0] = T + 1;
+            ix.state[bh * 4 + 1] = M + 1;
+        }
+    }
+}
+
+int lc_launch_append(const lc_index* idx, void* K, void* V, const int64_t ks[3],
+                     const void* k_new, const void* v_new, const uint8_t* close_host,
+                     uint32_t, hipStream_t stream) {
+    const LcDev& ix = idx->dev;
+    LcCloseBits bits;
+    for (int i = 0; i < 32; ++i) bits.w[i] = 0u;
+    if (close_host)
+        for (int b = 0; b < ix.B; ++b)
+            if (close_host[b]) bits.w[b >> 5] |= 1u << (b & 31);
+    hipLaunchKernelGGL(lc_append_kernel, dim3(ix.H, ix.B), dim3(LC_BT), 0, stream, ix,
+                       static_cast<uint16_t*>(K), static_cast<uint16_t*>(V),
+                       (long long)ks[0], (long long)ks[1], (long long)ks[2],
+                       static_cast<const uint16_t*>(k_new), static_cast<const uint16_t*>(v_new), bits,
+                       idx->cfg.geometry);
+    LC_HIP_CHECK(hipGetLastError());
+    return LC_OK;
+}

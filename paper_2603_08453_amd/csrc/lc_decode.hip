@@ -1,0 +1,314 @@
+// Sparse attention for one decode step: split-K flash-decode over the selected
+// chunks (plus the open tail), merged by the last split to finish.
+//
+// Grid (split, KV head, sequence), 256 threads = 16 groups of 16 lanes.  A group
+// owns a contiguous run of the split's tokens; its 16 lanes each hold 8 of the
+// 128 columns, so one K (or V) row is one 16-byte load per lane and four rows
+// make a full 1 KiB wavefront load.  Logits for the G query heads of the group
+// are reduced across the 16 lanes; the softmax is kept online in base 2.
+#include "lc_device.h"
+#include "lc_internal.h"
+
+#define LC_DEC_THREADS 256
+#define LC_DEC_GROUPS 16
+#define LC_DEC_UNROLL 4
+#define LC_DEC_MIN_TOKENS_PER_SPLIT 64
+#define LC_LOG2E 1.4426950408889634f
+#define LC_LN2 0.6931471805599453f
+
+struct LcDecodeArgs {
+    LcDev ix;
+    const uint16_t* q;
+    const uint16_t* K;
+    const uint16_t* V;
+    long long ks_seq, ks_head, ks_tok;
+    const int32_t* ids;
+    const int32_t* counts;
+    int cap;
+    float* part_acc;      // [B][H][S][G][d]
+    float* part_ml;       // [B][H][S][G][2]
+    float* out;           // [B][H*G][d]
+    float* lse;           // [B][H*G] or null
+    int id_cap_lds;       // entries of the LDS run table
+};
+
+template <int G>
+__global__ void __launch_bounds__(LC_DEC_THREADS)
+lc_decode_kernel(const LcDecodeArgs a) {
+    extern __shared__ int lds_dyn[];
+    __shared__ int scan_sh[8];
+    __shared__ int last_sh;
+    __shared__ float comb_ml[LC_DEC_THREADS / 64][G][2];
+    __shared__ float comb_acc[LC_DEC_THREADS / 64][G][LC_D];
+
+    const LcDev& ix = a.ix;
+    const int s = blockIdx.x, S = gridDim.x, h = blockIdx.y, b = blockIdx.z;
+    const int bh = b * ix.H + h;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int sub = tid & 15, grp = tid >> 4;
+
+    const int T = ix.state[bh * 4 + 0];
+    const int M = ix.state[bh * 4 + 1];
+    int n_ids = a.counts[bh];
+    n_ids = max(0, min(n_ids, min(a.cap, a.id_cap_lds)));
+    const int* bnd = ix.bounds + (size_t)b * (ix.cap[0] + 1);
+    const int32_t* ids = a.ids + (size_t)bh * a.cap;
+
+    // ---- run table in LDS: start row and exclusive token prefix of each selected chunk,
+    // then the open tail as the last run.
+    int* run_start = lds_dyn;                       // [n_ids + 1]
+    int* run_off = lds_dyn + a.id_cap_lds + 1;      // [n_ids + 2]
+    int carry = 0;
+    for (int t0 = 0; t0 < n_ids + 1; t0 += LC_DEC_THREADS) {
+        const int i = t0 + tid;
+        int st = 0, ln = 0;
+        if (i < n_ids) {
+            const int id = max(0, min(ids[i], M - 1));
+            st = bnd[id];
+            ln = bnd[id + 1] - st;
+        } else if (i == n_ids) {
+            st = bnd[M];
+            ln = T - st;
+        }
+        int tot;
+        const int ex = lc_block_scan<LC_DEC_THREADS>(ln, scan_sh, &tot);
+        if (i <= n_ids) { run_start[i] = st; run_off[i] = carry + ex; }
+        carry += tot;
+    }
+    const int n_runs = n_ids + 1;
+    const int n_tok = carry;
+    if (tid == 0) run_off[n_runs] = n_tok;
+    __syncthreads();
+
+    int S_eff = (n_tok + LC_DEC_MIN_TOKENS_PER_SPLIT - 1) / LC_DEC_MIN_TOKENS_PER_SPLIT;
+    S_eff = max(1, min(S, S_eff));
+
+    if (s < S_eff) {
+        const int lo = (int)(((long long)n_tok * s) / S_eff);
+        const int hi = (int)(((long long)n_tok * (s + 1)) / S_eff);
+        // this group's contiguous slice of [lo, hi)
+        const int per = (hi - lo + LC_DEC_GROUPS - 1) / LC_DEC_GROUPS;
+        int t = min(hi, lo + grp * per);
+        const int t_end = min(hi, t + per);
+
+        // query fragments: lane `sub` holds columns [8 sub, 8 sub + 8) of each head, pre-scaled
+        float qf[G][8];
+        {
+            const uint16_t* qb = a.q + ((size_t)b * ix.H * G + (size_t)h * G) * LC_D;
+            const float scale = 0.08838834764831845f * LC_LOG2E;     // log2(e) / sqrt(128)
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                const uint4 v = *reinterpret_cast<const uint4*>(qb + g * LC_D + 8 * sub);
+                lc_unpack8(v, qf[g]);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) qf[g][i] *= scale;
+            }
+        }
+        float m[G], l[G], acc[G][8];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            m[g] = LC_NEG_INF;
+            l[g] = 0.f;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[g][i] = 0.f;
+        }
+
+        // locate the run holding token t (largest r with run_off[r] <= t)
+        int r = 0;
+        if (t < t_end) {
+            int lo_r = 0, hi_r = n_runs;            // run_off[lo_r] <= t < run_off[hi_r]
+            while (hi_r - lo_r > 1) {
+                const int mid = (lo_r + hi_r) >> 1;
+                if (run_off[mid] <= t) lo_r = mid; else hi_r = mid;
+            }
+            r = lo_r;
+        }
+        const uint16_t* Kb = a.K + (size_t)b * a.ks_seq + (size_t)h * a.ks_head;
+        const uint16_t* Vb = a.V + (size_t)b * a.ks_seq + (size_t)h * a.ks_head;
+
+        while (t < t_end) {
+            uint4 kv[LC_DEC_UNROLL], vv[LC_DEC_UNROLL];
+            bool live[LC_DEC_UNROLL];
+#pragma unroll
+            for (int u = 0; u < LC_DEC_UNROLL; ++u) {
+                live[u] = (t + u) < t_end;
+                if (live[u]) {
+                    while (run_off[r + 1] <= t + u) ++r;      // empty runs are skipped too
+                    const long long row = run_start[r] + (t + u - run_off[r]);
+                    kv[u] = *reinterpret_cast<const uint4*>(Kb + row * a.ks_tok + 8 * sub);
+                    vv[u] = *reinterpret_cast<const uint4*>(Vb + row * a.ks_tok + 8 * sub);
+                }
+            }
+            float x[LC_DEC_UNROLL][G];
+#pragma unroll
+            for (int u = 0; u < LC_DEC_UNROLL; ++u) {
+                float kf[8];
+                if (live[u]) lc_unpack8(kv[u], kf);
+#pragma unroll
+                for (int g = 0; g < G; ++g) {
+                    float p = 0.f;
+                    if (live[u]) {
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) p = fmaf(kf[i], qf[g][i], p);
+                    }
+                    p = lc_sum16(p);
+                    x[u][g] = live[u] ? p : LC_NEG_INF;
+                }
+            }
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                float mx = m[g];
+#pragma unroll
+                for (int u = 0; u < LC_DEC_UNROLL; ++u) mx = fmaxf(mx, x[u][g]);
+                const float sc = exp2f(m[g] - mx);          // m = -inf, mx finite: 0
+                m[g] = mx;
+                l[g] *= sc;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) acc[g][i] *= sc;
+            }
+#pragma unroll
+            for (int u = 0; u < LC_DEC_UNROLL; ++u) {
+                if (live[u]) {
+                    float vf[8];
+                    lc_unpack8(vv[u], vf);
+#pragma unroll
+                    for (int g = 0; g < G; ++g) {
+                        const float p = exp2f(x[u][g] - m[g]);
+                        l[g] += p;
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) acc[g][i] = fmaf(p, vf[i], acc[g][i]);
+                    }
+                }
+            }
+            t += LC_DEC_UNROLL;
+        }
+
+        // ---- combine the 4 groups of a wave (xor 16, 32), then the waves through LDS
+#pragma unroll
+        for (int off = 16; off < 64; off <<= 1) {
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                const float m_o = __shfl_xor(m[g], off);
+                const float l_o = __shfl_xor(l[g], off);
+                const float mx = fmaxf(m[g], m_o);
+                const float sa = (m[g] == LC_NEG_INF) ? 0.f : exp2f(m[g] - mx);
+                const float sb = (m_o == LC_NEG_INF) ? 0.f : exp2f(m_o - mx);
+                l[g] = l[g] * sa + l_o * sb;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const float a_o = __shfl_xor(acc[g][i], off);
+                    acc[g][i] = acc[g][i] * sa + a_o * sb;
+                }
+                m[g] = mx;
+            }
+        }
+        if (lane < 16) {
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                if (lane == 0) { comb_ml[wave][g][0] = m[g]; comb_ml[wave][g][1] = l[g]; }
+#pragma unroll
+                for (int i = 0; i < 8; ++i) comb_acc[wave][g][8 * lane + i] = acc[g][i];
+            }
+        }
+        __syncthreads();
+        float* pacc = a.part_acc + ((size_t)bh * S + s) * G * LC_D;
+        float* pml = a.part_ml + ((size_t)bh * S + s) * G * 2;
+        for (int e = tid; e < G * LC_D; e += LC_DEC_THREADS) {
+            const int g = e / LC_D, c = e % LC_D;
+            float mx = LC_NEG_INF;
+#pragma unroll
+            for (int w = 0; w < LC_DEC_THREADS / 64; ++w) mx = fmaxf(mx, comb_ml[w][g][0]);
+            float num = 0.f, den = 0.f;
+#pragma unroll
+            for (int w = 0; w < LC_DEC_THREADS / 64; ++w) {
+                const float mw = comb_ml[w][g][0];
+                const float sc = (mw == LC_NEG_INF) ? 0.f : exp2f(mw - mx);
+                num = fmaf(comb_acc[w][g][c], sc, num);
+                den = fmaf(comb_ml[w][g][1], sc, den);
+            }
+            pacc[e] = num;
+            if (c == 0) { pml[2 * g] = mx; pml[2 * g + 1] = den; }
+        }
+    }
+
+    // ---- the last split to arrive merges (log-sum-exp merge of the partial results)
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) {
+        const int old = atomicAdd(&ix.sync[bh * 4 + 1], 1);
+        last_sh = (old == S - 1) ? 1 : 0;
+    }
+    __syncthreads();
+    if (!last_sh) return;
+    __threadfence();
+
+    const float* pacc = a.part_acc + (size_t)bh * S * G * LC_D;
+    const float* pml = a.part_ml + (size_t)bh * S * G * 2;
+    for (int e = tid; e < G * LC_D; e += LC_DEC_THREADS) {
+        const int g = e / LC_D, c = e % LC_D;
+        float mx = LC_NEG_INF;
+        if (n_tok > 0)
+            for (int sp = 0; sp < S_eff; ++sp) mx = fmaxf(mx, __builtin_nontemporal_load(&pml[(sp * G + g) * 2]));
+        float num = 0.f, den = 0.f;
+        if (n_tok > 0) {
+            for (int sp = 0; sp < S_eff; ++sp) {
+                const float ms = __builtin_nontemporal_load(&pml[(sp * G + g) * 2]);
+                const float ls = __builtin_nontemporal_load(&pml[(sp * G + g) * 2 + 1]);
+                const float sc = (ms == LC_NEG_INF) ? 0.f : exp2f(ms - mx);
+                num = fmaf(__builtin_nontemporal_load(&pacc[((size_t)sp * G + g) * LC_D + c]), sc, num);
+                den = fmaf(ls, sc, den);
+            }
+        }
+        const size_t o = ((size_t)b * ix.H * G + (size_t)h * G + g);
+        a.out[o * LC_D + c] = den > 0.f ? num / den : 0.f;
+        if (a.lse && c == 0) a.lse[o] = den > 0.f ? (mx + log2f(den)) * LC_LN2 : LC_NEG_INF;
+    }
+    if (tid == 0) ix.sync[bh * 4 + 1] = 0;
+}
+
+template <int G>
+static int launch_decode_g(const LcDecodeArgs& a, int splits, hipStream_t stream) {
+    const size_t lds = (size_t)(2 * a.id_cap_lds + 4) * sizeof(int);
+    if (lds > 48 * 1024)
+        LC_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&lc_decode_kernel<G>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(lc_decode_kernel<G>, dim3(splits, a.ix.H, a.ix.B), dim3(LC_DEC_THREADS), lds, stream, a);
+    LC_HIP_CHECK(hipGetLastError());
+    return LC_OK;
+}
+
+int lc_launch_decode(const lc_index* idx, const LcWs& ws, const void* q, const void* K, const void* V,
+                     const int64_t ks[3], const int32_t* ids, const int32_t* counts, int cap, int G,
+                     int splits, float* out, float* lse, hipStream_t stream) {
+    LcDecodeArgs a;
+    a.ix = idx->dev;
+    a.q = static_cast<const uint16_t*>(q);
+    a.K = static_cast<const uint16_t*>(K);
+    a.V = static_cast<const uint16_t*>(V);
+    a.ks_seq = ks[0];
+    a.ks_head = ks[1];
+    a.ks_tok = ks[2];
+    a.ids = ids;
+    a.counts = counts;
+    a.cap = cap;
+    a.part_acc = ws.part_acc;
+    a.part_ml = ws.part_ml;
+    a.out = out;
+    a.lse = lse;
+    int max_M = 0;
+    for (int b = 0; b < idx->B; ++b)
+        if (idx->M[b] > max_M) max_M = idx->M[b];
+    a.id_cap_lds = cap < max_M ? cap : max_M;          // a (sequence, head) never lists more ids than it has chunks
+    if (a.id_cap_lds < 1) a.id_cap_lds = 1;
+    switch (G) {
+        case 1: return launch_decode_g<1>(a, splits, stream);
+        case 2: return launch_decode_g<2>(a, splits, stream);
+        case 3: return launch_decode_g<3>(a, splits, stream);
+        case 4: return launch_decode_g<4>(a, splits, stream);
+        case 5: return launch_decode_g<5>(a, splits, stream);
+        case 6: return launch_decode_g<6>(a, splits, stream);
+        case 7: return launch_decode_g<7>(a, splits, stream);
+        case 8: return launch_decode_g<8>(a, splits, stream);
+    }
+    return LC_ERR_BAD_SHAPE;
+}

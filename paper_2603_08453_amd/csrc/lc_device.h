@@ -1,0 +1,223 @@
+// Device-side building blocks shared by the kernels (wave64, gfx950).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#define LC_D 128                  // head dimension the kernels are written for
+#define LC_NEG_INF (-__builtin_huge_valf())
+
+// ---------------------------------------------------------------- bf16 unpacking
+// A 32-bit word holds two bf16 values; widening is a shift or a mask.
+__device__ __forceinline__ float lc_bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float lc_bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+__device__ __forceinline__ void lc_unpack8(const uint4& v, float (&f)[8]) {
+    f[0] = lc_bf16_lo(v.x); f[1] = lc_bf16_hi(v.x);
+    f[2] = lc_bf16_lo(v.y); f[3] = lc_bf16_hi(v.y);
+    f[4] = lc_bf16_lo(v.z); f[5] = lc_bf16_hi(v.z);
+    f[6] = lc_bf16_lo(v.w); f[7] = lc_bf16_hi(v.w);
+}
+
+__device__ __forceinline__ uint16_t lc_f32_to_bf16(float f) {     // round to nearest even
+    uint32_t u = __float_as_uint(f);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// ---------------------------------------------------------------- reductions
+// Sum / max over the 16 consecutive lanes that share (lane >> 4).
+__device__ __forceinline__ float lc_sum16(float v) {
+    v += __shfl_xor(v, 1);
+    v += __shfl_xor(v, 2);
+    v += __shfl_xor(v, 4);
+    v += __shfl_xor(v, 8);
+    return v;
+}
+__device__ __forceinline__ float lc_sum64(float v) {
+    v = lc_sum16(v);
+    v += __shfl_xor(v, 16);
+    v += __shfl_xor(v, 32);
+    return v;
+}
+__device__ __forceinline__ float lc_max64(float v) {
+    for (int m = 1; m < 64; m <<= 1) v = fmaxf(v, __shfl_xor(v, m));
+    return v;
+}
+
+// ---------------------------------------------------------------- score keys
+// Order-preserving map float -> uint32 (larger score = larger key).  -inf (empty
+// or pruned node) maps to 0, which no finite score produces: key 0 = "not a candidate".
+__device__ __forceinline__ uint32_t lc_score_key(float s) {
+    if (s == LC_NEG_INF) return 0u;
+    s += 0.0f;                                        // -0 -> +0 so equal scores share a key
+    uint32_t u = __float_as_uint(s);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float lc_key_score(uint32_t k) {
+    if (k == 0u) return LC_NEG_INF;
+    uint32_t u = (k & 0x80000000u) ? (k & 0x7fffffffu) : ~k;
+    return __uint_as_float(u);
+}
+
+// ---------------------------------------------------------------- Eq. 2 for one node
+// Called by the 16 lanes of a group; lane `sub` holds the query fragments for
+// floats [4 sub, 4 sub + 4) and [64 + 4 sub, 64 + 4 sub + 4) of each of the G heads.
+// Returns max_g (q_g . mu + |q_g| R) / sqrt(d) in every lane of the group.
+// The operation order is fixed (explicit fma chain) so that every kernel that
+// scores the same node obtains the same bits.
+template <int G>
+__device__ __forceinline__ float lc_score_node(const float* __restrict__ center, float R, int sub,
+                                               const float (&qf)[G][8], const float (&qn)[G]) {
+    const float4 a = *reinterpret_cast<const float4*>(center + 4 * sub);
+    const float4 b = *reinterpret_cast<const float4*>(center + 64 + 4 * sub);
+    float best = LC_NEG_INF;
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        float p = a.x * qf[g][0];
+        p = fmaf(a.y, qf[g][1], p);
+        p = fmaf(a.z, qf[g][2], p);
+        p = fmaf(a.w, qf[g][3], p);
+        p = fmaf(b.x, qf[g][4], p);
+        p = fmaf(b.y, qf[g][5], p);
+        p = fmaf(b.z, qf[g][6], p);
+        p = fmaf(b.w, qf[g][7], p);
+        p = lc_sum16(p);
+        const float ub = fmaf(qn[g], R, p) * 0.08838834764831845f;      // 1/sqrt(128)
+        best = fmaxf(best, ub);
+    }
+    return best;
+}
+
+// Load the query group of KV head h into registers (fragments as above) and
+// compute the norms.  q: bf16 [H_q][d] of this sequence.
+template <int G>
+__device__ __forceinline__ void lc_load_query_frags(const uint16_t* __restrict__ q, int h, int sub,
+                                                    float (&qf)[G][8], float (&qn)[G]) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        const uint16_t* row = q + (size_t)(h * G + g) * LC_D;
+        const uint2 a = *reinterpret_cast<const uint2*>(row + 4 * sub);
+        const uint2 b = *reinterpret_cast<const uint2*>(row + 64 + 4 * sub);
+        qf[g][0] = lc_bf16_lo(a.x); qf[g][1] = lc_bf16_hi(a.x);
+        qf[g][2] = lc_bf16_lo(a.y); qf[g][3] = lc_bf16_hi(a.y);
+        qf[g][4] = lc_bf16_lo(b.x); qf[g][5] = lc_bf16_hi(b.x);
+        qf[g][6] = lc_bf16_lo(b.y); qf[g][7] = lc_bf16_hi(b.y);
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) s = fmaf(qf[g][i], qf[g][i], s);
+        qn[g] = sqrtf(lc_sum16(s));
+    }
+}
+
+// ---------------------------------------------------------------- block scan
+// Exclusive prefix sum of one int per thread over a block of NT threads.
+// `sh` needs NT/64 + 1 ints.  Returns the exclusive prefix; *total = block sum.
+template <int NT>
+__device__ __forceinline__ int lc_block_scan(int v, int* sh, int* total) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int inc = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int t = __shfl_up(inc, off);
+        if (lane >= off) inc += t;
+    }
+    __syncthreads();                 // protect sh from the previous use
+    if (lane == 63) sh[wave] = inc;
+    __syncthreads();
+    int base = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < NT / 64; ++w) {
+        const int s = sh[w];
+        if (w < wave) base += s;
+        tot += s;
+    }
+    *total = tot;
+    return base + inc - v;
+}
+
+// ---------------------------------------------------------------- weighted radix select
+// Items i in [0, n) with key(i) != 0, ordered by (key descending, i ascending).
+// Finds the longest prefix whose weights sum to <= W and that holds <= C items.
+// Result: items with key > kstar are in; items with key == kstar are in while,
+// taken in ascending i, their running weight stays <= remW and their running
+// count <= remC; `all` set = every candidate fits (kstar = 0).
+struct LcSel {
+    uint32_t kstar;
+    int remW;
+    int remC;
+    int all;
+};
+
+// sh: 2*256 + 4 ints of LDS.  All NT threads must call.
+template <int NT, typename KeyF, typename WgtF>
+__device__ __forceinline__ LcSel lc_block_select(int n, long long W, long long C, KeyF key, WgtF wgt, int* sh) {
+    int* hw = sh;
+    int* hc = sh + 256;
+    int* res = sh + 512;
+    uint32_t prefix = 0u, mask = 0u;
+    long long remW = W, remC = C;
+    LcSel out;
+    out.all = 0;
+    for (int pass = 0; pass < 4; ++pass) {
+        const int shift = 24 - 8 * pass;
+        for (int i = threadIdx.x; i < 256; i += NT) { hw[i] = 0; hc[i] = 0; }
+        __syncthreads();
+        for (int i = threadIdx.x; i < n; i += NT) {
+            const uint32_t k = key(i);
+            if (k != 0u && (k & mask) == prefix) {
+                const int b = (k >> shift) & 255;
+                atomicAdd(&hw[b], wgt(i));
+                atomicAdd(&hc[b], 1);
+            }
+        }
+        __syncthreads();
+        if (threadIdx.x < 64) {
+            const int l = threadIdx.x;
+            int w[4], c[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { w[j] = hw[255 - (4 * l + j)]; c[j] = hc[255 - (4 * l + j)]; }
+            long long sw = (long long)w[0] + w[1] + w[2] + w[3];
+            long long sc = (long long)c[0] + c[1] + c[2] + c[3];
+            long long iw = sw, ic = sc;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const long long tw = __shfl_up(iw, off), tc = __shfl_up(ic, off);
+                if (l >= off) { iw += tw; ic += tc; }
+            }
+            long long cw = iw - sw, cc = ic - sc;           // weight / count of all higher bins
+            int found = -1;
+            long long fw = 0, fc = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (found < 0) {
+                    if (cw + w[j] > remW || cc + c[j] > remC) { found = 255 - (4 * l + j); fw = cw; fc = cc; }
+                    else { cw += w[j]; cc += c[j]; }
+                }
+            }
+            const unsigned long long bal = __ballot(found >= 0);
+            if (bal == 0ull) {
+                if (l == 0) res[0] = -1;
+            } else {
+                const int first = __ffsll((long long)bal) - 1;        // lowest lane = highest bins
+                if (l == first) { res[0] = found; res[1] = (int)fw; res[2] = (int)fc; }
+            }
+        }
+        __syncthreads();
+        const int found = res[0];
+        if (found < 0) {            // everything (still in scope) fits; only possible in pass 0
+            out.all = 1;
+            break;
+        }
+        remW -= res[1];
+        remC -= res[2];
+        prefix |= (uint32_t)found << shift;
+        mask |= 255u << shift;
+        __syncthreads();
+    }
+    __syncthreads();
+    out.kstar = out.all ? 0u : prefix;
+    out.remW = (int)(remW > 0x7fffffffLL ? 0x7fffffffLL : remW);
+    out.remC = (int)(remC > 0x7fffffffLL ? 0x7fffffffLL : remC);
+    return out;
+}

@@ -1,0 +1,84 @@
+// Host-side structures shared by the translation units of liblychee.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include <vector>
+
+#include "lychee.h"
+
+// Device-side view of an index, passed to kernels by value.
+// Per-level arrays are indexed [(b * H + h) * cap[l] + n]; centers carry d floats per node.
+struct LcDev {
+    int B, H, d, L, F;
+    int cap[LC_MAX_LEVELS];
+    int* state;      // [B][H][4]: {T, M, 0, 0}: tokens written, closed chunks (one copy per head)
+    int* nlev;       // [B][LC_MAX_LEVELS]: nodes per level (entry 0 unused: level 0 has M nodes)
+    int* bounds;     // [B][cap[0] + 1]: chunk boundaries (shared by the heads of a sequence)
+    int* sync;       // [B][H][4]: arrival counters of the fused kernels; zero between calls
+    float* center[LC_MAX_LEVELS];
+    float* radius[LC_MAX_LEVELS];
+    int* parent[LC_MAX_LEVELS];
+    int* ntok[LC_MAX_LEVELS];
+    int* nchunk[LC_MAX_LEVELS];
+};
+
+struct lc_index {
+    lc_config cfg;
+    int B, H_kv, d;
+    int device;
+    void* buf;
+    size_t bytes;
+    LcDev dev;
+    std::vector<int> T;      // host mirror, per sequence
+    std::vector<int> M;      // host mirror, per sequence
+    std::vector<int> N;      // [B][LC_MAX_LEVELS] nodes per level (N[b][0] mirrors M)
+};
+
+// Layout of the index buffer: fills dev pointers from base; returns total bytes.
+size_t lc_layout_index(const lc_config* cfg, int B, int H, int d, void* base, LcDev* dev);
+
+// Workspace carve-up (all offsets 256-byte aligned).
+struct LcWs {
+    // retrieval
+    uint32_t* keys;      // [B][H][cap0] order-preserving score keys of the chunks (0 = not a candidate)
+    uint8_t* kept1;      // [B][H][cap1] level-1 nodes whose children are scored
+    float* scores;       // [B][H][cap0] scratch scores when the caller passes none
+    // decode
+    float* part_acc;     // [B][H][S][G][d]
+    float* part_ml;      // [B][H][S][G][2]
+    // build
+    float* dirs;         // [B][H][cap0][d] unit directions of the level being clustered
+    float* cent_a;       // [B][H][cap1][d] centroids (ping)
+    float* cent_b;       // [B][H][cap1][d] centroids (pong)
+    int* labels;         // [B][H][cap0]
+    int* anc;            // [B][H][cap0] chunk -> ancestor at the level being built
+    size_t total;
+};
+size_t lc_layout_ws(const lc_config* cfg, int B, int H_q, int H, int d, int splits, void* base, LcWs* ws);
+int lc_auto_splits(const lc_config* cfg, int B, int H);
+
+void lc_set_hip_error(hipError_t e);
+#define LC_HIP_CHECK(expr)                       \
+    do {                                         \
+        hipError_t _e = (expr);                  \
+        if (_e != hipSuccess) {                  \
+            lc_set_hip_error(_e);                \
+            return LC_ERR_HIP;                   \
+        }                                        \
+    } while (0)
+
+// Launchers (each enqueues on `stream` and returns LC_OK or LC_ERR_HIP).
+int lc_launch_build(const lc_index* idx, const LcWs& ws, const void* K, const int64_t ks[3],
+                    int max_M, hipStream_t stream);
+int lc_launch_retrieve(const lc_index* idx, const LcWs& ws, const void* q, int G, int budget,
+                       int32_t* ids, int32_t* counts, float* scores, int cap,
+                       int max_M, int max_upper, hipStream_t stream);
+int lc_launch_decode(const lc_index* idx, const LcWs& ws, const void* q, const void* K, const void* V,
+                     const int64_t ks[3], const int32_t* ids, const int32_t* counts, int cap, int G,
+                     int splits, float* out, float* lse, hipStream_t stream);
+int lc_launch_append(const lc_index* idx, void* K, void* V, const int64_t ks[3],
+                     const void* k_new, const void* v_new, const uint8_t* close_dev_flags_or_null,
+                     uint32_t close_mask_lo, hipStream_t stream);

@@ -1,0 +1,363 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same
+seeded inputs and the identical stored index.
+
+Bars (written here, derived in the design notes):
+  * chunk-id sets: identical to the oracle's, except that chunks whose oracle score
+    lies within 1e-5 (relative, logit units) of the cutoff may differ; ties by lower id.
+  * chunk scores: float32 vs float64, |diff| <= 2e-5 * max(1, |score|).
+  * attention: bf16 inputs, float32 accumulation: max abs error <= 1e-2 and
+    relative L2 error <= 2e-3 against the float64 oracle.
+"""
+import math
+from dataclasses import replace
+
+import numpy as np
+import pytest
+
+import lc_workloads as wl
+from oracle import lychee_oracle as orc
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+ATTN_MAX_ABS = 1e-2
+ATTN_REL_L2 = 2e-3
+SCORE_REL = 2e-5
+
+
+@pytest.fixture(scope="module")
+def G():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from tests import gpu_common
+    return gpu_common
+
+
+def _say(msg):
+    print(f"[case] {msg}", flush=True)
+
+
+def _q_group(case, qi, b, h):
+    g = case.w.G
+    return wl.bf16_bits_to_f64(case.seqs[b].Q[qi, h * g:(h + 1) * g])
+
+
+def _q_batch(case, qi):
+    return np.stack([s.Q[qi] for s in case.seqs])
+
+
+def _check_retrieve(G, case, qbits, budget, policy=orc.POLICY_EXACT, beam=None, sink=0, tag=""):
+    from paper_2603_08453_amd import binding as lc
+    w = case.w
+    lc.lc_set_policy(case.idx, policy, beam, sink)
+    ids, scores, _ = G.gpu_retrieve(case, qbits, budget)
+    for b in range(w.B):
+        for h in range(w.H_kv):
+            oi = case.oidx[b][h]
+            q = wl.bf16_bits_to_f64(qbits[b, h * w.G:(h + 1) * w.G])
+            s_ref = orc.node_scores(oi, 0, q)
+            pinned = orc.pinned_chunks(oi, sink)
+            where = f"{tag} b={b} h={h} budget={budget} policy={policy} sink={sink}"
+            if policy == orc.POLICY_EXACT:
+                H.accept_ids(ids[b][h], s_ref, oi.lens(), budget, pinned=pinned)
+                ref = orc.retrieve_flat(oi, q, budget, sink)
+                if len(ref) != len(ids[b][h]) or np.any(ref != ids[b][h]):
+                    _say(f"in-band difference at {where}: oracle {len(ref)} ids, gpu {len(ids[b][h])}")
+            else:
+                st = {}
+                ref = orc.retrieve_beam(oi, q, budget, beam, sink, st)
+                assert ids[b][h].tolist() == ref.tolist(), where
+            # scores: every chunk the GPU scored must agree with the oracle; selected chunks must be scored
+            sg = scores[b, h, : oi.M]
+            scored = np.isfinite(sg)
+            assert np.all(np.abs(sg[scored] - s_ref[scored]) <= SCORE_REL * np.maximum(1.0, np.abs(s_ref[scored]))), where
+            free = np.setdiff1d(ids[b][h], pinned)
+            assert np.all(scored[free]), where
+    return ids
+
+
+def _check_decode(G, case, qbits, ids_per_bh, tag=""):
+    w = case.w
+    out, lse = G.gpu_decode(case, qbits, ids_per_bh)
+    ref = np.zeros((w.B, w.H_q, w.d))
+    ref_lse = np.zeros((w.B, w.H_q))
+    for b in range(w.B):
+        for h in range(w.H_kv):
+            oi = case.oidx[b][h]
+            q = wl.bf16_bits_to_f64(qbits[b, h * w.G:(h + 1) * w.G])
+            o, l = orc.sparse_decode(q, case.Kf(b, h), case.Vf(b, h), oi.bounds, oi.T, ids_per_bh[b][h])
+            ref[b, h * w.G:(h + 1) * w.G] = o
+            ref_lse[b, h * w.G:(h + 1) * w.G] = l
+    mx, rel = G.attention_errors(out, ref)
+    _say(f"{tag}: attention max|err| {mx:.2e}, rel L2 {rel:.2e}")
+    assert np.all(np.isfinite(out))
+    assert mx <= ATTN_MAX_ABS and rel <= ATTN_REL_L2, (tag, mx, rel)
+    fin = np.isfinite(ref_lse)
+    assert np.array_equal(fin, np.isfinite(lse))
+    assert np.all(lse[~fin] == -np.inf)
+    assert np.all(np.abs(lse[fin] - ref_lse[fin]) <= 1e-3), tag
+    return out
+
+
+# ----------------------------------------------------------------- C1: the reference config
+
+@pytest.fixture(scope="module")
+def c1(G):
+    _say("building C1 (4K tokens, 8 KV heads, L=2, F=16)")
+    return G.make_case(wl.C1)
+
+
+def test_c1_retrieve_exact(G, c1):
+    for budget in (1024, 300, 17):
+        _check_retrieve(G, c1, _q_batch(c1, 0), budget, tag="C1")
+
+
+def test_c1_decode_with_oracle_ids(G, c1):
+    qb = _q_batch(c1, 0)
+    ids = [[orc.retrieve_flat(c1.oidx[0][h], _q_group(c1, 0, 0, h), 1024) for h in range(8)]]
+    _check_decode(G, c1, qb, ids, tag="C1 budget 1024")
+
+
+def test_c1_end_to_end_own_ids(G, c1):
+    qb = _q_batch(c1, 0)
+    ids = _check_retrieve(G, c1, qb, 1024, tag="C1 e2e")
+    _check_decode(G, c1, qb, ids, tag="C1 e2e (gpu ids)")
+
+
+def test_c1_full_budget_is_dense_attention(G, c1):
+    """Budget >= context: every chunk selected and the output equals dense softmax attention
+    computed by library routines (not by the oracle)."""
+    qb = _q_batch(c1, 0)
+    ids = _check_retrieve(G, c1, qb, 4096, tag="C1 dense")
+    M = c1.oidx[0][0].M
+    assert all(ids[0][h].tolist() == list(range(M)) for h in range(8))
+    out, lse = G.gpu_decode(c1, qb, ids)
+    for h in range(8):
+        ref, ref_lse = H.dense_attention_library(_q_group(c1, 0, 0, h), c1.Kf(0, h), c1.Vf(0, h))
+        mx, rel = G.attention_errors(out[0, 4 * h:4 * h + 4], ref)
+        assert mx <= ATTN_MAX_ABS and rel <= ATTN_REL_L2
+        assert np.all(np.abs(lse[0, 4 * h:4 * h + 4] - ref_lse) <= 1e-3)
+
+
+def test_c1_edge_budgets_and_zero_query(G, c1):
+    qb = _q_batch(c1, 0)
+    ids = _check_retrieve(G, c1, qb, 0, tag="C1 budget 0")
+    assert all(len(ids[0][h]) == 0 for h in range(8))
+    out, lse = G.gpu_decode(c1, qb, ids)                  # nothing selected, no open tail
+    assert np.all(out == 0) and np.all(lse == -np.inf)
+    q0 = np.zeros_like(qb)
+    ids = _check_retrieve(G, c1, q0, 200, tag="C1 q=0")
+    lens = c1.oidx[0][0].lens()
+    k = int(np.searchsorted(np.cumsum(lens), 200, side="right"))
+    assert all(ids[0][h].tolist() == list(range(k)) for h in range(8))     # lowest ids first on ties
+    out, _ = G.gpu_decode(c1, q0, ids)                    # equal logits: plain mean of the attended V
+    for h in range(8):
+        rows = np.arange(c1.oidx[0][h].bounds[k])
+        want = c1.Vf(0, h)[rows].mean(axis=0)
+        assert np.abs(out[0, 4 * h] - want).max() <= 1e-3
+
+
+def test_c1_sink_and_beam(G, c1):
+    qb = _q_batch(c1, 0)
+    _check_retrieve(G, c1, qb, 512, sink=16, tag="C1 sink")
+    _check_retrieve(G, c1, qb, 512, sink=100, tag="C1 sink100")
+    _check_retrieve(G, c1, qb, 1024, policy=orc.POLICY_BEAM, beam=[0, 3], tag="C1 beam top-3")
+    _check_retrieve(G, c1, qb, 1024, policy=orc.POLICY_BEAM, beam=[12, 2], tag="C1 beam leaf 12")
+    _check_retrieve(G, c1, qb, 1024, policy=orc.POLICY_BEAM, beam=[0, 0], sink=40, tag="C1 beam unbounded")
+    from paper_2603_08453_amd import binding as lc
+    lc.lc_set_policy(c1.idx, lc.LC_POLICY_EXACT, None, 0)
+
+
+def test_c1_repeatable(G, c1):
+    """Two runs give bit-identical ids and outputs (no order-dependent atomics)."""
+    qb = _q_batch(c1, 0)
+    a, sa, _ = G.gpu_retrieve(c1, qb, 1024)
+    b, sb, _ = G.gpu_retrieve(c1, qb, 1024)
+    assert all(np.array_equal(x, y) for x, y in zip(a[0], b[0]))
+    assert np.array_equal(sa, sb, equal_nan=True)
+    o1, l1 = G.gpu_decode(c1, qb, a)
+    o2, l2 = G.gpu_decode(c1, qb, a)
+    assert np.array_equal(o1, o2) and np.array_equal(l1, l2)
+
+
+# ----------------------------------------------------------------- small, ragged, tails, deep trees
+
+@pytest.mark.parametrize("name,kw,tails", [
+    ("tiny-L1", dict(levels=1, fanout=4), None),
+    ("tiny-L3-tail", dict(levels=3, fanout=3, T=700), [9]),
+    ("tiny-L4-G1", dict(levels=4, fanout=2, H_q=2, H_kv=2, T=900), [1]),
+    ("tiny-G8", dict(levels=2, fanout=5, H_q=8, H_kv=1, T=600), [0]),
+    ("ragged-G7", dict(B=3, H_q=14, H_kv=2, levels=3, fanout=4, T=0, T_range=(300, 1500), chunk_lo=2, chunk_hi=40),
+     [0, 33, 5]),
+    ("one-chunk", dict(levels=2, fanout=4, T=20, chunk_lo=20, chunk_hi=20), None),
+])
+def test_small_cases(G, name, kw, tails):
+    w = wl.tiny(name, **kw)
+    _say(f"{name}: {w}")
+    case = G.make_case(w, tails=tails)
+    qb = _q_batch(case, 0)
+    for budget in (0, 1, 50, w.budget, 10 ** 6):
+        ids = _check_retrieve(G, case, qb, budget, tag=name)
+        _check_decode(G, case, qb, ids, tag=f"{name} budget {budget}")
+    if w.levels > 1:
+        beam = [0] + [2] * (w.levels - 1)
+        _check_retrieve(G, case, qb, w.budget, policy=orc.POLICY_BEAM, beam=beam, tag=name + " beam")
+    _check_retrieve(G, case, qb, 64, sink=7, tag=name + " sink")
+
+
+def test_pruning_happens_and_stays_exact(G):
+    """Tightly clustered keys: the level-by-level pass skips most chunks (their scores come
+    back as -inf = never computed) and the selection still equals the flat scan."""
+    w = wl.tiny("tight", levels=3, fanout=4, T=4000, chunk_lo=4, chunk_hi=12, budget=60, H_q=4, H_kv=2)
+    case = G.make_case(w, offset_std=3.0, noise_std=0.02)
+    qb = _q_batch(case, 0)
+    _check_retrieve(G, case, qb, 60, tag="tight")
+    _, scores, _ = G.gpu_retrieve(case, qb, 60)
+    M = case.oidx[0][0].M
+    scored = np.isfinite(scores[0, :, :M]).sum(axis=1)
+    _say(f"tight clusters: scored {scored.tolist()} of {M} chunks per head")
+    assert np.all(scored < M)
+
+
+def test_split_count_does_not_change_the_result(G):
+    w = wl.tiny("splits", levels=2, fanout=4, T=3000, chunk_lo=4, chunk_hi=32, budget=1500)
+    outs = []
+    for splits in (1, 3, 16):
+        case = G.make_case(w, decode_splits=splits, tails=[5])
+        qb = _q_batch(case, 0)
+        ids = [[orc.retrieve_flat(case.oidx[0][h], _q_group(case, 0, 0, h), 1500) for h in range(w.H_kv)]]
+        outs.append(_check_decode(G, case, qb, ids, tag=f"splits={splits}"))
+    assert np.abs(outs[0] - outs[1]).max() <= 1e-4 and np.abs(outs[0] - outs[2]).max() <= 1e-4
+
+
+# ----------------------------------------------------------------- index build on the GPU
+
+@pytest.mark.parametrize("geometry", [orc.TOKEN_BALL, orc.PAPER_UNIT])
+def test_build_index_matches_oracle(G, geometry):
+    from paper_2603_08453_amd import binding as lc
+    w = wl.tiny("build", B=2, levels=3, fanout=4, T=0, T_range=(800, 1600), chunk_lo=3, chunk_hi=30)
+    case = G.make_case(w, tails=[4, 0], geometry=geometry, build_on="gpu")
+    blob = lc.unpack_blob(lc.lc_index_export(case.idx))
+    same_topology = 0
+    for b in range(w.B):
+        s = blob["seqs"][b]
+        assert s["T"] == case.seqs[b].T and np.array_equal(s["bounds"], case.seqs[b].bounds)
+        for h in range(w.H_kv):
+            oi = case.oidx[b][h]
+            gi = G.levels_to_oracle_index(s["heads"][h], s["bounds"], s["T"], w.fanout, geometry)
+            assert [gi.n(l) for l in range(w.levels)] == [oi.n(l) for l in range(w.levels)]
+            # level 0 never depends on clustering: direct parity
+            assert np.allclose(gi.center[0], oi.center[0], rtol=2e-6, atol=2e-6)
+            assert np.all(gi.radius[0] >= oi.radius[0] * (1 - 1e-6))
+            assert np.all(gi.radius[0] <= oi.radius[0] * (1 + 2e-5) + 1e-7)
+            # invariants of the GPU-built index, by brute force
+            H.check_covering_invariant(gi, case.Kf(b, h), slack=1e-6)
+            H.check_counts(gi)
+            if all(np.array_equal(gi.parent[l], oi.parent[l]) for l in range(w.levels - 1)):
+                same_topology += 1
+                for l in range(1, w.levels):
+                    live = oi.nchunk[l] > 0
+                    assert np.allclose(gi.center[l][live], oi.center[l][live], rtol=1e-5, atol=1e-5)
+                    assert np.all(gi.radius[l][live] >= oi.radius[l][live] * (1 - 1e-6))
+                    assert np.all(gi.radius[l][live] <= oi.radius[l][live] * (1 + 5e-5) + 1e-6)
+    _say(f"build geometry={geometry}: {same_topology}/{w.B * w.H_kv} (seq, head) trees have the oracle's topology")
+    assert same_topology >= (w.B * w.H_kv) // 2
+    # retrieval on the GPU-built index is exact with respect to its own stored values
+    qb = _q_batch(case, 0)
+    ids, scores, _ = G.gpu_retrieve(case, qb, w.budget)
+    for b in range(w.B):
+        s = blob["seqs"][b]
+        for h in range(w.H_kv):
+            gi = G.levels_to_oracle_index(s["heads"][h], s["bounds"], s["T"], w.fanout, geometry)
+            q = wl.bf16_bits_to_f64(qb[b, h * w.G:(h + 1) * w.G])
+            H.accept_ids(ids[b][h], orc.node_scores(gi, 0, q), gi.lens(), w.budget)
+
+
+# ----------------------------------------------------------------- lazy update
+
+@pytest.mark.parametrize("geometry,L", [(orc.TOKEN_BALL, 3), (orc.TOKEN_BALL, 1), (orc.PAPER_UNIT, 2)])
+def test_append_stream_matches_oracle(G, geometry, L):
+    import torch
+    from paper_2603_08453_amd import binding as lc
+    steps = 150
+    w = wl.tiny("stream", B=2, levels=L, fanout=4, T=0, T_range=(300, 500), chunk_lo=3, chunk_hi=20,
+                stream_close_lo=3, stream_close_hi=17)
+    case = G.make_case(w, tails=[2, 0], geometry=geometry, extra_tokens=steps, extra_chunks=steps)
+    streams = [wl.make_stream(w, b, steps) for b in range(w.B)]
+    Kf = [[np.vstack([case.Kf(b, h), np.zeros((steps, w.d))]) for h in range(w.H_kv)] for b in range(w.B)]
+    Vf = [[np.vstack([case.Vf(b, h), np.zeros((steps, w.d))]) for h in range(w.H_kv)] for b in range(w.B)]
+    parent_mismatch = 0
+    for t in range(steps):
+        k_bits = np.stack([st.k[t] for st in streams])
+        v_bits = np.stack([st.v[t] for st in streams])
+        close = [int(st.close[t]) for st in streams]
+        if t % 2 == 1:
+            close[1] = 0                       # sequences close at different times
+        lc.lc_append(case.idx, case.K, case.V, G.to_bf16_tensor(k_bits), G.to_bf16_tensor(v_bits), close, case.ws)
+        for b in range(w.B):
+            for h in range(w.H_kv):
+                oi = case.oidx[b][h]
+                Kf[b][h][oi.T] = wl.bf16_bits_to_f64(k_bits[b, h])
+                Vf[b][h][oi.T] = wl.bf16_bits_to_f64(v_bits[b, h])
+                orc.append_token(oi)
+                if close[b]:
+                    orc.close_chunk(oi, Kf[b][h])
+        if t % 50 == 49 or t == steps - 1:
+            torch.cuda.synchronize()
+            blob = lc.unpack_blob(lc.lc_index_export(case.idx))
+            for b in range(w.B):
+                s = blob["seqs"][b]
+                T, M, _ = case.idx.info(b)
+                assert (T, M) == (case.oidx[b][0].T, case.oidx[b][0].M) == (s["T"], len(s["bounds"]) - 1)
+                assert np.array_equal(s["bounds"], case.oidx[b][0].bounds)
+                for h in range(w.H_kv):
+                    oi = case.oidx[b][h]
+                    gi = G.levels_to_oracle_index(s["heads"][h], s["bounds"], s["T"], w.fanout, geometry)
+                    H.check_covering_invariant(gi, Kf[b][h], slack=1e-6)
+                    H.check_counts(gi)
+                    if L > 1 and not np.array_equal(gi.parent[0], oi.parent[0]):
+                        parent_mismatch += 1
+                        continue
+                    for l in range(L):
+                        live = oi.nchunk[l] > 0
+                        assert np.allclose(gi.center[l][live], oi.center[l][live], rtol=2e-5, atol=2e-5), (t, b, h, l)
+                        assert np.all(gi.radius[l][live] >= oi.radius[l][live] * (1 - 1e-6))
+                        assert np.all(gi.radius[l][live] <= oi.radius[l][live] * (1 + 1e-3) + 1e-5)
+    _say(f"append L={L} geometry={geometry}: parent choice differed from the oracle in {parent_mismatch} checks")
+    assert parent_mismatch == 0
+    # the cache rows were written, and retrieval + attention over the grown index agree
+    for b in range(w.B):
+        for h in range(w.H_kv):
+            T = case.oidx[b][h].T
+            got = case.K[b, h, :T].float().cpu().numpy()
+            assert np.array_equal(got, Kf[b][h][:T].astype(np.float32))
+    qb = np.stack([st.q[steps - 1] for st in streams])
+    lc.lc_set_policy(case.idx, lc.LC_POLICY_EXACT, None, 0)
+    ids, scores, _ = G.gpu_retrieve(case, qb, 120)
+    out, lse = G.gpu_decode(case, qb, ids)
+    for b in range(w.B):
+        for h in range(w.H_kv):
+            oi = case.oidx[b][h]
+            q = wl.bf16_bits_to_f64(qb[b, h * w.G:(h + 1) * w.G])
+            H.accept_ids(ids[b][h], orc.node_scores(oi, 0, q), oi.lens(), 120)
+            ref, _ = orc.sparse_decode(q, Kf[b][h], Vf[b][h], oi.bounds, oi.T, ids[b][h])
+            mx, rel = G.attention_errors(out[b, h * w.G:(h + 1) * w.G], ref)
+            assert mx <= ATTN_MAX_ABS and rel <= ATTN_REL_L2
+
+
+def test_capacity_errors(G):
+    from paper_2603_08453_amd import binding as lc
+    w = wl.tiny("cap", levels=2, fanout=4, T=100)
+    case = G.make_case(w)              # no room for more tokens or chunks
+    k = G.to_bf16_tensor(np.zeros((1, w.H_kv, w.d), dtype=np.uint16))
+    with pytest.raises(lc.LycheeError) as e:
+        lc.lc_append(case.idx, case.K, case.V, k, k, [0], case.ws)
+    assert e.value.code == lc.LC_ERR_CAPACITY
+    import torch
+    ids = torch.zeros((1, w.H_kv, 2), dtype=torch.int32, device="cuda")
+    counts = torch.zeros((1, w.H_kv), dtype=torch.int32, device="cuda")
+    q = G.to_bf16_tensor(case.seqs[0].Q[0][None])
+    with pytest.raises(lc.LycheeError) as e:
+        lc.lc_retrieve(case.idx, q, 64, ids, counts, case.ws)
+    assert e.value.code == lc.LC_ERR_CAPACITY
