@@ -1,0 +1,342 @@
+"""Benchmark of the LycheeCluster decode hot path on one MI355X.
+
+A step = one decode step of one attention layer over the whole batch:
+lc_retrieve (Eq. 2 scoring, pruning, budget selection) followed by
+lc_sparse_decode (split-K attention over the selected chunks + merge).
+Inputs are seeded synthetic tensors, resident in HBM before the timed region.
+To keep the numbers honest about HBM, consecutive steps walk over several
+replicas of (K, V, index) whose total footprint exceeds the 256 MB last-level
+cache several times, and use a different query each step.
+
+Prints one JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import lc_workloads as wl  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--workload", default="C3-128K", choices=sorted(wl.WORKLOADS))
+    ap.add_argument("--replicas", type=int, default=0, help="0 = 32 (or as many as fit in 64 GiB)")
+    ap.add_argument("--queries", type=int, default=16)
+    ap.add_argument("--policy", default="exact", choices=["exact", "beam"])
+    ap.add_argument("--splits", type=int, default=0)
+    ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--profile-only", action="store_true",
+                    help="skip the CPU baseline and the eager/graph comparison (for rocprofv3 runs)")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build targets one GPU; --gpus must be 1 (no collectives, no sharding).",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2603_08453_amd import binding as lc
+    lc.lib()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    w = wl.WORKLOADS[args.workload]
+    G = w.G
+
+    # ------------------------------------------------------------- inputs
+    t0 = time.time()
+    lens = wl.seq_lengths(w)
+    seqs = [wl.make_sequence(w, b, lens[b]) for b in range(w.B)]
+    Tmax = max(s.T for s in seqs)
+    Mmax = max(len(s.bounds) - 1 for s in seqs)
+    extra = 64
+    cfg = lc.lc_config_default(levels=w.levels, fanout=w.fanout, max_chunks=Mmax + extra, max_tokens=Tmax + extra,
+                               decode_splits=args.splits)
+    if args.policy == "beam":
+        cfg.policy = lc.LC_POLICY_BEAM
+        beam = [0] * lc.LC_MAX_LEVELS
+        for l in range(1, w.levels):
+            beam[l] = 4 if l >= 2 else 16
+        for i, v in enumerate(beam):
+            cfg.beam[i] = v
+    to_t = lambda bits: torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(torch.bfloat16)
+    K0 = torch.zeros((w.B, w.H_kv, Tmax + extra, w.d), dtype=torch.bfloat16, device=dev)
+    V0 = torch.zeros_like(K0)
+    for b, s in enumerate(seqs):
+        K0[b, :, : s.T] = to_t(s.K).to(dev)
+        V0[b, :, : s.T] = to_t(s.V).to(dev)
+    nq = args.queries
+    Qs = []
+    for i in range(nq):
+        qb = np.stack([wl.make_queries(w, b, seqs[b].offsets, 1, stream=100 + i)[0][0] for b in range(w.B)])
+        Qs.append(to_t(qb).to(dev))
+    index_bytes = lc.lc_index_bytes(cfg, w.B, w.H_kv)
+    ws_bytes = lc.lc_workspace_bytes(cfg, w.B, w.H_q, w.H_kv)
+    kv_bytes = 2 * K0.numel() * 2
+    # one replica per "layer": 32 of them (as in a 32-layer model) unless that exceeds 64 GiB;
+    # 32 x the index alone already exceeds the 256 MB last-level cache at the headline config
+    R = args.replicas or max(2, min(32, int((64 << 30) // (kv_bytes + index_bytes))))
+    gen_s = time.time() - t0
+
+    reps = []
+    build_ms = []
+    for r in range(R):
+        K = K0 if r == 0 else K0.clone()
+        V = V0 if r == 0 else V0.clone()
+        ib = torch.zeros(index_bytes, dtype=torch.uint8, device=dev)
+        ws = torch.zeros(ws_bytes, dtype=torch.uint8, device=dev)
+        torch.cuda.synchronize()
+        tb = time.perf_counter()
+        idx = lc.lc_build_index(cfg, K, [s.T for s in seqs], [s.bounds for s in seqs], ib, ws)
+        torch.cuda.synchronize()
+        build_ms.append((time.perf_counter() - tb) * 1e3)
+        reps.append(dict(K=K, V=V, ib=ib, ws=ws, idx=idx))
+    cap = int(min(Mmax + extra, w.budget + 8))
+    ids_q = [torch.zeros((w.B, w.H_kv, cap), dtype=torch.int32, device=dev) for _ in range(nq)]
+    counts_q = [torch.zeros((w.B, w.H_kv), dtype=torch.int32, device=dev) for _ in range(nq)]
+    out = torch.zeros((w.B, w.H_q, w.d), dtype=torch.float32, device=dev)
+
+    def retrieve(i):
+        rp = reps[i % R]
+        lc.lc_retrieve(rp["idx"], Qs[i % nq], w.budget, ids_q[i % nq], counts_q[i % nq], rp["ws"])
+
+    def attend(i):
+        rp = reps[i % R]
+        lc.lc_sparse_decode(rp["idx"], Qs[i % nq], rp["K"], rp["V"], ids_q[i % nq], counts_q[i % nq], out, rp["ws"])
+
+    def step(i):
+        retrieve(i)
+        attend(i)
+
+    # ------------------------------------------------------------- algorithmic bytes
+    # attended tokens per query (the index replicas are identical, so one pass over the queries suffices)
+    tok_per_q, chunks_per_q, scored_per_q = [], [], []
+    scores = torch.zeros((w.B, w.H_kv, cfg.max_chunks), dtype=torch.float32, device=dev)
+    bounds_np = [s.bounds.astype(np.int64) for s in seqs]
+    for i in range(nq):
+        lc.lc_retrieve(reps[0]["idx"], Qs[i], w.budget, ids_q[i], counts_q[i], reps[0]["ws"], scores=scores)
+        torch.cuda.synchronize()
+        ih, ch, sh = ids_q[i].cpu().numpy(), counts_q[i].cpu().numpy(), scores.cpu().numpy()
+        tok = 0
+        for b in range(w.B):
+            ln = np.diff(bounds_np[b])
+            for h in range(w.H_kv):
+                tok += int(ln[ih[b, h, : ch[b, h]]].sum()) + (seqs[b].T - int(bounds_np[b][-1]))
+        tok_per_q.append(tok)
+        chunks_per_q.append(int(ch.sum()))
+        scored_per_q.append(int(np.isfinite(sh[:, :, :Mmax]).sum()))
+    io_small = w.B * w.H_q * w.d * (2 + 4)
+    attend_bytes = float(np.mean(tok_per_q)) * 4 * w.d + io_small
+    n_upper = sum(sum(reps[0]["idx"].info(b)[2][1:]) for b in range(w.B)) * w.H_kv
+    node_bytes = w.d * 4 + 4 + 4
+    retrieve_bytes = (float(np.mean(scored_per_q)) + n_upper) * node_bytes \
+        + sum(len(bn) - 1 for bn in bounds_np) * w.H_kv * 8 + w.B * w.H_q * w.d * 2 + float(np.mean(chunks_per_q)) * 4
+
+    # ------------------------------------------------------------- timing
+    def timed(fn, n, start=0):
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for i in range(start, start + n):
+            fn(i)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) / n
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    eager_s = timed(step, args.steps)
+
+    # HIP graphs: launch overhead out of the way.  K steps = full graphs of `unit` steps + one remainder graph.
+    side = torch.cuda.Stream()
+
+    def capture(fn, n):
+        g = torch.cuda.CUDAGraph()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for i in range(4):
+                fn(i)
+            side.synchronize()
+            with torch.cuda.graph(g, stream=side):
+                for i in range(n):
+                    fn(i)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        return g
+
+    def graph_us_per_launch(fn, total):
+        """Average time per call of fn over exactly `total` calls replayed from graphs, by HIP events
+        recorded on the stream the graphs are launched on."""
+        unit = min(total, 256)
+        full, rem = divmod(total, unit)
+        g_full = capture(fn, unit)
+        g_rem = capture(fn, rem) if rem else None
+        g_full.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t = time.perf_counter()
+        e0.record()
+        for _ in range(full):
+            g_full.replay()
+        if g_rem is not None:
+            g_rem.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t) / total
+        return e0.elapsed_time(e1) * 1e3 / total, wall
+
+    graph_s = attend_us = retrieve_us = None
+    if not args.no_graph:
+        try:
+            _, graph_s = graph_us_per_launch(step, args.steps)
+            attend_us, _ = graph_us_per_launch(attend, args.steps)
+            retrieve_us, _ = graph_us_per_launch(retrieve, args.steps)
+            for i in range(nq):           # leave ids consistent with the queries again
+                retrieve(i)
+        except Exception as e:       # graph capture only optimises the launch path
+            print(f"bench.py: HIP graph capture failed ({e}); falling back to eager event timing", file=sys.stderr)
+            graph_s = None
+    if attend_us is None:
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+              for _ in range(min(args.steps, 512))]
+        for i, (e0, e1) in enumerate(ev):
+            retrieve(i)
+            e0.record()
+            attend(i)
+            e1.record()
+        torch.cuda.synchronize()
+        attend_us = float(np.mean([e0.elapsed_time(e1) for e0, e1 in ev])) * 1e3
+        for i, (e0, e1) in enumerate(ev):
+            e0.record()
+            retrieve(i)
+            e1.record()
+            attend(i)
+        torch.cuda.synchronize()
+        retrieve_us = float(np.mean([e0.elapsed_time(e1) for e0, e1 in ev])) * 1e3
+
+    # warm (cache-resident) figure: one replica, one query
+    def step_warm(i):
+        rp = reps[0]
+        lc.lc_retrieve(rp["idx"], Qs[0], w.budget, ids_q[0], counts_q[0], rp["ws"])
+        lc.lc_sparse_decode(rp["idx"], Qs[0], rp["K"], rp["V"], ids_q[0], counts_q[0], out, rp["ws"])
+    for i in range(20):
+        step_warm(i)
+    warm_s = timed(step_warm, min(args.steps, 500))
+
+    # append (lazy update), timed separately: one token per step, a chunk closes every 32 tokens
+    st = wl.make_stream(w, 0, extra)
+    kn = [to_t(np.stack([st.k[t]] * w.B)).to(dev) for t in range(extra)]
+    vn = [to_t(np.stack([st.v[t]] * w.B)).to(dev) for t in range(extra)]
+    torch.cuda.synchronize()
+    ta = time.perf_counter()
+    n_app = extra - 2
+    for t in range(n_app):
+        lc.lc_append(reps[0]["idx"], reps[0]["K"], reps[0]["V"], kn[t], vn[t],
+                     [1 if (t % 32 == 31) else 0] * w.B, reps[0]["ws"])
+    torch.cuda.synchronize()
+    append_us = (time.perf_counter() - ta) / n_app * 1e6
+
+    best_s = graph_s if (graph_s is not None and graph_s < eager_s) else eager_s
+    step_bytes = attend_bytes + retrieve_bytes
+
+    # ------------------------------------------------------------- CPU baseline (the oracle, as it stands)
+    cpu = None
+    if not (args.no_cpu_baseline or args.profile_only):
+        from oracle import lychee_oracle as orc
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = 1
+        b0 = 0
+        s0 = seqs[b0]
+        heads = list(range(w.H_kv))
+        tb = time.perf_counter()
+        oidx, Kf, Vf = {}, {}, {}
+        for h in heads:
+            Kf[h] = wl.bf16_bits_to_f64(s0.K[h])
+            Vf[h] = wl.bf16_bits_to_f64(s0.V[h])
+            oidx[h] = orc.build_index(Kf[h], s0.bounds, s0.T, w.levels, w.fanout)
+            if time.perf_counter() - tb > 60 and len(oidx) >= 2:
+                break
+        heads = sorted(oidx)
+        cpu_build_s = (time.perf_counter() - tb) / len(heads)
+        n_done, tc = 0, time.perf_counter()
+        while time.perf_counter() - tc < args.cpu_seconds:
+            qb = wl.bf16_bits_to_f64(wl.make_queries(w, b0, s0.offsets, 1, stream=100 + (n_done % nq))[0][0])
+            for h in heads:
+                q = qb[h * G:(h + 1) * G]
+                sel = orc.retrieve_flat(oidx[h], q, w.budget)
+                orc.sparse_decode(q, Kf[h], Vf[h], oidx[h].bounds, oidx[h].T, sel)
+            n_done += 1
+        per_seq_step = (time.perf_counter() - tc) / n_done * (w.H_kv / len(heads))
+        cpu = {"value": round(per_seq_step * w.B * 1e6, 1), "unit": "us/step", "cores": int(cores), "kind": "oracle",
+               "sample": f"{n_done} decode steps (flat-scan retrieve + attend) of sequence 0, "
+                         f"{len(heads)} of {w.H_kv} KV heads, scaled to {w.B} sequence(s) x {w.H_kv} heads; "
+                         f"oracle index build {cpu_build_s:.1f} s per (sequence, head), not included"}
+
+    res = {
+        "metric": "us per decode step per layer (retrieve+attend), 128K ctx" if w.name.startswith("C3") else
+                  "us per decode step per layer (retrieve+attend)",
+        "value": round(best_s * 1e6, 2),
+        "unit": "us/step",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(best_s * 1e3, 5),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16 in, f32 accumulate",
+        "data": "synthetic (seeded; clustered keys, queries biased to 3 chunks)",
+        "config": {"workload": w.name, "batch": w.B, "q_heads": w.H_q, "kv_heads": w.H_kv, "head_dim": w.d,
+                   "context": Tmax, "chunks": Mmax, "levels": w.levels, "fanout": w.fanout, "budget": w.budget,
+                   "policy": args.policy, "replicas": R, "queries": nq,
+                   "launch": "hip-graph" if best_s == graph_s else "eager"},
+        "roofline": {"bound": "hbm", "achieved": round(attend_bytes / (attend_us * 1e-6) / 1e9, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(attend_bytes / (attend_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+                     "traffic": None, "kernel": "lc_decode_kernel",
+                     "bytes_per_launch": round(attend_bytes), "us_per_launch": round(attend_us, 2)},
+        "cpu_baseline": cpu,
+        "extra": {
+            "eager_us": round(eager_s * 1e6, 2),
+            "graph_us": None if graph_s is None else round(graph_s * 1e6, 2),
+            "warm_cache_us": round(warm_s * 1e6, 2),
+            "retrieve_us_event": round(retrieve_us, 2),
+            "attend_us_event": round(attend_us, 2),
+            "append_us": round(append_us, 2),
+            "build_ms": round(float(np.median(build_ms)), 2),
+            "step_bytes": round(step_bytes),
+            "retrieve_bytes": round(retrieve_bytes),
+            "attend_bytes": round(attend_bytes),
+            "step_GBps": round(step_bytes / best_s / 1e9, 1),
+            "step_frac_of_hbm_peak": round(step_bytes / best_s / 1e9 / HBM_PEAK_GBS, 4),
+            "tokens_attended_per_step": round(float(np.mean(tok_per_q)), 1),
+            "chunks_selected_per_step": round(float(np.mean(chunks_per_q)), 1),
+            "chunks_scored_per_step": round(float(np.mean(scored_per_q)), 1),
+            "input_gen_s": round(gen_s, 1),
+        },
+    }
+    print(json.dumps(res), flush=True)
+
+
+if __name__ == "__main__":
+    main()

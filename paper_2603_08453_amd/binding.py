@@ -30,7 +30,7 @@ LC_POLICY_EXACT = 0
 LC_POLICY_BEAM = 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "liblychee.so")
+LIB_PATH = os.environ.get("LYCHEE_LIB", os.path.join(_HERE, "liblychee.so"))
 
 
 class LcConfig(ctypes.Structure):

@@ -24,7 +24,7 @@ bool config_ok(const lc_config* c) {
     if (c->max_chunks < 1 || c->max_tokens < 1) return false;
     if (c->max_chunks > c->max_tokens) return false;
     if (c->max_tokens > (1 << 30)) return false;
-    if (c->decode_splits < 0 || c->decode_splits > 1024) return false;
+    if (c->decode_splits < 0 || c->decode_splits > 256) return false;
     return true;
 }
 
@@ -93,14 +93,14 @@ size_t lc_layout_ws(const lc_config* cfg, int B, int H_q, int H, int d, int spli
     const size_t BH = (size_t)B * H;
     Carver c{static_cast<char*>(base), 0};
     W->keys = c.take<uint32_t>(BH * cap[0]);
-    W->kept1 = c.take<uint8_t>(BH * cap1);
+    W->want = c.take<uint8_t>(BH * cap[0]);
+    W->scratch = c.take<int>(BH * 4 * cap[0]);
     W->scores = c.take<float>(BH * cap[0]);
     W->part_acc = c.take<float>((size_t)B * H_q * splits * d);
     W->part_ml = c.take<float>((size_t)B * H_q * splits * 2);
     W->dirs = c.take<float>(BH * cap[0] * d);
     W->cent_a = c.take<float>(BH * cap1 * d);
     W->cent_b = c.take<float>(BH * cap1 * d);
-    W->labels = c.take<int>(BH * cap[0]);
     W->anc = c.take<int>(BH * cap[0]);
     W->total = align_up(c.off);
     return W->total;

@@ -13,8 +13,11 @@
 #define LC_DEC_GROUPS 16
 #define LC_DEC_UNROLL 4
 #define LC_DEC_MIN_TOKENS_PER_SPLIT 64
+#define LC_DEC_MAX_SPLITS 256
 #define LC_LOG2E 1.4426950408889634f
 #define LC_LN2 0.6931471805599453f
+
+LC_STAMP_DECL(lc_dbg_decode)
 
 struct LcDecodeArgs {
     LcDev ix;
@@ -40,6 +43,10 @@ lc_decode_kernel(const LcDecodeArgs a) {
     __shared__ int last_sh;
     __shared__ float comb_ml[LC_DEC_THREADS / 64][G][2];
     __shared__ float comb_acc[LC_DEC_THREADS / 64][G][LC_D];
+    __shared__ float mrg_m[LC_DEC_MAX_SPLITS * G];
+    __shared__ float mrg_l[LC_DEC_MAX_SPLITS * G];
+    __shared__ float mrg_hd[2 * G];
+    __shared__ float4 mrg_red[LC_DEC_THREADS];
 
     const LcDev& ix = a.ix;
     const int s = blockIdx.x, S = gridDim.x, h = blockIdx.y, b = blockIdx.z;
@@ -47,12 +54,15 @@ lc_decode_kernel(const LcDecodeArgs a) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int sub = tid & 15, grp = tid >> 4;
 
+    LC_STAMP0(lc_dbg_decode, 0);
+    const int* bnd = ix.bounds + (size_t)b * (ix.cap[0] + 1);
+    const int32_t* ids = a.ids + (size_t)bh * a.cap;
+    // independent loads first: the id a thread will need is fetched before the count is known
+    const int id_first = (tid < a.cap) ? ids[tid] : 0;
     const int T = ix.state[bh * 4 + 0];
     const int M = ix.state[bh * 4 + 1];
     int n_ids = a.counts[bh];
     n_ids = max(0, min(n_ids, min(a.cap, a.id_cap_lds)));
-    const int* bnd = ix.bounds + (size_t)b * (ix.cap[0] + 1);
-    const int32_t* ids = a.ids + (size_t)bh * a.cap;
 
     // ---- run table in LDS: start row and exclusive token prefix of each selected chunk,
     // then the open tail as the last run.
@@ -63,7 +73,7 @@ lc_decode_kernel(const LcDecodeArgs a) {
         const int i = t0 + tid;
         int st = 0, ln = 0;
         if (i < n_ids) {
-            const int id = max(0, min(ids[i], M - 1));
+            const int id = max(0, min(t0 == 0 ? id_first : ids[i], M - 1));
             st = bnd[id];
             ln = bnd[id + 1] - st;
         } else if (i == n_ids) {
@@ -75,6 +85,7 @@ lc_decode_kernel(const LcDecodeArgs a) {
         if (i <= n_ids) { run_start[i] = st; run_off[i] = carry + ex; }
         carry += tot;
     }
+    LC_STAMP0(lc_dbg_decode, 1);
     const int n_runs = n_ids + 1;
     const int n_tok = carry;
     if (tid == 0) run_off[n_runs] = n_tok;
@@ -183,6 +194,7 @@ lc_decode_kernel(const LcDecodeArgs a) {
             t += LC_DEC_UNROLL;
         }
 
+        LC_STAMP0(lc_dbg_decode, 2);
         // ---- combine the 4 groups of a wave (xor 16, 32), then the waves through LDS
 #pragma unroll
         for (int off = 16; off < 64; off <<= 1) {
@@ -226,43 +238,76 @@ lc_decode_kernel(const LcDecodeArgs a) {
                 num = fmaf(comb_acc[w][g][c], sc, num);
                 den = fmaf(comb_ml[w][g][1], sc, den);
             }
-            pacc[e] = num;
-            if (c == 0) { pml[2 * g] = mx; pml[2 * g + 1] = den; }
+            lc_store_agent(&pacc[e], num);
+            if (c == 0) { lc_store_agent(&pml[2 * g], mx); lc_store_agent(&pml[2 * g + 1], den); }
         }
     }
 
+    LC_STAMP0(lc_dbg_decode, 3);
     // ---- the last split to arrive merges (log-sum-exp merge of the partial results)
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) {
-        const int old = atomicAdd(&ix.sync[bh * 4 + 1], 1);
-        last_sh = (old == S - 1) ? 1 : 0;
-    }
-    __syncthreads();
-    if (!last_sh) return;
-    __threadfence();
+    if (!lc_arrive_last(&ix.sync[bh * 4 + 1], S, &last_sh)) return;
 
+    LC_STAMP(lc_dbg_decode, 4);
+    // partial (m, l) of every split -> LDS; per head: global max, scale of each split, denominator
     const float* pacc = a.part_acc + (size_t)bh * S * G * LC_D;
     const float* pml = a.part_ml + (size_t)bh * S * G * 2;
-    for (int e = tid; e < G * LC_D; e += LC_DEC_THREADS) {
-        const int g = e / LC_D, c = e % LC_D;
-        float mx = LC_NEG_INF;
-        if (n_tok > 0)
-            for (int sp = 0; sp < S_eff; ++sp) mx = fmaxf(mx, __builtin_nontemporal_load(&pml[(sp * G + g) * 2]));
-        float num = 0.f, den = 0.f;
-        if (n_tok > 0) {
-            for (int sp = 0; sp < S_eff; ++sp) {
-                const float ms = __builtin_nontemporal_load(&pml[(sp * G + g) * 2]);
-                const float ls = __builtin_nontemporal_load(&pml[(sp * G + g) * 2 + 1]);
-                const float sc = (ms == LC_NEG_INF) ? 0.f : exp2f(ms - mx);
-                num = fmaf(__builtin_nontemporal_load(&pacc[((size_t)sp * G + g) * LC_D + c]), sc, num);
-                den = fmaf(ls, sc, den);
-            }
-        }
-        const size_t o = ((size_t)b * ix.H * G + (size_t)h * G + g);
-        a.out[o * LC_D + c] = den > 0.f ? num / den : 0.f;
-        if (a.lse && c == 0) a.lse[o] = den > 0.f ? (mx + log2f(den)) * LC_LN2 : LC_NEG_INF;
+    const int n_part = (n_tok > 0) ? S_eff : 0;
+    for (int e = tid; e < n_part * G; e += LC_DEC_THREADS) {
+        mrg_m[e] = lc_load_agent(pml + 2 * e);
+        mrg_l[e] = lc_load_agent(pml + 2 * e + 1);
     }
+    __syncthreads();
+    for (int g = wave; g < G; g += LC_DEC_THREADS / 64) {
+        float mx = LC_NEG_INF;
+        for (int sp = lane; sp < n_part; sp += 64) mx = fmaxf(mx, mrg_m[sp * G + g]);
+        mx = lc_max64(mx);
+        float den = 0.f;
+        for (int sp = lane; sp < n_part; sp += 64) {
+            const float ms = mrg_m[sp * G + g];
+            const float sc = (ms == LC_NEG_INF) ? 0.f : exp2f(ms - mx);
+            mrg_m[sp * G + g] = sc;                     // from here on: the split's scale
+            den = fmaf(mrg_l[sp * G + g], sc, den);
+        }
+        den = lc_sum64(den);
+        if (lane == 0) { mrg_hd[2 * g] = mx; mrg_hd[2 * g + 1] = den; }
+    }
+    __syncthreads();
+    LC_STAMP(lc_dbg_decode, 5);
+    constexpr int NV = G * (LC_D / 4);                       // float4 slots of the output
+    constexpr int WAYS = (LC_DEC_THREADS / NV) > 0 ? (LC_DEC_THREADS / NV) : 1;
+    float4 acc4 = make_float4(0.f, 0.f, 0.f, 0.f);
+    const int v = tid % NV, wy = tid / NV;
+    const int g = v / (LC_D / 4), c4 = v % (LC_D / 4);
+    if (wy < WAYS) {
+#pragma unroll 8
+        for (int sp = wy; sp < n_part; sp += WAYS) {
+            const float* px = pacc + ((size_t)sp * G + g) * LC_D + 4 * c4;
+            const float4 x = make_float4(lc_load_agent(px), lc_load_agent(px + 1), lc_load_agent(px + 2),
+                                         lc_load_agent(px + 3));
+            const float sc = mrg_m[sp * G + g];
+            acc4.x = fmaf(x.x, sc, acc4.x);
+            acc4.y = fmaf(x.y, sc, acc4.y);
+            acc4.z = fmaf(x.z, sc, acc4.z);
+            acc4.w = fmaf(x.w, sc, acc4.w);
+        }
+        if (WAYS > 1 && wy > 0) mrg_red[(wy - 1) * NV + v] = acc4;
+    }
+    __syncthreads();
+    LC_STAMP(lc_dbg_decode, 6);
+    if (wy == 0) {
+#pragma unroll
+        for (int k = 1; k < WAYS; ++k) {
+            const float4 o4 = mrg_red[(k - 1) * NV + v];
+            acc4.x += o4.x; acc4.y += o4.y; acc4.z += o4.z; acc4.w += o4.w;
+        }
+        const float mx = mrg_hd[2 * g], den = mrg_hd[2 * g + 1];
+        const float inv = den > 0.f ? 1.0f / den : 0.f;
+        const size_t o = ((size_t)b * ix.H * G + (size_t)h * G + g);
+        *reinterpret_cast<float4*>(a.out + o * LC_D + 4 * c4) =
+            make_float4(acc4.x * inv, acc4.y * inv, acc4.z * inv, acc4.w * inv);
+        if (a.lse && c4 == 0) a.lse[o] = den > 0.f ? (mx + log2f(den)) * LC_LN2 : LC_NEG_INF;
+    }
+    LC_STAMP(lc_dbg_decode, 7);
     if (tid == 0) ix.sync[bh * 4 + 1] = 0;
 }
 

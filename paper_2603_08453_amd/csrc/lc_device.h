@@ -5,6 +5,20 @@
 #include <stdint.h>
 
 #define LC_D 128                  // head dimension the kernels are written for
+
+// Development aid (off in the product build): phase time stamps of one workgroup.
+#ifdef LC_DBG_TIMES
+#define LC_STAMP_DECL(name) __device__ unsigned long long name[32]; \
+    extern "C" int name##_read(unsigned long long* host) { \
+        return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(name), sizeof(name)); }
+#define LC_STAMP0(name, i) do { if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) \
+    name[i] = wall_clock64(); } while (0)
+#define LC_STAMP(name, i) do { if (blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) name[i] = wall_clock64(); } while (0)
+#else
+#define LC_STAMP_DECL(name)
+#define LC_STAMP0(name, i)
+#define LC_STAMP(name, i)
+#endif
 #define LC_NEG_INF (-__builtin_huge_valf())
 
 // ---------------------------------------------------------------- bf16 unpacking
@@ -45,6 +59,41 @@ __device__ __forceinline__ float lc_max64(float v) {
     return v;
 }
 
+// ---------------------------------------------------------------- cross-workgroup hand-off
+// Several workgroups produce partial results and the last one to arrive consumes them.
+// A device-scope fence (__threadfence) writes back the whole L2 of the XCD on this chip,
+// which costs tens of microseconds when hundreds of workgroups do it.  Instead the
+// hand-off data itself is stored and loaded at agent scope (relaxed atomics: the
+// accesses are performed at the device-coherent level and leave no dirty L2 lines),
+// the producer waits for its stores to complete (workgroup-scope release = s_waitcnt)
+// before it bumps the arrival counter, and the consumer reads only after it has seen
+// the final count.
+__device__ __forceinline__ void lc_store_agent(float* p, float v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void lc_store_agent(uint32_t* p, uint32_t v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float lc_load_agent(const float* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint32_t lc_load_agent(const uint32_t* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// Returns true in every thread of the last workgroup to arrive at `counter` (of `expected`).
+__device__ __forceinline__ bool lc_arrive_last(int* counter, int expected, int* flag_sh) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");       // this thread's stores have completed
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const int old = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *flag_sh = (old == expected - 1) ? 1 : 0;
+    }
+    __syncthreads();
+    const bool last = *flag_sh != 0;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    return last;
+}
+
 // ---------------------------------------------------------------- score keys
 // Order-preserving map float -> uint32 (larger score = larger key).  -inf (empty
 // or pruned node) maps to 0, which no finite score produces: key 0 = "not a candidate".
@@ -66,27 +115,39 @@ __device__ __forceinline__ float lc_key_score(uint32_t k) {
 // Returns max_g (q_g . mu + |q_g| R) / sqrt(d) in every lane of the group.
 // The operation order is fixed (explicit fma chain) so that every kernel that
 // scores the same node obtains the same bits.
+struct LcNodeFrag {
+    float4 a, b;        // floats [4 sub, 4 sub + 4) and [64 + 4 sub, 64 + 4 sub + 4) of the center
+};
+__device__ __forceinline__ LcNodeFrag lc_load_node(const float* __restrict__ center, int sub) {
+    LcNodeFrag f;
+    f.a = *reinterpret_cast<const float4*>(center + 4 * sub);
+    f.b = *reinterpret_cast<const float4*>(center + 64 + 4 * sub);
+    return f;
+}
 template <int G>
-__device__ __forceinline__ float lc_score_node(const float* __restrict__ center, float R, int sub,
-                                               const float (&qf)[G][8], const float (&qn)[G]) {
-    const float4 a = *reinterpret_cast<const float4*>(center + 4 * sub);
-    const float4 b = *reinterpret_cast<const float4*>(center + 64 + 4 * sub);
+__device__ __forceinline__ float lc_score_frag(const LcNodeFrag& f, float R, const float (&qf)[G][8],
+                                               const float (&qn)[G]) {
     float best = LC_NEG_INF;
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-        float p = a.x * qf[g][0];
-        p = fmaf(a.y, qf[g][1], p);
-        p = fmaf(a.z, qf[g][2], p);
-        p = fmaf(a.w, qf[g][3], p);
-        p = fmaf(b.x, qf[g][4], p);
-        p = fmaf(b.y, qf[g][5], p);
-        p = fmaf(b.z, qf[g][6], p);
-        p = fmaf(b.w, qf[g][7], p);
+        float p = f.a.x * qf[g][0];
+        p = fmaf(f.a.y, qf[g][1], p);
+        p = fmaf(f.a.z, qf[g][2], p);
+        p = fmaf(f.a.w, qf[g][3], p);
+        p = fmaf(f.b.x, qf[g][4], p);
+        p = fmaf(f.b.y, qf[g][5], p);
+        p = fmaf(f.b.z, qf[g][6], p);
+        p = fmaf(f.b.w, qf[g][7], p);
         p = lc_sum16(p);
         const float ub = fmaf(qn[g], R, p) * 0.08838834764831845f;      // 1/sqrt(128)
         best = fmaxf(best, ub);
     }
     return best;
+}
+template <int G>
+__device__ __forceinline__ float lc_score_node(const float* __restrict__ center, float R, int sub,
+                                               const float (&qf)[G][8], const float (&qn)[G]) {
+    return lc_score_frag<G>(lc_load_node(center, sub), R, qf, qn);
 }
 
 // Load the query group of KV head h into registers (fragments as above) and
@@ -142,6 +203,10 @@ __device__ __forceinline__ int lc_block_scan(int v, int* sh, int* total) {
 // Result: items with key > kstar are in; items with key == kstar are in while,
 // taken in ascending i, their running weight stays <= remW and their running
 // count <= remC; `all` set = every candidate fits (kstar = 0).
+//
+// The digits are taken from the highest bit in which the keys differ downward
+// (scores of one query sit in a narrow range, so their top bits agree): at most
+// four 8-bit passes, and the LDS histogram atomics spread over many bins.
 struct LcSel {
     uint32_t kstar;
     int remW;
@@ -149,26 +214,54 @@ struct LcSel {
     int all;
 };
 
-// sh: 2*256 + 4 ints of LDS.  All NT threads must call.
+// sh: 2*256 + 8 ints of LDS.  All NT threads must call.
 template <int NT, typename KeyF, typename WgtF>
 __device__ __forceinline__ LcSel lc_block_select(int n, long long W, long long C, KeyF key, WgtF wgt, int* sh) {
     int* hw = sh;
     int* hc = sh + 256;
     int* res = sh + 512;
-    uint32_t prefix = 0u, mask = 0u;
-    long long remW = W, remC = C;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     LcSel out;
     out.all = 0;
-    for (int pass = 0; pass < 4; ++pass) {
-        const int shift = 24 - 8 * pass;
+    out.kstar = 0u;
+    out.remW = 0;
+    out.remC = 0;
+    // ---- range of the candidate keys
+    uint32_t kmin = 0xffffffffu, kmax = 0u;
+    for (int i = threadIdx.x; i < n; i += NT) {
+        const uint32_t k = key(i);
+        if (k != 0u) { kmin = min(kmin, k); kmax = max(kmax, k); }
+    }
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) {
+        kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, m));
+        kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, m));
+    }
+    __syncthreads();
+    if (lane == 0) { hw[wave] = (int)kmin; hc[wave] = (int)kmax; }
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < NT / 64; ++w) { kmin = min(kmin, (uint32_t)hw[w]); kmax = max(kmax, (uint32_t)hc[w]); }
+    __syncthreads();
+    if (kmax == 0u) { out.all = 1; return out; }            // no candidate at all
+    const uint32_t diff = kmin ^ kmax;
+    int top = diff ? 32 - __clz(diff) : 0;                   // bits [0, top) may differ
+    uint32_t mask = top >= 32 ? 0u : ~((1u << top) - 1u);
+    uint32_t prefix = kmax & mask;
+    long long remW = W, remC = C;
+    const bool count_c = C < 0x7fffffffLL;
+    bool first = true;
+    while (top > 0) {
+        const int width = top >= 8 ? 8 : top;
+        const int shift = top - width;
         for (int i = threadIdx.x; i < 256; i += NT) { hw[i] = 0; hc[i] = 0; }
         __syncthreads();
         for (int i = threadIdx.x; i < n; i += NT) {
             const uint32_t k = key(i);
             if (k != 0u && (k & mask) == prefix) {
-                const int b = (k >> shift) & 255;
+                const int b = (k >> shift) & ((1 << width) - 1);
                 atomicAdd(&hw[b], wgt(i));
-                atomicAdd(&hc[b], 1);
+                if (count_c) atomicAdd(&hc[b], 1);
             }
         }
         __syncthreads();
@@ -199,25 +292,52 @@ __device__ __forceinline__ LcSel lc_block_select(int n, long long W, long long C
             if (bal == 0ull) {
                 if (l == 0) res[0] = -1;
             } else {
-                const int first = __ffsll((long long)bal) - 1;        // lowest lane = highest bins
-                if (l == first) { res[0] = found; res[1] = (int)fw; res[2] = (int)fc; }
+                const int firstl = __ffsll((long long)bal) - 1;       // lowest lane = highest bins
+                if (l == firstl) { res[0] = found; res[1] = (int)fw; res[2] = (int)fc; }
             }
         }
         __syncthreads();
         const int found = res[0];
-        if (found < 0) {            // everything (still in scope) fits; only possible in pass 0
-            out.all = 1;
+        if (found < 0) {            // everything in scope fits: only possible in the first pass
+            out.all = first ? 1 : 0;
             break;
         }
         remW -= res[1];
         remC -= res[2];
         prefix |= (uint32_t)found << shift;
-        mask |= 255u << shift;
+        mask |= (uint32_t)((1 << width) - 1) << shift;
+        top = shift;
+        first = false;
         __syncthreads();
     }
     __syncthreads();
+    // all keys equal (top == 0 from the start): the single key group is the tie group
     out.kstar = out.all ? 0u : prefix;
-    out.remW = (int)(remW > 0x7fffffffLL ? 0x7fffffffLL : remW);
-    out.remC = (int)(remC > 0x7fffffffLL ? 0x7fffffffLL : remC);
+    out.remW = (int)(remW > 0x7fffffffLL ? 0x7fffffffLL : (remW < 0 ? -1 : remW));
+    out.remC = (int)(remC > 0x7fffffffLL ? 0x7fffffffLL : (remC < 0 ? -1 : remC));
     return out;
+}
+
+// ---------------------------------------------------------------- counting select (small n)
+// For item i among n candidates: number and total weight of the items that precede it in the
+// (key descending, index ascending) order.  `keys` and `wgts` are 16-byte aligned LDS arrays,
+// zero-padded to a multiple of 4 entries (key 0 = not a candidate; it never precedes anything).
+// Every thread reads the same addresses at the same time (LDS broadcast), four entries a load.
+__device__ __forceinline__ void lc_rank_before(int n, const uint32_t* keys, const int* wgts, int i, uint32_t ki,
+                                               int* count_before, int* weight_before) {
+    int cb = 0, wb = 0;
+    const int n4 = (n + 3) & ~3;
+#pragma unroll 4
+    for (int j = 0; j < n4; j += 4) {
+        const uint4 k = *reinterpret_cast<const uint4*>(keys + j);
+        const int4 w = *reinterpret_cast<const int4*>(wgts + j);
+        const bool b0 = k.x > ki || (k.x == ki && j + 0 < i);
+        const bool b1 = k.y > ki || (k.y == ki && j + 1 < i);
+        const bool b2 = k.z > ki || (k.z == ki && j + 2 < i);
+        const bool b3 = k.w > ki || (k.w == ki && j + 3 < i);
+        cb += (int)b0 + (int)b1 + (int)b2 + (int)b3;
+        wb += (b0 ? w.x : 0) + (b1 ? w.y : 0) + (b2 ? w.z : 0) + (b3 ? w.w : 0);
+    }
+    *count_before = cb;
+    *weight_before = wb;
 }

@@ -44,7 +44,8 @@ size_t lc_layout_index(const lc_config* cfg, int B, int H, int d, void* base, Lc
 struct LcWs {
     // retrieval
     uint32_t* keys;      // [B][H][cap0] order-preserving score keys of the chunks (0 = not a candidate)
-    uint8_t* kept1;      // [B][H][cap1] level-1 nodes whose children are scored
+    uint8_t* want;       // [B][H][cap0] 1 = this chunk's score is needed
+    int* scratch;        // [B][H][4 * cap0] chunk-level staging when it does not fit in LDS
     float* scores;       // [B][H][cap0] scratch scores when the caller passes none
     // decode
     float* part_acc;     // [B][H][S][G][d]
@@ -53,7 +54,6 @@ struct LcWs {
     float* dirs;         // [B][H][cap0][d] unit directions of the level being clustered
     float* cent_a;       // [B][H][cap1][d] centroids (ping)
     float* cent_b;       // [B][H][cap1][d] centroids (pong)
-    int* labels;         // [B][H][cap0]
     int* anc;            // [B][H][cap0] chunk -> ancestor at the level being built
     size_t total;
 };

@@ -1,17 +1,21 @@
 // Retrieval kernels: Eq. 2 node scoring, level-by-level pruning, budget selection.
 //
-// Kernel 1 (lc_upper_kernel): one workgroup per (sequence, KV head).  Scores every
-// internal node (levels >= 1), keeps score keys and frontier flags in LDS, and
-// walks the levels top-down:
+// Kernel 1 (lc_upper_kernel): one workgroup per (sequence, KV head).  It stages the
+// tree's small arrays (parents, subtree token counts, chunk lengths) in LDS with a
+// few batched loads, scores every internal node (levels >= 1), and walks the levels
+// top-down with the frontier held in LDS:
 //   EXACT  probe pass  -> a lower bound tau0 of the selection cutoff,
 //          verify pass -> every node whose bound reaches tau0 stays;
 //   BEAM   keep the beam[l] best frontier nodes per level (Algorithm 1).
-// It leaves a byte map of the level-1 nodes whose chunks must be scored.
+// It leaves one byte per chunk: score it or not.
 //
 // Kernel 2 (lc_leaf_kernel): many workgroups per (sequence, KV head) score the
-// surviving chunks; the last workgroup to finish for a (sequence, head) runs the
-// weighted radix select over the chunk keys (weights = chunk lengths) and emits
-// the ids in ascending order.
+// wanted chunks; the last workgroup to finish for a (sequence, head) pulls the keys
+// into LDS, runs the weighted radix select (weights = chunk lengths) and emits the
+// ids in ascending order.
+//
+// The kernels are latency-bound at batch 1, so global loads are issued in batches
+// and nothing reads global memory element by element inside a dependent loop.
 #include "lc_device.h"
 #include "lc_internal.h"
 
@@ -19,33 +23,92 @@
 #define LC_RT_GROUPS (LC_RT_THREADS / 16)
 #define LC_LEAF_CHUNKS_PER_BLOCK 32
 #define LC_TAU_SLACK 1e-3f
+#define LC_COUNT_SELECT_MAX 1024         // up to this many candidates the O(n^2 / threads) rank is used
+
+LC_STAMP_DECL(lc_dbg_upper)
+LC_STAMP_DECL(lc_dbg_leaf)
 
 struct LcRetrieveArgs {
     LcDev ix;
     const uint16_t* q;       // [B][H_q][d]
     uint32_t* keys;          // [B][H][cap0]
-    uint8_t* kept1;          // [B][H][cap1]
+    uint8_t* want;           // [B][H][cap0] 1 = score this chunk
     float* scores;           // [B][H][cap0] or null
     int32_t* ids;            // [B][H][cap]
     int32_t* counts;         // [B][H]
+    int* scratch;            // [B][H][4 * cap0] ints: chunk-level staging when it does not fit in LDS
     int cap;
     int budget;
     int policy;
     int sink;
     int beam[LC_MAX_LEVELS];
-    int upper_cap;           // LDS entries available for internal nodes
+    int upper_cap;           // LDS entries for internal nodes
+    int chunk_cap;           // upper kernel: LDS entries of the probe list; leaf kernel: LDS entries for
+                             // the select's staging, 0 = stage in `scratch` (global memory)
 };
+
+// Selection among n <= LC_COUNT_SELECT_MAX candidates whose keys / weights sit in 16-byte aligned,
+// zero-padded LDS arrays.
+//   mode 0: keep the longest prefix with weight <= W and count <= C  (exact ties by index)
+//   mode 1: keep the shortest prefix whose weight reaches W (everything if it never does)
+// Writes flags[i] for i < n.  Returns, in every thread, the smallest kept key (0 if nothing kept)
+// and whether the kept weight reached W (mode 1).
+template <int NT>
+__device__ __forceinline__ void lc_small_select(int n, int mode, long long W, long long C, const uint32_t* keys,
+                                                const int* wgts, uint8_t* flags, int* sh, uint32_t* min_kept,
+                                                int* reached) {
+    uint32_t mk = 0xffffffffu;
+    int hit = 0;
+    for (int i = threadIdx.x; i < n; i += NT) {
+        const uint32_t ki = keys[i];
+        int keep = 0;
+        if (ki != 0u) {
+            int cb, wb;
+            lc_rank_before(n, keys, wgts, i, ki, &cb, &wb);
+            const int wi = wgts[i];
+            if (mode == 0) keep = ((long long)wb + wi <= W && (long long)cb + 1 <= C) ? 1 : 0;
+            else {
+                keep = ((long long)wb < W) ? 1 : 0;
+                if (keep && (long long)wb + wi >= W) hit = 1;
+            }
+        }
+        flags[i] = (uint8_t)keep;
+        if (keep) mk = min(mk, ki);
+    }
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) {
+        mk = min(mk, (uint32_t)__shfl_xor((int)mk, m));
+        hit |= __shfl_xor(hit, m);
+    }
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) { sh[threadIdx.x >> 6] = (int)mk; sh[32 + (threadIdx.x >> 6)] = hit; }
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < NT / 64; ++w) { mk = min(mk, (uint32_t)sh[w]); hit |= sh[32 + w]; }
+    __syncthreads();
+    *min_kept = (mk == 0xffffffffu) ? 0u : mk;
+    *reached = hit;
+}
 
 // ---------------------------------------------------------------------------------
 // kernel 1: internal levels
 // ---------------------------------------------------------------------------------
+// One workgroup of 1024 threads (64 groups of 16 lanes) per (sequence, head).  All
+// global loads of a phase are issued before any of them is used: at batch 1 the
+// kernel's duration is a chain of memory round trips, not bandwidth.
+#define LC_UP_THREADS 1024
+#define LC_UP_GROUPS (LC_UP_THREADS / 16)
+#define LC_UP_PER_THREAD 4
+
 template <int G>
-__global__ void __launch_bounds__(LC_RT_THREADS)
+__global__ void __launch_bounds__(LC_UP_THREADS)
 lc_upper_kernel(const LcRetrieveArgs a) {
     extern __shared__ int lds_dyn[];
-    __shared__ int sel_sh[516];
+    __shared__ int sel_sh[520];
     __shared__ int off_sh[LC_MAX_LEVELS + 1];
+    constexpr int NB = (G <= 4) ? 4 : 2;          // nodes in flight per group
 
+    LC_STAMP0(lc_dbg_upper, 0);
     const LcDev& ix = a.ix;
     const int h = blockIdx.x, b = blockIdx.y;
     const int bh = b * ix.H + h;
@@ -54,147 +117,263 @@ lc_upper_kernel(const LcRetrieveArgs a) {
     const int L = ix.L;
     const int M = ix.state[bh * 4 + 1];
 
-    // LDS: keys[NU] (uint32) | flag arrays fr[NU], kp[NU] (bytes)
     if (tid == 0) {
         int o = 0;
         for (int l = 1; l < L; ++l) { off_sh[l] = o; o += ix.nlev[b * LC_MAX_LEVELS + l]; }
         off_sh[L] = o;
         off_sh[0] = 0;
     }
-    __syncthreads();
-    const int NU = off_sh[L];
+    // LDS carve-up: internal nodes (UC entries each), select scratch, probe list (PC entries each)
+    const int UC = a.upper_cap, PC = a.chunk_cap;
+    const int SC = UC > PC ? UC : PC;
     uint32_t* ukey = reinterpret_cast<uint32_t*>(lds_dyn);
-    uint8_t* fr = reinterpret_cast<uint8_t*>(ukey + a.upper_cap);
-    uint8_t* kp = fr + a.upper_cap;
+    int* untok = lds_dyn + UC;
+    int* upar = lds_dyn + 2 * UC;
+    uint8_t* fr = reinterpret_cast<uint8_t*>(lds_dyn + 3 * UC);
+    uint8_t* kp = fr + UC;
+    uint32_t* ek = reinterpret_cast<uint32_t*>(lds_dyn + 3 * UC + UC / 2);      // UC, PC multiples of 64
+    int* ew = reinterpret_cast<int*>(ek) + SC;
+    int* plist = ew + SC;
+    int* plen = plist + PC;
+    uint32_t* pkey = reinterpret_cast<uint32_t*>(plen + PC);
 
     float qf[G][8], qn[G];
     lc_load_query_frags<G>(a.q + (size_t)b * ix.H * G * LC_D, h, sub, qf, qn);
+    __syncthreads();
+    const int NU = off_sh[L];
+    LC_STAMP0(lc_dbg_upper, 1);
 
-    // ---- score every internal node
-    for (int l = 1; l < L; ++l) {
-        const int n_l = off_sh[l + 1] - off_sh[l];
-        const size_t base = (size_t)bh * ix.cap[l];
-        for (int n = grp; n < n_l; n += LC_RT_GROUPS) {
-            const float R = ix.radius[l][base + n];
-            const int nch = ix.nchunk[l][base + n];
-            float s = lc_score_node<G>(ix.center[l] + (base + n) * LC_D, R, sub, qf, qn);
-            if (nch <= 0) s = LC_NEG_INF;
-            if (sub == 0) ukey[off_sh[l] + n] = lc_score_key(s);
+    // ---- internal nodes, all levels as one list: parents, token counts, scores
+    auto level_of = [&](int u) -> int {
+        int l = 1;
+        while (l + 1 < L && u >= off_sh[l + 1]) ++l;
+        return l;
+    };
+    for (int u = tid; u < NU; u += LC_UP_THREADS) {
+        const int l = level_of(u);
+        const size_t n = (size_t)bh * ix.cap[l] + (u - off_sh[l]);
+        untok[u] = ix.ntok[l][n];
+        upar[u] = ix.parent[l][n];
+    }
+    for (int u0 = grp; u0 < NU; u0 += NB * LC_UP_GROUPS) {
+        LcNodeFrag f[NB];
+        float R[NB];
+        int nc[NB];
+#pragma unroll
+        for (int k = 0; k < NB; ++k) {
+            const int u = min(u0 + k * LC_UP_GROUPS, NU - 1);
+            const int l = level_of(u);
+            const size_t n = (size_t)bh * ix.cap[l] + (u - off_sh[l]);
+            f[k] = lc_load_node(ix.center[l] + n * LC_D, sub);
+            R[k] = ix.radius[l][n];
+            nc[k] = ix.nchunk[l][n];
+        }
+#pragma unroll
+        for (int k = 0; k < NB; ++k) {
+            const int u = u0 + k * LC_UP_GROUPS;
+            float s = lc_score_frag<G>(f[k], R[k], qf, qn);
+            if (nc[k] <= 0) s = LC_NEG_INF;
+            if (sub == 0 && u < NU) ukey[u] = lc_score_key(s);
         }
     }
     __syncthreads();
+    LC_STAMP0(lc_dbg_upper, 2);
 
-    uint8_t* kept1_out = a.kept1 + (size_t)bh * ix.cap[1];
-    const int n1 = off_sh[2] - off_sh[1];
-
+    uint8_t* want = a.want + (size_t)bh * ix.cap[0];
+    const int* bnd = ix.bounds + (size_t)b * (ix.cap[0] + 1);
+    const int* par0 = ix.parent[0] + (size_t)bh * ix.cap[0];
     if (a.budget <= 0) {
-        for (int n = tid; n < n1; n += LC_RT_THREADS) kept1_out[n] = 0;
+        for (int j = tid; j < M; j += LC_UP_THREADS) want[j] = 0;
         return;
     }
+    const int o1 = off_sh[1];
 
-    if (a.policy == LC_POLICY_BEAM) {
-        // frontier of the top level: every node
-        for (int n = tid; n < NU; n += LC_RT_THREADS) fr[n] = (n >= off_sh[L - 1]) ? 1 : 0;
-        __syncthreads();
-        for (int l = L - 1; l >= 1; --l) {
-            const int o = off_sh[l], n_l = off_sh[l + 1] - o;
-            const long long C = a.beam[l] > 0 ? a.beam[l] : 0x7fffffffLL;
-            auto keyf = [&](int i) -> uint32_t { return fr[o + i] ? ukey[o + i] : 0u; };
-            auto wf = [&](int) -> int { return 0; };
-            const LcSel r = lc_block_select<LC_RT_THREADS>(n_l, 0x7fffffffffffLL, C, keyf, wf, sel_sh);
-            // ties at kstar: ascending id while the count allows
-            int tie_c = 0;
-            for (int t0 = 0; t0 < n_l; t0 += LC_RT_THREADS) {
-                const int i = t0 + tid;
-                const uint32_t k = (i < n_l) ? keyf(i) : 0u;
-                const int eq = (!r.all && k != 0u && k == r.kstar) ? 1 : 0;
-                int tot;
-                const int ex = lc_block_scan<LC_RT_THREADS>(eq, sel_sh, &tot);
-                if (i < n_l) kp[o + i] = (k != 0u && (k > r.kstar || (eq && tie_c + ex + 1 <= r.remC))) ? 1 : 0;
-                tie_c += tot;
+    // want[j] = (level-1 parent kept) and not pinned; streamed, loads batched
+    auto write_want = [&]() {
+        const bool word_ok = (reinterpret_cast<uintptr_t>(want) & 3u) == 0;
+        for (int j0 = tid * LC_UP_PER_THREAD; j0 < M; j0 += LC_UP_THREADS * LC_UP_PER_THREAD) {
+            int p[LC_UP_PER_THREAD], s0[LC_UP_PER_THREAD];
+#pragma unroll
+            for (int k = 0; k < LC_UP_PER_THREAD; ++k) {
+                const int j = min(j0 + k, M - 1);
+                p[k] = par0[j];
+                s0[k] = a.sink > 0 ? bnd[j] : 0;
             }
-            __syncthreads();
-            if (l >= 2) {
-                const int ob = off_sh[l - 1], n_b = off_sh[l] - ob;
-                const size_t pb = (size_t)bh * ix.cap[l - 1];
-                for (int n = tid; n < n_b; n += LC_RT_THREADS) fr[ob + n] = kp[o + ix.parent[l - 1][pb + n]];
-                __syncthreads();
+            uint32_t packed = 0u;
+#pragma unroll
+            for (int k = 0; k < LC_UP_PER_THREAD; ++k)
+                packed |= (uint32_t)((s0[k] >= a.sink && kp[o1 + p[k]]) ? 1u : 0u) << (8 * k);
+            if (j0 + LC_UP_PER_THREAD <= M && word_ok) {
+                *reinterpret_cast<uint32_t*>(want + j0) = packed;          // j0 is a multiple of 4
+            } else {
+                for (int k = 0; k < LC_UP_PER_THREAD && j0 + k < M; ++k)
+                    want[j0 + k] = (uint8_t)((packed >> (8 * k)) & 1u);
             }
         }
-        for (int n = tid; n < n1; n += LC_RT_THREADS) kept1_out[n] = kp[off_sh[1] + n];
+    };
+    // frontier-filtered keys and weights of level l -> aligned select scratch (zero padded)
+    auto stage_level = [&](int l, bool with_tokens) -> int {
+        const int o = off_sh[l], n_l = off_sh[l + 1] - o;
+        const int n4 = (n_l + 3) & ~3;
+        for (int i = tid; i < n4; i += LC_UP_THREADS) {
+            const bool in = i < n_l && fr[o + i];
+            ek[i] = in ? ukey[o + i] : 0u;
+            ew[i] = (in && with_tokens) ? untok[o + i] : 0;
+        }
+        __syncthreads();
+        return n_l;
+    };
+    auto children_frontier = [&](int l) {             // fr[level l-1] = kp[parent at level l]
+        const int o = off_sh[l];
+        const int ob = off_sh[l - 1], n_b = off_sh[l] - ob;
+        for (int n = tid; n < n_b; n += LC_UP_THREADS) fr[ob + n] = kp[o + upar[ob + n]];
+        __syncthreads();
+    };
+
+    for (int n = tid; n < NU; n += LC_UP_THREADS) fr[n] = (n >= off_sh[L - 1]) ? 1 : 0;
+    __syncthreads();
+
+    if (a.policy == LC_POLICY_BEAM) {
+        for (int l = L - 1; l >= 1; --l) {
+            const int o = off_sh[l];
+            const long long C = a.beam[l] > 0 ? a.beam[l] : 0x7fffffffLL;
+            const int n_l = stage_level(l, false);
+            if (n_l <= LC_COUNT_SELECT_MAX) {
+                uint32_t mk;
+                int reached;
+                lc_small_select<LC_UP_THREADS>(n_l, 0, 0x7fffffffffffLL, C, ek, ew, kp + o, sel_sh, &mk, &reached);
+            } else {
+                auto keyf = [&](int i) -> uint32_t { return ek[i]; };
+                auto wf = [&](int) -> int { return 0; };
+                const LcSel r = lc_block_select<LC_UP_THREADS>(n_l, 0x7fffffffffffLL, C, keyf, wf, sel_sh);
+                int tie_c = 0;
+                for (int t0 = 0; t0 < n_l; t0 += LC_UP_THREADS) {
+                    const int i = t0 + tid;
+                    const uint32_t k = (i < n_l) ? ek[i] : 0u;
+                    const int eq = (!r.all && k != 0u && k == r.kstar) ? 1 : 0;
+                    int tot;
+                    const int ex = lc_block_scan<LC_UP_THREADS>(eq, sel_sh, &tot);
+                    if (i < n_l) kp[o + i] = (k != 0u && (k > r.kstar || (eq && tie_c + ex + 1 <= r.remC))) ? 1 : 0;
+                    tie_c += tot;
+                }
+            }
+            __syncthreads();
+            if (l >= 2) children_frontier(l);
+        }
+        write_want();
         return;
     }
 
     // ---- EXACT, probe pass: going down, keep the best frontier nodes until their
-    // subtree token counts reach the budget (whole tie groups are kept).
-    for (int n = tid; n < NU; n += LC_RT_THREADS) fr[n] = (n >= off_sh[L - 1]) ? 1 : 0;
-    __syncthreads();
+    // subtree token counts reach the budget.
     for (int l = L - 1; l >= 1; --l) {
-        const int o = off_sh[l], n_l = off_sh[l + 1] - o;
-        const size_t nb = (size_t)bh * ix.cap[l];
-        auto keyf = [&](int i) -> uint32_t { return fr[o + i] ? ukey[o + i] : 0u; };
-        auto wf = [&](int i) -> int { return ix.ntok[l][nb + i]; };
-        const LcSel r = lc_block_select<LC_RT_THREADS>(n_l, (long long)a.budget - 1, 0x7fffffffLL, keyf, wf, sel_sh);
-        for (int i = tid; i < n_l; i += LC_RT_THREADS) {
-            const uint32_t k = keyf(i);
-            kp[o + i] = (k != 0u && (r.all || k >= r.kstar)) ? 1 : 0;
+        const int o = off_sh[l];
+        const int n_l = stage_level(l, true);
+        if (n_l <= LC_COUNT_SELECT_MAX) {
+            uint32_t mk;
+            int reached;
+            lc_small_select<LC_UP_THREADS>(n_l, 1, (long long)a.budget, 0x7fffffffLL, ek, ew, kp + o, sel_sh, &mk, &reached);
+        } else {
+            auto keyf = [&](int i) -> uint32_t { return ek[i]; };
+            auto wf = [&](int i) -> int { return ew[i]; };
+            const LcSel r = lc_block_select<LC_UP_THREADS>(n_l, (long long)a.budget - 1, 0x7fffffffLL, keyf, wf, sel_sh);
+            for (int i = tid; i < n_l; i += LC_UP_THREADS)
+                kp[o + i] = (ek[i] != 0u && (r.all || ek[i] >= r.kstar)) ? 1 : 0;      // whole tie group
         }
         __syncthreads();
-        if (l >= 2) {
-            const int ob = off_sh[l - 1], n_b = off_sh[l] - ob;
-            const size_t pb = (size_t)bh * ix.cap[l - 1];
-            for (int n = tid; n < n_b; n += LC_RT_THREADS) fr[ob + n] = kp[o + ix.parent[l - 1][pb + n]];
-            __syncthreads();
-        }
+        if (l >= 2) children_frontier(l);
     }
-    // score the probe's chunks (children of the kept level-1 nodes)
-    uint32_t* pkeys = a.keys + (size_t)bh * ix.cap[0];
-    {
-        const size_t cb = (size_t)bh * ix.cap[0];
-        const int* bnd = ix.bounds + (size_t)b * (ix.cap[0] + 1);
-        const int o1 = off_sh[1];
-        for (int j0 = 0; j0 < M; j0 += LC_RT_GROUPS) {
-            const int j = j0 + grp;
-            if (j < M) {
-                uint32_t key = 0u;
-                const int p = ix.parent[0][cb + j];
-                if (kp[o1 + p] && bnd[j] >= a.sink) {
-                    const float s = lc_score_node<G>(ix.center[0] + (cb + j) * LC_D, ix.radius[0][cb + j], sub, qf, qn);
-                    key = lc_score_key(s);
-                }
-                if (sub == 0) pkeys[j] = key;
+    LC_STAMP0(lc_dbg_upper, 3);
+    // ---- compact the probe's chunks (children of the kept level-1 nodes, not pinned) into LDS.
+    // The list holds at most PC chunks; dropping the rest only weakens tau0, never the result.
+    int n_probe = 0;
+    for (int base = 0; base < M; base += LC_UP_THREADS * LC_UP_PER_THREAD) {
+        const int j0 = base + tid * LC_UP_PER_THREAD;
+        int p[LC_UP_PER_THREAD], s0[LC_UP_PER_THREAD + 1];
+#pragma unroll
+        for (int k = 0; k < LC_UP_PER_THREAD; ++k) p[k] = par0[max(0, min(j0 + k, M - 1))];
+#pragma unroll
+        for (int k = 0; k <= LC_UP_PER_THREAD; ++k) s0[k] = bnd[min(j0 + k, M)];
+        int f[LC_UP_PER_THREAD], cnt = 0;
+#pragma unroll
+        for (int k = 0; k < LC_UP_PER_THREAD; ++k) {
+            f[k] = (j0 + k < M && s0[k] >= a.sink && kp[o1 + p[k]]) ? 1 : 0;
+            cnt += f[k];
+        }
+        int tot;
+        int pos = n_probe + lc_block_scan<LC_UP_THREADS>(cnt, sel_sh, &tot);
+#pragma unroll
+        for (int k = 0; k < LC_UP_PER_THREAD; ++k) {
+            if (f[k]) {
+                if (pos < PC) { plist[pos] = j0 + k; plen[pos] = s0[k + 1] - s0[k]; }
+                ++pos;
             }
         }
+        n_probe += tot;
+    }
+    n_probe = min(n_probe, PC);
+    __syncthreads();
+    LC_STAMP0(lc_dbg_upper, 4);
+    // ---- score them
+    {
+        const size_t cb = (size_t)bh * ix.cap[0];
+        for (int i0 = grp; i0 < n_probe; i0 += NB * LC_UP_GROUPS) {
+            LcNodeFrag f[NB];
+            float R[NB];
+#pragma unroll
+            for (int k = 0; k < NB; ++k) {
+                const int j = plist[min(i0 + k * LC_UP_GROUPS, n_probe - 1)];
+                f[k] = lc_load_node(ix.center[0] + (cb + j) * LC_D, sub);
+                R[k] = ix.radius[0][cb + j];
+            }
+#pragma unroll
+            for (int k = 0; k < NB; ++k) {
+                const int i = i0 + k * LC_UP_GROUPS;
+                const float s = lc_score_frag<G>(f[k], R[k], qf, qn);
+                if (sub == 0 && i < n_probe) pkey[i] = lc_score_key(s);
+            }
+        }
+        // zero padding for the vector reads of the select
+        if (tid < 4 && n_probe + tid < ((n_probe + 3) & ~3)) { pkey[n_probe + tid] = 0u; plen[n_probe + tid] = 0; }
     }
     __syncthreads();
-    uint32_t tau_key;
+    LC_STAMP0(lc_dbg_upper, 5);
+    // ---- tau0: the score at which the probe chunks' cumulative length reaches the budget
+    uint32_t tau_key = 1u;                  // keep everything unless the probe proves a cutoff
     {
-        const int* bnd = ix.bounds + (size_t)b * (ix.cap[0] + 1);
-        auto keyf = [&](int i) -> uint32_t { return pkeys[i]; };
-        auto wf = [&](int i) -> int { return bnd[i + 1] - bnd[i]; };
-        const LcSel r = lc_block_select<LC_RT_THREADS>(M, (long long)a.budget - 1, 0x7fffffffLL, keyf, wf, sel_sh);
-        if (r.all) {
-            tau_key = 1u;                                 // fewer than `budget` probe tokens: keep everything
+        uint32_t cut = 0u;
+        int reached = 0;
+        if (n_probe <= LC_COUNT_SELECT_MAX) {
+            lc_small_select<LC_UP_THREADS>(n_probe, 1, (long long)a.budget, 0x7fffffffLL, pkey, plen,
+                                           reinterpret_cast<uint8_t*>(ek), sel_sh, &cut, &reached);
         } else {
-            const float tau = lc_key_score(r.kstar);
+            auto keyf = [&](int i) -> uint32_t { return pkey[i]; };
+            auto wf = [&](int i) -> int { return plen[i]; };
+            const LcSel r = lc_block_select<LC_UP_THREADS>(n_probe, (long long)a.budget - 1, 0x7fffffffLL, keyf, wf, sel_sh);
+            reached = r.all ? 0 : 1;
+            cut = r.kstar;
+        }
+        if (reached && cut != 0u) {
+            const float tau = lc_key_score(cut);
             tau_key = lc_score_key(tau - LC_TAU_SLACK * fmaxf(1.0f, fabsf(tau)));
             if (tau_key == 0u) tau_key = 1u;
         }
     }
+    LC_STAMP0(lc_dbg_upper, 6);
     // ---- verify pass: keep every node whose bound reaches tau0 and whose parent was kept
     {
         const int o = off_sh[L - 1], n_l = off_sh[L] - o;
-        for (int i = tid; i < n_l; i += LC_RT_THREADS) kp[o + i] = (ukey[o + i] >= tau_key) ? 1 : 0;
+        for (int i = tid; i < n_l; i += LC_UP_THREADS) kp[o + i] = (ukey[o + i] >= tau_key) ? 1 : 0;
         __syncthreads();
     }
     for (int l = L - 2; l >= 1; --l) {
         const int o = off_sh[l], n_l = off_sh[l + 1] - o, oa = off_sh[l + 1];
-        const size_t pb = (size_t)bh * ix.cap[l];
-        for (int i = tid; i < n_l; i += LC_RT_THREADS)
-            kp[o + i] = (ukey[o + i] >= tau_key && kp[oa + ix.parent[l][pb + i]]) ? 1 : 0;
+        for (int i = tid; i < n_l; i += LC_UP_THREADS)
+            kp[o + i] = (ukey[o + i] >= tau_key && kp[oa + upar[o + i]]) ? 1 : 0;
         __syncthreads();
     }
-    for (int n = tid; n < n1; n += LC_RT_THREADS) kept1_out[n] = kp[off_sh[1] + n];
+    write_want();
+    LC_STAMP0(lc_dbg_upper, 7);
 }
 
 // ---------------------------------------------------------------------------------
@@ -203,7 +382,8 @@ lc_upper_kernel(const LcRetrieveArgs a) {
 template <int G>
 __global__ void __launch_bounds__(LC_RT_THREADS)
 lc_leaf_kernel(const LcRetrieveArgs a) {
-    __shared__ int sel_sh[516];
+    extern __shared__ int lds_dyn[];
+    __shared__ int sel_sh[520];
     __shared__ int last_sh;
 
     const LcDev& ix = a.ix;
@@ -211,79 +391,126 @@ lc_leaf_kernel(const LcRetrieveArgs a) {
     const int bh = b * ix.H + h;
     const int tid = threadIdx.x;
     const int sub = tid & 15, grp = tid >> 4;
-    const int M = ix.state[bh * 4 + 1];
     const size_t cb = (size_t)bh * ix.cap[0];
     const int* bnd = ix.bounds + (size_t)b * (ix.cap[0] + 1);
     uint32_t* keys = a.keys + cb;
     float* scores = a.scores ? a.scores + cb : nullptr;
-    const uint8_t* kept1 = (ix.L > 1) ? a.kept1 + (size_t)bh * ix.cap[1] : nullptr;
+    const uint8_t* want = a.want + cb;
+    const bool have_want = ix.L > 1;
 
+    LC_STAMP0(lc_dbg_leaf, 0);
+    // loads that do not depend on M are issued together with it (the arrays are cap0 long)
     const int j_lo = blockIdx.x * LC_LEAF_CHUNKS_PER_BLOCK;
-    if (j_lo < M && a.budget > 0) {
-        float qf[G][8], qn[G];
-        lc_load_query_frags<G>(a.q + (size_t)b * ix.H * G * LC_D, h, sub, qf, qn);
+    int jj[LC_LEAF_CHUNKS_PER_BLOCK / LC_RT_GROUPS];
+    int wv[LC_LEAF_CHUNKS_PER_BLOCK / LC_RT_GROUPS];
+    float rv[LC_LEAF_CHUNKS_PER_BLOCK / LC_RT_GROUPS];
 #pragma unroll
-        for (int r = 0; r < LC_LEAF_CHUNKS_PER_BLOCK / LC_RT_GROUPS; ++r) {
-            const int j = j_lo + r * LC_RT_GROUPS + grp;
-            if (j < M) {
-                bool want = bnd[j] >= a.sink;
-                if (want && kept1) want = kept1[ix.parent[0][cb + j]] != 0;
-                float s = LC_NEG_INF;
-                if (want) s = lc_score_node<G>(ix.center[0] + (cb + j) * LC_D, ix.radius[0][cb + j], sub, qf, qn);
-                if (sub == 0) {
-                    keys[j] = lc_score_key(s);
-                    if (scores) scores[j] = s;
+    for (int r = 0; r < LC_LEAF_CHUNKS_PER_BLOCK / LC_RT_GROUPS; ++r) {
+        const int j = min(j_lo + r * LC_RT_GROUPS + grp, ix.cap[0] - 1);
+        jj[r] = j;
+        wv[r] = have_want ? (int)want[j] : (bnd[j] >= a.sink ? 1 : 0);
+        rv[r] = ix.radius[0][cb + j];
+    }
+    const int M = ix.state[bh * 4 + 1];
+
+    LC_STAMP0(lc_dbg_leaf, 1);
+    if (j_lo < M) {
+        if (a.budget > 0) {
+            float qf[G][8], qn[G];
+            lc_load_query_frags<G>(a.q + (size_t)b * ix.H * G * LC_D, h, sub, qf, qn);
+            float sv[LC_LEAF_CHUNKS_PER_BLOCK / LC_RT_GROUPS];
+#pragma unroll
+            for (int r = 0; r < LC_LEAF_CHUNKS_PER_BLOCK / LC_RT_GROUPS; ++r) {
+                const int j = j_lo + r * LC_RT_GROUPS + grp;
+                sv[r] = LC_NEG_INF;
+                if (j < M && wv[r]) sv[r] = lc_score_node<G>(ix.center[0] + (cb + jj[r]) * LC_D, rv[r], sub, qf, qn);
+            }
+#pragma unroll
+            for (int r = 0; r < LC_LEAF_CHUNKS_PER_BLOCK / LC_RT_GROUPS; ++r) {
+                const int j = j_lo + r * LC_RT_GROUPS + grp;
+                if (j < M && sub == 0) {
+                    lc_store_agent(&keys[j], lc_score_key(sv[r]));
+                    if (scores) scores[j] = sv[r];
                 }
             }
-        }
-    } else if (j_lo < M) {
-        for (int j = j_lo + tid; j < min(M, j_lo + LC_LEAF_CHUNKS_PER_BLOCK); j += LC_RT_THREADS) {
-            keys[j] = 0u;
-            if (scores) scores[j] = LC_NEG_INF;
+        } else {
+            for (int j = j_lo + tid; j < min(M, j_lo + LC_LEAF_CHUNKS_PER_BLOCK); j += LC_RT_THREADS) {
+                lc_store_agent(&keys[j], 0u);
+                if (scores) scores[j] = LC_NEG_INF;
+            }
         }
     }
 
+    LC_STAMP0(lc_dbg_leaf, 2);
     // ---- last workgroup of this (sequence, head) selects
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) {
-        const int old = atomicAdd(&ix.sync[bh * 4 + 0], 1);
-        last_sh = (old == (int)gridDim.x - 1) ? 1 : 0;
+    if (!lc_arrive_last(&ix.sync[bh * 4 + 0], (int)gridDim.x, &last_sh)) return;
+
+    LC_STAMP(lc_dbg_leaf, 3);
+    // stage keys and lengths (pinned chunks get length -1) in LDS, or fall back to global scratch
+    uint32_t* skey;
+    int* slen;
+    if (a.chunk_cap > 0) {
+        skey = reinterpret_cast<uint32_t*>(lds_dyn);
+        slen = lds_dyn + a.chunk_cap;
+    } else {
+        int* g = a.scratch + (size_t)bh * 4 * ix.cap[0];
+        skey = reinterpret_cast<uint32_t*>(g);
+        slen = g + ix.cap[0];
+    }
+#pragma unroll 4
+    for (int j = tid; j < M; j += LC_RT_THREADS) {
+        const int s0 = bnd[j], s1 = bnd[j + 1];
+        skey[j] = lc_load_agent(&keys[j]);
+        slen[j] = (s0 < a.sink) ? -1 : (s1 - s0);
     }
     __syncthreads();
-    if (!last_sh) return;
-    __threadfence();
 
-    auto keyf = [&](int i) -> uint32_t { return __builtin_nontemporal_load(&keys[i]); };
-    auto wf = [&](int i) -> int { return bnd[i + 1] - bnd[i]; };
+    LC_STAMP(lc_dbg_leaf, 4);
+    auto keyf = [&](int i) -> uint32_t { return skey[i]; };
+    auto wf = [&](int i) -> int { return slen[i]; };
     const long long C = (a.policy == LC_POLICY_BEAM && a.beam[0] > 0) ? a.beam[0] : 0x7fffffffLL;
     const LcSel r = lc_block_select<LC_RT_THREADS>(M, a.budget > 0 ? (long long)a.budget : 0LL, C, keyf, wf, sel_sh);
 
-    int32_t* ids = a.ids + (size_t)bh * a.cap;
-    int base = 0, tie_w = 0, tie_c = 0;
-    for (int t0 = 0; t0 < M; t0 += LC_RT_THREADS) {
-        const int i = t0 + tid;
-        const bool valid = i < M;
-        const uint32_t k = valid ? keyf(i) : 0u;
-        const bool pinned = valid && bnd[i] < a.sink;
-        const int eq = (!r.all && k != 0u && k == r.kstar) ? 1 : 0;
-        const int w = eq ? wf(i) : 0;
-        int sel = (pinned || (k != 0u && k > r.kstar)) ? 1 : 0;
-        if (__syncthreads_or(eq)) {
-            int tot_w, tot_c;
-            const int ex_w = lc_block_scan<LC_RT_THREADS>(w, sel_sh, &tot_w);
-            const int ex_c = lc_block_scan<LC_RT_THREADS>(eq, sel_sh, &tot_c);
-            if (eq && (long long)tie_w + ex_w + w <= r.remW && tie_c + ex_c + 1 <= r.remC) sel = 1;
-            tie_w += tot_w;
-            tie_c += tot_c;
-        }
-        int tot_s;
-        const int ex_s = lc_block_scan<LC_RT_THREADS>(sel, sel_sh, &tot_s);
-        if (sel && base + ex_s < a.cap) ids[base + ex_s] = i;
-        base += tot_s;
+    LC_STAMP(lc_dbg_leaf, 5);
+    // each thread owns a contiguous run of chunks: one scan for the ties, one for the output slots
+    int E = (M + LC_RT_THREADS - 1) / LC_RT_THREADS;
+    E |= 1;                                             // odd stride: no LDS bank conflicts
+    const int lo = min(M, tid * E), hi = min(M, lo + E);
+    int my_tie_w = 0, my_tie_c = 0;
+    for (int i = lo; i < hi; ++i) {
+        const uint32_t k = skey[i];
+        if (!r.all && k != 0u && k == r.kstar) { my_tie_w += slen[i]; my_tie_c += 1; }
     }
+    int tot_w, tot_c;
+    const int tie_w0 = lc_block_scan<LC_RT_THREADS>(my_tie_w, sel_sh, &tot_w);
+    const int tie_c0 = lc_block_scan<LC_RT_THREADS>(my_tie_c, sel_sh, &tot_c);
+    // selected(i): pinned, or above the cutoff key, or a tie that still fits (ties in ascending id)
+    auto walk = [&](bool emit, int pos, int32_t* ids) -> int {
+        int tw = tie_w0, tc = tie_c0, n_sel = 0;
+        for (int i = lo; i < hi; ++i) {
+            const uint32_t k = skey[i];
+            const int ln = slen[i];
+            int sel = (ln < 0) ? 1 : ((k != 0u && k > r.kstar) ? 1 : 0);
+            if (ln >= 0 && !r.all && k != 0u && k == r.kstar) {
+                tw += ln;
+                tc += 1;
+                if (tw <= r.remW && tc <= r.remC) sel = 1;
+            }
+            if (sel) {
+                if (emit && pos + n_sel < a.cap) ids[pos + n_sel] = i;
+                ++n_sel;
+            }
+        }
+        return n_sel;
+    };
+    int32_t* ids = a.ids + (size_t)bh * a.cap;
+    const int my_sel = walk(false, 0, ids);
+    int tot_s;
+    const int pos = lc_block_scan<LC_RT_THREADS>(my_sel, sel_sh, &tot_s);
+    walk(true, pos, ids);
+    LC_STAMP(lc_dbg_leaf, 6);
     if (tid == 0) {
-        a.counts[bh] = min(base, a.cap);
+        a.counts[bh] = min(tot_s, a.cap);
         ix.sync[bh * 4 + 0] = 0;                 // ready for the next call
     }
 }
@@ -292,17 +519,31 @@ lc_leaf_kernel(const LcRetrieveArgs a) {
 // launcher
 // ---------------------------------------------------------------------------------
 template <int G>
-static int launch_retrieve_g(const LcRetrieveArgs& a, int max_M, int max_upper, hipStream_t stream) {
+static int launch_retrieve_g(LcRetrieveArgs& a, int max_M, hipStream_t stream) {
     const LcDev& ix = a.ix;
+    const int mc = ((max_M + 63) / 64) * 64;
+    const size_t lds_limit = 150 * 1024;
     if (ix.L > 1) {
-        const size_t lds = (size_t)a.upper_cap * 4 + 2 * (size_t)a.upper_cap;
-        hipLaunchKernelGGL(lc_upper_kernel<G>, dim3(ix.H, ix.B), dim3(LC_RT_THREADS), lds, stream, a);
+        // internal nodes: 14 bytes each; select scratch: 8 bytes x max(UC, PC); probe list: 12 bytes each
+        const size_t uc = a.upper_cap;
+        size_t pc = mc;
+        while (pc > 64 && uc * 14 + (uc > pc ? uc : pc) * 8 + pc * 12 > lds_limit) pc -= 64;
+        a.chunk_cap = (int)pc;
+        const size_t lds = uc * 14 + (uc > pc ? uc : pc) * 8 + pc * 12;
+        if (lds > 48 * 1024)
+            LC_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&lc_upper_kernel<G>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        hipLaunchKernelGGL(lc_upper_kernel<G>, dim3(ix.H, ix.B), dim3(LC_UP_THREADS), lds, stream, a);
         LC_HIP_CHECK(hipGetLastError());
     }
+    a.chunk_cap = ((size_t)mc * 8 <= lds_limit) ? mc : 0;
+    const size_t lds2 = (size_t)a.chunk_cap * 8;
+    if (lds2 > 48 * 1024)
+        LC_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&lc_leaf_kernel<G>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2));
     const int nblk = max_M > 0 ? (max_M + LC_LEAF_CHUNKS_PER_BLOCK - 1) / LC_LEAF_CHUNKS_PER_BLOCK : 1;
-    hipLaunchKernelGGL(lc_leaf_kernel<G>, dim3(nblk, ix.H, ix.B), dim3(LC_RT_THREADS), 0, stream, a);
+    hipLaunchKernelGGL(lc_leaf_kernel<G>, dim3(nblk, ix.H, ix.B), dim3(LC_RT_THREADS), lds2, stream, a);
     LC_HIP_CHECK(hipGetLastError());
-    (void)max_upper;
     return LC_OK;
 }
 
@@ -313,10 +554,11 @@ int lc_launch_retrieve(const lc_index* idx, const LcWs& ws, const void* q, int G
     a.ix = idx->dev;
     a.q = static_cast<const uint16_t*>(q);
     a.keys = ws.keys;
-    a.kept1 = ws.kept1;
+    a.want = ws.want;
     a.scores = scores;
     a.ids = ids;
     a.counts = counts;
+    a.scratch = ws.scratch;
     a.cap = cap;
     a.budget = budget;
     a.policy = idx->cfg.policy;
@@ -324,15 +566,16 @@ int lc_launch_retrieve(const lc_index* idx, const LcWs& ws, const void* q, int G
     for (int l = 0; l < LC_MAX_LEVELS; ++l) a.beam[l] = idx->cfg.beam[l];
     a.upper_cap = ((max_upper + 63) / 64) * 64;
     if (a.upper_cap < 64) a.upper_cap = 64;
+    a.chunk_cap = 0;
     switch (G) {
-        case 1: return launch_retrieve_g<1>(a, max_M, max_upper, stream);
-        case 2: return launch_retrieve_g<2>(a, max_M, max_upper, stream);
-        case 3: return launch_retrieve_g<3>(a, max_M, max_upper, stream);
-        case 4: return launch_retrieve_g<4>(a, max_M, max_upper, stream);
-        case 5: return launch_retrieve_g<5>(a, max_M, max_upper, stream);
-        case 6: return launch_retrieve_g<6>(a, max_M, max_upper, stream);
-        case 7: return launch_retrieve_g<7>(a, max_M, max_upper, stream);
-        case 8: return launch_retrieve_g<8>(a, max_M, max_upper, stream);
+        case 1: return launch_retrieve_g<1>(a, max_M, stream);
+        case 2: return launch_retrieve_g<2>(a, max_M, stream);
+        case 3: return launch_retrieve_g<3>(a, max_M, stream);
+        case 4: return launch_retrieve_g<4>(a, max_M, stream);
+        case 5: return launch_retrieve_g<5>(a, max_M, stream);
+        case 6: return launch_retrieve_g<6>(a, max_M, stream);
+        case 7: return launch_retrieve_g<7>(a, max_M, stream);
+        case 8: return launch_retrieve_g<8>(a, max_M, stream);
     }
     return LC_ERR_BAD_SHAPE;
 }
