@@ -63,6 +63,14 @@ enum { LC_GEOMETRY_TOKEN_BALL = 0, LC_GEOMETRY_PAPER_UNIT = 1 };
  * BEAM: Algorithm 1's top-k per level (beam[l] nodes kept at level l). */
 enum { LC_POLICY_EXACT = 0, LC_POLICY_BEAM = 1 };
 
+/* EXACT only: whether the level-by-level pruning pass runs before the chunks are
+ * scored.  The selection is the same either way (it is defined as the flat scan);
+ * the pass costs a few dependent memory round trips and pays off only when the
+ * chunk level is large.  AUTO runs it when the chunk-level index of the whole
+ * batch exceeds LC_PRUNE_AUTO_BYTES.  BEAM always walks the levels. */
+enum { LC_PRUNE_AUTO = 0, LC_PRUNE_ALWAYS = 1, LC_PRUNE_NEVER = 2 };
+#define LC_PRUNE_AUTO_BYTES (32u << 20)
+
 typedef struct lc_config {
     int32_t levels;                 /* L >= 1, counts the chunk level (paper: 3)            */
     int32_t fanout;                 /* F >= 1                                               */
@@ -76,12 +84,13 @@ typedef struct lc_config {
     int32_t max_chunks;             /* capacity: closed chunks per sequence                 */
     int32_t max_tokens;             /* capacity: tokens per sequence (rows of K and V)      */
     int32_t decode_splits;          /* split-K factor of the attention kernel; 0 = auto     */
+    int32_t prune;                  /* LC_PRUNE_*                                           */
 } lc_config;
 
 typedef struct lc_index lc_index;   /* opaque host-side handle */
 
 /* Fill *cfg with defaults: levels 3, fanout 16, kmeans_iters 10, TOKEN_BALL,
- * EXACT, no beam limits, sink 0, capacities 0 (the caller must set them). */
+ * EXACT, no beam limits, sink 0, prune AUTO, capacities 0 (the caller must set them). */
 void lc_config_default(lc_config* cfg /* host */);
 
 /* Text for an error code (static storage). */
@@ -129,6 +138,8 @@ int lc_build_index(lc_index** out, const lc_config* cfg,
 /* Change the retrieval policy of an existing index (host state only). */
 int lc_set_policy(lc_index* idx, int policy, const int32_t* beam /* host, LC_MAX_LEVELS, may be NULL */,
                   int sink_tokens);
+/* Change the pruning mode (LC_PRUNE_*) of an existing index (host state only). */
+int lc_set_prune(lc_index* idx, int prune);
 
 /*
  * lc_retrieve -- hierarchical retrieval for one decode step (Eq. 2, Algorithm 1

@@ -28,6 +28,9 @@ LC_GEOMETRY_TOKEN_BALL = 0
 LC_GEOMETRY_PAPER_UNIT = 1
 LC_POLICY_EXACT = 0
 LC_POLICY_BEAM = 1
+LC_PRUNE_AUTO = 0
+LC_PRUNE_ALWAYS = 1
+LC_PRUNE_NEVER = 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("LYCHEE_LIB", os.path.join(_HERE, "liblychee.so"))
@@ -45,6 +48,7 @@ class LcConfig(ctypes.Structure):
         ("max_chunks", ctypes.c_int32),
         ("max_tokens", ctypes.c_int32),
         ("decode_splits", ctypes.c_int32),
+        ("prune", ctypes.c_int32),
     ]
 
 
@@ -86,6 +90,8 @@ def lib() -> ctypes.CDLL:
     L.lc_build_index.restype = ctypes.c_int
     L.lc_set_policy.argtypes = [vp, ctypes.c_int, i32p, ctypes.c_int]
     L.lc_set_policy.restype = ctypes.c_int
+    L.lc_set_prune.argtypes = [vp, ctypes.c_int]
+    L.lc_set_prune.restype = ctypes.c_int
     L.lc_retrieve.argtypes = [vp, vp, ctypes.c_int, ctypes.c_int, vp, vp, f32p, ctypes.c_int, vp, ctypes.c_size_t, vp]
     L.lc_retrieve.restype = ctypes.c_int
     L.lc_sparse_decode.argtypes = [vp, vp, vp, vp, i64p, vp, vp, ctypes.c_int, ctypes.c_int, vp, vp,
@@ -206,6 +212,10 @@ def lc_set_policy(idx: Index, policy: int, beam: Optional[Sequence[int]] = None,
     if beam is not None:
         arr = _i32(list(beam) + [0] * (LC_MAX_LEVELS - len(beam)))
     _check(lib().lc_set_policy(idx.handle, policy, arr, sink_tokens), "lc_set_policy")
+
+
+def lc_set_prune(idx: Index, prune: int) -> None:
+    _check(lib().lc_set_prune(idx.handle, prune), "lc_set_prune")
 
 
 def lc_retrieve(idx: Index, q, budget: int, chunk_ids, counts, ws, scores=None, stream=None) -> None:

@@ -25,6 +25,7 @@ bool config_ok(const lc_config* c) {
     if (c->max_chunks > c->max_tokens) return false;
     if (c->max_tokens > (1 << 30)) return false;
     if (c->decode_splits < 0 || c->decode_splits > 256) return false;
+    if (c->prune != LC_PRUNE_AUTO && c->prune != LC_PRUNE_ALWAYS && c->prune != LC_PRUNE_NEVER) return false;
     return true;
 }
 
@@ -77,10 +78,11 @@ size_t lc_layout_index(const lc_config* cfg, int B, int H, int d, void* base, Lc
 
 int lc_auto_splits(const lc_config* cfg, int B, int H) {
     if (cfg->decode_splits > 0) return cfg->decode_splits;
-    // aim for ~1024 workgroups over the 256 compute units
-    int s = (1024 + B * H - 1) / (B * H);
+    // one workgroup per compute unit (256): at small batch the kernel is a chain of memory
+    // round trips and every extra split lengthens the merge
+    int s = (256 + B * H - 1) / (B * H);
     if (s < 1) s = 1;
-    if (s > 64) s = 64;
+    if (s > 32) s = 32;
     return s;
 }
 
@@ -283,6 +285,13 @@ int lc_set_policy(lc_index* idx, int policy, const int32_t* beam, int sink_token
     return LC_OK;
 }
 
+int lc_set_prune(lc_index* idx, int prune) {
+    if (!idx) return LC_ERR_INVALID_ARG;
+    if (prune != LC_PRUNE_AUTO && prune != LC_PRUNE_ALWAYS && prune != LC_PRUNE_NEVER) return LC_ERR_INVALID_ARG;
+    idx->cfg.prune = prune;
+    return LC_OK;
+}
+
 int lc_index_info(const lc_index* idx, int b, int32_t* T, int32_t* M, int32_t* n_per_level) {
     if (!idx || b < 0 || b >= idx->B) return LC_ERR_INVALID_ARG;
     if (T) *T = idx->T[b];
@@ -313,9 +322,11 @@ int lc_retrieve(const lc_index* idx, const void* q, int H_q, int budget, int32_t
     if (ws_bytes < lc_layout_ws(&idx->cfg, idx->B, H_q, idx->H_kv, idx->d, splits, nullptr, nullptr))
         return LC_ERR_WORKSPACE_TOO_SMALL;
     int max_M = 0, max_upper = 0;
+    long long leaf_bytes = 0;
     for (int b = 0; b < idx->B; ++b) {
         const int M = idx->M[b];
         if (M > max_M) max_M = M;
+        leaf_bytes += (long long)M * idx->H_kv * (idx->d * 4 + 8);
         // every chunk holds >= 1 token: at most `budget` chunks fit, plus the pinned ones
         long long need = (long long)budget + idx->cfg.sink_tokens;
         if (need > M) need = M;
@@ -327,8 +338,14 @@ int lc_retrieve(const lc_index* idx, const void* q, int H_q, int budget, int32_t
     if (max_upper > 8192) return LC_ERR_CAPACITY;       // internal nodes of one (sequence, head) live in LDS
     LcWs w;
     lc_layout_ws(&idx->cfg, idx->B, H_q, idx->H_kv, idx->d, splits, ws, &w);
-    return lc_launch_retrieve(idx, w, q, H_q / idx->H_kv, budget, chunk_ids, counts, scores, cap, max_M, max_upper,
-                              static_cast<hipStream_t>(stream));
+    // walk the internal levels?  BEAM: always.  EXACT: by mode; the result does not depend on it.
+    bool walk = idx->cfg.levels > 1;
+    if (walk && idx->cfg.policy == LC_POLICY_EXACT) {
+        if (idx->cfg.prune == LC_PRUNE_NEVER) walk = false;
+        else if (idx->cfg.prune == LC_PRUNE_AUTO) walk = leaf_bytes > (long long)LC_PRUNE_AUTO_BYTES;
+    }
+    return lc_launch_retrieve(idx, w, q, H_q / idx->H_kv, budget, chunk_ids, counts, scores, cap, max_M,
+                              walk ? max_upper : -1, static_cast<hipStream_t>(stream));
 }
 
 int lc_sparse_decode(const lc_index* idx, const void* q, const void* K, const void* V, const int64_t kv_strides[3],

@@ -11,7 +11,6 @@
 
 #define LC_DEC_THREADS 256
 #define LC_DEC_GROUPS 16
-#define LC_DEC_UNROLL 4
 #define LC_DEC_MIN_TOKENS_PER_SPLIT 64
 #define LC_DEC_MAX_SPLITS 256
 #define LC_LOG2E 1.4426950408889634f
@@ -48,6 +47,9 @@ lc_decode_kernel(const LcDecodeArgs a) {
     __shared__ float mrg_hd[2 * G];
     __shared__ float4 mrg_red[LC_DEC_THREADS];
 
+    // tokens in flight per group: at small batch each group owns only a handful of tokens and the
+    // loop is one memory round trip per batch, so the batch is as deep as the registers allow
+    constexpr int LC_DEC_UNROLL = (G <= 4) ? 8 : 4;
     const LcDev& ix = a.ix;
     const int s = blockIdx.x, S = gridDim.x, h = blockIdx.y, b = blockIdx.z;
     const int bh = b * ix.H + h;
@@ -57,8 +59,15 @@ lc_decode_kernel(const LcDecodeArgs a) {
     LC_STAMP0(lc_dbg_decode, 0);
     const int* bnd = ix.bounds + (size_t)b * (ix.cap[0] + 1);
     const int32_t* ids = a.ids + (size_t)bh * a.cap;
-    // independent loads first: the id a thread will need is fetched before the count is known
+    // independent loads first: the id a thread will need is fetched before the count is known,
+    // and so are the query fragments (lane `sub` holds columns [8 sub, 8 sub + 8) of each head)
     const int id_first = (tid < a.cap) ? ids[tid] : 0;
+    uint4 qraw[G];
+    {
+        const uint16_t* qb = a.q + ((size_t)b * ix.H * G + (size_t)h * G) * LC_D;
+#pragma unroll
+        for (int g = 0; g < G; ++g) qraw[g] = *reinterpret_cast<const uint4*>(qb + g * LC_D + 8 * sub);
+    }
     const int T = ix.state[bh * 4 + 0];
     const int M = ix.state[bh * 4 + 1];
     int n_ids = a.counts[bh];
@@ -102,15 +111,12 @@ lc_decode_kernel(const LcDecodeArgs a) {
         int t = min(hi, lo + grp * per);
         const int t_end = min(hi, t + per);
 
-        // query fragments: lane `sub` holds columns [8 sub, 8 sub + 8) of each head, pre-scaled
         float qf[G][8];
         {
-            const uint16_t* qb = a.q + ((size_t)b * ix.H * G + (size_t)h * G) * LC_D;
             const float scale = 0.08838834764831845f * LC_LOG2E;     // log2(e) / sqrt(128)
 #pragma unroll
             for (int g = 0; g < G; ++g) {
-                const uint4 v = *reinterpret_cast<const uint4*>(qb + g * LC_D + 8 * sub);
-                lc_unpack8(v, qf[g]);
+                lc_unpack8(qraw[g], qf[g]);
 #pragma unroll
                 for (int i = 0; i < 8; ++i) qf[g][i] *= scale;
             }
@@ -137,6 +143,7 @@ lc_decode_kernel(const LcDecodeArgs a) {
         const uint16_t* Kb = a.K + (size_t)b * a.ks_seq + (size_t)h * a.ks_head;
         const uint16_t* Vb = a.V + (size_t)b * a.ks_seq + (size_t)h * a.ks_head;
 
+        LC_STAMP0(lc_dbg_decode, 8);
         while (t < t_end) {
             uint4 kv[LC_DEC_UNROLL], vv[LC_DEC_UNROLL];
             bool live[LC_DEC_UNROLL];
@@ -150,6 +157,7 @@ lc_decode_kernel(const LcDecodeArgs a) {
                     vv[u] = *reinterpret_cast<const uint4*>(Vb + row * a.ks_tok + 8 * sub);
                 }
             }
+            LC_STAMP0(lc_dbg_decode, 9);
             float x[LC_DEC_UNROLL][G];
 #pragma unroll
             for (int u = 0; u < LC_DEC_UNROLL; ++u) {
@@ -166,6 +174,7 @@ lc_decode_kernel(const LcDecodeArgs a) {
                     x[u][g] = live[u] ? p : LC_NEG_INF;
                 }
             }
+            LC_STAMP0(lc_dbg_decode, 10);
 #pragma unroll
             for (int g = 0; g < G; ++g) {
                 float mx = m[g];
@@ -192,6 +201,7 @@ lc_decode_kernel(const LcDecodeArgs a) {
                 }
             }
             t += LC_DEC_UNROLL;
+            LC_STAMP0(lc_dbg_decode, 11);
         }
 
         LC_STAMP0(lc_dbg_decode, 2);
@@ -279,16 +289,27 @@ lc_decode_kernel(const LcDecodeArgs a) {
     const int v = tid % NV, wy = tid / NV;
     const int g = v / (LC_D / 4), c4 = v % (LC_D / 4);
     if (wy < WAYS) {
-#pragma unroll 8
-        for (int sp = wy; sp < n_part; sp += WAYS) {
-            const float* px = pacc + ((size_t)sp * G + g) * LC_D + 4 * c4;
-            const float4 x = make_float4(lc_load_agent(px), lc_load_agent(px + 1), lc_load_agent(px + 2),
-                                         lc_load_agent(px + 3));
-            const float sc = mrg_m[sp * G + g];
-            acc4.x = fmaf(x.x, sc, acc4.x);
-            acc4.y = fmaf(x.y, sc, acc4.y);
-            acc4.z = fmaf(x.z, sc, acc4.z);
-            acc4.w = fmaf(x.w, sc, acc4.w);
+        // MR partials per round, all their loads in flight before the first is used
+        constexpr int MR = (G <= 4) ? 16 : 8;
+        for (int sp0 = wy; sp0 < n_part; sp0 += MR * WAYS) {
+            float4 x[MR];
+            float sc[MR];
+#pragma unroll
+            for (int k = 0; k < MR; ++k) {
+                const int sp = sp0 + k * WAYS;
+                const int spc = min(sp, n_part - 1);
+                const float* px = pacc + ((size_t)spc * G + g) * LC_D + 4 * c4;
+                x[k] = make_float4(lc_load_agent(px), lc_load_agent(px + 1), lc_load_agent(px + 2),
+                                   lc_load_agent(px + 3));
+                sc[k] = sp < n_part ? mrg_m[spc * G + g] : 0.f;
+            }
+#pragma unroll
+            for (int k = 0; k < MR; ++k) {
+                acc4.x = fmaf(x[k].x, sc[k], acc4.x);
+                acc4.y = fmaf(x[k].y, sc[k], acc4.y);
+                acc4.z = fmaf(x[k].z, sc[k], acc4.z);
+                acc4.w = fmaf(x[k].w, sc[k], acc4.w);
+            }
         }
         if (WAYS > 1 && wy > 0) mrg_red[(wy - 1) * NV + v] = acc4;
     }

@@ -14,7 +14,10 @@
 #define LC_STAMP0(name, i) do { if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) \
     name[i] = wall_clock64(); } while (0)
 #define LC_STAMP(name, i) do { if (blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) name[i] = wall_clock64(); } while (0)
+static __device__ unsigned long long lc_dbg_sel[32];
+#define LC_SEL_STAMP(i) do { if (blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) lc_dbg_sel[i] = wall_clock64(); } while (0)
 #else
+#define LC_SEL_STAMP(i)
 #define LC_STAMP_DECL(name)
 #define LC_STAMP0(name, i)
 #define LC_STAMP(name, i)
@@ -40,12 +43,18 @@ __device__ __forceinline__ uint16_t lc_f32_to_bf16(float f) {     // round to ne
 }
 
 // ---------------------------------------------------------------- reductions
-// Sum / max over the 16 consecutive lanes that share (lane >> 4).
+// Sum over the 16 consecutive lanes that share (lane >> 4): exactly one DPP row, so the
+// butterfly runs on the vector ALU (quad permutes, then half-row and full-row mirrors)
+// instead of going through the LDS crossbar as a generic shuffle would.
+template <int CTRL>
+__device__ __forceinline__ float lc_dpp(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
 __device__ __forceinline__ float lc_sum16(float v) {
-    v += __shfl_xor(v, 1);
-    v += __shfl_xor(v, 2);
-    v += __shfl_xor(v, 4);
-    v += __shfl_xor(v, 8);
+    v += lc_dpp<0xB1>(v);      // quad_perm [1,0,3,2]: lane ^ 1
+    v += lc_dpp<0x4E>(v);      // quad_perm [2,3,0,1]: lane ^ 2
+    v += lc_dpp<0x141>(v);     // row_half_mirror: the other quad of the same half-row
+    v += lc_dpp<0x140>(v);     // row_mirror: the other half-row
     return v;
 }
 __device__ __forceinline__ float lc_sum64(float v) {
@@ -214,36 +223,58 @@ struct LcSel {
     int all;
 };
 
-// sh: 2*256 + 8 ints of LDS.  All NT threads must call.
+// Min / max over the 64 lanes of a wave: DPP within the 16-lane rows, then two cross-row steps.
+template <int CTRL>
+__device__ __forceinline__ uint32_t lc_dpp_u(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, 0xF, 0xF, false);
+}
+__device__ __forceinline__ uint32_t lc_wave_min_u(uint32_t v) {
+    v = min(v, lc_dpp_u<0xB1>(v)); v = min(v, lc_dpp_u<0x4E>(v));
+    v = min(v, lc_dpp_u<0x141>(v)); v = min(v, lc_dpp_u<0x140>(v));
+    v = min(v, (uint32_t)__shfl_xor((int)v, 16)); v = min(v, (uint32_t)__shfl_xor((int)v, 32));
+    return v;
+}
+__device__ __forceinline__ uint32_t lc_wave_max_u(uint32_t v) {
+    v = max(v, lc_dpp_u<0xB1>(v)); v = max(v, lc_dpp_u<0x4E>(v));
+    v = max(v, lc_dpp_u<0x141>(v)); v = max(v, lc_dpp_u<0x140>(v));
+    v = max(v, (uint32_t)__shfl_xor((int)v, 16)); v = max(v, (uint32_t)__shfl_xor((int)v, 32));
+    return v;
+}
+
+// sh: LC_SEL_SH ints of LDS.  All NT threads must call.  `kmin` / `kmax`: this thread's partial
+// range of the candidate keys it has already seen (0xffffffff / 0 if none); with have_range false
+// the routine scans the keys itself.
+#define LC_SEL_SH 584
 template <int NT, typename KeyF, typename WgtF>
-__device__ __forceinline__ LcSel lc_block_select(int n, long long W, long long C, KeyF key, WgtF wgt, int* sh) {
+__device__ __forceinline__ LcSel lc_block_select(int n, long long W, long long C, KeyF key, WgtF wgt, int* sh,
+                                                 bool have_range = false, uint32_t kmin = 0xffffffffu,
+                                                 uint32_t kmax = 0u) {
     int* hw = sh;
     int* hc = sh + 256;
     int* res = sh + 512;
+    int* mm = sh + 520;                          // 2 x 32 ints, used by nothing else
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     LcSel out;
     out.all = 0;
     out.kstar = 0u;
     out.remW = 0;
     out.remC = 0;
+    LC_SEL_STAMP(0);
     // ---- range of the candidate keys
-    uint32_t kmin = 0xffffffffu, kmax = 0u;
-    for (int i = threadIdx.x; i < n; i += NT) {
-        const uint32_t k = key(i);
-        if (k != 0u) { kmin = min(kmin, k); kmax = max(kmax, k); }
+    if (!have_range) {
+        for (int i = threadIdx.x; i < n; i += NT) {
+            const uint32_t k = key(i);
+            if (k != 0u) { kmin = min(kmin, k); kmax = max(kmax, k); }
+        }
     }
-#pragma unroll
-    for (int m = 1; m < 64; m <<= 1) {
-        kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, m));
-        kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, m));
-    }
-    __syncthreads();
-    if (lane == 0) { hw[wave] = (int)kmin; hc[wave] = (int)kmax; }
+    kmin = lc_wave_min_u(kmin);
+    kmax = lc_wave_max_u(kmax);
+    if (lane == 0) { mm[wave] = (int)kmin; mm[32 + wave] = (int)kmax; }
     __syncthreads();
 #pragma unroll
-    for (int w = 0; w < NT / 64; ++w) { kmin = min(kmin, (uint32_t)hw[w]); kmax = max(kmax, (uint32_t)hc[w]); }
-    __syncthreads();
-    if (kmax == 0u) { out.all = 1; return out; }            // no candidate at all
+    for (int w = 0; w < NT / 64; ++w) { kmin = min(kmin, (uint32_t)mm[w]); kmax = max(kmax, (uint32_t)mm[32 + w]); }
+    LC_SEL_STAMP(1);
+    if (kmax == 0u) { out.all = 1; __syncthreads(); return out; }            // no candidate at all
     const uint32_t diff = kmin ^ kmax;
     int top = diff ? 32 - __clz(diff) : 0;                   // bits [0, top) may differ
     uint32_t mask = top >= 32 ? 0u : ~((1u << top) - 1u);
@@ -251,9 +282,12 @@ __device__ __forceinline__ LcSel lc_block_select(int n, long long W, long long C
     long long remW = W, remC = C;
     const bool count_c = C < 0x7fffffffLL;
     bool first = true;
+    int npass = 0;
+    (void)npass;
     while (top > 0) {
         const int width = top >= 8 ? 8 : top;
         const int shift = top - width;
+        LC_SEL_STAMP(2 + 3 * npass);
         for (int i = threadIdx.x; i < 256; i += NT) { hw[i] = 0; hc[i] = 0; }
         __syncthreads();
         for (int i = threadIdx.x; i < n; i += NT) {
@@ -265,6 +299,7 @@ __device__ __forceinline__ LcSel lc_block_select(int n, long long W, long long C
             }
         }
         __syncthreads();
+        LC_SEL_STAMP(3 + 3 * npass);
         if (threadIdx.x < 64) {
             const int l = threadIdx.x;
             int w[4], c[4];
@@ -297,6 +332,8 @@ __device__ __forceinline__ LcSel lc_block_select(int n, long long W, long long C
             }
         }
         __syncthreads();
+        LC_SEL_STAMP(4 + 3 * npass);
+        ++npass;
         const int found = res[0];
         if (found < 0) {            // everything in scope fits: only possible in the first pass
             out.all = first ? 1 : 0;

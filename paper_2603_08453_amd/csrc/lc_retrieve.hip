@@ -21,12 +21,17 @@
 
 #define LC_RT_THREADS 256
 #define LC_RT_GROUPS (LC_RT_THREADS / 16)
-#define LC_LEAF_CHUNKS_PER_BLOCK 32
+#define LC_LEAF_CHUNKS_PER_BLOCK 64
 #define LC_TAU_SLACK 1e-3f
 #define LC_COUNT_SELECT_MAX 1024         // up to this many candidates the O(n^2 / threads) rank is used
 
 LC_STAMP_DECL(lc_dbg_upper)
 LC_STAMP_DECL(lc_dbg_leaf)
+#ifdef LC_DBG_TIMES
+extern "C" int lc_dbg_sel_read(unsigned long long* host) {
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(lc_dbg_sel), sizeof(lc_dbg_sel));
+}
+#endif
 
 struct LcRetrieveArgs {
     LcDev ix;
@@ -43,6 +48,7 @@ struct LcRetrieveArgs {
     int sink;
     int beam[LC_MAX_LEVELS];
     int upper_cap;           // LDS entries for internal nodes
+    int walk;                // 1 = the internal levels were walked and `want` is valid
     int chunk_cap;           // upper kernel: LDS entries of the probe list; leaf kernel: LDS entries for
                              // the select's staging, 0 = stage in `scratch` (global memory)
 };
@@ -104,7 +110,7 @@ template <int G>
 __global__ void __launch_bounds__(LC_UP_THREADS)
 lc_upper_kernel(const LcRetrieveArgs a) {
     extern __shared__ int lds_dyn[];
-    __shared__ int sel_sh[520];
+    __shared__ int sel_sh[LC_SEL_SH];
     __shared__ int off_sh[LC_MAX_LEVELS + 1];
     constexpr int NB = (G <= 4) ? 4 : 2;          // nodes in flight per group
 
@@ -379,11 +385,15 @@ lc_upper_kernel(const LcRetrieveArgs a) {
 // ---------------------------------------------------------------------------------
 // kernel 2: chunk scoring + budget selection by the last workgroup
 // ---------------------------------------------------------------------------------
+// 1024 threads = 64 groups: one chunk per group while scoring; the last workgroup has
+// enough threads to hold a few keys each during the select.
+#define LC_LF_THREADS 1024
+#define LC_LF_GROUPS (LC_LF_THREADS / 16)
 template <int G>
-__global__ void __launch_bounds__(LC_RT_THREADS)
+__global__ void __launch_bounds__(LC_LF_THREADS)
 lc_leaf_kernel(const LcRetrieveArgs a) {
     extern __shared__ int lds_dyn[];
-    __shared__ int sel_sh[520];
+    __shared__ int sel_sh[LC_SEL_SH];
     __shared__ int last_sh;
 
     const LcDev& ix = a.ix;
@@ -396,17 +406,17 @@ lc_leaf_kernel(const LcRetrieveArgs a) {
     uint32_t* keys = a.keys + cb;
     float* scores = a.scores ? a.scores + cb : nullptr;
     const uint8_t* want = a.want + cb;
-    const bool have_want = ix.L > 1;
+    const bool have_want = a.walk != 0;
 
     LC_STAMP0(lc_dbg_leaf, 0);
     // loads that do not depend on M are issued together with it (the arrays are cap0 long)
     const int j_lo = blockIdx.x * LC_LEAF_CHUNKS_PER_BLOCK;
-    int jj[LC_LEAF_CHUNKS_PER_BLOCK / LC_RT_GROUPS];
-    int wv[LC_LEAF_CHUNKS_PER_BLOCK / LC_RT_GROUPS];
-    float rv[LC_LEAF_CHUNKS_PER_BLOCK / LC_RT_GROUPS];
+    int jj[LC_LEAF_CHUNKS_PER_BLOCK / LC_LF_GROUPS];
+    int wv[LC_LEAF_CHUNKS_PER_BLOCK / LC_LF_GROUPS];
+    float rv[LC_LEAF_CHUNKS_PER_BLOCK / LC_LF_GROUPS];
 #pragma unroll
-    for (int r = 0; r < LC_LEAF_CHUNKS_PER_BLOCK / LC_RT_GROUPS; ++r) {
-        const int j = min(j_lo + r * LC_RT_GROUPS + grp, ix.cap[0] - 1);
+    for (int r = 0; r < LC_LEAF_CHUNKS_PER_BLOCK / LC_LF_GROUPS; ++r) {
+        const int j = min(j_lo + r * LC_LF_GROUPS + grp, ix.cap[0] - 1);
         jj[r] = j;
         wv[r] = have_want ? (int)want[j] : (bnd[j] >= a.sink ? 1 : 0);
         rv[r] = ix.radius[0][cb + j];
@@ -418,23 +428,23 @@ lc_leaf_kernel(const LcRetrieveArgs a) {
         if (a.budget > 0) {
             float qf[G][8], qn[G];
             lc_load_query_frags<G>(a.q + (size_t)b * ix.H * G * LC_D, h, sub, qf, qn);
-            float sv[LC_LEAF_CHUNKS_PER_BLOCK / LC_RT_GROUPS];
+            float sv[LC_LEAF_CHUNKS_PER_BLOCK / LC_LF_GROUPS];
 #pragma unroll
-            for (int r = 0; r < LC_LEAF_CHUNKS_PER_BLOCK / LC_RT_GROUPS; ++r) {
-                const int j = j_lo + r * LC_RT_GROUPS + grp;
+            for (int r = 0; r < LC_LEAF_CHUNKS_PER_BLOCK / LC_LF_GROUPS; ++r) {
+                const int j = j_lo + r * LC_LF_GROUPS + grp;
                 sv[r] = LC_NEG_INF;
                 if (j < M && wv[r]) sv[r] = lc_score_node<G>(ix.center[0] + (cb + jj[r]) * LC_D, rv[r], sub, qf, qn);
             }
 #pragma unroll
-            for (int r = 0; r < LC_LEAF_CHUNKS_PER_BLOCK / LC_RT_GROUPS; ++r) {
-                const int j = j_lo + r * LC_RT_GROUPS + grp;
+            for (int r = 0; r < LC_LEAF_CHUNKS_PER_BLOCK / LC_LF_GROUPS; ++r) {
+                const int j = j_lo + r * LC_LF_GROUPS + grp;
                 if (j < M && sub == 0) {
                     lc_store_agent(&keys[j], lc_score_key(sv[r]));
                     if (scores) scores[j] = sv[r];
                 }
             }
         } else {
-            for (int j = j_lo + tid; j < min(M, j_lo + LC_LEAF_CHUNKS_PER_BLOCK); j += LC_RT_THREADS) {
+            for (int j = j_lo + tid; j < min(M, j_lo + LC_LEAF_CHUNKS_PER_BLOCK); j += LC_LF_THREADS) {
                 lc_store_agent(&keys[j], 0u);
                 if (scores) scores[j] = LC_NEG_INF;
             }
@@ -457,11 +467,14 @@ lc_leaf_kernel(const LcRetrieveArgs a) {
         skey = reinterpret_cast<uint32_t*>(g);
         slen = g + ix.cap[0];
     }
+    uint32_t kmin = 0xffffffffu, kmax = 0u;
 #pragma unroll 4
-    for (int j = tid; j < M; j += LC_RT_THREADS) {
+    for (int j = tid; j < M; j += LC_LF_THREADS) {
         const int s0 = bnd[j], s1 = bnd[j + 1];
-        skey[j] = lc_load_agent(&keys[j]);
+        const uint32_t k = lc_load_agent(&keys[j]);
+        skey[j] = k;
         slen[j] = (s0 < a.sink) ? -1 : (s1 - s0);
+        if (k != 0u) { kmin = min(kmin, k); kmax = max(kmax, k); }
     }
     __syncthreads();
 
@@ -469,11 +482,12 @@ lc_leaf_kernel(const LcRetrieveArgs a) {
     auto keyf = [&](int i) -> uint32_t { return skey[i]; };
     auto wf = [&](int i) -> int { return slen[i]; };
     const long long C = (a.policy == LC_POLICY_BEAM && a.beam[0] > 0) ? a.beam[0] : 0x7fffffffLL;
-    const LcSel r = lc_block_select<LC_RT_THREADS>(M, a.budget > 0 ? (long long)a.budget : 0LL, C, keyf, wf, sel_sh);
+    const LcSel r = lc_block_select<LC_LF_THREADS>(M, a.budget > 0 ? (long long)a.budget : 0LL, C, keyf, wf, sel_sh,
+                                                   true, kmin, kmax);
 
     LC_STAMP(lc_dbg_leaf, 5);
     // each thread owns a contiguous run of chunks: one scan for the ties, one for the output slots
-    int E = (M + LC_RT_THREADS - 1) / LC_RT_THREADS;
+    int E = (M + LC_LF_THREADS - 1) / LC_LF_THREADS;
     E |= 1;                                             // odd stride: no LDS bank conflicts
     const int lo = min(M, tid * E), hi = min(M, lo + E);
     int my_tie_w = 0, my_tie_c = 0;
@@ -481,9 +495,12 @@ lc_leaf_kernel(const LcRetrieveArgs a) {
         const uint32_t k = skey[i];
         if (!r.all && k != 0u && k == r.kstar) { my_tie_w += slen[i]; my_tie_c += 1; }
     }
+    // tie prefixes in ascending id: weights always, counts only when a count limit is set
     int tot_w, tot_c;
-    const int tie_w0 = lc_block_scan<LC_RT_THREADS>(my_tie_w, sel_sh, &tot_w);
-    const int tie_c0 = lc_block_scan<LC_RT_THREADS>(my_tie_c, sel_sh, &tot_c);
+    int tie_w0, tie_c0;
+    tie_w0 = lc_block_scan<LC_LF_THREADS>(my_tie_w, sel_sh, &tot_w);
+    if (C < 0x7fffffffLL) tie_c0 = lc_block_scan<LC_LF_THREADS>(my_tie_c, sel_sh, &tot_c);
+    else tie_c0 = 0;                     // no count limit: remC is "infinite", the count never binds
     // selected(i): pinned, or above the cutoff key, or a tie that still fits (ties in ascending id)
     auto walk = [&](bool emit, int pos, int32_t* ids) -> int {
         int tw = tie_w0, tc = tie_c0, n_sel = 0;
@@ -506,7 +523,7 @@ lc_leaf_kernel(const LcRetrieveArgs a) {
     int32_t* ids = a.ids + (size_t)bh * a.cap;
     const int my_sel = walk(false, 0, ids);
     int tot_s;
-    const int pos = lc_block_scan<LC_RT_THREADS>(my_sel, sel_sh, &tot_s);
+    const int pos = lc_block_scan<LC_LF_THREADS>(my_sel, sel_sh, &tot_s);
     walk(true, pos, ids);
     LC_STAMP(lc_dbg_leaf, 6);
     if (tid == 0) {
@@ -523,7 +540,7 @@ static int launch_retrieve_g(LcRetrieveArgs& a, int max_M, hipStream_t stream) {
     const LcDev& ix = a.ix;
     const int mc = ((max_M + 63) / 64) * 64;
     const size_t lds_limit = 150 * 1024;
-    if (ix.L > 1) {
+    if (a.walk) {
         // internal nodes: 14 bytes each; select scratch: 8 bytes x max(UC, PC); probe list: 12 bytes each
         const size_t uc = a.upper_cap;
         size_t pc = mc;
@@ -542,7 +559,7 @@ static int launch_retrieve_g(LcRetrieveArgs& a, int max_M, hipStream_t stream) {
         LC_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&lc_leaf_kernel<G>),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2));
     const int nblk = max_M > 0 ? (max_M + LC_LEAF_CHUNKS_PER_BLOCK - 1) / LC_LEAF_CHUNKS_PER_BLOCK : 1;
-    hipLaunchKernelGGL(lc_leaf_kernel<G>, dim3(nblk, ix.H, ix.B), dim3(LC_RT_THREADS), lds2, stream, a);
+    hipLaunchKernelGGL(lc_leaf_kernel<G>, dim3(nblk, ix.H, ix.B), dim3(LC_LF_THREADS), lds2, stream, a);
     LC_HIP_CHECK(hipGetLastError());
     return LC_OK;
 }
@@ -564,6 +581,8 @@ int lc_launch_retrieve(const lc_index* idx, const LcWs& ws, const void* q, int G
     a.policy = idx->cfg.policy;
     a.sink = idx->cfg.sink_tokens;
     for (int l = 0; l < LC_MAX_LEVELS; ++l) a.beam[l] = idx->cfg.beam[l];
+    a.walk = (max_upper >= 0 && idx->cfg.levels > 1) ? 1 : 0;
+    if (max_upper < 0) max_upper = 0;
     a.upper_cap = ((max_upper + 63) / 64) * 64;
     if (a.upper_cap < 64) a.upper_cap = 64;
     a.chunk_cap = 0;

@@ -63,7 +63,7 @@ class Case:
 def make_case(w: wl.Workload, tails: Optional[Sequence[int]] = None, extra_tokens: int = 0,
               extra_chunks: int = 0, geometry: int = orc.TOKEN_BALL, build_on: str = "oracle",
               offset_std: float = 0.5, noise_std: float = 1.0, cap: Optional[int] = None,
-              decode_splits: int = 0) -> Case:
+              decode_splits: int = 0, prune: int = 1) -> Case:
     """build_on = "oracle": the oracle builds the index and the GPU imports it (identical
     stored values on both sides); "gpu": lc_build_index builds it (the oracle index is still
     built for comparison)."""
@@ -84,7 +84,8 @@ def make_case(w: wl.Workload, tails: Optional[Sequence[int]] = None, extra_token
     Mmax = max(len(s.bounds) - 1 for s in seqs)
     Tcap = Tmax + extra_tokens
     cfg = lc.lc_config_default(levels=w.levels, fanout=w.fanout, geometry=geometry,
-                               max_chunks=Mmax + extra_chunks, max_tokens=Tcap, decode_splits=decode_splits)
+                               max_chunks=Mmax + extra_chunks, max_tokens=Tcap, decode_splits=decode_splits,
+                               prune=prune)      # default 1 = always walk the levels, so the pruning path is what is tested
     oidx = [[orc.build_index(wl.bf16_bits_to_f64(s.K[h]), s.bounds, s.T, w.levels, w.fanout, geometry=geometry)
              for h in range(w.H_kv)] for s in seqs]
 

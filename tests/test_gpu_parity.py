@@ -220,6 +220,20 @@ def test_pruning_happens_and_stays_exact(G):
     assert np.all(scored < M)
 
 
+def test_prune_modes_give_the_same_ids(G, c1):
+    """The level walk is an optimisation of EXACT retrieval: always / never / auto agree bit for bit."""
+    from paper_2603_08453_amd import binding as lc
+    qb = _q_batch(c1, 0)
+    got = []
+    for mode in (lc.LC_PRUNE_ALWAYS, lc.LC_PRUNE_NEVER, lc.LC_PRUNE_AUTO):
+        lc.lc_set_prune(c1.idx, mode)
+        ids, _, _ = G.gpu_retrieve(c1, qb, 777)
+        got.append(ids)
+    lc.lc_set_prune(c1.idx, lc.LC_PRUNE_ALWAYS)
+    for h in range(8):
+        assert got[0][0][h].tolist() == got[1][0][h].tolist() == got[2][0][h].tolist()
+
+
 def test_split_count_does_not_change_the_result(G):
     w = wl.tiny("splits", levels=2, fanout=4, T=3000, chunk_lo=4, chunk_hi=32, budget=1500)
     outs = []

@@ -34,7 +34,7 @@ def test_config_struct_matches_header(L):
     cfg = lc.lc_config_default()
     assert (cfg.levels, cfg.fanout, cfg.kmeans_iters) == (3, 16, 10)
     assert cfg.geometry == lc.LC_GEOMETRY_TOKEN_BALL and cfg.policy == lc.LC_POLICY_EXACT
-    assert ctypes.sizeof(lc.LcConfig) == 4 * (5 + lc.LC_MAX_LEVELS + 4)
+    assert ctypes.sizeof(lc.LcConfig) == 4 * (5 + lc.LC_MAX_LEVELS + 5)
     hdr = open(os.path.join(ROOT, "include", "lychee.h")).read()
     assert f"#define LC_MAX_LEVELS {lc.LC_MAX_LEVELS}" in hdr
     assert f"#define LC_MAX_GROUP {lc.LC_MAX_GROUP}" in hdr
