@@ -42,8 +42,9 @@ def parse():
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
-    ap.add_argument("--profile-only", action="store_true",
-                    help="skip the CPU baseline and the eager/graph comparison (for rocprofv3 runs)")
+    ap.add_argument("--pmc-mode", action="store_true",
+                    help="for rocprofv3 --pmc runs: eager steps only, then a plain device copy of known size "
+                         "(2 x 256 MiB) that calibrates the byte counters")
     return ap.parse_args()
 
 
@@ -163,6 +164,15 @@ def main():
         step(i)
     torch.cuda.synchronize()
     eager_s = timed(step, args.steps)
+    if args.pmc_mode:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"pmc_mode": True, "eager_us": round(eager_s * 1e6, 2), "calibration_copy_bytes": 256 << 20,
+                          "attend_bytes": round(attend_bytes), "retrieve_bytes": round(retrieve_bytes)}), flush=True)
+        return
 
     # HIP graphs: launch overhead out of the way.  K steps = full graphs of `unit` steps + one remainder graph.
     side = torch.cuda.Stream()
@@ -231,6 +241,30 @@ def main():
         torch.cuda.synchronize()
         retrieve_us = float(np.mean([e0.elapsed_time(e1) for e0, e1 in ev])) * 1e3
 
+    # the same step with the level-by-level walk forced on (EXACT: same ids, more kernels), and with the
+    # paper's per-level top-k (BEAM: 4 nodes kept at each internal level but 16 at level 1)
+    walk_us = beam_us = None
+    if graph_s is not None and args.policy == "exact" and w.levels > 1:
+        try:
+            for rp in reps:
+                lc.lc_set_prune(rp["idx"], lc.LC_PRUNE_ALWAYS)
+            _, t_walk = graph_us_per_launch(step, args.steps)
+            walk_us = t_walk * 1e6
+            beam = [0] * lc.LC_MAX_LEVELS
+            for l in range(1, w.levels):
+                beam[l] = 4 if l >= 2 else 16
+            for rp in reps:
+                lc.lc_set_policy(rp["idx"], lc.LC_POLICY_BEAM, beam, 0)
+            _, t_beam = graph_us_per_launch(step, args.steps)
+            beam_us = t_beam * 1e6
+        finally:
+            for rp in reps:
+                lc.lc_set_policy(rp["idx"], lc.LC_POLICY_EXACT, None, 0)
+                lc.lc_set_prune(rp["idx"], lc.LC_PRUNE_AUTO)
+            for i in range(nq):
+                retrieve(i)
+            torch.cuda.synchronize()
+
     # warm (cache-resident) figure: one replica, one query
     def step_warm(i):
         rp = reps[0]
@@ -258,7 +292,7 @@ def main():
 
     # ------------------------------------------------------------- CPU baseline (the oracle, as it stands)
     cpu = None
-    if not (args.no_cpu_baseline or args.profile_only):
+    if not args.no_cpu_baseline:
         from oracle import lychee_oracle as orc
         try:
             from threadpoolctl import threadpool_info
@@ -292,6 +326,9 @@ def main():
                          f"{len(heads)} of {w.H_kv} KV heads, scaled to {w.B} sequence(s) x {w.H_kv} heads; "
                          f"oracle index build {cpu_build_s:.1f} s per (sequence, head), not included"}
 
+    from paper_2603_08453_amd.profsum import read_traffic
+    traffic = read_traffic(os.path.join(ROOT, "profiles", f"lc_decode_step_{w.name}_hbm_traffic.md"),
+                           f"lc_decode_kernel<{G}>")
     res = {
         "metric": "us per decode step per layer (retrieve+attend), 128K ctx" if w.name.startswith("C3") else
                   "us per decode step per layer (retrieve+attend)",
@@ -313,13 +350,15 @@ def main():
         "roofline": {"bound": "hbm", "achieved": round(attend_bytes / (attend_us * 1e-6) / 1e9, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(attend_bytes / (attend_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
-                     "traffic": None, "kernel": "lc_decode_kernel",
+                     "traffic": traffic, "kernel": "lc_decode_kernel",
                      "bytes_per_launch": round(attend_bytes), "us_per_launch": round(attend_us, 2)},
         "cpu_baseline": cpu,
         "extra": {
             "eager_us": round(eager_s * 1e6, 2),
             "graph_us": None if graph_s is None else round(graph_s * 1e6, 2),
             "warm_cache_us": round(warm_s * 1e6, 2),
+            "level_walk_forced_us": None if walk_us is None else round(walk_us, 2),
+            "beam_policy_us": None if beam_us is None else round(beam_us, 2),
             "retrieve_us_event": round(retrieve_us, 2),
             "attend_us_event": round(attend_us, 2),
             "append_us": round(append_us, 2),

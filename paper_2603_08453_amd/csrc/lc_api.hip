@@ -78,9 +78,9 @@ size_t lc_layout_index(const lc_config* cfg, int B, int H, int d, void* base, Lc
 
 int lc_auto_splits(const lc_config* cfg, int B, int H) {
     if (cfg->decode_splits > 0) return cfg->decode_splits;
-    // one workgroup per compute unit (256): at small batch the kernel is a chain of memory
+    // about two workgroups per compute unit (512 in all): at small batch the kernel is a chain of memory
     // round trips and every extra split lengthens the merge
-    int s = (256 + B * H - 1) / (B * H);
+    int s = (512 + B * H - 1) / (B * H);
     if (s < 1) s = 1;
     if (s > 32) s = 32;
     return s;

@@ -13,6 +13,7 @@
 #define LC_DEC_GROUPS 16
 #define LC_DEC_MIN_TOKENS_PER_SPLIT 64
 #define LC_DEC_MAX_SPLITS 256
+#define LC_DEC_TILE 2048          // tokens of a split whose cache rows are resolved into LDS at a time
 #define LC_LOG2E 1.4426950408889634f
 #define LC_LN2 0.6931471805599453f
 
@@ -39,17 +40,18 @@ __global__ void __launch_bounds__(LC_DEC_THREADS)
 lc_decode_kernel(const LcDecodeArgs a) {
     extern __shared__ int lds_dyn[];
     __shared__ int scan_sh[8];
+    __shared__ int rows[LC_DEC_TILE];
     __shared__ int last_sh;
     __shared__ float comb_ml[LC_DEC_THREADS / 64][G][2];
-    __shared__ float comb_acc[LC_DEC_THREADS / 64][G][LC_D];
+    __shared__ __attribute__((aligned(16))) float comb_acc[LC_DEC_THREADS / 64][G][LC_D];
     __shared__ float mrg_m[LC_DEC_MAX_SPLITS * G];
     __shared__ float mrg_l[LC_DEC_MAX_SPLITS * G];
     __shared__ float mrg_hd[2 * G];
     __shared__ float4 mrg_red[LC_DEC_THREADS];
 
-    // tokens in flight per group: at small batch each group owns only a handful of tokens and the
-    // loop is one memory round trip per batch, so the batch is as deep as the registers allow
-    constexpr int LC_DEC_UNROLL = (G <= 4) ? 8 : 4;
+    // tokens per batch of loads; two batches are in flight per group (the next one is issued
+    // before the current one is consumed)
+    constexpr int U = (G <= 4) ? 4 : 2;
     const LcDev& ix = a.ix;
     const int s = blockIdx.x, S = gridDim.x, h = blockIdx.y, b = blockIdx.z;
     const int bh = b * ix.H + h;
@@ -106,11 +108,6 @@ lc_decode_kernel(const LcDecodeArgs a) {
     if (s < S_eff) {
         const int lo = (int)(((long long)n_tok * s) / S_eff);
         const int hi = (int)(((long long)n_tok * (s + 1)) / S_eff);
-        // this group's contiguous slice of [lo, hi)
-        const int per = (hi - lo + LC_DEC_GROUPS - 1) / LC_DEC_GROUPS;
-        int t = min(hi, lo + grp * per);
-        const int t_end = min(hi, t + per);
-
         float qf[G][8];
         {
             const float scale = 0.08838834764831845f * LC_LOG2E;     // log2(e) / sqrt(128)
@@ -129,57 +126,45 @@ lc_decode_kernel(const LcDecodeArgs a) {
 #pragma unroll
             for (int i = 0; i < 8; ++i) acc[g][i] = 0.f;
         }
-
-        // locate the run holding token t (largest r with run_off[r] <= t)
-        int r = 0;
-        if (t < t_end) {
-            int lo_r = 0, hi_r = n_runs;            // run_off[lo_r] <= t < run_off[hi_r]
-            while (hi_r - lo_r > 1) {
-                const int mid = (lo_r + hi_r) >> 1;
-                if (run_off[mid] <= t) lo_r = mid; else hi_r = mid;
-            }
-            r = lo_r;
-        }
         const uint16_t* Kb = a.K + (size_t)b * a.ks_seq + (size_t)h * a.ks_head;
         const uint16_t* Vb = a.V + (size_t)b * a.ks_seq + (size_t)h * a.ks_head;
 
-        LC_STAMP0(lc_dbg_decode, 8);
-        while (t < t_end) {
-            uint4 kv[LC_DEC_UNROLL], vv[LC_DEC_UNROLL];
-            bool live[LC_DEC_UNROLL];
+        // K and V rows of up to U tokens starting at position tt of the tile, all loads issued at once
+        int t_end = 0;
+        auto issue = [&](int tt, uint4 (&kv)[U], uint4 (&vv)[U]) {
 #pragma unroll
-            for (int u = 0; u < LC_DEC_UNROLL; ++u) {
-                live[u] = (t + u) < t_end;
-                if (live[u]) {
-                    while (run_off[r + 1] <= t + u) ++r;      // empty runs are skipped too
-                    const long long row = run_start[r] + (t + u - run_off[r]);
+            for (int u = 0; u < U; ++u) {
+                if (tt + u < t_end) {
+                    const long long row = rows[tt + u];
                     kv[u] = *reinterpret_cast<const uint4*>(Kb + row * a.ks_tok + 8 * sub);
                     vv[u] = *reinterpret_cast<const uint4*>(Vb + row * a.ks_tok + 8 * sub);
                 }
             }
-            LC_STAMP0(lc_dbg_decode, 9);
-            float x[LC_DEC_UNROLL][G];
+        };
+        // logits of the U tokens for the G heads, one online-softmax update, then P.V
+        auto consume = [&](int tt, const uint4 (&kv)[U], const uint4 (&vv)[U]) {
+            float x[U][G];
 #pragma unroll
-            for (int u = 0; u < LC_DEC_UNROLL; ++u) {
+            for (int u = 0; u < U; ++u) {
+                const bool live = tt + u < t_end;
                 float kf[8];
-                if (live[u]) lc_unpack8(kv[u], kf);
+                if (live) lc_unpack8(kv[u], kf);
 #pragma unroll
                 for (int g = 0; g < G; ++g) {
                     float p = 0.f;
-                    if (live[u]) {
+                    if (live) {
 #pragma unroll
                         for (int i = 0; i < 8; ++i) p = fmaf(kf[i], qf[g][i], p);
                     }
                     p = lc_sum16(p);
-                    x[u][g] = live[u] ? p : LC_NEG_INF;
+                    x[u][g] = live ? p : LC_NEG_INF;
                 }
             }
-            LC_STAMP0(lc_dbg_decode, 10);
 #pragma unroll
             for (int g = 0; g < G; ++g) {
                 float mx = m[g];
 #pragma unroll
-                for (int u = 0; u < LC_DEC_UNROLL; ++u) mx = fmaxf(mx, x[u][g]);
+                for (int u = 0; u < U; ++u) mx = fmaxf(mx, x[u][g]);
                 const float sc = exp2f(m[g] - mx);          // m = -inf, mx finite: 0
                 m[g] = mx;
                 l[g] *= sc;
@@ -187,8 +172,8 @@ lc_decode_kernel(const LcDecodeArgs a) {
                 for (int i = 0; i < 8; ++i) acc[g][i] *= sc;
             }
 #pragma unroll
-            for (int u = 0; u < LC_DEC_UNROLL; ++u) {
-                if (live[u]) {
+            for (int u = 0; u < U; ++u) {
+                if (tt + u < t_end) {
                     float vf[8];
                     lc_unpack8(vv[u], vf);
 #pragma unroll
@@ -200,8 +185,39 @@ lc_decode_kernel(const LcDecodeArgs a) {
                     }
                 }
             }
-            t += LC_DEC_UNROLL;
-            LC_STAMP0(lc_dbg_decode, 11);
+        };
+
+        LC_STAMP0(lc_dbg_decode, 8);
+        // The split's tokens are handled in tiles; for each tile the workgroup first writes the cache
+        // row of every token into LDS (one binary search over the run table per token, in parallel),
+        // then every group streams a contiguous slice of the tile with two batches of loads in flight.
+        for (int tile0 = lo; tile0 < hi; tile0 += LC_DEC_TILE) {
+            const int tl = min(LC_DEC_TILE, hi - tile0);
+            __syncthreads();
+            for (int i = tid; i < tl; i += LC_DEC_THREADS) {
+                const int tok = tile0 + i;
+                int lo_r = 0, hi_r = n_runs;            // run_off[lo_r] <= tok < run_off[hi_r]
+                while (hi_r - lo_r > 1) {
+                    const int mid = (lo_r + hi_r) >> 1;
+                    if (run_off[mid] <= tok) lo_r = mid; else hi_r = mid;
+                }
+                rows[i] = run_start[lo_r] + (tok - run_off[lo_r]);
+            }
+            __syncthreads();
+            const int per = (tl + LC_DEC_GROUPS - 1) / LC_DEC_GROUPS;
+            int t = min(tl, grp * per);
+            t_end = min(tl, t + per);
+            uint4 kA[U], vA[U], kB[U], vB[U];
+            if (t < t_end) issue(t, kA, vA);
+            while (t < t_end) {
+                if (t + U < t_end) issue(t + U, kB, vB);
+                consume(t, kA, vA);
+                t += U;
+                if (t >= t_end) break;
+                if (t + U < t_end) issue(t + U, kA, vA);
+                consume(t, kB, vB);
+                t += U;
+            }
         }
 
         LC_STAMP0(lc_dbg_decode, 2);
@@ -233,23 +249,27 @@ lc_decode_kernel(const LcDecodeArgs a) {
             }
         }
         __syncthreads();
-        float* pacc = a.part_acc + ((size_t)bh * S + s) * G * LC_D;
+        // one float4 slot of the split's partial per thread, stored at agent scope
         float* pml = a.part_ml + ((size_t)bh * S + s) * G * 2;
-        for (int e = tid; e < G * LC_D; e += LC_DEC_THREADS) {
-            const int g = e / LC_D, c = e % LC_D;
+        const __amdgpu_buffer_rsrc_t pacc_w = lc_buffer(a.part_acc + ((size_t)bh * S + s) * G * LC_D);
+        for (int v = tid; v < G * (LC_D / 4); v += LC_DEC_THREADS) {
+            const int g = v / (LC_D / 4), c4 = v % (LC_D / 4);
             float mx = LC_NEG_INF;
 #pragma unroll
             for (int w = 0; w < LC_DEC_THREADS / 64; ++w) mx = fmaxf(mx, comb_ml[w][g][0]);
-            float num = 0.f, den = 0.f;
+            float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
+            float den = 0.f;
 #pragma unroll
             for (int w = 0; w < LC_DEC_THREADS / 64; ++w) {
                 const float mw = comb_ml[w][g][0];
                 const float sc = (mw == LC_NEG_INF) ? 0.f : exp2f(mw - mx);
-                num = fmaf(comb_acc[w][g][c], sc, num);
+                const float4 x = *reinterpret_cast<const float4*>(&comb_acc[w][g][4 * c4]);
+                num.x = fmaf(x.x, sc, num.x); num.y = fmaf(x.y, sc, num.y);
+                num.z = fmaf(x.z, sc, num.z); num.w = fmaf(x.w, sc, num.w);
                 den = fmaf(comb_ml[w][g][1], sc, den);
             }
-            lc_store_agent(&pacc[e], num);
-            if (c == 0) { lc_store_agent(&pml[2 * g], mx); lc_store_agent(&pml[2 * g + 1], den); }
+            lc_store_agent4(pacc_w, v * 16, num);
+            if (c4 == 0) { lc_store_agent(&pml[2 * g], mx); lc_store_agent(&pml[2 * g + 1], den); }
         }
     }
 
@@ -259,7 +279,7 @@ lc_decode_kernel(const LcDecodeArgs a) {
 
     LC_STAMP(lc_dbg_decode, 4);
     // partial (m, l) of every split -> LDS; per head: global max, scale of each split, denominator
-    const float* pacc = a.part_acc + (size_t)bh * S * G * LC_D;
+    const __amdgpu_buffer_rsrc_t pacc_r = lc_buffer(a.part_acc + (size_t)bh * S * G * LC_D);
     const float* pml = a.part_ml + (size_t)bh * S * G * 2;
     const int n_part = (n_tok > 0) ? S_eff : 0;
     for (int e = tid; e < n_part * G; e += LC_DEC_THREADS) {
@@ -298,9 +318,7 @@ lc_decode_kernel(const LcDecodeArgs a) {
             for (int k = 0; k < MR; ++k) {
                 const int sp = sp0 + k * WAYS;
                 const int spc = min(sp, n_part - 1);
-                const float* px = pacc + ((size_t)spc * G + g) * LC_D + 4 * c4;
-                x[k] = make_float4(lc_load_agent(px), lc_load_agent(px + 1), lc_load_agent(px + 2),
-                                   lc_load_agent(px + 3));
+                x[k] = lc_load_agent4(pacc_r, ((spc * G + g) * LC_D + 4 * c4) * 4);
                 sc[k] = sp < n_part ? mrg_m[spc * G + g] : 0.f;
             }
 #pragma unroll

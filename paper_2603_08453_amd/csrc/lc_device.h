@@ -74,8 +74,8 @@ __device__ __forceinline__ float lc_max64(float v) {
 // which costs tens of microseconds when hundreds of workgroups do it.  Instead the
 // hand-off data itself is stored and loaded at agent scope (relaxed atomics: the
 // accesses are performed at the device-coherent level and leave no dirty L2 lines),
-// the producer waits for its stores to complete (workgroup-scope release = s_waitcnt)
-// before it bumps the arrival counter, and the consumer reads only after it has seen
+// the producer waits for its stores to complete (s_waitcnt vmcnt(0)) before it bumps the
+// arrival counter, and the consumer reads only after it has seen
 // the final count.
 __device__ __forceinline__ void lc_store_agent(float* p, float v) {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -89,9 +89,29 @@ __device__ __forceinline__ float lc_load_agent(const float* p) {
 __device__ __forceinline__ uint32_t lc_load_agent(const uint32_t* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+// 16-byte versions through buffer instructions with the agent-scope cache policy (sc1).
+typedef int lc_v4i __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t lc_buffer(const void* base) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, 0x7fffffff, 0x00020000);
+}
+__device__ __forceinline__ float4 lc_load_agent4(__amdgpu_buffer_rsrc_t r, int byte_offset) {
+    const lc_v4i v = __builtin_amdgcn_raw_buffer_load_b128(r, byte_offset, 0, 16);
+    const int x = v.x, y = v.y, z = v.z, w = v.w;         // element values first, then reinterpret
+    return make_float4(__int_as_float(x), __int_as_float(y), __int_as_float(z), __int_as_float(w));
+}
+__device__ __forceinline__ void lc_store_agent4(__amdgpu_buffer_rsrc_t r, int byte_offset, float4 f) {
+    lc_v4i v;
+    v.x = __float_as_int(f.x); v.y = __float_as_int(f.y);
+    v.z = __float_as_int(f.z); v.w = __float_as_int(f.w);
+    __builtin_amdgcn_raw_buffer_store_b128(v, r, byte_offset, 0, 16);
+}
 // Returns true in every thread of the last workgroup to arrive at `counter` (of `expected`).
 __device__ __forceinline__ bool lc_arrive_last(int* counter, int expected, int* flag_sh) {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");       // this thread's stores have completed
+    // Wait until this thread's hand-off stores have been acknowledged (they are write-through, so
+    // the acknowledgement means they are visible device-wide).  A workgroup-scope fence alone does
+    // not wait for stores to complete, so the counters are drained explicitly.
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
     if (threadIdx.x == 0) {
         const int old = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
