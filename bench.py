@@ -8,7 +8,7 @@ To keep the numbers honest about HBM, consecutive steps walk over several
 replicas of (K, V, index) whose total footprint exceeds the 256 MB last-level
 cache several times, and use a different query each step.
 
-Prints one JSON line (see README for the fields).
+Prints one JSON line: metric/value/unit, config, roofline (dominant kernel vs HBM peak), cpu_baseline, extra.
 """
 from __future__ import annotations
 
