@@ -379,13 +379,22 @@ __device__ __forceinline__ LcSel lc_block_select(int n, long long W, long long C
 // For item i among n candidates: number and total weight of the items that precede it in the
 // (key descending, index ascending) order.  `keys` and `wgts` are 16-byte aligned LDS arrays,
 // zero-padded to a multiple of 4 entries (key 0 = not a candidate; it never precedes anything).
-// Every thread reads the same addresses at the same time (LDS broadcast), four entries a load.
-__device__ __forceinline__ void lc_rank_before(int n, const uint32_t* keys, const int* wgts, int i, uint32_t ki,
-                                               int* count_before, int* weight_before) {
+// The 16 lanes of a group share one item: lane `part` scans every 16th vector of four entries
+// (neighbouring lanes read neighbouring vectors, the four groups of a wave read the same ones),
+// and the partial counts are summed over the DPP row.  Returned in every lane of the group.
+__device__ __forceinline__ int lc_sum16_i(int v) {
+    v += __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xF, 0xF, true);
+    v += __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xF, 0xF, true);
+    v += __builtin_amdgcn_update_dpp(0, v, 0x141, 0xF, 0xF, true);
+    v += __builtin_amdgcn_update_dpp(0, v, 0x140, 0xF, 0xF, true);
+    return v;
+}
+__device__ __forceinline__ void lc_rank_before16(int n, const uint32_t* keys, const int* wgts, int i, uint32_t ki,
+                                                 int part, int* count_before, int* weight_before) {
     int cb = 0, wb = 0;
-    const int n4 = (n + 3) & ~3;
-#pragma unroll 4
-    for (int j = 0; j < n4; j += 4) {
+    const int nv = (n + 3) >> 2;
+    for (int jv = part; jv < nv; jv += 16) {
+        const int j = 4 * jv;
         const uint4 k = *reinterpret_cast<const uint4*>(keys + j);
         const int4 w = *reinterpret_cast<const int4*>(wgts + j);
         const bool b0 = k.x > ki || (k.x == ki && j + 0 < i);
@@ -395,6 +404,6 @@ __device__ __forceinline__ void lc_rank_before(int n, const uint32_t* keys, cons
         cb += (int)b0 + (int)b1 + (int)b2 + (int)b3;
         wb += (b0 ? w.x : 0) + (b1 ? w.y : 0) + (b2 ? w.z : 0) + (b3 ? w.w : 0);
     }
-    *count_before = cb;
-    *weight_before = wb;
+    *count_before = lc_sum16_i(cb);
+    *weight_before = lc_sum16_i(wb);
 }

@@ -57,20 +57,22 @@ struct LcRetrieveArgs {
 // zero-padded LDS arrays.
 //   mode 0: keep the longest prefix with weight <= W and count <= C  (exact ties by index)
 //   mode 1: keep the shortest prefix whose weight reaches W (everything if it never does)
-// Writes flags[i] for i < n.  Returns, in every thread, the smallest kept key (0 if nothing kept)
-// and whether the kept weight reached W (mode 1).
-template <int NT>
+// Writes flags[i] for i < n.  With REDUCE it also returns, in every thread, the smallest kept key
+// (0 if nothing kept) and whether the kept weight reached W (mode 1); that costs three barriers.
+template <int NT, bool REDUCE>
 __device__ __forceinline__ void lc_small_select(int n, int mode, long long W, long long C, const uint32_t* keys,
                                                 const int* wgts, uint8_t* flags, int* sh, uint32_t* min_kept,
                                                 int* reached) {
     uint32_t mk = 0xffffffffu;
     int hit = 0;
-    for (int i = threadIdx.x; i < n; i += NT) {
-        const uint32_t ki = keys[i];
+    const int part = threadIdx.x & 15;
+    for (int base = 0; base < n; base += NT / 16) {           // NT/16 items per round, 16 lanes each
+        const int i = base + (threadIdx.x >> 4);
+        const uint32_t ki = i < n ? keys[i] : 0u;
+        int cb, wb;
+        lc_rank_before16(ki != 0u ? n : 0, keys, wgts, i, ki, part, &cb, &wb);
         int keep = 0;
         if (ki != 0u) {
-            int cb, wb;
-            lc_rank_before(n, keys, wgts, i, ki, &cb, &wb);
             const int wi = wgts[i];
             if (mode == 0) keep = ((long long)wb + wi <= W && (long long)cb + 1 <= C) ? 1 : 0;
             else {
@@ -78,8 +80,13 @@ __device__ __forceinline__ void lc_small_select(int n, int mode, long long W, lo
                 if (keep && (long long)wb + wi >= W) hit = 1;
             }
         }
-        flags[i] = (uint8_t)keep;
+        if (part == 0 && i < n) flags[i] = (uint8_t)keep;
         if (keep) mk = min(mk, ki);
+    }
+    if (!REDUCE) {                   // flags only: the caller synchronises before it reads them
+        *min_kept = 0u;
+        *reached = 0;
+        return;
     }
 #pragma unroll
     for (int m = 1; m < 64; m <<= 1) {
@@ -99,6 +106,16 @@ __device__ __forceinline__ void lc_small_select(int n, int mode, long long W, lo
 // ---------------------------------------------------------------------------------
 // kernel 1: internal levels
 // ---------------------------------------------------------------------------------
+// LDS bytes of the upper kernel: 13 per internal-node slot (key, token count, parent, kept flag),
+// 16 per select-scratch slot (two key/weight buffers), 12 per probe-list slot.
+__host__ __device__ inline int lc_upper_scratch_entries(int UC, int PC) {
+    const int q = ((PC / 4 + 63) / 64) * 64;            // the tau step parks PC flag bytes there
+    return UC > q ? UC : q;
+}
+__host__ __device__ inline size_t lc_upper_lds_bytes(int UC, int PC) {
+    return (size_t)UC * 13 + (size_t)lc_upper_scratch_entries(UC, PC) * 16 + (size_t)PC * 12;
+}
+
 // One workgroup of 1024 threads (64 groups of 16 lanes) per (sequence, head).  All
 // global loads of a phase are issued before any of them is used: at batch 1 the
 // kernel's duration is a chain of memory round trips, not bandwidth.
@@ -131,20 +148,34 @@ lc_upper_kernel(const LcRetrieveArgs a) {
     }
     // LDS carve-up: internal nodes (UC entries each), select scratch, probe list (PC entries each)
     const int UC = a.upper_cap, PC = a.chunk_cap;
-    const int SC = UC > PC ? UC : PC;
+    const int SC = lc_upper_scratch_entries(UC, PC);
     uint32_t* ukey = reinterpret_cast<uint32_t*>(lds_dyn);
     int* untok = lds_dyn + UC;
     int* upar = lds_dyn + 2 * UC;
-    uint8_t* fr = reinterpret_cast<uint8_t*>(lds_dyn + 3 * UC);
-    uint8_t* kp = fr + UC;
-    uint32_t* ek = reinterpret_cast<uint32_t*>(lds_dyn + 3 * UC + UC / 2);      // UC, PC multiples of 64
-    int* ew = reinterpret_cast<int*>(ek) + SC;
-    int* plist = ew + SC;
+    uint8_t* kp = reinterpret_cast<uint8_t*>(lds_dyn + 3 * UC);
+    // two (key, weight) staging buffers for the per-level selects, used alternately
+    uint32_t* ekA = reinterpret_cast<uint32_t*>(lds_dyn + 3 * UC + UC / 4);     // UC, PC multiples of 64
+    int* ewA = reinterpret_cast<int*>(ekA) + SC;
+    uint32_t* ekB = reinterpret_cast<uint32_t*>(ewA + SC);
+    int* ewB = reinterpret_cast<int*>(ekB) + SC;
+    int* plist = ewB + SC;
     int* plen = plist + PC;
     uint32_t* pkey = reinterpret_cast<uint32_t*>(plen + PC);
 
     float qf[G][8], qn[G];
     lc_load_query_frags<G>(a.q + (size_t)b * ix.H * G * LC_D, h, sub, qf, qn);
+    // prefetch what the chunk pass will need much later (parents and boundaries of this thread's
+    // first LC_UP_PER_THREAD chunks): the arrays are cap[0] long, so no count is needed to load them
+    int pf_p[LC_UP_PER_THREAD], pf_s[LC_UP_PER_THREAD + 1];
+    {
+        const int* bnd_e = ix.bounds + (size_t)b * (ix.cap[0] + 1);
+        const int* par_e = ix.parent[0] + (size_t)bh * ix.cap[0];
+        const int j0 = tid * LC_UP_PER_THREAD;
+#pragma unroll
+        for (int k = 0; k < LC_UP_PER_THREAD; ++k) pf_p[k] = par_e[min(j0 + k, ix.cap[0] - 1)];
+#pragma unroll
+        for (int k = 0; k <= LC_UP_PER_THREAD; ++k) pf_s[k] = bnd_e[min(j0 + k, ix.cap[0])];
+    }
     __syncthreads();
     const int NU = off_sh[L];
     LC_STAMP0(lc_dbg_upper, 1);
@@ -217,37 +248,30 @@ lc_upper_kernel(const LcRetrieveArgs a) {
             }
         }
     };
-    // frontier-filtered keys and weights of level l -> aligned select scratch (zero padded)
-    auto stage_level = [&](int l, bool with_tokens) -> int {
-        const int o = off_sh[l], n_l = off_sh[l + 1] - o;
-        const int n4 = (n_l + 3) & ~3;
-        for (int i = tid; i < n4; i += LC_UP_THREADS) {
-            const bool in = i < n_l && fr[o + i];
-            ek[i] = in ? ukey[o + i] : 0u;
-            ew[i] = (in && with_tokens) ? untok[o + i] : 0;
+    // Per-level selection.  The candidates of a level (frontier nodes: key, weight; others: 0) sit in
+    // one staging buffer; the select writes kept flags; the children of the kept nodes are staged into
+    // the other buffer for the next level.  Two barriers per level.
+    uint32_t* ek = ekA;
+    int* ew = ewA;
+    uint32_t* ek_next = ekB;
+    int* ew_next = ewB;
+    const bool with_tokens = a.policy == LC_POLICY_EXACT;
+    {
+        const int o = off_sh[L - 1], n_l = off_sh[L] - o;
+        for (int i = tid; i < ((n_l + 3) & ~3); i += LC_UP_THREADS) {
+            ek[i] = i < n_l ? ukey[o + i] : 0u;
+            ew[i] = (i < n_l && with_tokens) ? untok[o + i] : 0;
         }
         __syncthreads();
-        return n_l;
-    };
-    auto children_frontier = [&](int l) {             // fr[level l-1] = kp[parent at level l]
-        const int o = off_sh[l];
-        const int ob = off_sh[l - 1], n_b = off_sh[l] - ob;
-        for (int n = tid; n < n_b; n += LC_UP_THREADS) fr[ob + n] = kp[o + upar[ob + n]];
-        __syncthreads();
-    };
-
-    for (int n = tid; n < NU; n += LC_UP_THREADS) fr[n] = (n >= off_sh[L - 1]) ? 1 : 0;
-    __syncthreads();
-
-    if (a.policy == LC_POLICY_BEAM) {
-        for (int l = L - 1; l >= 1; --l) {
-            const int o = off_sh[l];
+    }
+    for (int l = L - 1; l >= 1; --l) {
+        const int o = off_sh[l], n_l = off_sh[l + 1] - o;
+        uint32_t mk;
+        int reached;
+        if (a.policy == LC_POLICY_BEAM) {
             const long long C = a.beam[l] > 0 ? a.beam[l] : 0x7fffffffLL;
-            const int n_l = stage_level(l, false);
             if (n_l <= LC_COUNT_SELECT_MAX) {
-                uint32_t mk;
-                int reached;
-                lc_small_select<LC_UP_THREADS>(n_l, 0, 0x7fffffffffffLL, C, ek, ew, kp + o, sel_sh, &mk, &reached);
+                lc_small_select<LC_UP_THREADS, false>(n_l, 0, 0x7fffffffffffLL, C, ek, ew, kp + o, sel_sh, &mk, &reached);
             } else {
                 auto keyf = [&](int i) -> uint32_t { return ek[i]; };
                 auto wf = [&](int) -> int { return 0; };
@@ -263,31 +287,37 @@ lc_upper_kernel(const LcRetrieveArgs a) {
                     tie_c += tot;
                 }
             }
-            __syncthreads();
-            if (l >= 2) children_frontier(l);
+        } else {
+            // EXACT, probe pass: keep the best frontier nodes until their subtree token counts reach the budget
+            if (n_l <= LC_COUNT_SELECT_MAX) {
+                lc_small_select<LC_UP_THREADS, false>(n_l, 1, (long long)a.budget, 0x7fffffffLL, ek, ew, kp + o, sel_sh, &mk, &reached);
+            } else {
+                auto keyf = [&](int i) -> uint32_t { return ek[i]; };
+                auto wf = [&](int i) -> int { return ew[i]; };
+                const LcSel r = lc_block_select<LC_UP_THREADS>(n_l, (long long)a.budget - 1, 0x7fffffffLL, keyf, wf, sel_sh);
+                for (int i = tid; i < n_l; i += LC_UP_THREADS)
+                    kp[o + i] = (ek[i] != 0u && (r.all || ek[i] >= r.kstar)) ? 1 : 0;      // whole tie group
+            }
         }
+        LC_STAMP0(lc_dbg_upper, 8 + 3 * (L - 1 - l));
+        __syncthreads();
+        LC_STAMP0(lc_dbg_upper, 9 + 3 * (L - 1 - l));
+        if (l >= 2) {                 // stage the children of the kept nodes as the next level's candidates
+            const int ob = off_sh[l - 1], n_b = off_sh[l] - ob;
+            for (int n = tid; n < ((n_b + 3) & ~3); n += LC_UP_THREADS) {
+                const bool in = n < n_b && kp[o + upar[ob + n]];
+                ek_next[n] = in ? ukey[ob + n] : 0u;
+                ew_next[n] = (in && with_tokens) ? untok[ob + n] : 0;
+            }
+            __syncthreads();
+            uint32_t* tk = ek; ek = ek_next; ek_next = tk;
+            int* tw = ew; ew = ew_next; ew_next = tw;
+        }
+        LC_STAMP0(lc_dbg_upper, 10 + 3 * (L - 1 - l));
+    }
+    if (a.policy == LC_POLICY_BEAM) {
         write_want();
         return;
-    }
-
-    // ---- EXACT, probe pass: going down, keep the best frontier nodes until their
-    // subtree token counts reach the budget.
-    for (int l = L - 1; l >= 1; --l) {
-        const int o = off_sh[l];
-        const int n_l = stage_level(l, true);
-        if (n_l <= LC_COUNT_SELECT_MAX) {
-            uint32_t mk;
-            int reached;
-            lc_small_select<LC_UP_THREADS>(n_l, 1, (long long)a.budget, 0x7fffffffLL, ek, ew, kp + o, sel_sh, &mk, &reached);
-        } else {
-            auto keyf = [&](int i) -> uint32_t { return ek[i]; };
-            auto wf = [&](int i) -> int { return ew[i]; };
-            const LcSel r = lc_block_select<LC_UP_THREADS>(n_l, (long long)a.budget - 1, 0x7fffffffLL, keyf, wf, sel_sh);
-            for (int i = tid; i < n_l; i += LC_UP_THREADS)
-                kp[o + i] = (ek[i] != 0u && (r.all || ek[i] >= r.kstar)) ? 1 : 0;      // whole tie group
-        }
-        __syncthreads();
-        if (l >= 2) children_frontier(l);
     }
     LC_STAMP0(lc_dbg_upper, 3);
     // ---- compact the probe's chunks (children of the kept level-1 nodes, not pinned) into LDS.
@@ -296,10 +326,17 @@ lc_upper_kernel(const LcRetrieveArgs a) {
     for (int base = 0; base < M; base += LC_UP_THREADS * LC_UP_PER_THREAD) {
         const int j0 = base + tid * LC_UP_PER_THREAD;
         int p[LC_UP_PER_THREAD], s0[LC_UP_PER_THREAD + 1];
+        if (base == 0) {
 #pragma unroll
-        for (int k = 0; k < LC_UP_PER_THREAD; ++k) p[k] = par0[max(0, min(j0 + k, M - 1))];
+            for (int k = 0; k < LC_UP_PER_THREAD; ++k) p[k] = pf_p[k];
 #pragma unroll
-        for (int k = 0; k <= LC_UP_PER_THREAD; ++k) s0[k] = bnd[min(j0 + k, M)];
+            for (int k = 0; k <= LC_UP_PER_THREAD; ++k) s0[k] = pf_s[k];
+        } else {
+#pragma unroll
+            for (int k = 0; k < LC_UP_PER_THREAD; ++k) p[k] = par0[max(0, min(j0 + k, M - 1))];
+#pragma unroll
+            for (int k = 0; k <= LC_UP_PER_THREAD; ++k) s0[k] = bnd[min(j0 + k, M)];
+        }
         int f[LC_UP_PER_THREAD], cnt = 0;
 #pragma unroll
         for (int k = 0; k < LC_UP_PER_THREAD; ++k) {
@@ -350,8 +387,8 @@ lc_upper_kernel(const LcRetrieveArgs a) {
         uint32_t cut = 0u;
         int reached = 0;
         if (n_probe <= LC_COUNT_SELECT_MAX) {
-            lc_small_select<LC_UP_THREADS>(n_probe, 1, (long long)a.budget, 0x7fffffffLL, pkey, plen,
-                                           reinterpret_cast<uint8_t*>(ek), sel_sh, &cut, &reached);
+            lc_small_select<LC_UP_THREADS, true>(n_probe, 1, (long long)a.budget, 0x7fffffffLL, pkey, plen,
+                                                 reinterpret_cast<uint8_t*>(ekA), sel_sh, &cut, &reached);
         } else {
             auto keyf = [&](int i) -> uint32_t { return pkey[i]; };
             auto wf = [&](int i) -> int { return plen[i]; };
@@ -541,12 +578,12 @@ static int launch_retrieve_g(LcRetrieveArgs& a, int max_M, hipStream_t stream) {
     const int mc = ((max_M + 63) / 64) * 64;
     const size_t lds_limit = 150 * 1024;
     if (a.walk) {
-        // internal nodes: 14 bytes each; select scratch: 8 bytes x max(UC, PC); probe list: 12 bytes each
-        const size_t uc = a.upper_cap;
-        size_t pc = mc;
-        while (pc > 64 && uc * 14 + (uc > pc ? uc : pc) * 8 + pc * 12 > lds_limit) pc -= 64;
-        a.chunk_cap = (int)pc;
-        const size_t lds = uc * 14 + (uc > pc ? uc : pc) * 8 + pc * 12;
+        // as long a probe list as LDS holds next to the internal-node slots
+        const int uc = a.upper_cap;
+        int pc = mc;
+        while (pc > 64 && lc_upper_lds_bytes(uc, pc) > lds_limit) pc -= 64;
+        a.chunk_cap = pc;
+        const size_t lds = lc_upper_lds_bytes(uc, pc);
         if (lds > 48 * 1024)
             LC_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&lc_upper_kernel<G>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
