@@ -278,55 +278,59 @@ lc_decode_kernel(const LcDecodeArgs a) {
     if (!lc_arrive_last(&ix.sync[bh * 4 + 1], S, &last_sh)) return;
 
     LC_STAMP(lc_dbg_decode, 4);
-    // partial (m, l) of every split -> LDS; per head: global max, scale of each split, denominator
+    // The accumulator partials do not depend on the scales, so their loads go out first and fly
+    // while the (m, l) pairs are fetched and turned into per-split scales.
     const __amdgpu_buffer_rsrc_t pacc_r = lc_buffer(a.part_acc + (size_t)bh * S * G * LC_D);
     const float* pml = a.part_ml + (size_t)bh * S * G * 2;
     const int n_part = (n_tok > 0) ? S_eff : 0;
+    constexpr int NV = G * (LC_D / 4);                       // float4 slots of the output
+    constexpr int WAYS = (LC_DEC_THREADS / NV) > 0 ? (LC_DEC_THREADS / NV) : 1;
+    constexpr int MR = (G <= 4) ? 16 : 8;                    // partials per round and thread
+    const int v = tid % NV, wy = tid / NV;
+    const int g = v / (LC_D / 4), c4 = v % (LC_D / 4);
+    float4 x[MR];
+    auto load_round = [&](int sp0) {
+#pragma unroll
+        for (int k = 0; k < MR; ++k) {
+            const int spc = min(sp0 + k * WAYS, n_part - 1);
+            x[k] = lc_load_agent4(pacc_r, ((spc * G + g) * LC_D + 4 * c4) * 4);
+        }
+    };
+    if (wy < WAYS && n_part > 0) load_round(wy);
+    // partial (m, l) of every split -> LDS; per head: global max, scale of each split, denominator
     for (int e = tid; e < n_part * G; e += LC_DEC_THREADS) {
         mrg_m[e] = lc_load_agent(pml + 2 * e);
         mrg_l[e] = lc_load_agent(pml + 2 * e + 1);
     }
     __syncthreads();
-    for (int g = wave; g < G; g += LC_DEC_THREADS / 64) {
+    for (int gg = wave; gg < G; gg += LC_DEC_THREADS / 64) {
         float mx = LC_NEG_INF;
-        for (int sp = lane; sp < n_part; sp += 64) mx = fmaxf(mx, mrg_m[sp * G + g]);
+        for (int sp = lane; sp < n_part; sp += 64) mx = fmaxf(mx, mrg_m[sp * G + gg]);
         mx = lc_max64(mx);
         float den = 0.f;
         for (int sp = lane; sp < n_part; sp += 64) {
-            const float ms = mrg_m[sp * G + g];
+            const float ms = mrg_m[sp * G + gg];
             const float sc = (ms == LC_NEG_INF) ? 0.f : exp2f(ms - mx);
-            mrg_m[sp * G + g] = sc;                     // from here on: the split's scale
-            den = fmaf(mrg_l[sp * G + g], sc, den);
+            mrg_m[sp * G + gg] = sc;                    // from here on: the split's scale
+            den = fmaf(mrg_l[sp * G + gg], sc, den);
         }
         den = lc_sum64(den);
-        if (lane == 0) { mrg_hd[2 * g] = mx; mrg_hd[2 * g + 1] = den; }
+        if (lane == 0) { mrg_hd[2 * gg] = mx; mrg_hd[2 * gg + 1] = den; }
     }
     __syncthreads();
     LC_STAMP(lc_dbg_decode, 5);
-    constexpr int NV = G * (LC_D / 4);                       // float4 slots of the output
-    constexpr int WAYS = (LC_DEC_THREADS / NV) > 0 ? (LC_DEC_THREADS / NV) : 1;
     float4 acc4 = make_float4(0.f, 0.f, 0.f, 0.f);
-    const int v = tid % NV, wy = tid / NV;
-    const int g = v / (LC_D / 4), c4 = v % (LC_D / 4);
     if (wy < WAYS) {
-        // MR partials per round, all their loads in flight before the first is used
-        constexpr int MR = (G <= 4) ? 16 : 8;
         for (int sp0 = wy; sp0 < n_part; sp0 += MR * WAYS) {
-            float4 x[MR];
-            float sc[MR];
+            if (sp0 != wy) load_round(sp0);
 #pragma unroll
             for (int k = 0; k < MR; ++k) {
                 const int sp = sp0 + k * WAYS;
-                const int spc = min(sp, n_part - 1);
-                x[k] = lc_load_agent4(pacc_r, ((spc * G + g) * LC_D + 4 * c4) * 4);
-                sc[k] = sp < n_part ? mrg_m[spc * G + g] : 0.f;
-            }
-#pragma unroll
-            for (int k = 0; k < MR; ++k) {
-                acc4.x = fmaf(x[k].x, sc[k], acc4.x);
-                acc4.y = fmaf(x[k].y, sc[k], acc4.y);
-                acc4.z = fmaf(x[k].z, sc[k], acc4.z);
-                acc4.w = fmaf(x[k].w, sc[k], acc4.w);
+                const float sc = sp < n_part ? mrg_m[sp * G + g] : 0.f;
+                acc4.x = fmaf(x[k].x, sc, acc4.x);
+                acc4.y = fmaf(x[k].y, sc, acc4.y);
+                acc4.z = fmaf(x[k].z, sc, acc4.z);
+                acc4.w = fmaf(x[k].w, sc, acc4.w);
             }
         }
         if (WAYS > 1 && wy > 0) mrg_red[(wy - 1) * NV + v] = acc4;
