@@ -167,12 +167,20 @@ def test_c4_streaming_2048_steps(G):
     out = torch.zeros((1, w.H_q, w.d), dtype=torch.float32, device="cuda")
     prev_r = None
     n_closed = 0
+    from paper_2603_08453_amd import diagnostics as D
+    history, jac, hit, rec = [], [], [], []
     for t in range(steps):
         close = int(st.close[t])
         lc.lc_append(case.idx, case.K, case.V, k_dev[t:t + 1], v_dev[t:t + 1], [close], case.ws)
         lc.lc_retrieve(case.idx, q_dev[t:t + 1], w.budget, ids, counts, case.ws)
         lc.lc_sparse_decode(case.idx, q_dev[t:t + 1], case.K, case.V, ids, counts, out, case.ws)
         n_closed += close
+        if t % 4 == 0:                     # stability of the retrieved sets of head 0 (Appendix D metrics)
+            cur = ids[0, 0, : int(counts[0, 0])].cpu().numpy().tolist()
+            if history:
+                jac.append(D.jaccard(history[-1], cur))
+                hit.append(D.window_hit(history, cur, w=32))
+            history.append(cur)
         for h in range(w.H_kv):
             oi = case.oidx[0][h]
             Kf[h][oi.T] = wl.bf16_bits_to_f64(st.k[t, h])
@@ -211,9 +219,15 @@ def test_c4_streaming_2048_steps(G):
                 ref, _ = orc.sparse_decode(q, Kf[h], Vf[h], gi.bounds, gi.T, got)
                 mx, rel = G.attention_errors(out_h[0, h * w.G:(h + 1) * w.G], ref)
                 assert mx <= ATTN_MAX_ABS and rel <= ATTN_REL_L2, (t, h, mx, rel)
+                if h == 0:                 # recall of the true top-256 tokens of the first query head
+                    logits = Kf[h][:gi.T] @ q[0]
+                    rec.append(D.recall_rate(logits, D.selected_tokens(gi.bounds, gi.T, got), 256))
             hh = (t // 256 + 1) % w.H_kv
             prev_r = (hh, [r.copy() for r in G.levels_to_oracle_index(
                 s["heads"][hh], s["bounds"], s["T"], w.fanout, orc.TOKEN_BALL).radius])
             _say(f"C4 step {t + 1}: {n_closed} chunks grafted, T={T}, M={M}, heads whose parent choices "
                  f"differ from the oracle: {mism}")
             assert mism == 0
+    _say(f"C4 stream diagnostics (head 0): mean Jaccard of consecutive sampled sets {np.mean(jac):.3f}, "
+         f"mean window hit (w=32) {np.mean(hit):.3f}, recall of the true top-256 tokens {np.mean(rec):.3f}")
+    assert 0.0 <= np.mean(jac) <= 1.0 and 0.0 <= np.mean(hit) <= 1.0 and 0.0 <= np.mean(rec) <= 1.0

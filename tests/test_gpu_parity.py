@@ -220,6 +220,31 @@ def test_pruning_happens_and_stays_exact(G):
     assert np.all(scored < M)
 
 
+def test_paper_literal_algorithm1(G):
+    """The paper's own configuration of Algorithm 1: unit-norm representatives with radius 0
+    (PAPER_UNIT), top-k_g coarse units then top-k_c fine clusters (BEAM), *all* chunks of the kept
+    fine clusters attended (no chunk-level limit: budget = everything), attention sink of 16 tokens,
+    chunks of 8..16 tokens, 2 chunks per fine cluster on average."""
+    from paper_2603_08453_amd import binding as lc
+    w = wl.tiny("paper", levels=3, fanout=2, T=3000, chunk_lo=8, chunk_hi=16, H_q=8, H_kv=2)
+    case = G.make_case(w, geometry=orc.PAPER_UNIT)
+    qb = _q_batch(case, 0)
+    k_c, k_g = 12, 6
+    beam = [0, k_c, k_g]
+    ids = _check_retrieve(G, case, qb, 10 ** 9, policy=orc.POLICY_BEAM, beam=beam, sink=16, tag="paper-literal")
+    for h in range(w.H_kv):
+        oi = case.oidx[0][h]
+        kept_clusters = set(oi.parent[0][ids[0][h]].tolist())
+        pinned = set(orc.pinned_chunks(oi, 16).tolist())
+        free_clusters = set(oi.parent[0][[j for j in ids[0][h] if j not in pinned]].tolist())
+        assert len(free_clusters) <= k_c
+        # every chunk of a kept fine cluster is there
+        for c in free_clusters:
+            assert set(np.nonzero(oi.parent[0] == c)[0].tolist()) - pinned <= set(ids[0][h].tolist())
+    _check_decode(G, case, qb, ids, tag="paper-literal attention")
+    lc.lc_set_policy(case.idx, lc.LC_POLICY_EXACT, None, 0)
+
+
 def test_prune_modes_give_the_same_ids(G, c1):
     """The level walk is an optimisation of EXACT retrieval: always / never / auto agree bit for bit."""
     from paper_2603_08453_amd import binding as lc
