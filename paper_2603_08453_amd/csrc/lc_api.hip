@@ -97,7 +97,6 @@ size_t lc_layout_ws(const lc_config* cfg, int B, int H_q, int H, int d, int spli
     W->keys = c.take<uint32_t>(BH * cap[0]);
     W->want = c.take<uint8_t>(BH * cap[0]);
     W->scratch = c.take<int>(BH * 4 * cap[0]);
-    W->scores = c.take<float>(BH * cap[0]);
     W->part_acc = c.take<float>((size_t)B * H_q * splits * d);
     W->part_ml = c.take<float>((size_t)B * H_q * splits * 2);
     W->dirs = c.take<float>(BH * cap[0] * d);

@@ -36,12 +36,6 @@ __device__ __forceinline__ void lc_unpack8(const uint4& v, float (&f)[8]) {
     f[6] = lc_bf16_lo(v.w); f[7] = lc_bf16_hi(v.w);
 }
 
-__device__ __forceinline__ uint16_t lc_f32_to_bf16(float f) {     // round to nearest even
-    uint32_t u = __float_as_uint(f);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
-}
-
 // ---------------------------------------------------------------- reductions
 // Sum over the 16 consecutive lanes that share (lane >> 4): exactly one DPP row, so the
 // butterfly runs on the vector ALU (quad permutes, then half-row and full-row mirrors)

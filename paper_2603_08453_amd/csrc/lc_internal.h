@@ -46,7 +46,6 @@ struct LcWs {
     uint32_t* keys;      // [B][H][cap0] order-preserving score keys of the chunks (0 = not a candidate)
     uint8_t* want;       // [B][H][cap0] 1 = this chunk's score is needed
     int* scratch;        // [B][H][4 * cap0] chunk-level staging when it does not fit in LDS
-    float* scores;       // [B][H][cap0] scratch scores when the caller passes none
     // decode
     float* part_acc;     // [B][H][S][G][d]
     float* part_ml;      // [B][H][S][G][2]

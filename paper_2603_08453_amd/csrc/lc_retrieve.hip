@@ -1,8 +1,8 @@
 // Retrieval kernels: Eq. 2 node scoring, level-by-level pruning, budget selection.
 //
 // Kernel 1 (lc_upper_kernel): one workgroup per (sequence, KV head).  It stages the
-// tree's small arrays (parents, subtree token counts, chunk lengths) in LDS with a
-// few batched loads, scores every internal node (levels >= 1), and walks the levels
+// internal nodes' small arrays (parents, subtree token counts) in LDS with a few
+// batched loads, scores every internal node (levels >= 1), and walks the levels
 // top-down with the frontier held in LDS:
 //   EXACT  probe pass  -> a lower bound tau0 of the selection cutoff,
 //          verify pass -> every node whose bound reaches tau0 stays;
@@ -19,8 +19,6 @@
 #include "lc_device.h"
 #include "lc_internal.h"
 
-#define LC_RT_THREADS 256
-#define LC_RT_GROUPS (LC_RT_THREADS / 16)
 #define LC_LEAF_CHUNKS_PER_BLOCK 64
 #define LC_TAU_SLACK 1e-3f
 #define LC_COUNT_SELECT_MAX 1024         // up to this many candidates the O(n^2 / threads) rank is used
