@@ -215,6 +215,34 @@ int lc_index_import(lc_index** out, const lc_config* cfg, const void* blob /* ho
 
 void lc_index_destroy(lc_index* idx);
 
+/*
+ * lc_chunk_tokens -- structure-aware chunk boundaries for a token stream
+ * (Section 4.3 "Structure-Aware Chunking", Appendix C separator table).  Host
+ * routine, no GPU work: its output is the chunk_bounds argument of
+ * lc_build_index and decides the close_chunk bits of lc_append.
+ * Tokens are accumulated greedily; once a chunk holds min_len tokens the
+ * delimiter of strongest level among its tokens min_len..max_len ends the chunk
+ * (the earliest one of that level); with no delimiter the chunk ends at max_len
+ * tokens.  The last chunk of the text may be shorter than min_len.
+ * A token's level comes from the end of its text, trailing blanks and tabs
+ * ignored for levels 1-3:
+ *   1  contains a blank line, "---", "***" or a code fence, or ends in } ] >
+ *   2  contains a newline, or ends in . ? ! or their full-width forms
+ *   3  ends in , ; : or their full-width forms or the ideographic comma
+ *   4  ends in a blank or tab
+ *
+ *   text     host: the tokens' UTF-8 bytes, concatenated
+ *   offsets  host int64[n+1]: token i is text[offsets[i] .. offsets[i+1])
+ *   n        number of tokens (0 allowed)
+ *   bounds   host int32[capacity] out: b_0 = 0 < ... < b_M = n
+ *   n_chunks host out: M
+ * Returns LC_ERR_INVALID_ARG for NULL pointers, min_len < 1, max_len < min_len or
+ * decreasing offsets; LC_ERR_CAPACITY if capacity < M + 1 (nothing useful is
+ * left in bounds then; capacity n + 1 always suffices).
+ */
+int lc_chunk_tokens(const char* text, const int64_t* offsets, int n, int min_len, int max_len,
+                    int32_t* bounds, int capacity, int* n_chunks);
+
 #ifdef __cplusplus
 }
 #endif

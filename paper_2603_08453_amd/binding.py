@@ -107,6 +107,9 @@ def lib() -> ctypes.CDLL:
     L.lc_index_import.restype = ctypes.c_int
     L.lc_index_destroy.argtypes = [vp]
     L.lc_index_destroy.restype = None
+    L.lc_chunk_tokens.argtypes = [ctypes.c_char_p, i64p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                  i32p, ctypes.c_int, ctypes.POINTER(ctypes.c_int)]
+    L.lc_chunk_tokens.restype = ctypes.c_int
     _lib = L
     return L
 
@@ -264,6 +267,23 @@ def lc_index_import(cfg: LcConfig, blob: bytes, index_buf, stream=None) -> Index
     _check(rc, "lc_index_import")
     hdr = np.frombuffer(blob[:64], dtype=np.int32)
     return Index(out.value, cfg, index_buf, int(hdr[2]), int(hdr[3]))
+
+
+def lc_chunk_tokens(tokens: Sequence[str], min_len: int, max_len: int) -> List[int]:
+    """Chunk boundaries of a token stream given as the tokens' texts (host routine)."""
+    raw = [t.encode("utf-8") for t in tokens]
+    n = len(raw)
+    off = (ctypes.c_int64 * (n + 1))()
+    acc = 0
+    for i, r in enumerate(raw):
+        off[i] = acc
+        acc += len(r)
+    off[n] = acc
+    bounds = (ctypes.c_int32 * (n + 1))()
+    m = ctypes.c_int(0)
+    _check(lib().lc_chunk_tokens(b"".join(raw), off, n, int(min_len), int(max_len), bounds, n + 1,
+                                 ctypes.byref(m)), "lc_chunk_tokens")
+    return [int(bounds[i]) for i in range(m.value + 1)]
 
 
 # ------------------------------------------------------------------ blob (de)serialisation
