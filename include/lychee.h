@@ -171,6 +171,8 @@ int lc_retrieve(const lc_index* idx, const void* q, int H_q, int budget,
  *   chunk_ids, counts, cap   as produced by lc_retrieve (ids ascending, distinct)
  *   out        float32 [B][H_q][d]; an empty active set gives 0
  *   lse        optional float32 [B][H_q]: ln sum exp(logit); -inf if empty
+ * One (sequence, head) slab of the cache must span less than 2 GiB
+ * (cfg.max_tokens * kv_strides[2] * 2 bytes), else LC_ERR_BAD_SHAPE.
  */
 int lc_sparse_decode(const lc_index* idx, const void* q, const void* K, const void* V,
                      const int64_t kv_strides[3],

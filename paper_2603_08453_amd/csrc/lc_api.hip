@@ -359,12 +359,8 @@ int lc_sparse_decode(const lc_index* idx, const void* q, const void* K, const vo
     const int splits = lc_auto_splits(&idx->cfg, idx->B, idx->H_kv);
     if (ws_bytes < lc_layout_ws(&idx->cfg, idx->B, H_q, idx->H_kv, idx->d, splits, nullptr, nullptr))
         return LC_ERR_WORKSPACE_TOO_SMALL;
-    int max_M = 0;
-    for (int b = 0; b < idx->B; ++b)
-        if (idx->M[b] > max_M) max_M = idx->M[b];
-    int eff_cap = cap < max_M ? cap : max_M;
-    if (eff_cap < 1) eff_cap = 1;
-    if (eff_cap > 16000) return LC_ERR_CAPACITY;        // the run table of one (sequence, head) lives in LDS
+    // the kernel addresses the rows of one (sequence, head) with 32-bit byte offsets
+    if ((long long)idx->cfg.max_tokens * kv_strides[2] * 2 >= (1LL << 31)) return LC_ERR_BAD_SHAPE;
     LcWs w;
     lc_layout_ws(&idx->cfg, idx->B, H_q, idx->H_kv, idx->d, splits, ws, &w);
     return lc_launch_decode(idx, w, q, K, V, kv_strides, chunk_ids, counts, cap, H_q / idx->H_kv, splits, out, lse,

@@ -2,10 +2,15 @@
 // chunks (plus the open tail), merged by the last split to finish.
 //
 // Grid (split, KV head, sequence), 256 threads = 16 groups of 16 lanes.  A group
-// owns a contiguous run of the split's tokens; its 16 lanes each hold 8 of the
-// 128 columns, so one K (or V) row is one 16-byte load per lane and four rows
-// make a full 1 KiB wavefront load.  Logits for the G query heads of the group
-// are reduced across the 16 lanes; the softmax is kept online in base 2.
+// owns a contiguous run of the split's tokens and handles them U at a time.
+//   Q.K^T runs on the matrix cores: the 4 groups of a wavefront together hold 16
+//   tokens, whose K rows form the 16 x 128 A operand of four 16x16x32 bf16 MFMAs;
+//   the B operand is the query block (head n in column n).  The result leaves lane
+//   (group, n) with the logits of the group's own tokens for head n, so each lane
+//   keeps the online softmax (base 2) of one head and the probabilities reach the
+//   other 15 lanes of the group by DPP row broadcasts.
+//   P.V stays on the vector ALU: lane n of a group holds columns [8n, 8n + 8) of a
+//   V row (one 16-byte load), four rows make a full 1 KiB wavefront load.
 #include "lc_device.h"
 #include "lc_internal.h"
 
@@ -13,9 +18,13 @@
 #define LC_DEC_GROUPS 16
 #define LC_DEC_MIN_TOKENS_PER_SPLIT 64
 #define LC_DEC_MAX_SPLITS 256
-#define LC_DEC_TILE 2048          // tokens of a split whose cache rows are resolved into LDS at a time
+#define LC_DEC_TILE 1024          // tokens of a split whose cache rows are resolved into LDS at a time
+#define LC_DEC_E 2                // selected ids per thread and pass of the row resolution
 #define LC_LOG2E 1.4426950408889634f
 #define LC_LN2 0.6931471805599453f
+
+typedef __bf16 lc_bf16x8 __attribute__((ext_vector_type(8)));
+typedef float lc_f32x4 __attribute__((ext_vector_type(4)));
 
 LC_STAMP_DECL(lc_dbg_decode)
 
@@ -32,15 +41,36 @@ struct LcDecodeArgs {
     float* part_ml;       // [B][H][S][G][2]
     float* out;           // [B][H*G][d]
     float* lse;           // [B][H*G] or null
-    int id_cap_lds;       // entries of the LDS run table
 };
+
+// Value of lane `src` (0..15) of the caller's 16-lane row, in every lane of the row.
+template <int SRC>
+__device__ __forceinline__ float lc_row_bcast(float v) {
+    return lc_dpp<0x150 + SRC>(v);
+}
+__device__ __forceinline__ float lc_row_bcast_n(float v, int src) {      // src folds to a constant once unrolled
+    switch (src) {
+        case 0: return lc_row_bcast<0>(v);
+        case 1: return lc_row_bcast<1>(v);
+        case 2: return lc_row_bcast<2>(v);
+        case 3: return lc_row_bcast<3>(v);
+        case 4: return lc_row_bcast<4>(v);
+        case 5: return lc_row_bcast<5>(v);
+        case 6: return lc_row_bcast<6>(v);
+        default: return lc_row_bcast<7>(v);
+    }
+}
+// exp2 of (x - ref) where x may be -inf (gives 0); ref is finite.
+__device__ __forceinline__ float lc_exp2_rel(float x, float ref) { return exp2f(x - ref); }
 
 template <int G>
 __global__ void __launch_bounds__(LC_DEC_THREADS)
 lc_decode_kernel(const LcDecodeArgs a) {
-    extern __shared__ int lds_dyn[];
     __shared__ int scan_sh[8];
     __shared__ int rows[LC_DEC_TILE];
+    __shared__ int win_off[LC_DEC_TILE + 2];      // first token position of the entries that overlap the tile
+    __shared__ int win_st[LC_DEC_TILE + 2];       // and their first cache row
+    __shared__ int win_hd[2];                     // {index of the tile's first entry, entries in the window}
     __shared__ int last_sh;
     __shared__ float comb_ml[LC_DEC_THREADS / 64][G][2];
     __shared__ __attribute__((aligned(16))) float comb_acc[LC_DEC_THREADS / 64][G][LC_D];
@@ -49,58 +79,67 @@ lc_decode_kernel(const LcDecodeArgs a) {
     __shared__ float mrg_hd[2 * G];
     __shared__ float4 mrg_red[LC_DEC_THREADS];
 
-    // tokens per batch of loads; two batches are in flight per group (the next one is issued
-    // before the current one is consumed)
+    // tokens per group and batch of loads; two batches are in flight per group (the next one is
+    // issued before the current one is consumed)
     constexpr int U = (G <= 4) ? 4 : 2;
+    constexpr int E = LC_DEC_E;
     const LcDev& ix = a.ix;
     const int s = blockIdx.x, S = gridDim.x, h = blockIdx.y, b = blockIdx.z;
     const int bh = b * ix.H + h;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int sub = tid & 15, grp = tid >> 4;
+    const int sub = tid & 15, grp = tid >> 4, q4 = lane >> 4;
 
     LC_STAMP0(lc_dbg_decode, 0);
     const int* bnd = ix.bounds + (size_t)b * (ix.cap[0] + 1);
     const int32_t* ids = a.ids + (size_t)bh * a.cap;
-    // independent loads first: the id a thread will need is fetched before the count is known,
-    // and so are the query fragments (lane `sub` holds columns [8 sub, 8 sub + 8) of each head)
-    const int id_first = (tid < a.cap) ? ids[tid] : 0;
-    uint4 qraw[G];
-    {
-        const uint16_t* qb = a.q + ((size_t)b * ix.H * G + (size_t)h * G) * LC_D;
+    // independent loads first: the ids a thread will need are fetched before the count is known,
+    // and so is the query block in MFMA B layout (lane (q4, n): head n, columns 8 q4 + 32 j + [0, 8))
+    int idv[E];
 #pragma unroll
-        for (int g = 0; g < G; ++g) qraw[g] = *reinterpret_cast<const uint4*>(qb + g * LC_D + 8 * sub);
+    for (int e = 0; e < E; ++e) idv[e] = (tid * E + e < a.cap) ? ids[tid * E + e] : 0;
+    uint4 qb[4];
+    {
+        const uint16_t* qh = a.q + ((size_t)b * ix.H * G + (size_t)h * G + min(sub, G - 1)) * LC_D + 8 * q4;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) qb[j] = *reinterpret_cast<const uint4*>(qh + 32 * j);
     }
     const int T = ix.state[bh * 4 + 0];
     const int M = ix.state[bh * 4 + 1];
     int n_ids = a.counts[bh];
-    n_ids = max(0, min(n_ids, min(a.cap, a.id_cap_lds)));
+    n_ids = (M > 0) ? max(0, min(n_ids, a.cap)) : 0;
 
-    // ---- run table in LDS: start row and exclusive token prefix of each selected chunk,
-    // then the open tail as the last run.
-    int* run_start = lds_dyn;                       // [n_ids + 1]
-    int* run_off = lds_dyn + a.id_cap_lds + 1;      // [n_ids + 2]
-    int carry = 0;
-    for (int t0 = 0; t0 < n_ids + 1; t0 += LC_DEC_THREADS) {
-        const int i = t0 + tid;
-        int st = 0, ln = 0;
-        if (i < n_ids) {
-            const int id = max(0, min(t0 == 0 ? id_first : ids[i], M - 1));
-            st = bnd[id];
-            ln = bnd[id + 1] - st;
-        } else if (i == n_ids) {
-            st = bnd[M];
-            ln = T - st;
+    // ---- the attended tokens are the selected chunks in list order, then the open tail.  Entry i
+    // of that list is (first cache row, length); thread t of a pass owns entries [E t, E t + E).
+    const int n_runs = n_ids + 1;
+    auto entries = [&](int base, bool preloaded, int (&st)[E], int (&ln)[E]) -> int {
+        int sum = 0;
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            const int i = base + tid * E + e;
+            st[e] = 0;
+            ln[e] = 0;
+            if (i < n_ids) {
+                const int id = max(0, min(preloaded ? idv[e] : ids[i], M - 1));
+                st[e] = bnd[id];
+                ln[e] = max(0, bnd[id + 1] - st[e]);
+            } else if (i == n_ids) {
+                st[e] = bnd[M];
+                ln[e] = max(0, T - st[e]);
+            }
+            sum += ln[e];
         }
-        int tot;
-        const int ex = lc_block_scan<LC_DEC_THREADS>(ln, scan_sh, &tot);
-        if (i <= n_ids) { run_start[i] = st; run_off[i] = carry + ex; }
-        carry += tot;
+        return sum;
+    };
+    int st0[E], ln0[E];                     // the first pass stays in registers
+    int tot0;
+    const int ex0 = lc_block_scan<LC_DEC_THREADS>(entries(0, true, st0, ln0), scan_sh, &tot0);
+    int n_tok = tot0;
+    for (int base = LC_DEC_THREADS * E; base < n_runs; base += LC_DEC_THREADS * E) {
+        int st[E], ln[E], tot;
+        lc_block_scan<LC_DEC_THREADS>(entries(base, false, st, ln), scan_sh, &tot);
+        n_tok += tot;
     }
     LC_STAMP0(lc_dbg_decode, 1);
-    const int n_runs = n_ids + 1;
-    const int n_tok = carry;
-    if (tid == 0) run_off[n_runs] = n_tok;
-    __syncthreads();
 
     int S_eff = (n_tok + LC_DEC_MIN_TOKENS_PER_SPLIT - 1) / LC_DEC_MIN_TOKENS_PER_SPLIT;
     S_eff = max(1, min(S, S_eff));
@@ -108,115 +147,159 @@ lc_decode_kernel(const LcDecodeArgs a) {
     if (s < S_eff) {
         const int lo = (int)(((long long)n_tok * s) / S_eff);
         const int hi = (int)(((long long)n_tok * (s + 1)) / S_eff);
-        float qf[G][8];
-        {
-            const float scale = 0.08838834764831845f * LC_LOG2E;     // log2(e) / sqrt(128)
-#pragma unroll
-            for (int g = 0; g < G; ++g) {
-                lc_unpack8(qraw[g], qf[g]);
-#pragma unroll
-                for (int i = 0; i < 8; ++i) qf[g][i] *= scale;
-            }
-        }
-        float m[G], l[G], acc[G][8];
+        const float scale = 0.08838834764831845f * LC_LOG2E;     // log2(e) / sqrt(128)
+        // softmax state of head `sub` over this group's tokens (lanes sub >= G repeat head G-1)
+        float m_run = LC_NEG_INF, l_run = 0.f;
+        float acc[G][8];
 #pragma unroll
         for (int g = 0; g < G; ++g) {
-            m[g] = LC_NEG_INF;
-            l[g] = 0.f;
 #pragma unroll
             for (int i = 0; i < 8; ++i) acc[g][i] = 0.f;
         }
-        const uint16_t* Kb = a.K + (size_t)b * a.ks_seq + (size_t)h * a.ks_head;
-        const uint16_t* Vb = a.V + (size_t)b * a.ks_seq + (size_t)h * a.ks_head;
+        // K and V of this (sequence, head) as buffer resources: one 32-bit byte offset per row
+        // (the host has checked that the slab spans less than 2 GiB)
+        const __amdgpu_buffer_rsrc_t Kr = lc_buffer(a.K + (size_t)b * a.ks_seq + (size_t)h * a.ks_head);
+        const __amdgpu_buffer_rsrc_t Vr = lc_buffer(a.V + (size_t)b * a.ks_seq + (size_t)h * a.ks_head);
+        const int row_bytes = (int)a.ks_tok * 2;
 
-        // K and V rows of up to U tokens starting at position tt of the tile, all loads issued at once
-        int t_end = 0;
-        auto issue = [&](int tt, uint4 (&kv)[U], uint4 (&vv)[U]) {
+        // A lane loads K for token (sub & 3) of group (sub >> 2) of its wavefront -- row `sub` of the
+        // MFMA A operand -- and V for the tokens of its own group.
+        const int gk = (wave << 2) + (sub >> 2), uk = sub & 3;
+        int tv = 0, tv_end = 0, tk = 0, tk_end = 0;
+        auto issue = [&](int it, lc_v4i (&kv)[4], lc_v4i (&vv)[U]) {
+            const int k_tok = tk + it * U + uk;
+            if (uk < U && k_tok < tk_end) {
+                const int ko = rows[k_tok] * row_bytes + 16 * q4;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) kv[j] = __builtin_amdgcn_raw_buffer_load_b128(Kr, ko + 64 * j, 0, 0);
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) kv[j] = lc_v4i{0, 0, 0, 0};
+            }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                if (tt + u < t_end) {
-                    const long long row = rows[tt + u];
-                    kv[u] = *reinterpret_cast<const uint4*>(Kb + row * a.ks_tok + 8 * sub);
-                    vv[u] = *reinterpret_cast<const uint4*>(Vb + row * a.ks_tok + 8 * sub);
-                }
+                const int v_tok = tv + it * U + u;
+                if (v_tok < tv_end)
+                    vv[u] = __builtin_amdgcn_raw_buffer_load_b128(Vr, rows[v_tok] * row_bytes + 16 * sub, 0, 0);
+                else
+                    vv[u] = lc_v4i{0, 0, 0, 0};
             }
         };
-        // logits of the U tokens for the G heads, one online-softmax update, then P.V
-        auto consume = [&](int tt, const uint4 (&kv)[U], const uint4 (&vv)[U]) {
-            float x[U][G];
+        // logits of the wavefront's 16 tokens for all heads (MFMA), one online-softmax update of
+        // this lane's head, then P.V for every head with the broadcast probabilities
+        auto consume = [&](int it, const lc_v4i (&kv)[4], const lc_v4i (&vv)[U]) {
+            lc_f32x4 d = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(lc_bf16x8, kv[j]),
+                                                            __builtin_bit_cast(lc_bf16x8, qb[j]), d, 0, 0, 0);
+            // d[i]: token 4 q4 + i of the wavefront = token i of this lane's group, head `sub`
+            float x[U];
+            float mx = m_run;
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const bool live = tt + u < t_end;
-                float kf[8];
-                if (live) lc_unpack8(kv[u], kf);
-#pragma unroll
-                for (int g = 0; g < G; ++g) {
-                    float p = 0.f;
-                    if (live) {
-#pragma unroll
-                        for (int i = 0; i < 8; ++i) p = fmaf(kf[i], qf[g][i], p);
-                    }
-                    p = lc_sum16(p);
-                    x[u][g] = live ? p : LC_NEG_INF;
-                }
+                x[u] = (tv + it * U + u < tv_end) ? d[u] * scale : LC_NEG_INF;
+                mx = fmaxf(mx, x[u]);
             }
+            const float ref = (mx == LC_NEG_INF) ? 0.f : mx;
+            const float sc = lc_exp2_rel(m_run, ref);
+            float p[U];
+            float psum = 0.f;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                p[u] = lc_exp2_rel(x[u], ref);
+                psum += p[u];
+            }
+            l_run = fmaf(l_run, sc, psum);
+            m_run = mx;
 #pragma unroll
             for (int g = 0; g < G; ++g) {
-                float mx = m[g];
+                const float sg = lc_row_bcast_n(sc, g);
 #pragma unroll
-                for (int u = 0; u < U; ++u) mx = fmaxf(mx, x[u][g]);
-                const float sc = exp2f(m[g] - mx);          // m = -inf, mx finite: 0
-                m[g] = mx;
-                l[g] *= sc;
-#pragma unroll
-                for (int i = 0; i < 8; ++i) acc[g][i] *= sc;
+                for (int i = 0; i < 8; ++i) acc[g][i] *= sg;
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                if (tt + u < t_end) {
-                    float vf[8];
-                    lc_unpack8(vv[u], vf);
+                float vf[8];
+                {
+                    const int v0 = vv[u].x, v1 = vv[u].y, v2 = vv[u].z, v3 = vv[u].w;
+                    lc_unpack8(make_uint4((uint32_t)v0, (uint32_t)v1, (uint32_t)v2, (uint32_t)v3), vf);
+                }
 #pragma unroll
-                    for (int g = 0; g < G; ++g) {
-                        const float p = exp2f(x[u][g] - m[g]);
-                        l[g] += p;
+                for (int g = 0; g < G; ++g) {
+                    const float pg = lc_row_bcast_n(p[u], g);
 #pragma unroll
-                        for (int i = 0; i < 8; ++i) acc[g][i] = fmaf(p, vf[i], acc[g][i]);
-                    }
+                    for (int i = 0; i < 8; ++i) acc[g][i] = fmaf(pg, vf[i], acc[g][i]);
                 }
             }
         };
 
         LC_STAMP0(lc_dbg_decode, 8);
         // The split's tokens are handled in tiles; for each tile the workgroup first writes the cache
-        // row of every token into LDS (one binary search over the run table per token, in parallel),
-        // then every group streams a contiguous slice of the tile with two batches of loads in flight.
+        // row of every token into LDS (the few entries that overlap the tile go into a window, then
+        // one small binary search per token, in parallel), then every group streams a contiguous
+        // slice of the tile.
         for (int tile0 = lo; tile0 < hi; tile0 += LC_DEC_TILE) {
             const int tl = min(LC_DEC_TILE, hi - tile0);
-            __syncthreads();
-            for (int i = tid; i < tl; i += LC_DEC_THREADS) {
-                const int tok = tile0 + i;
-                int lo_r = 0, hi_r = n_runs;            // run_off[lo_r] <= tok < run_off[hi_r]
-                while (hi_r - lo_r > 1) {
-                    const int mid = (lo_r + hi_r) >> 1;
-                    if (run_off[mid] <= tok) lo_r = mid; else hi_r = mid;
+            // phase 0 finds the entry that holds the tile's first token, phase 1 copies the entries
+            // that overlap the tile into the window (at most one per token, plus an empty tail)
+            for (int phase = 0; phase < 2; ++phase) {
+                __syncthreads();
+                const int first = phase ? win_hd[0] : 0;
+                auto visit = [&](int base, int off, const int (&st)[E], const int (&ln)[E]) {
+#pragma unroll
+                    for (int e = 0; e < E; ++e) {
+                        const int i = base + tid * E + e;
+                        if (phase == 0) {
+                            if (off <= tile0 && tile0 < off + ln[e]) win_hd[0] = i;
+                        } else if (i >= first && off < tile0 + tl && i < n_runs) {
+                            const int w = i - first;
+                            if (w < LC_DEC_TILE + 2) { win_off[w] = off; win_st[w] = st[e]; }
+                            if (off + ln[e] >= tile0 + tl && ln[e] > 0) win_hd[1] = min(w + 1, LC_DEC_TILE + 2);
+                        }
+                        off += ln[e];
+                    }
+                };
+                visit(0, ex0, st0, ln0);
+                int carry = tot0;
+                for (int base = LC_DEC_THREADS * E; base < n_runs; base += LC_DEC_THREADS * E) {
+                    int st[E], ln[E], tot;
+                    const int ex = lc_block_scan<LC_DEC_THREADS>(entries(base, false, st, ln), scan_sh, &tot);
+                    visit(base, carry + ex, st, ln);
+                    carry += tot;
                 }
-                rows[i] = run_start[lo_r] + (tok - run_off[lo_r]);
             }
             __syncthreads();
+            {
+                const int n_win = win_hd[1];
+                const int row_max = max(T - 1, 0);
+                for (int i = tid; i < tl; i += LC_DEC_THREADS) {
+                    const int tok = tile0 + i;
+                    int lo_w = 0, hi_w = n_win;             // win_off[lo_w] <= tok < win_off[hi_w]
+                    while (hi_w - lo_w > 1) {
+                        const int mid = (lo_w + hi_w) >> 1;
+                        if (win_off[mid] <= tok) lo_w = mid; else hi_w = mid;
+                    }
+                    rows[i] = max(0, min(win_st[lo_w] + (tok - win_off[lo_w]), row_max));
+                }
+            }
+            __syncthreads();
+            LC_STAMP0(lc_dbg_decode, 9);
             const int per = (tl + LC_DEC_GROUPS - 1) / LC_DEC_GROUPS;
-            int t = min(tl, grp * per);
-            t_end = min(tl, t + per);
-            uint4 kA[U], vA[U], kB[U], vB[U];
-            if (t < t_end) issue(t, kA, vA);
-            while (t < t_end) {
-                if (t + U < t_end) issue(t + U, kB, vB);
-                consume(t, kA, vA);
-                t += U;
-                if (t >= t_end) break;
-                if (t + U < t_end) issue(t + U, kA, vA);
-                consume(t, kB, vB);
-                t += U;
+            const int n_it = (per + U - 1) / U;            // the same for every wavefront: the MFMA needs all lanes
+            tv = min(tl, grp * per);
+            tv_end = min(tl, tv + per);
+            tk = min(tl, gk * per);
+            tk_end = min(tl, tk + per);
+            lc_v4i kA[4], vA[U], kB[4], vB[U];
+            issue(0, kA, vA);
+            for (int it = 0; it < n_it; it += 2) {
+                if (it + 1 < n_it) issue(it + 1, kB, vB);
+                consume(it, kA, vA);
+                LC_STAMP0(lc_dbg_decode, 10);
+                if (it + 1 >= n_it) break;
+                if (it + 2 < n_it) issue(it + 2, kA, vA);
+                consume(it + 1, kB, vB);
             }
         }
 
@@ -224,26 +307,28 @@ lc_decode_kernel(const LcDecodeArgs a) {
         // ---- combine the 4 groups of a wave (xor 16, 32), then the waves through LDS
 #pragma unroll
         for (int off = 16; off < 64; off <<= 1) {
+            const float m_o = __shfl_xor(m_run, off);
+            const float l_o = __shfl_xor(l_run, off);
+            const float mx = fmaxf(m_run, m_o);
+            const float ref = (mx == LC_NEG_INF) ? 0.f : mx;
+            const float sa = lc_exp2_rel(m_run, ref);
+            const float sb = lc_exp2_rel(m_o, ref);
+            l_run = l_run * sa + l_o * sb;
+            m_run = mx;
 #pragma unroll
             for (int g = 0; g < G; ++g) {
-                const float m_o = __shfl_xor(m[g], off);
-                const float l_o = __shfl_xor(l[g], off);
-                const float mx = fmaxf(m[g], m_o);
-                const float sa = (m[g] == LC_NEG_INF) ? 0.f : exp2f(m[g] - mx);
-                const float sb = (m_o == LC_NEG_INF) ? 0.f : exp2f(m_o - mx);
-                l[g] = l[g] * sa + l_o * sb;
+                const float sag = lc_row_bcast_n(sa, g), sbg = lc_row_bcast_n(sb, g);
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
                     const float a_o = __shfl_xor(acc[g][i], off);
-                    acc[g][i] = acc[g][i] * sa + a_o * sb;
+                    acc[g][i] = acc[g][i] * sag + a_o * sbg;
                 }
-                m[g] = mx;
             }
         }
         if (lane < 16) {
+            if (lane < G) { comb_ml[wave][lane][0] = m_run; comb_ml[wave][lane][1] = l_run; }
 #pragma unroll
             for (int g = 0; g < G; ++g) {
-                if (lane == 0) { comb_ml[wave][g][0] = m[g]; comb_ml[wave][g][1] = l[g]; }
 #pragma unroll
                 for (int i = 0; i < 8; ++i) comb_acc[wave][g][8 * lane + i] = acc[g][i];
             }
@@ -356,11 +441,7 @@ lc_decode_kernel(const LcDecodeArgs a) {
 
 template <int G>
 static int launch_decode_g(const LcDecodeArgs& a, int splits, hipStream_t stream) {
-    const size_t lds = (size_t)(2 * a.id_cap_lds + 4) * sizeof(int);
-    if (lds > 48 * 1024)
-        LC_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&lc_decode_kernel<G>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    hipLaunchKernelGGL(lc_decode_kernel<G>, dim3(splits, a.ix.H, a.ix.B), dim3(LC_DEC_THREADS), lds, stream, a);
+    hipLaunchKernelGGL(lc_decode_kernel<G>, dim3(splits, a.ix.H, a.ix.B), dim3(LC_DEC_THREADS), 0, stream, a);
     LC_HIP_CHECK(hipGetLastError());
     return LC_OK;
 }
@@ -383,11 +464,6 @@ int lc_launch_decode(const lc_index* idx, const LcWs& ws, const void* q, const v
     a.part_ml = ws.part_ml;
     a.out = out;
     a.lse = lse;
-    int max_M = 0;
-    for (int b = 0; b < idx->B; ++b)
-        if (idx->M[b] > max_M) max_M = idx->M[b];
-    a.id_cap_lds = cap < max_M ? cap : max_M;          // a (sequence, head) never lists more ids than it has chunks
-    if (a.id_cap_lds < 1) a.id_cap_lds = 1;
     switch (G) {
         case 1: return launch_decode_g<1>(a, splits, stream);
         case 2: return launch_decode_g<2>(a, splits, stream);

@@ -19,7 +19,6 @@
 #include "lc_device.h"
 #include "lc_internal.h"
 
-#define LC_LEAF_CHUNKS_PER_BLOCK 64
 #define LC_TAU_SLACK 1e-3f
 #define LC_COUNT_SELECT_MAX 1024         // up to this many candidates the O(n^2 / threads) rank is used
 
@@ -417,18 +416,201 @@ lc_upper_kernel(const LcRetrieveArgs a) {
     LC_STAMP0(lc_dbg_upper, 7);
 }
 
+// Kernel 2 runs 1024 threads = 64 groups: one chunk per group while scoring; the last workgroup
+// has enough threads to hold a few keys each during the select.
+#define LC_LF_THREADS 1024
+#define LC_LF_THREADS_MAX LC_LF_THREADS
+#define LC_LF_GROUPS (LC_LF_THREADS / 16)
+
+// ---------------------------------------------------------------------------------
+// budget selection over the staged chunk keys (last workgroup of kernel 2)
+// ---------------------------------------------------------------------------------
+// Candidates are the chunks with key != 0, ordered by (key descending, id ascending); the
+// selection is the longest prefix with total length <= W and at most C chunks.
+//   1. One histogram pass over 1024 bins that span [lowest, highest] candidate key linearly
+//      (length and count per bin), a descending scan finds the bin in which the prefix ends.
+//   2. That bin usually holds a handful of chunks: they are copied to a short list and ranked
+//      against each other directly (16 lanes per chunk), which decides each of them exactly.
+//      A bin with more chunks than the list holds is split again (step 1 on its key range); a
+//      bin that is a single key value is a tie group and is cut by a scan in id order.
+// On return chunk i is selected iff skey[i] > thr: the chunks of the last bin have had their key
+// replaced by 0xffffffff (selected) or 0 (not).
+#define LC_LS_BITS 10
+#define LC_LS_BINS (1 << LC_LS_BITS)
+#define LC_LS_CAND 256
+struct LcLeafSelSh {
+    int hw[LC_LS_BINS];
+    int hc[LC_LS_BINS];
+    uint32_t ck[LC_LS_CAND];
+    int cl[LC_LS_CAND];
+    int ci[LC_LS_CAND];
+    int scan[2 * (LC_LF_THREADS_MAX / 64)];
+    int mm[2 * (LC_LF_THREADS_MAX / 64)];
+    int res[4];
+    int ncand;
+};
+
+// exclusive prefix sums of two values over the workgroup, sharing the barriers
+template <int NT>
+__device__ __forceinline__ void lc_block_scan2(int a, int b, int* sh, int* ea, int* eb) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int ia = a, ib = b;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int ta = __shfl_up(ia, off), tb = __shfl_up(ib, off);
+        if (lane >= off) { ia += ta; ib += tb; }
+    }
+    __syncthreads();                 // protect sh from the previous use
+    if (lane == 63) { sh[wave] = ia; sh[NT / 64 + wave] = ib; }
+    __syncthreads();
+    int ba = 0, bb = 0;
+#pragma unroll
+    for (int w = 0; w < NT / 64; ++w) {
+        if (w < wave) { ba += sh[w]; bb += sh[NT / 64 + w]; }
+    }
+    *ea = ba + ia - a;
+    *eb = bb + ib - b;
+}
+
+template <int NT>
+__device__ __forceinline__ uint32_t lc_leaf_select(int n, uint32_t* skey, const int* slen, long long W, long long C,
+                                                   uint32_t kmin, uint32_t kmax, LcLeafSelSh& sh) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    LC_SEL_STAMP(0);
+    kmin = lc_wave_min_u(kmin);
+    kmax = lc_wave_max_u(kmax);
+    if (lane == 0) { sh.mm[wave] = (int)kmin; sh.mm[NT / 64 + wave] = (int)kmax; }
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < NT / 64; ++w) { kmin = min(kmin, (uint32_t)sh.mm[w]); kmax = max(kmax, (uint32_t)sh.mm[NT / 64 + w]); }
+    if (kmax == 0u) return 0u;                                   // no candidate at all
+    int remW = (int)(W > 0x7fffffffLL ? 0x7fffffffLL : (W < 0 ? 0 : W));
+    int remC = (int)(C > 0x7fffffffLL ? 0x7fffffffLL : (C < 0 ? 0 : C));
+    uint32_t lo = kmin, hi = kmax;
+    int pass = 0;
+    (void)pass;
+    for (;;) {
+        LC_SEL_STAMP(1 + 4 * pass);
+        const uint32_t span = hi - lo;
+        const int bits = span ? 32 - __clz(span) : 0;
+        const int shift = bits > LC_LS_BITS ? bits - LC_LS_BITS : 0;     // (span >> shift) < LC_LS_BINS
+        for (int i = tid; i < LC_LS_BINS; i += NT) { sh.hw[i] = 0; sh.hc[i] = 0; }
+        if (tid == 0) { sh.res[0] = -1; sh.ncand = 0; }
+        __syncthreads();
+        for (int i = tid; i < n; i += NT) {
+            const uint32_t k = skey[i];
+            if (k >= lo && k <= hi) {
+                const int bin = (int)((k - lo) >> shift);
+                atomicAdd(&sh.hw[bin], slen[i]);
+                atomicAdd(&sh.hc[bin], 1);
+            }
+        }
+        __syncthreads();
+        LC_SEL_STAMP(2 + 4 * pass);
+        // descending scan: thread t looks at bin 1023 - t (at PER consecutive bins with fewer threads)
+        constexpr int PER = LC_LS_BINS / NT;
+        int w[PER], c[PER], sw = 0, sc = 0;
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            const int bin = LC_LS_BINS - 1 - (tid * PER + j);
+            w[j] = sh.hw[bin];
+            c[j] = sh.hc[bin];
+            sw += w[j];
+            sc += c[j];
+        }
+        int cw, cc;
+        lc_block_scan2<NT>(sw, sc, sh.scan, &cw, &cc);       // length / count of all higher bins
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            // the prefix ends in the first bin that no longer fits: everything above it fits, it does not
+            if (cw <= remW && cc <= remC && ((long long)cw + w[j] > remW || cc + c[j] > remC)) {
+                sh.res[0] = LC_LS_BINS - 1 - (tid * PER + j);
+                sh.res[1] = cw;
+                sh.res[2] = cc;
+                sh.res[3] = c[j];
+            }
+            cw += w[j];
+            cc += c[j];
+        }
+        __syncthreads();
+        LC_SEL_STAMP(3 + 4 * pass);
+        const int fb = sh.res[0];
+        if (fb < 0) return lo - 1u;                               // every candidate in scope fits
+        remW -= sh.res[1];
+        remC -= sh.res[2];
+        const int nc = sh.res[3];
+        const uint32_t blo = lo + ((uint32_t)fb << shift);
+        const unsigned long long bend = (unsigned long long)blo + ((1ull << shift) - 1ull);
+        const uint32_t bhi = bend < (unsigned long long)hi ? (uint32_t)bend : hi;
+        if (nc <= LC_LS_CAND) {
+            // ---- short list, ranked directly
+            for (int i = tid; i < n; i += NT) {
+                const uint32_t k = skey[i];
+                if (k >= blo && k <= bhi) {
+                    const int pos = atomicAdd(&sh.ncand, 1);
+                    if (pos < LC_LS_CAND) { sh.ck[pos] = k; sh.cl[pos] = slen[i]; sh.ci[pos] = i; }
+                }
+            }
+            __syncthreads();
+            LC_SEL_STAMP(4 + 4 * pass);
+            const int part = tid & 15;
+            for (int c0 = 0; c0 < nc; c0 += NT / 16) {
+                const int me = c0 + (tid >> 4);
+                const bool valid = me < nc;
+                const uint32_t km = valid ? sh.ck[me] : 0u;
+                const int im = valid ? sh.ci[me] : 0;
+                const int lm = valid ? sh.cl[me] : 0;
+                int wb = 0, cb = 0;
+                for (int j = part; j < nc; j += 16) {
+                    const uint32_t kj = sh.ck[j];
+                    const bool before = kj > km || (kj == km && sh.ci[j] < im);
+                    wb += before ? sh.cl[j] : 0;
+                    cb += before ? 1 : 0;
+                }
+                wb = lc_sum16_i(wb);
+                cb = lc_sum16_i(cb);
+                if (valid && part == 0) skey[im] = ((long long)wb + lm <= remW && cb + 1 <= remC) ? 0xffffffffu : 0u;
+            }
+            __syncthreads();
+            return bhi;
+        }
+        if (blo == bhi) {
+            // ---- a tie group too large for the list: cut it in id order
+            int E = (n + NT - 1) / NT;
+            E |= 1;                                               // odd stride: no LDS bank conflicts
+            const int i0 = min(n, tid * E), i1 = min(n, i0 + E);
+            int my_w = 0, my_c = 0;
+            for (int i = i0; i < i1; ++i)
+                if (skey[i] == blo) { my_w += slen[i]; my_c += 1; }
+            int tw, tc;
+            lc_block_scan2<NT>(my_w, my_c, sh.scan, &tw, &tc);
+            long long rw = tw;
+            int rc = tc;
+            for (int i = i0; i < i1; ++i) {
+                if (skey[i] == blo) {
+                    rw += slen[i];
+                    rc += 1;
+                    skey[i] = (rw <= remW && rc <= remC) ? 0xffffffffu : 0u;
+                }
+            }
+            __syncthreads();
+            return bhi;
+        }
+        lo = blo;
+        hi = bhi;
+        ++pass;
+        __syncthreads();
+    }
+}
+
 // ---------------------------------------------------------------------------------
 // kernel 2: chunk scoring + budget selection by the last workgroup
 // ---------------------------------------------------------------------------------
-// 1024 threads = 64 groups: one chunk per group while scoring; the last workgroup has
-// enough threads to hold a few keys each during the select.
-#define LC_LF_THREADS 1024
-#define LC_LF_GROUPS (LC_LF_THREADS / 16)
-template <int G>
+template <int G, int R>
 __global__ void __launch_bounds__(LC_LF_THREADS)
 lc_leaf_kernel(const LcRetrieveArgs a) {
     extern __shared__ int lds_dyn[];
-    __shared__ int sel_sh[LC_SEL_SH];
+    __shared__ LcLeafSelSh sel_sh;
     __shared__ int last_sh;
 
     const LcDev& ix = a.ix;
@@ -445,12 +627,12 @@ lc_leaf_kernel(const LcRetrieveArgs a) {
 
     LC_STAMP0(lc_dbg_leaf, 0);
     // loads that do not depend on M are issued together with it (the arrays are cap0 long)
-    const int j_lo = blockIdx.x * LC_LEAF_CHUNKS_PER_BLOCK;
-    int jj[LC_LEAF_CHUNKS_PER_BLOCK / LC_LF_GROUPS];
-    int wv[LC_LEAF_CHUNKS_PER_BLOCK / LC_LF_GROUPS];
-    float rv[LC_LEAF_CHUNKS_PER_BLOCK / LC_LF_GROUPS];
+    const int j_lo = blockIdx.x * (R * LC_LF_GROUPS);
+    int jj[R];
+    int wv[R];
+    float rv[R];
 #pragma unroll
-    for (int r = 0; r < LC_LEAF_CHUNKS_PER_BLOCK / LC_LF_GROUPS; ++r) {
+    for (int r = 0; r < R; ++r) {
         const int j = min(j_lo + r * LC_LF_GROUPS + grp, ix.cap[0] - 1);
         jj[r] = j;
         wv[r] = have_want ? (int)want[j] : (bnd[j] >= a.sink ? 1 : 0);
@@ -463,15 +645,15 @@ lc_leaf_kernel(const LcRetrieveArgs a) {
         if (a.budget > 0) {
             float qf[G][8], qn[G];
             lc_load_query_frags<G>(a.q + (size_t)b * ix.H * G * LC_D, h, sub, qf, qn);
-            float sv[LC_LEAF_CHUNKS_PER_BLOCK / LC_LF_GROUPS];
+            float sv[R];
 #pragma unroll
-            for (int r = 0; r < LC_LEAF_CHUNKS_PER_BLOCK / LC_LF_GROUPS; ++r) {
+            for (int r = 0; r < R; ++r) {
                 const int j = j_lo + r * LC_LF_GROUPS + grp;
                 sv[r] = LC_NEG_INF;
                 if (j < M && wv[r]) sv[r] = lc_score_node<G>(ix.center[0] + (cb + jj[r]) * LC_D, rv[r], sub, qf, qn);
             }
 #pragma unroll
-            for (int r = 0; r < LC_LEAF_CHUNKS_PER_BLOCK / LC_LF_GROUPS; ++r) {
+            for (int r = 0; r < R; ++r) {
                 const int j = j_lo + r * LC_LF_GROUPS + grp;
                 if (j < M && sub == 0) {
                     lc_store_agent(&keys[j], lc_score_key(sv[r]));
@@ -479,7 +661,7 @@ lc_leaf_kernel(const LcRetrieveArgs a) {
                 }
             }
         } else {
-            for (int j = j_lo + tid; j < min(M, j_lo + LC_LEAF_CHUNKS_PER_BLOCK); j += LC_LF_THREADS) {
+            for (int j = j_lo + tid; j < min(M, j_lo + (R * LC_LF_GROUPS)); j += LC_LF_THREADS) {
                 lc_store_agent(&keys[j], 0u);
                 if (scores) scores[j] = LC_NEG_INF;
             }
@@ -514,52 +696,26 @@ lc_leaf_kernel(const LcRetrieveArgs a) {
     __syncthreads();
 
     LC_STAMP(lc_dbg_leaf, 4);
-    auto keyf = [&](int i) -> uint32_t { return skey[i]; };
-    auto wf = [&](int i) -> int { return slen[i]; };
     const long long C = (a.policy == LC_POLICY_BEAM && a.beam[0] > 0) ? a.beam[0] : 0x7fffffffLL;
-    const LcSel r = lc_block_select<LC_LF_THREADS>(M, a.budget > 0 ? (long long)a.budget : 0LL, C, keyf, wf, sel_sh,
-                                                   true, kmin, kmax);
+    const uint32_t thr = lc_leaf_select<LC_LF_THREADS>(M, skey, slen, a.budget > 0 ? (long long)a.budget : 0LL, C,
+                                                       kmin, kmax, sel_sh);
 
     LC_STAMP(lc_dbg_leaf, 5);
-    // each thread owns a contiguous run of chunks: one scan for the ties, one for the output slots
+    // each thread owns a contiguous run of chunks, so the ids come out ascending: count, scan, write
     int E = (M + LC_LF_THREADS - 1) / LC_LF_THREADS;
     E |= 1;                                             // odd stride: no LDS bank conflicts
     const int lo = min(M, tid * E), hi = min(M, lo + E);
-    int my_tie_w = 0, my_tie_c = 0;
-    for (int i = lo; i < hi; ++i) {
-        const uint32_t k = skey[i];
-        if (!r.all && k != 0u && k == r.kstar) { my_tie_w += slen[i]; my_tie_c += 1; }
-    }
-    // tie prefixes in ascending id: weights always, counts only when a count limit is set
-    int tot_w, tot_c;
-    int tie_w0, tie_c0;
-    tie_w0 = lc_block_scan<LC_LF_THREADS>(my_tie_w, sel_sh, &tot_w);
-    if (C < 0x7fffffffLL) tie_c0 = lc_block_scan<LC_LF_THREADS>(my_tie_c, sel_sh, &tot_c);
-    else tie_c0 = 0;                     // no count limit: remC is "infinite", the count never binds
-    // selected(i): pinned, or above the cutoff key, or a tie that still fits (ties in ascending id)
-    auto walk = [&](bool emit, int pos, int32_t* ids) -> int {
-        int tw = tie_w0, tc = tie_c0, n_sel = 0;
-        for (int i = lo; i < hi; ++i) {
-            const uint32_t k = skey[i];
-            const int ln = slen[i];
-            int sel = (ln < 0) ? 1 : ((k != 0u && k > r.kstar) ? 1 : 0);
-            if (ln >= 0 && !r.all && k != 0u && k == r.kstar) {
-                tw += ln;
-                tc += 1;
-                if (tw <= r.remW && tc <= r.remC) sel = 1;
-            }
-            if (sel) {
-                if (emit && pos + n_sel < a.cap) ids[pos + n_sel] = i;
-                ++n_sel;
-            }
-        }
-        return n_sel;
-    };
-    int32_t* ids = a.ids + (size_t)bh * a.cap;
-    const int my_sel = walk(false, 0, ids);
+    int my_sel = 0;
+    for (int i = lo; i < hi; ++i) my_sel += (slen[i] < 0 || skey[i] > thr) ? 1 : 0;
     int tot_s;
-    const int pos = lc_block_scan<LC_LF_THREADS>(my_sel, sel_sh, &tot_s);
-    walk(true, pos, ids);
+    int pos = lc_block_scan<LC_LF_THREADS>(my_sel, sel_sh.scan, &tot_s);
+    int32_t* ids = a.ids + (size_t)bh * a.cap;
+    for (int i = lo; i < hi; ++i) {
+        if (slen[i] < 0 || skey[i] > thr) {
+            if (pos < a.cap) ids[pos] = i;
+            ++pos;
+        }
+    }
     LC_STAMP(lc_dbg_leaf, 6);
     if (tid == 0) {
         a.counts[bh] = min(tot_s, a.cap);
@@ -570,6 +726,18 @@ lc_leaf_kernel(const LcRetrieveArgs a) {
 // ---------------------------------------------------------------------------------
 // launcher
 // ---------------------------------------------------------------------------------
+template <int G, int R>
+static int launch_leaf(const LcRetrieveArgs& a, int max_M, size_t lds, hipStream_t stream) {
+    if (lds > 48 * 1024)
+        LC_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&lc_leaf_kernel<G, R>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    const int per = R * LC_LF_GROUPS;
+    const int nblk = max_M > 0 ? (max_M + per - 1) / per : 1;
+    hipLaunchKernelGGL((lc_leaf_kernel<G, R>), dim3(nblk, a.ix.H, a.ix.B), dim3(LC_LF_THREADS), lds, stream, a);
+    LC_HIP_CHECK(hipGetLastError());
+    return LC_OK;
+}
+
 template <int G>
 static int launch_retrieve_g(LcRetrieveArgs& a, int max_M, hipStream_t stream) {
     const LcDev& ix = a.ix;
@@ -588,15 +756,20 @@ static int launch_retrieve_g(LcRetrieveArgs& a, int max_M, hipStream_t stream) {
         hipLaunchKernelGGL(lc_upper_kernel<G>, dim3(ix.H, ix.B), dim3(LC_UP_THREADS), lds, stream, a);
         LC_HIP_CHECK(hipGetLastError());
     }
-    a.chunk_cap = ((size_t)mc * 8 <= lds_limit) ? mc : 0;
+    a.chunk_cap = ((size_t)mc * 8 + sizeof(LcLeafSelSh) + 1024 <= lds_limit) ? mc : 0;
     const size_t lds2 = (size_t)a.chunk_cap * 8;
-    if (lds2 > 48 * 1024)
-        LC_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&lc_leaf_kernel<G>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2));
-    const int nblk = max_M > 0 ? (max_M + LC_LEAF_CHUNKS_PER_BLOCK - 1) / LC_LEAF_CHUNKS_PER_BLOCK : 1;
-    hipLaunchKernelGGL(lc_leaf_kernel<G>, dim3(nblk, ix.H, ix.B), dim3(LC_LF_THREADS), lds2, stream, a);
-    LC_HIP_CHECK(hipGetLastError());
-    return LC_OK;
+    // chunks per group: the fewest for which there is at most one workgroup per compute unit
+    // (measured: beyond that the kernel gets slower, not faster)
+    int r = 1;
+#ifdef LC_LEAF_FORCE_R
+    r = LC_LEAF_FORCE_R;
+#else
+    while (r < 8 && (long long)((max_M + 64 * r - 1) / (64 * r)) * ix.H * ix.B > 256) r *= 2;
+#endif
+    if (r == 1) return launch_leaf<G, 1>(a, max_M, lds2, stream);
+    if (r == 2) return launch_leaf<G, 2>(a, max_M, lds2, stream);
+    if (r == 4) return launch_leaf<G, 4>(a, max_M, lds2, stream);
+    return launch_leaf<G, 8>(a, max_M, lds2, stream);
 }
 
 int lc_launch_retrieve(const lc_index* idx, const LcWs& ws, const void* q, int G, int budget,

@@ -63,10 +63,11 @@ class Case:
 def make_case(w: wl.Workload, tails: Optional[Sequence[int]] = None, extra_tokens: int = 0,
               extra_chunks: int = 0, geometry: int = orc.TOKEN_BALL, build_on: str = "oracle",
               offset_std: float = 0.5, noise_std: float = 1.0, cap: Optional[int] = None,
-              decode_splits: int = 0, prune: int = 1) -> Case:
+              decode_splits: int = 0, prune: int = 1, mutate=None) -> Case:
     """build_on = "oracle": the oracle builds the index and the GPU imports it (identical
     stored values on both sides); "gpu": lc_build_index builds it (the oracle index is still
-    built for comparison)."""
+    built for comparison).  `mutate(seqs)` may edit the drawn sequences in place before anything
+    is built from them."""
     import torch
     from paper_2603_08453_amd import binding as lc
 
@@ -80,6 +81,8 @@ def make_case(w: wl.Workload, tails: Optional[Sequence[int]] = None, extra_token
             keep = max(1, min(keep, len(s.bounds) - 1))
             s.bounds = s.bounds[: keep + 1].copy()
         seqs.append(s)
+    if mutate is not None:
+        mutate(seqs)
     Tmax = max(s.T for s in seqs)
     Mmax = max(len(s.bounds) - 1 for s in seqs)
     Tcap = Tmax + extra_tokens

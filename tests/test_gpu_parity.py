@@ -220,6 +220,55 @@ def test_pruning_happens_and_stays_exact(G):
     assert np.all(scored < M)
 
 
+def test_select_with_a_large_tie_group(G):
+    """q = 0 makes every chunk score equal: several hundred chunks tie at the cutoff, more than the
+    selection's short list holds, so the cut is made in id order by a scan."""
+    w = wl.tiny("ties", levels=2, fanout=8, T=4000, chunk_lo=4, chunk_hi=12, H_q=4, H_kv=2, budget=1000)
+    case = G.make_case(w)
+    M = case.oidx[0][0].M
+    assert M > 300
+    q0 = np.zeros_like(_q_batch(case, 0))
+    lens = case.oidx[0][0].lens()
+    for budget in (0, 7, 1000, 2500, 10 ** 6):
+        ids = _check_retrieve(G, case, q0, budget, tag="ties")
+        k = int(np.searchsorted(np.cumsum(lens), budget, side="right"))
+        assert all(ids[0][h].tolist() == list(range(k)) for h in range(w.H_kv)), budget
+    # a chunk-count limit cuts the same tie group
+    ids = _check_retrieve(G, case, q0, 10 ** 6, policy=orc.POLICY_BEAM, beam=[300, 0], tag="ties beam")
+    assert all(ids[0][h].tolist() == list(range(300)) for h in range(w.H_kv))
+    ids = _check_retrieve(G, case, q0, 600, policy=orc.POLICY_BEAM, beam=[300, 0], sink=30, tag="ties beam sink")
+    from paper_2603_08453_amd import binding as lc
+    lc.lc_set_policy(case.idx, lc.LC_POLICY_EXACT, None, 0)
+
+
+def test_select_with_a_crowded_score_range(G):
+    """One chunk with a very negative score stretches the score range so far that thousands of
+    chunks share a few histogram bins: the bin holding the cutoff must be split again."""
+    w = wl.tiny("crowded", levels=2, fanout=8, T=9000, chunk_lo=2, chunk_hi=4, H_q=2, H_kv=1, budget=600)
+
+    def outlier(seqs):
+        for s in seqs:
+            q = wl.bf16_bits_to_f64(s.Q[0])                                  # [H_q][d]
+            u = -(q / np.linalg.norm(q, axis=1, keepdims=True)).sum(axis=0)
+            c = (len(s.bounds) - 1) // 2
+            rows = slice(int(s.bounds[c]), int(s.bounds[c + 1]))
+            s.K[0, rows] = wl.f32_to_bf16_bits((40.0 * u).astype(np.float32))[None, :]
+
+    case = G.make_case(w, mutate=outlier)
+    qb = _q_batch(case, 0)
+    oi = case.oidx[0][0]
+    s_ref = orc.node_scores(oi, 0, wl.bf16_bits_to_f64(qb[0]))
+    pos = s_ref[s_ref > 0]
+    _say(f"crowded: M={oi.M}, min score {s_ref.min():.2f}, positive scores {pos.min():.3f}..{pos.max():.3f}")
+    assert s_ref.min() < -1.0 and len(pos) > 2500 and pos.max() / pos.min() < 16.0
+    for prune in (0, 2):
+        from paper_2603_08453_amd import binding as lc
+        lc.lc_set_prune(case.idx, prune)
+        for budget in (3, 600, 5000, 10 ** 6):
+            ids = _check_retrieve(G, case, qb, budget, tag=f"crowded prune={prune}")
+        _check_decode(G, case, qb, ids, tag="crowded")
+
+
 def test_paper_literal_algorithm1(G):
     """The paper's own configuration of Algorithm 1: unit-norm representatives with radius 0
     (PAPER_UNIT), top-k_g coarse units then top-k_c fine clusters (BEAM), *all* chunks of the kept
