@@ -445,7 +445,7 @@ struct LcLeafSelSh {
     int cl[LC_LS_CAND];
     int ci[LC_LS_CAND];
     int scan[2 * (LC_LF_THREADS_MAX / 64)];
-    int mm[2 * (LC_LF_THREADS_MAX / 64)];
+    int mm[2];                     // lowest / highest candidate key
     int res[4];
     int ncand;
 };
@@ -472,31 +472,46 @@ __device__ __forceinline__ void lc_block_scan2(int a, int b, int* sh, int* ea, i
     *eb = bb + ib - b;
 }
 
+// Called by every thread before the keys are staged: empties the histogram and the key range.
+template <int NT>
+__device__ __forceinline__ void lc_leaf_select_prepare(LcLeafSelSh& sh) {
+    for (int i = threadIdx.x; i < LC_LS_BINS; i += NT) { sh.hw[i] = 0; sh.hc[i] = 0; }
+    if (threadIdx.x == 0) { sh.res[0] = -1; sh.ncand = 0; sh.mm[0] = (int)0xffffffffu; sh.mm[1] = 0; }
+}
+// Called by every thread with the range of the candidate keys it staged (0xffffffff / 0 if none);
+// a barrier must follow before lc_leaf_select.
+__device__ __forceinline__ void lc_leaf_select_range(uint32_t kmin, uint32_t kmax, LcLeafSelSh& sh) {
+    kmin = min(kmin, lc_dpp_u<0xB1>(kmin)); kmin = min(kmin, lc_dpp_u<0x4E>(kmin));
+    kmin = min(kmin, lc_dpp_u<0x141>(kmin)); kmin = min(kmin, lc_dpp_u<0x140>(kmin));
+    kmax = max(kmax, lc_dpp_u<0xB1>(kmax)); kmax = max(kmax, lc_dpp_u<0x4E>(kmax));
+    kmax = max(kmax, lc_dpp_u<0x141>(kmax)); kmax = max(kmax, lc_dpp_u<0x140>(kmax));
+    if ((threadIdx.x & 15) == 0 && kmax != 0u) {
+        atomicMin(reinterpret_cast<unsigned int*>(&sh.mm[0]), kmin);
+        atomicMax(reinterpret_cast<unsigned int*>(&sh.mm[1]), kmax);
+    }
+}
+
 template <int NT>
 __device__ __forceinline__ uint32_t lc_leaf_select(int n, uint32_t* skey, const int* slen, long long W, long long C,
-                                                   uint32_t kmin, uint32_t kmax, LcLeafSelSh& sh) {
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+                                                   LcLeafSelSh& sh) {
+    const int tid = threadIdx.x;
     LC_SEL_STAMP(0);
-    kmin = lc_wave_min_u(kmin);
-    kmax = lc_wave_max_u(kmax);
-    if (lane == 0) { sh.mm[wave] = (int)kmin; sh.mm[NT / 64 + wave] = (int)kmax; }
-    __syncthreads();
-#pragma unroll
-    for (int w = 0; w < NT / 64; ++w) { kmin = min(kmin, (uint32_t)sh.mm[w]); kmax = max(kmax, (uint32_t)sh.mm[NT / 64 + w]); }
+    const uint32_t kmin = (uint32_t)sh.mm[0], kmax = (uint32_t)sh.mm[1];
     if (kmax == 0u) return 0u;                                   // no candidate at all
     int remW = (int)(W > 0x7fffffffLL ? 0x7fffffffLL : (W < 0 ? 0 : W));
     int remC = (int)(C > 0x7fffffffLL ? 0x7fffffffLL : (C < 0 ? 0 : C));
     uint32_t lo = kmin, hi = kmax;
     int pass = 0;
-    (void)pass;
     for (;;) {
         LC_SEL_STAMP(1 + 4 * pass);
         const uint32_t span = hi - lo;
         const int bits = span ? 32 - __clz(span) : 0;
         const int shift = bits > LC_LS_BITS ? bits - LC_LS_BITS : 0;     // (span >> shift) < LC_LS_BINS
-        for (int i = tid; i < LC_LS_BINS; i += NT) { sh.hw[i] = 0; sh.hc[i] = 0; }
-        if (tid == 0) { sh.res[0] = -1; sh.ncand = 0; }
-        __syncthreads();
+        if (pass > 0) {                                                  // the first pass was prepared by the caller
+            for (int i = tid; i < LC_LS_BINS; i += NT) { sh.hw[i] = 0; sh.hc[i] = 0; }
+            if (tid == 0) { sh.res[0] = -1; sh.ncand = 0; }
+            __syncthreads();
+        }
         for (int i = tid; i < n; i += NT) {
             const uint32_t k = skey[i];
             if (k >= lo && k <= hi) {
@@ -638,19 +653,31 @@ lc_leaf_kernel(const LcRetrieveArgs a) {
         wv[r] = have_want ? (int)want[j] : (bnd[j] >= a.sink ? 1 : 0);
         rv[r] = ix.radius[0][cb + j];
     }
+    // Without a level walk every chunk below M is scored, so its center can be fetched right away
+    // instead of one memory round trip later (with a walk the centers of pruned chunks are the
+    // traffic the walk exists to save, so there the load waits for the verdict).
+    constexpr bool kSpec = R <= 2 || (R == 4 && G <= 7);      // as far as the registers of a 1024-thread workgroup go
+    LcNodeFrag pre[kSpec ? R : 1];
+    if (kSpec && !have_want) {
+#pragma unroll
+        for (int r = 0; r < (kSpec ? R : 1); ++r) pre[r] = lc_load_node(ix.center[0] + (cb + jj[r]) * LC_D, sub);
+    }
+    float qf[G][8], qn[G];
+    lc_load_query_frags<G>(a.q + (size_t)b * ix.H * G * LC_D, h, sub, qf, qn);
     const int M = ix.state[bh * 4 + 1];
 
     LC_STAMP0(lc_dbg_leaf, 1);
     if (j_lo < M) {
         if (a.budget > 0) {
-            float qf[G][8], qn[G];
-            lc_load_query_frags<G>(a.q + (size_t)b * ix.H * G * LC_D, h, sub, qf, qn);
             float sv[R];
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 const int j = j_lo + r * LC_LF_GROUPS + grp;
                 sv[r] = LC_NEG_INF;
-                if (j < M && wv[r]) sv[r] = lc_score_node<G>(ix.center[0] + (cb + jj[r]) * LC_D, rv[r], sub, qf, qn);
+                if (j < M && wv[r]) {
+                    if (kSpec && !have_want) sv[r] = lc_score_frag<G>(pre[kSpec ? r : 0], rv[r], qf, qn);
+                    else sv[r] = lc_score_node<G>(ix.center[0] + (cb + jj[r]) * LC_D, rv[r], sub, qf, qn);
+                }
             }
 #pragma unroll
             for (int r = 0; r < R; ++r) {
@@ -670,6 +697,9 @@ lc_leaf_kernel(const LcRetrieveArgs a) {
 
     LC_STAMP0(lc_dbg_leaf, 2);
     // ---- last workgroup of this (sequence, head) selects
+    // (every workgroup empties its select histogram on the way: whichever turns out to be the last
+    // finds it ready behind the barriers of the arrival)
+    lc_leaf_select_prepare<LC_LF_THREADS>(sel_sh);
     if (!lc_arrive_last(&ix.sync[bh * 4 + 0], (int)gridDim.x, &last_sh)) return;
 
     LC_STAMP(lc_dbg_leaf, 3);
@@ -693,24 +723,37 @@ lc_leaf_kernel(const LcRetrieveArgs a) {
         slen[j] = (s0 < a.sink) ? -1 : (s1 - s0);
         if (k != 0u) { kmin = min(kmin, k); kmax = max(kmax, k); }
     }
+    lc_leaf_select_range(kmin, kmax, sel_sh);
     __syncthreads();
 
     LC_STAMP(lc_dbg_leaf, 4);
     const long long C = (a.policy == LC_POLICY_BEAM && a.beam[0] > 0) ? a.beam[0] : 0x7fffffffLL;
     const uint32_t thr = lc_leaf_select<LC_LF_THREADS>(M, skey, slen, a.budget > 0 ? (long long)a.budget : 0LL, C,
-                                                       kmin, kmax, sel_sh);
+                                                       sel_sh);
 
     LC_STAMP(lc_dbg_leaf, 5);
     // each thread owns a contiguous run of chunks, so the ids come out ascending: count, scan, write
     int E = (M + LC_LF_THREADS - 1) / LC_LF_THREADS;
     E |= 1;                                             // odd stride: no LDS bank conflicts
     const int lo = min(M, tid * E), hi = min(M, lo + E);
+    // (the verdicts of up to 64 chunks stay in a register mask; longer runs read LDS again)
+    unsigned long long mask = 0ull;
     int my_sel = 0;
-    for (int i = lo; i < hi; ++i) my_sel += (slen[i] < 0 || skey[i] > thr) ? 1 : 0;
+    for (int i = lo; i < hi; ++i) {
+        const bool sel = slen[i] < 0 || skey[i] > thr;
+        if (sel && i - lo < 64) mask |= 1ull << (i - lo);
+        my_sel += sel ? 1 : 0;
+    }
     int tot_s;
     int pos = lc_block_scan<LC_LF_THREADS>(my_sel, sel_sh.scan, &tot_s);
     int32_t* ids = a.ids + (size_t)bh * a.cap;
-    for (int i = lo; i < hi; ++i) {
+    while (mask) {
+        const int k = __ffsll((long long)mask) - 1;
+        mask &= mask - 1ull;
+        if (pos < a.cap) ids[pos] = lo + k;
+        ++pos;
+    }
+    for (int i = lo + 64; i < hi; ++i) {
         if (slen[i] < 0 || skey[i] > thr) {
             if (pos < a.cap) ids[pos] = i;
             ++pos;
