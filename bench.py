@@ -1,8 +1,9 @@
 """Benchmark of the LycheeCluster decode hot path on one MI355X.
 
-A step = one decode step of one attention layer over the whole batch:
-lc_retrieve (Eq. 2 scoring, pruning, budget selection) followed by
-lc_sparse_decode (split-K attention over the selected chunks + merge).
+A step = one decode step of one attention layer over the whole batch: Eq. 2 scoring of the
+chunks (with pruning when the index is large), budget selection, split-K attention over the
+selected chunks and the merge -- by default through lc_decode_step (two kernels, the second one
+selects and attends), with --separate through lc_retrieve followed by lc_sparse_decode.
 Inputs are seeded synthetic tensors, resident in HBM before the timed region.
 To keep the numbers honest about HBM, consecutive steps walk over several
 replicas of (K, V, index) whose total footprint exceeds the 256 MB last-level
@@ -39,6 +40,7 @@ def parse():
     ap.add_argument("--queries", type=int, default=16)
     ap.add_argument("--policy", default="exact", choices=["exact", "beam"])
     ap.add_argument("--splits", type=int, default=0)
+    ap.add_argument("--separate", action="store_true", help="time lc_retrieve + lc_sparse_decode instead of lc_decode_step")
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
@@ -123,9 +125,15 @@ def main():
         rp = reps[i % R]
         lc.lc_sparse_decode(rp["idx"], Qs[i % nq], rp["K"], rp["V"], ids_q[i % nq], counts_q[i % nq], out, rp["ws"])
 
-    def step(i):
+    def step_separate(i):
         retrieve(i)
         attend(i)
+
+    def step_fused(i):
+        rp = reps[i % R]
+        lc.lc_decode_step(rp["idx"], Qs[i % nq], rp["K"], rp["V"], w.budget, out, rp["ws"])
+
+    step = step_separate if args.separate else step_fused
 
     # ------------------------------------------------------------- algorithmic bytes
     # attended tokens per query (the index replicas are identical, so one pass over the queries suffices)
@@ -212,10 +220,11 @@ def main():
         wall = (time.perf_counter() - t) / total
         return e0.elapsed_time(e1) * 1e3 / total, wall
 
-    graph_s = attend_us = retrieve_us = None
+    graph_s = attend_us = retrieve_us = separate_s = None
     if not args.no_graph:
         try:
             _, graph_s = graph_us_per_launch(step, args.steps)
+            _, separate_s = graph_us_per_launch(step_separate, args.steps)
             attend_us, _ = graph_us_per_launch(attend, args.steps)
             retrieve_us, _ = graph_us_per_launch(retrieve, args.steps)
             for i in range(nq):           # leave ids consistent with the queries again
@@ -240,6 +249,22 @@ def main():
             attend(i)
         torch.cuda.synchronize()
         retrieve_us = float(np.mean([e0.elapsed_time(e1) for e0, e1 in ev])) * 1e3
+
+    # the two kernels of lc_decode_step, timed with an event the library records between them
+    n_ev = min(args.steps, 512)
+    evs = [tuple(torch.cuda.Event(enable_timing=True) for _ in range(3)) for _ in range(n_ev)]
+    for i, (e0, em, e1) in enumerate(evs):
+        rp = reps[i % R]
+        em.record()                     # creates the event (torch does that lazily); the library records it again
+        lc.lc_set_probe_event(rp["idx"], em)
+        e0.record()
+        step_fused(i)
+        e1.record()
+    torch.cuda.synchronize()
+    for rp in reps:
+        lc.lc_set_probe_event(rp["idx"], None)
+    score_us = float(np.mean([e0.elapsed_time(em) for e0, em, e1 in evs])) * 1e3
+    fused_us = float(np.mean([em.elapsed_time(e1) for e0, em, e1 in evs])) * 1e3
 
     # the same step with the level-by-level walk forced on (EXACT: same ids, more kernels), and with the
     # paper's per-level top-k (BEAM: 4 nodes kept at each internal level but 16 at level 1)
@@ -268,8 +293,11 @@ def main():
     # warm (cache-resident) figure: one replica, one query
     def step_warm(i):
         rp = reps[0]
-        lc.lc_retrieve(rp["idx"], Qs[0], w.budget, ids_q[0], counts_q[0], rp["ws"])
-        lc.lc_sparse_decode(rp["idx"], Qs[0], rp["K"], rp["V"], ids_q[0], counts_q[0], out, rp["ws"])
+        if args.separate:
+            lc.lc_retrieve(rp["idx"], Qs[0], w.budget, ids_q[0], counts_q[0], rp["ws"])
+            lc.lc_sparse_decode(rp["idx"], Qs[0], rp["K"], rp["V"], ids_q[0], counts_q[0], out, rp["ws"])
+        else:
+            lc.lc_decode_step(rp["idx"], Qs[0], rp["K"], rp["V"], w.budget, out, rp["ws"])
     for i in range(20):
         step_warm(i)
     warm_s = timed(step_warm, min(args.steps, 500))
@@ -327,8 +355,14 @@ def main():
                          f"oracle index build {cpu_build_s:.1f} s per (sequence, head), not included"}
 
     from paper_2603_08453_amd.profsum import read_traffic
-    traffic = read_traffic(os.path.join(ROOT, "profiles", f"lc_decode_step_{w.name}_hbm_traffic.md"),
-                           f"lc_decode_kernel<{G}>")
+    # dominant kernel: the attention kernel (of lc_decode_step: it also repeats the selection, whose
+    # algorithmic input is one key and one boundary pair per chunk and head)
+    if args.separate:
+        dom_name, dom_us, dom_bytes = f"lc_decode_kernel<{G}, false>", attend_us, attend_bytes
+    else:
+        select_bytes = sum(len(bn) - 1 for bn in bounds_np) * w.H_kv * 12
+        dom_name, dom_us, dom_bytes = f"lc_decode_kernel<{G}, true>", fused_us, attend_bytes + select_bytes
+    traffic = read_traffic(os.path.join(ROOT, "profiles", f"lc_decode_step_{w.name}_hbm_traffic.md"), dom_name)
     res = {
         "metric": "us per decode step per layer (retrieve+attend), 128K ctx" if w.name.startswith("C3") else
                   "us per decode step per layer (retrieve+attend)",
@@ -346,12 +380,13 @@ def main():
         "config": {"workload": w.name, "batch": w.B, "q_heads": w.H_q, "kv_heads": w.H_kv, "head_dim": w.d,
                    "context": Tmax, "chunks": Mmax, "levels": w.levels, "fanout": w.fanout, "budget": w.budget,
                    "policy": args.policy, "replicas": R, "queries": nq,
+                   "entry": "lc_retrieve+lc_sparse_decode" if args.separate else "lc_decode_step",
                    "launch": "hip-graph" if best_s == graph_s else "eager"},
-        "roofline": {"bound": "hbm", "achieved": round(attend_bytes / (attend_us * 1e-6) / 1e9, 1),
+        "roofline": {"bound": "hbm", "achieved": round(dom_bytes / (dom_us * 1e-6) / 1e9, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(attend_bytes / (attend_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
-                     "traffic": traffic, "kernel": "lc_decode_kernel",
-                     "bytes_per_launch": round(attend_bytes), "us_per_launch": round(attend_us, 2)},
+                     "frac": round(dom_bytes / (dom_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+                     "traffic": traffic, "kernel": dom_name,
+                     "bytes_per_launch": round(dom_bytes), "us_per_launch": round(dom_us, 2)},
         "cpu_baseline": cpu,
         "extra": {
             "eager_us": round(eager_s * 1e6, 2),
@@ -359,6 +394,10 @@ def main():
             "warm_cache_us": round(warm_s * 1e6, 2),
             "level_walk_forced_us": None if walk_us is None else round(walk_us, 2),
             "beam_policy_us": None if beam_us is None else round(beam_us, 2),
+            "entry_points": "lc_retrieve + lc_sparse_decode" if args.separate else "lc_decode_step",
+            "separate_calls_us": None if separate_s is None else round(separate_s * 1e6, 2),
+            "score_kernels_us_event": round(score_us, 2),
+            "select_attend_kernel_us_event": round(fused_us, 2),
             "retrieve_us_event": round(retrieve_us, 2),
             "attend_us_event": round(attend_us, 2),
             "append_us": round(append_us, 2),

@@ -141,6 +141,11 @@ int lc_set_policy(lc_index* idx, int policy, const int32_t* beam /* host, LC_MAX
 /* Change the pruning mode (LC_PRUNE_*) of an existing index (host state only). */
 int lc_set_prune(lc_index* idx, int prune);
 
+/* Measurement aid (host state only): `event` is a hipEvent_t, or NULL to clear.  While set,
+ * lc_decode_step records it on its stream between its two kernels, so that a caller who brackets
+ * the call with events of its own can time each kernel.  Not for use under graph capture. */
+int lc_set_probe_event(lc_index* idx, void* event);
+
 /*
  * lc_retrieve -- hierarchical retrieval for one decode step (Eq. 2, Algorithm 1
  * steps 1-2).  Per (sequence, KV head) every node u gets the group score
@@ -178,6 +183,27 @@ int lc_sparse_decode(const lc_index* idx, const void* q, const void* K, const vo
                      const int64_t kv_strides[3],
                      const int32_t* chunk_ids, const int32_t* counts, int cap, int H_q,
                      float* out, float* lse, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * lc_decode_step -- lc_retrieve followed by lc_sparse_decode in one call (Algorithm 1
+ * steps 1-3; Eq. 2 scoring, budgeted selection, Eq. 1 over the active set), for
+ * callers that do not need the chunk list between the two.  Same selection (bit
+ * for bit) and same attention result as the two calls.  The chunk score keys go
+ * from the scoring kernel to the attention kernel through the workspace; every
+ * workgroup of the attention kernel repeats the selection of its (sequence,
+ * head) from them, so no chunk list travels through memory on the critical path.
+ * When a sequence has more chunks than the attention kernel can stage in LDS
+ * (several thousand; depends on G) the call runs the kernels of the two separate
+ * entry points instead.
+ *
+ *   chunk_ids, counts  optional outputs as in lc_retrieve (both or neither); cap
+ *                      is checked only when they are given
+ *   everything else    as in lc_retrieve / lc_sparse_decode
+ */
+int lc_decode_step(const lc_index* idx, const void* q, const void* K, const void* V,
+                   const int64_t kv_strides[3], int H_q, int budget,
+                   float* out, float* lse, int32_t* chunk_ids, int32_t* counts, int cap,
+                   void* ws, size_t ws_bytes, void* stream);
 
 /*
  * lc_append -- lazy update for one streamed token per sequence (Section 4.4,

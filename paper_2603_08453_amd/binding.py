@@ -97,6 +97,11 @@ def lib() -> ctypes.CDLL:
     L.lc_sparse_decode.argtypes = [vp, vp, vp, vp, i64p, vp, vp, ctypes.c_int, ctypes.c_int, vp, vp,
                                    vp, ctypes.c_size_t, vp]
     L.lc_sparse_decode.restype = ctypes.c_int
+    L.lc_decode_step.argtypes = [vp, vp, vp, vp, i64p, ctypes.c_int, ctypes.c_int, vp, vp, vp, vp, ctypes.c_int,
+                                 vp, ctypes.c_size_t, vp]
+    L.lc_decode_step.restype = ctypes.c_int
+    L.lc_set_probe_event.argtypes = [vp, vp]
+    L.lc_set_probe_event.restype = ctypes.c_int
     L.lc_append.argtypes = [vp, vp, vp, i64p, vp, vp, u8p, vp, ctypes.c_size_t, vp]
     L.lc_append.restype = ctypes.c_int
     L.lc_index_info.argtypes = [vp, ctypes.c_int, i32p, i32p, i32p]
@@ -239,6 +244,23 @@ def lc_sparse_decode(idx: Index, q, K, V, chunk_ids, counts, out, ws, lse=None, 
                                 cap, H_q, _ptr(out), _ptr(lse), _ptr(ws), ws.numel() * ws.element_size(),
                                 _stream(stream))
     _check(rc, "lc_sparse_decode")
+
+
+def lc_set_probe_event(idx: Index, event) -> None:
+    """event: a recorded-capable torch.cuda.Event (timing enabled) or None."""
+    handle = None if event is None else int(event.cuda_event)
+    _check(lib().lc_set_probe_event(idx.handle, handle), "lc_set_probe_event")
+
+
+def lc_decode_step(idx: Index, q, K, V, budget: int, out, ws, lse=None, chunk_ids=None, counts=None,
+                   stream=None) -> None:
+    """q bf16 [B][H_q][d]; out f32 [B][H_q][d]; optional chunk_ids int32 [B][H_kv][cap] + counts."""
+    assert K.shape == V.shape and K.stride() == V.stride()
+    H_q = int(q.shape[1])
+    cap = int(chunk_ids.shape[-1]) if chunk_ids is not None else 0
+    _check(lib().lc_decode_step(idx.handle, _ptr(q), _ptr(K), _ptr(V), _strides3(K), H_q, int(budget), _ptr(out),
+                                _ptr(lse), _ptr(chunk_ids), _ptr(counts), cap, _ptr(ws),
+                                ws.numel() * ws.element_size(), _stream(stream)), "lc_decode_step")
 
 
 def lc_append(idx: Index, K, V, k_new, v_new, close_chunk: Optional[Sequence[int]], ws, stream=None) -> None:

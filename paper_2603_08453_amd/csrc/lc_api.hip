@@ -97,6 +97,8 @@ size_t lc_layout_ws(const lc_config* cfg, int B, int H_q, int H, int d, int spli
     W->keys = c.take<uint32_t>(BH * cap[0]);
     W->want = c.take<uint8_t>(BH * cap[0]);
     W->scratch = c.take<int>(BH * 4 * cap[0]);
+    W->ids_tmp = c.take<int32_t>(BH * cap[0]);
+    W->counts_tmp = c.take<int32_t>(BH);
     W->part_acc = c.take<float>((size_t)B * H_q * splits * d);
     W->part_ml = c.take<float>((size_t)B * H_q * splits * 2);
     W->dirs = c.take<float>(BH * cap[0] * d);
@@ -291,6 +293,12 @@ int lc_set_prune(lc_index* idx, int prune) {
     return LC_OK;
 }
 
+int lc_set_probe_event(lc_index* idx, void* event) {
+    if (!idx) return LC_ERR_INVALID_ARG;
+    idx->probe = static_cast<hipEvent_t>(event);
+    return LC_OK;
+}
+
 int lc_index_info(const lc_index* idx, int b, int32_t* T, int32_t* M, int32_t* n_per_level) {
     if (!idx || b < 0 || b >= idx->B) return LC_ERR_INVALID_ARG;
     if (T) *T = idx->T[b];
@@ -310,6 +318,38 @@ static int common_decode_checks(const lc_index* idx, const void* q, int H_q, int
     return LC_OK;
 }
 
+namespace {
+// What a retrieval over the current index needs: sizes, the capacity check, walk or flat scan.
+struct RetrievePlan {
+    int max_M = 0;
+    int max_upper = 0;
+    bool walk = false;
+};
+int plan_retrieve(const lc_index* idx, int budget, int cap, bool check_cap, RetrievePlan* p) {
+    long long leaf_bytes = 0;
+    for (int b = 0; b < idx->B; ++b) {
+        const int M = idx->M[b];
+        if (M > p->max_M) p->max_M = M;
+        leaf_bytes += (long long)M * idx->H_kv * (idx->d * 4 + 8);
+        // every chunk holds >= 1 token: at most `budget` chunks fit, plus the pinned ones
+        long long need = (long long)budget + idx->cfg.sink_tokens;
+        if (need > M) need = M;
+        if (check_cap && cap < need) return LC_ERR_CAPACITY;
+        int up = 0;
+        for (int l = 1; l < idx->cfg.levels; ++l) up += idx->N[(size_t)b * LC_MAX_LEVELS + l];
+        if (up > p->max_upper) p->max_upper = up;
+    }
+    if (p->max_upper > 8192) return LC_ERR_CAPACITY;       // internal nodes of one (sequence, head) live in LDS
+    // walk the internal levels?  BEAM: always.  EXACT: by mode; the result does not depend on it.
+    p->walk = idx->cfg.levels > 1;
+    if (p->walk && idx->cfg.policy == LC_POLICY_EXACT) {
+        if (idx->cfg.prune == LC_PRUNE_NEVER) p->walk = false;
+        else if (idx->cfg.prune == LC_PRUNE_AUTO) p->walk = leaf_bytes > (long long)LC_PRUNE_AUTO_BYTES;
+    }
+    return LC_OK;
+}
+}  // namespace
+
 int lc_retrieve(const lc_index* idx, const void* q, int H_q, int budget, int32_t* chunk_ids, int32_t* counts,
                 float* scores, int cap, void* ws, size_t ws_bytes, void* stream) {
     int rc = common_decode_checks(idx, q, H_q, cap);
@@ -320,31 +360,60 @@ int lc_retrieve(const lc_index* idx, const void* q, int H_q, int budget, int32_t
     const int splits = lc_auto_splits(&idx->cfg, idx->B, idx->H_kv);
     if (ws_bytes < lc_layout_ws(&idx->cfg, idx->B, H_q, idx->H_kv, idx->d, splits, nullptr, nullptr))
         return LC_ERR_WORKSPACE_TOO_SMALL;
-    int max_M = 0, max_upper = 0;
-    long long leaf_bytes = 0;
-    for (int b = 0; b < idx->B; ++b) {
-        const int M = idx->M[b];
-        if (M > max_M) max_M = M;
-        leaf_bytes += (long long)M * idx->H_kv * (idx->d * 4 + 8);
-        // every chunk holds >= 1 token: at most `budget` chunks fit, plus the pinned ones
-        long long need = (long long)budget + idx->cfg.sink_tokens;
-        if (need > M) need = M;
-        if (cap < need) return LC_ERR_CAPACITY;
-        int up = 0;
-        for (int l = 1; l < idx->cfg.levels; ++l) up += idx->N[(size_t)b * LC_MAX_LEVELS + l];
-        if (up > max_upper) max_upper = up;
-    }
-    if (max_upper > 8192) return LC_ERR_CAPACITY;       // internal nodes of one (sequence, head) live in LDS
+    RetrievePlan p;
+    rc = plan_retrieve(idx, budget, cap, true, &p);
+    if (rc) return rc;
     LcWs w;
     lc_layout_ws(&idx->cfg, idx->B, H_q, idx->H_kv, idx->d, splits, ws, &w);
-    // walk the internal levels?  BEAM: always.  EXACT: by mode; the result does not depend on it.
-    bool walk = idx->cfg.levels > 1;
-    if (walk && idx->cfg.policy == LC_POLICY_EXACT) {
-        if (idx->cfg.prune == LC_PRUNE_NEVER) walk = false;
-        else if (idx->cfg.prune == LC_PRUNE_AUTO) walk = leaf_bytes > (long long)LC_PRUNE_AUTO_BYTES;
+    return lc_launch_retrieve(idx, w, q, H_q / idx->H_kv, budget, chunk_ids, counts, scores, cap, p.max_M,
+                              p.walk ? p.max_upper : -1, 0, static_cast<hipStream_t>(stream));
+}
+
+int lc_decode_step(const lc_index* idx, const void* q, const void* K, const void* V, const int64_t kv_strides[3],
+                   int H_q, int budget, float* out, float* lse, int32_t* chunk_ids, int32_t* counts, int cap,
+                   void* ws, size_t ws_bytes, void* stream) {
+    const bool want_ids = chunk_ids != nullptr;
+    int rc = common_decode_checks(idx, q, H_q, want_ids ? cap : 1);
+    if (rc) return rc;
+    if (!K || !V || !out || !ws || budget < 0) return LC_ERR_INVALID_ARG;
+    if (want_ids != (counts != nullptr)) return LC_ERR_INVALID_ARG;
+    rc = check_strides(kv_strides);
+    if (rc) return rc;
+    if (!aligned16(K) || !aligned16(V) || (reinterpret_cast<uintptr_t>(ws) & 255u)) return LC_ERR_INVALID_ARG;
+    if ((long long)idx->cfg.max_tokens * kv_strides[2] * 2 >= (1LL << 31)) return LC_ERR_BAD_SHAPE;
+    const int splits = lc_auto_splits(&idx->cfg, idx->B, idx->H_kv);
+    if (ws_bytes < lc_layout_ws(&idx->cfg, idx->B, H_q, idx->H_kv, idx->d, splits, nullptr, nullptr))
+        return LC_ERR_WORKSPACE_TOO_SMALL;
+    RetrievePlan p;
+    rc = plan_retrieve(idx, budget, cap, want_ids, &p);
+    if (rc) return rc;
+    LcWs w;
+    lc_layout_ws(&idx->cfg, idx->B, H_q, idx->H_kv, idx->d, splits, ws, &w);
+    const int G = H_q / idx->H_kv;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (lc_decode_fused_fits(G, p.max_M)) {
+        // kernel 1 (and the level walk before it) leaves the chunk score keys in the workspace;
+        // kernel 2 selects from them in every workgroup and attends
+        rc = lc_launch_retrieve(idx, w, q, G, budget, nullptr, nullptr, nullptr, 1, p.max_M,
+                                p.walk ? p.max_upper : -1, 1, st);
+        if (rc) return rc;
+        if (idx->probe) LC_HIP_CHECK(hipEventRecord(idx->probe, st));
+        return lc_launch_decode_fused(idx, w, q, K, V, kv_strides, G, splits, budget, chunk_ids, counts,
+                                      want_ids ? cap : 0, p.max_M, out, lse, st);
     }
-    return lc_launch_retrieve(idx, w, q, H_q / idx->H_kv, budget, chunk_ids, counts, scores, cap, max_M,
-                              walk ? max_upper : -1, static_cast<hipStream_t>(stream));
+    // too many chunks to stage in LDS: the two kernels of lc_retrieve + lc_sparse_decode, with the
+    // chunk list in the caller's buffer or, without one, in the workspace
+    int32_t* ids = want_ids ? chunk_ids : w.ids_tmp;
+    int32_t* cnt = want_ids ? counts : w.counts_tmp;
+    int icap = cap;
+    if (!want_ids) {
+        int cap0 = idx->cfg.max_chunks;
+        icap = cap0 < 1 ? 1 : cap0;
+    }
+    rc = lc_launch_retrieve(idx, w, q, G, budget, ids, cnt, nullptr, icap, p.max_M, p.walk ? p.max_upper : -1, 0, st);
+    if (rc) return rc;
+    if (idx->probe) LC_HIP_CHECK(hipEventRecord(idx->probe, st));
+    return lc_launch_decode(idx, w, q, K, V, kv_strides, ids, cnt, icap, G, splits, out, lse, st);
 }
 
 int lc_sparse_decode(const lc_index* idx, const void* q, const void* K, const void* V, const int64_t kv_strides[3],

@@ -11,6 +11,8 @@
 //   other 15 lanes of the group by DPP row broadcasts.
 //   P.V stays on the vector ALU: lane n of a group holds columns [8n, 8n + 8) of a
 //   V row (one 16-byte load), four rows make a full 1 KiB wavefront load.
+#include <type_traits>
+
 #include "lc_device.h"
 #include "lc_internal.h"
 
@@ -19,6 +21,8 @@
 #define LC_DEC_MIN_TOKENS_PER_SPLIT 64
 #define LC_DEC_MAX_SPLITS 256
 #define LC_DEC_TILE 1024          // tokens of a split whose cache rows are resolved into LDS at a time
+#define LC_DEC_WIN 2048           // slots of the entry window of a tile: a power of two above LC_DEC_TILE + 2
+#define LC_DEC_SPEC 12            // fused step: chunks per thread staged before the chunk count has arrived
 #define LC_DEC_E 2                // selected ids per thread and pass of the row resolution
 #define LC_LOG2E 1.4426950408889634f
 #define LC_LN2 0.6931471805599453f
@@ -41,6 +45,12 @@ struct LcDecodeArgs {
     float* part_ml;       // [B][H][S][G][2]
     float* out;           // [B][H*G][d]
     float* lse;           // [B][H*G] or null
+    // fused step only (the kernel selects the chunks itself from their score keys):
+    const uint32_t* keys; // [B][H][cap0] score keys of the chunks (0 = not a candidate)
+    int32_t* ids_out;     // [B][H][cap] selected ids, ascending, or null
+    int32_t* counts_out;  // [B][H] or null
+    int budget, sink, count_limit;   // token budget, pinned prefix, chunk-count limit (0 = none)
+    int chunk_cap;        // LDS entries of the staged chunk arrays
 };
 
 // Value of lane `src` (0..15) of the caller's 16-lane row, in every lane of the row.
@@ -63,14 +73,20 @@ __device__ __forceinline__ float lc_row_bcast_n(float v, int src) {      // src 
 // exp2 of (x - ref) where x may be -inf (gives 0); ref is finite.
 __device__ __forceinline__ float lc_exp2_rel(float x, float ref) { return exp2f(x - ref); }
 
-template <int G>
+// FUSED = false: the chunk list comes from a.ids / a.counts.  FUSED = true: every workgroup first
+// repeats the budget selection of its (sequence, head) from the chunk score keys -- the same
+// deterministic routine on the same keys, so all splits agree -- and never reads a chunk list.
+template <int G, bool FUSED>
 __global__ void __launch_bounds__(LC_DEC_THREADS)
 lc_decode_kernel(const LcDecodeArgs a) {
+    extern __shared__ int lds_dyn[];             // FUSED: staged key, length, first row of every chunk
+    using SelStore = typename std::conditional<FUSED, LcLeafSelSh, int>::type;
+    __shared__ SelStore sel_store;
     __shared__ int scan_sh[8];
     __shared__ int rows[LC_DEC_TILE];
-    __shared__ int win_off[LC_DEC_TILE + 2];      // first token position of the entries that overlap the tile
-    __shared__ int win_st[LC_DEC_TILE + 2];       // and their first cache row
-    __shared__ int win_hd[2];                     // {index of the tile's first entry, entries in the window}
+    __shared__ int win_off[LC_DEC_WIN];           // first token position of the entries that overlap the tile
+    __shared__ int win_st[LC_DEC_WIN];            // and their first cache row
+    __shared__ int win_hd[2];                     // indices of the entries holding the tile's first / last token
     __shared__ int last_sh;
     __shared__ float comb_ml[LC_DEC_THREADS / 64][G][2];
     __shared__ __attribute__((aligned(16))) float comb_acc[LC_DEC_THREADS / 64][G][LC_D];
@@ -91,26 +107,30 @@ lc_decode_kernel(const LcDecodeArgs a) {
 
     LC_STAMP0(lc_dbg_decode, 0);
     const int* bnd = ix.bounds + (size_t)b * (ix.cap[0] + 1);
-    const int32_t* ids = a.ids + (size_t)bh * a.cap;
-    // independent loads first: the ids a thread will need are fetched before the count is known,
-    // and so is the query block in MFMA B layout (lane (q4, n): head n, columns 8 q4 + 32 j + [0, 8))
-    int idv[E];
-#pragma unroll
-    for (int e = 0; e < E; ++e) idv[e] = (tid * E + e < a.cap) ? ids[tid * E + e] : 0;
+    // the query block in MFMA B layout (lane (q4, n): head n, columns 8 q4 + 32 j + [0, 8))
     uint4 qb[4];
     {
         const uint16_t* qh = a.q + ((size_t)b * ix.H * G + (size_t)h * G + min(sub, G - 1)) * LC_D + 8 * q4;
 #pragma unroll
         for (int j = 0; j < 4; ++j) qb[j] = *reinterpret_cast<const uint4*>(qh + 32 * j);
     }
-    const int T = ix.state[bh * 4 + 0];
-    const int M = ix.state[bh * 4 + 1];
-    int n_ids = a.counts[bh];
-    n_ids = (M > 0) ? max(0, min(n_ids, a.cap)) : 0;
 
-    // ---- the attended tokens are the selected chunks in list order, then the open tail.  Entry i
-    // of that list is (first cache row, length); thread t of a pass owns entries [E t, E t + E).
-    const int n_runs = n_ids + 1;
+    // ---- the attended tokens are the selected chunks in ascending id order, then the open tail.
+    // Entry i of that list is (first cache row, length).  Both variants end up with: n_runs entries,
+    // n_tok tokens, and a way for each thread to walk the entries it owns with their token offsets.
+    int n_runs, n_tok, T;
+    // FUSED = false: thread t of a pass owns entries [E t, E t + E); the first pass stays in registers
+    const int32_t* ids = nullptr;
+    int n_ids = 0, M = 0;
+    int idv[E], st0[E], ln0[E];
+    int ex0 = 0, tot0 = 0;
+    // FUSED = true: thread t owns the chunks [c0, c1), of which those with skey > thr are selected
+    uint32_t* skey = nullptr;
+    int* slen = nullptr;
+    int* sstart = nullptr;
+    uint32_t thr = 0u;
+    int c0 = 0, c1 = 0, tok_off = 0, cnt_off = 0, my_tok = 0, n_sel = 0, n_sel_tok = 0, tail_st = 0, tail_ln = 0;
+
     auto entries = [&](int base, bool preloaded, int (&st)[E], int (&ln)[E]) -> int {
         int sum = 0;
 #pragma unroll
@@ -130,14 +150,96 @@ lc_decode_kernel(const LcDecodeArgs a) {
         }
         return sum;
     };
-    int st0[E], ln0[E];                     // the first pass stays in registers
-    int tot0;
-    const int ex0 = lc_block_scan<LC_DEC_THREADS>(entries(0, true, st0, ln0), scan_sh, &tot0);
-    int n_tok = tot0;
-    for (int base = LC_DEC_THREADS * E; base < n_runs; base += LC_DEC_THREADS * E) {
-        int st[E], ln[E], tot;
-        lc_block_scan<LC_DEC_THREADS>(entries(base, false, st, ln), scan_sh, &tot);
-        n_tok += tot;
+
+    if constexpr (!FUSED) {
+        ids = a.ids + (size_t)bh * a.cap;
+        // independent loads first: the ids a thread will need are fetched before the count is known
+#pragma unroll
+        for (int e = 0; e < E; ++e) idv[e] = (tid * E + e < a.cap) ? ids[tid * E + e] : 0;
+        T = ix.state[bh * 4 + 0];
+        M = ix.state[bh * 4 + 1];
+        n_ids = a.counts[bh];
+        n_ids = (M > 0) ? max(0, min(n_ids, a.cap)) : 0;
+        n_runs = n_ids + 1;
+        ex0 = lc_block_scan<LC_DEC_THREADS>(entries(0, true, st0, ln0), scan_sh, &tot0);
+        n_tok = tot0;
+        for (int base = LC_DEC_THREADS * E; base < n_runs; base += LC_DEC_THREADS * E) {
+            int st[E], ln[E], tot;
+            lc_block_scan<LC_DEC_THREADS>(entries(base, false, st, ln), scan_sh, &tot);
+            n_tok += tot;
+        }
+    } else {
+        LcLeafSelSh& sel_sh = sel_store;
+        skey = reinterpret_cast<uint32_t*>(lds_dyn);
+        slen = lds_dyn + a.chunk_cap;
+        sstart = lds_dyn + 2 * a.chunk_cap;
+        const uint32_t* keys = a.keys + (size_t)bh * ix.cap[0];
+        lc_leaf_select_prepare<LC_DEC_THREADS>(sel_sh);
+        // the first LC_DEC_SPEC chunks of every thread are fetched before the chunk count is known
+        // (the arrays are as long as the index's capacity), the rest in a loop afterwards
+        const int cap0 = ix.cap[0];
+        uint32_t kq[LC_DEC_SPEC];
+        int b0[LC_DEC_SPEC], b1[LC_DEC_SPEC];
+#pragma unroll
+        for (int u = 0; u < LC_DEC_SPEC; ++u) {
+            kq[u] = 0u;
+            b0[u] = b1[u] = 0;
+            if (u * LC_DEC_THREADS < a.chunk_cap) {            // none of the sequences has more chunks than that
+                const int j = min(tid + u * LC_DEC_THREADS, cap0 - 1);
+                kq[u] = keys[j];
+                b0[u] = bnd[j];
+                b1[u] = bnd[j + 1];
+            }
+        }
+        T = ix.state[bh * 4 + 0];
+        const int M_all = ix.state[bh * 4 + 1];
+        M = min(M_all, a.chunk_cap);
+        tail_st = bnd[M_all];
+        __syncthreads();
+        // stage every chunk: key (pinned chunks get the always-selected mark), length, first row
+        uint32_t kmin = 0xffffffffu, kmax = 0u;
+        auto stage = [&](int j, uint32_t k, int s0, int s1) {
+            if (k == 0xffffffffu) k = 0xfffffffeu;                 // the mark is reserved
+            const bool pinned = s0 < a.sink;
+            skey[j] = pinned ? 0xffffffffu : k;
+            slen[j] = max(0, s1 - s0);
+            sstart[j] = s0;
+            if (!pinned && k != 0u) { kmin = min(kmin, k); kmax = max(kmax, k); }
+        };
+#pragma unroll
+        for (int u = 0; u < LC_DEC_SPEC; ++u) {
+            const int j = tid + u * LC_DEC_THREADS;
+            if (j < M) stage(j, kq[u], b0[u], b1[u]);
+        }
+#pragma unroll 4
+        for (int j = tid + LC_DEC_SPEC * LC_DEC_THREADS; j < M; j += LC_DEC_THREADS) stage(j, keys[j], bnd[j], bnd[j + 1]);
+        lc_leaf_select_range(kmin, kmax, sel_sh);
+        __syncthreads();
+        LC_STAMP0(lc_dbg_decode, 11);
+        const long long C = a.count_limit > 0 ? (long long)a.count_limit : 0x7fffffffLL;
+        thr = lc_leaf_select<LC_DEC_THREADS>(M, skey, slen, a.budget > 0 ? (long long)a.budget : 0LL, C, sel_sh);
+        __syncthreads();
+        LC_STAMP0(lc_dbg_decode, 12);
+        // tokens and chunks selected before this thread's run of chunks
+        int Ec = (M + LC_DEC_THREADS - 1) / LC_DEC_THREADS;
+        Ec |= 1;                                                    // odd stride: no LDS bank conflicts
+        c0 = min(M, tid * Ec);
+        c1 = min(M, c0 + Ec);
+        int my_cnt = 0;
+#pragma unroll 4
+        for (int c = c0; c < c1; ++c)
+            if (skey[c] > thr) { my_tok += slen[c]; my_cnt += 1; }
+        lc_block_scan2<LC_DEC_THREADS>(my_tok, my_cnt, sel_sh.scan, &tok_off, &cnt_off, &n_sel_tok, &n_sel);
+        tail_ln = max(0, T - tail_st);
+        n_tok = n_sel_tok + tail_ln;
+        n_runs = n_sel + 1;
+        if (a.ids_out != nullptr && s == 0) {                       // the chunk list, for callers that want it
+            int32_t* io = a.ids_out + (size_t)bh * a.cap;
+            int r = cnt_off;
+            for (int c = c0; c < c1; ++c)
+                if (skey[c] > thr) { if (r < a.cap) io[r] = c; ++r; }
+            if (tid == 0 && a.counts_out != nullptr) a.counts_out[bh] = min(n_sel, a.cap);
+        }
     }
     LC_STAMP0(lc_dbg_decode, 1);
 
@@ -241,46 +343,63 @@ lc_decode_kernel(const LcDecodeArgs a) {
         // slice of the tile.
         for (int tile0 = lo; tile0 < hi; tile0 += LC_DEC_TILE) {
             const int tl = min(LC_DEC_TILE, hi - tile0);
-            // phase 0 finds the entry that holds the tile's first token, phase 1 copies the entries
-            // that overlap the tile into the window (at most one per token, plus an empty tail)
-            for (int phase = 0; phase < 2; ++phase) {
-                __syncthreads();
-                const int first = phase ? win_hd[0] : 0;
-                auto visit = [&](int base, int off, const int (&st)[E], const int (&ln)[E]) {
-#pragma unroll
-                    for (int e = 0; e < E; ++e) {
-                        const int i = base + tid * E + e;
-                        if (phase == 0) {
-                            if (off <= tile0 && tile0 < off + ln[e]) win_hd[0] = i;
-                        } else if (i >= first && off < tile0 + tl && i < n_runs) {
-                            const int w = i - first;
-                            if (w < LC_DEC_TILE + 2) { win_off[w] = off; win_st[w] = st[e]; }
-                            if (off + ln[e] >= tile0 + tl && ln[e] > 0) win_hd[1] = min(w + 1, LC_DEC_TILE + 2);
-                        }
-                        off += ln[e];
+            // Every entry that overlaps the tile goes into the window at slot (entry index mod window
+            // size) -- overlapping entries are consecutive and fewer than the window is long -- and the
+            // entries that hold the tile's first and last token leave their indices.
+            __syncthreads();
+            {
+                auto entry = [&](int i, int off, int st, int ln) {
+                    if (ln > 0 && off < tile0 + tl && tile0 < off + ln) {
+                        win_off[i & (LC_DEC_WIN - 1)] = off;
+                        win_st[i & (LC_DEC_WIN - 1)] = st;
+                        if (off <= tile0) win_hd[0] = i;
+                        if (tile0 + tl <= off + ln) win_hd[1] = i;
                     }
                 };
-                visit(0, ex0, st0, ln0);
-                int carry = tot0;
-                for (int base = LC_DEC_THREADS * E; base < n_runs; base += LC_DEC_THREADS * E) {
-                    int st[E], ln[E], tot;
-                    const int ex = lc_block_scan<LC_DEC_THREADS>(entries(base, false, st, ln), scan_sh, &tot);
-                    visit(base, carry + ex, st, ln);
-                    carry += tot;
+                if constexpr (!FUSED) {
+                    auto visit = [&](int base, int off, const int (&st)[E], const int (&ln)[E]) {
+#pragma unroll
+                        for (int e = 0; e < E; ++e) {
+                            entry(base + tid * E + e, off, st[e], ln[e]);
+                            off += ln[e];
+                        }
+                    };
+                    visit(0, ex0, st0, ln0);
+                    int carry = tot0;
+                    for (int base = LC_DEC_THREADS * E; base < n_runs; base += LC_DEC_THREADS * E) {
+                        int st[E], ln[E], tot;
+                        const int ex = lc_block_scan<LC_DEC_THREADS>(entries(base, false, st, ln), scan_sh, &tot);
+                        visit(base, carry + ex, st, ln);
+                        carry += tot;
+                    }
+                } else {
+                    // only a thread whose run of chunks overlaps the tile has anything to add
+                    if (tok_off < tile0 + tl && tile0 < tok_off + my_tok) {
+                        int off = tok_off, r = cnt_off;
+                        for (int c = c0; c < c1; ++c) {
+                            if (skey[c] > thr) {
+                                entry(r, off, sstart[c], slen[c]);
+                                off += slen[c];
+                                ++r;
+                            }
+                        }
+                    }
+                    if (tid == LC_DEC_THREADS - 1) entry(n_sel, n_sel_tok, tail_st, tail_ln);
                 }
             }
             __syncthreads();
             {
-                const int n_win = win_hd[1];
+                const int w_first = win_hd[0], w_last = win_hd[1];
                 const int row_max = max(T - 1, 0);
                 for (int i = tid; i < tl; i += LC_DEC_THREADS) {
                     const int tok = tile0 + i;
-                    int lo_w = 0, hi_w = n_win;             // win_off[lo_w] <= tok < win_off[hi_w]
+                    int lo_w = w_first, hi_w = w_last + 1;   // off[lo_w] <= tok < off[hi_w]
                     while (hi_w - lo_w > 1) {
                         const int mid = (lo_w + hi_w) >> 1;
-                        if (win_off[mid] <= tok) lo_w = mid; else hi_w = mid;
+                        if (win_off[mid & (LC_DEC_WIN - 1)] <= tok) lo_w = mid; else hi_w = mid;
                     }
-                    rows[i] = max(0, min(win_st[lo_w] + (tok - win_off[lo_w]), row_max));
+                    const int sl = lo_w & (LC_DEC_WIN - 1);
+                    rows[i] = max(0, min(win_st[sl] + (tok - win_off[sl]), row_max));
                 }
             }
             __syncthreads();
@@ -441,15 +560,13 @@ lc_decode_kernel(const LcDecodeArgs a) {
 
 template <int G>
 static int launch_decode_g(const LcDecodeArgs& a, int splits, hipStream_t stream) {
-    hipLaunchKernelGGL(lc_decode_kernel<G>, dim3(splits, a.ix.H, a.ix.B), dim3(LC_DEC_THREADS), 0, stream, a);
+    hipLaunchKernelGGL((lc_decode_kernel<G, false>), dim3(splits, a.ix.H, a.ix.B), dim3(LC_DEC_THREADS), 0, stream, a);
     LC_HIP_CHECK(hipGetLastError());
     return LC_OK;
 }
 
-int lc_launch_decode(const lc_index* idx, const LcWs& ws, const void* q, const void* K, const void* V,
-                     const int64_t ks[3], const int32_t* ids, const int32_t* counts, int cap, int G,
-                     int splits, float* out, float* lse, hipStream_t stream) {
-    LcDecodeArgs a;
+static void fill_common(LcDecodeArgs& a, const lc_index* idx, const LcWs& ws, const void* q, const void* K,
+                        const void* V, const int64_t ks[3], float* out, float* lse) {
     a.ix = idx->dev;
     a.q = static_cast<const uint16_t*>(q);
     a.K = static_cast<const uint16_t*>(K);
@@ -457,13 +574,30 @@ int lc_launch_decode(const lc_index* idx, const LcWs& ws, const void* q, const v
     a.ks_seq = ks[0];
     a.ks_head = ks[1];
     a.ks_tok = ks[2];
-    a.ids = ids;
-    a.counts = counts;
-    a.cap = cap;
+    a.ids = nullptr;
+    a.counts = nullptr;
+    a.cap = 0;
     a.part_acc = ws.part_acc;
     a.part_ml = ws.part_ml;
     a.out = out;
     a.lse = lse;
+    a.keys = nullptr;
+    a.ids_out = nullptr;
+    a.counts_out = nullptr;
+    a.budget = 0;
+    a.sink = 0;
+    a.count_limit = 0;
+    a.chunk_cap = 0;
+}
+
+int lc_launch_decode(const lc_index* idx, const LcWs& ws, const void* q, const void* K, const void* V,
+                     const int64_t ks[3], const int32_t* ids, const int32_t* counts, int cap, int G,
+                     int splits, float* out, float* lse, hipStream_t stream) {
+    LcDecodeArgs a;
+    fill_common(a, idx, ws, q, K, V, ks, out, lse);
+    a.ids = ids;
+    a.counts = counts;
+    a.cap = cap;
     switch (G) {
         case 1: return launch_decode_g<1>(a, splits, stream);
         case 2: return launch_decode_g<2>(a, splits, stream);
@@ -473,6 +607,79 @@ int lc_launch_decode(const lc_index* idx, const LcWs& ws, const void* q, const v
         case 6: return launch_decode_g<6>(a, splits, stream);
         case 7: return launch_decode_g<7>(a, splits, stream);
         case 8: return launch_decode_g<8>(a, splits, stream);
+    }
+    return LC_ERR_BAD_SHAPE;
+}
+
+// ---- fused step
+#define LC_DEC_LDS_TOTAL (150 * 1024)      // static + dynamic LDS a fused workgroup may take
+
+template <int G>
+static size_t fused_static_lds() {
+    static size_t cached = 0;
+    if (cached == 0) {
+        hipFuncAttributes attr;
+        if (hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(&lc_decode_kernel<G, true>)) != hipSuccess) {
+            (void)hipGetLastError();
+            return (size_t)LC_DEC_LDS_TOTAL;       // unknown: report "does not fit"
+        }
+        cached = attr.sharedSizeBytes;
+    }
+    return cached;
+}
+static int fused_chunk_cap(int max_M) { return ((max_M > 0 ? max_M : 1) + 63) / 64 * 64; }
+
+template <int G>
+static bool fused_fits_g(int max_M) {
+    return fused_static_lds<G>() + (size_t)fused_chunk_cap(max_M) * 12 <= (size_t)LC_DEC_LDS_TOTAL;
+}
+bool lc_decode_fused_fits(int G, int max_M) {
+    switch (G) {
+        case 1: return fused_fits_g<1>(max_M);
+        case 2: return fused_fits_g<2>(max_M);
+        case 3: return fused_fits_g<3>(max_M);
+        case 4: return fused_fits_g<4>(max_M);
+        case 5: return fused_fits_g<5>(max_M);
+        case 6: return fused_fits_g<6>(max_M);
+        case 7: return fused_fits_g<7>(max_M);
+        case 8: return fused_fits_g<8>(max_M);
+    }
+    return false;
+}
+
+template <int G>
+static int launch_fused_g(const LcDecodeArgs& a, int splits, hipStream_t stream) {
+    const size_t lds = (size_t)a.chunk_cap * 12;
+    if (lds > 16 * 1024)
+        LC_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&lc_decode_kernel<G, true>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL((lc_decode_kernel<G, true>), dim3(splits, a.ix.H, a.ix.B), dim3(LC_DEC_THREADS), lds, stream, a);
+    LC_HIP_CHECK(hipGetLastError());
+    return LC_OK;
+}
+
+int lc_launch_decode_fused(const lc_index* idx, const LcWs& ws, const void* q, const void* K, const void* V,
+                           const int64_t ks[3], int G, int splits, int budget, int32_t* ids_out,
+                           int32_t* counts_out, int cap, int max_M, float* out, float* lse, hipStream_t stream) {
+    LcDecodeArgs a;
+    fill_common(a, idx, ws, q, K, V, ks, out, lse);
+    a.keys = ws.keys;
+    a.ids_out = ids_out;
+    a.counts_out = counts_out;
+    a.cap = cap;
+    a.budget = budget;
+    a.sink = idx->cfg.sink_tokens;
+    a.count_limit = (idx->cfg.policy == LC_POLICY_BEAM && idx->cfg.beam[0] > 0) ? idx->cfg.beam[0] : 0;
+    a.chunk_cap = fused_chunk_cap(max_M);
+    switch (G) {
+        case 1: return launch_fused_g<1>(a, splits, stream);
+        case 2: return launch_fused_g<2>(a, splits, stream);
+        case 3: return launch_fused_g<3>(a, splits, stream);
+        case 4: return launch_fused_g<4>(a, splits, stream);
+        case 5: return launch_fused_g<5>(a, splits, stream);
+        case 6: return launch_fused_g<6>(a, splits, stream);
+        case 7: return launch_fused_g<7>(a, splits, stream);
+        case 8: return launch_fused_g<8>(a, splits, stream);
     }
     return LC_ERR_BAD_SHAPE;
 }

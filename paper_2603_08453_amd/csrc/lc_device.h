@@ -401,3 +401,209 @@ __device__ __forceinline__ void lc_rank_before16(int n, const uint32_t* keys, co
     *count_before = lc_sum16_i(cb);
     *weight_before = lc_sum16_i(wb);
 }
+
+#define LC_SELECT_THREADS_MAX 1024
+// ---------------------------------------------------------------------------------
+// budget selection over the staged chunk keys (used by the chunk-scoring kernel's last workgroup and by the fused decode step)
+// ---------------------------------------------------------------------------------
+// Candidates are the chunks with key != 0, ordered by (key descending, id ascending); the
+// selection is the longest prefix with total length <= W and at most C chunks.
+//   1. One histogram pass over 1024 bins that span [lowest, highest] candidate key linearly
+//      (length and count per bin), a descending scan finds the bin in which the prefix ends.
+//   2. That bin usually holds a handful of chunks: they are copied to a short list and ranked
+//      against each other directly (16 lanes per chunk), which decides each of them exactly.
+//      A bin with more chunks than the list holds is split again (step 1 on its key range); a
+//      bin that is a single key value is a tie group and is cut by a scan in id order.
+// On return chunk i is selected iff skey[i] > thr: the chunks of the last bin have had their key
+// replaced by 0xffffffff (selected) or 0 (not).
+#define LC_LS_BITS 10
+#define LC_LS_BINS (1 << LC_LS_BITS)
+#define LC_LS_CAND 256
+struct LcLeafSelSh {
+    int hw[LC_LS_BINS];
+    int hc[LC_LS_BINS];
+    uint32_t ck[LC_LS_CAND];
+    int cl[LC_LS_CAND];
+    int ci[LC_LS_CAND];
+    int scan[2 * (LC_SELECT_THREADS_MAX / 64)];
+    int mm[2];                     // lowest / highest candidate key
+    int res[4];
+    int ncand;
+};
+
+// exclusive prefix sums of two values over the workgroup, sharing the barriers
+template <int NT>
+__device__ __forceinline__ void lc_block_scan2(int a, int b, int* sh, int* ea, int* eb, int* ta = nullptr,
+                                               int* tb = nullptr) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int ia = a, ib = b;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int ta = __shfl_up(ia, off), tb = __shfl_up(ib, off);
+        if (lane >= off) { ia += ta; ib += tb; }
+    }
+    __syncthreads();                 // protect sh from the previous use
+    if (lane == 63) { sh[wave] = ia; sh[NT / 64 + wave] = ib; }
+    __syncthreads();
+    int ba = 0, bb = 0, sa = 0, sb = 0;
+#pragma unroll
+    for (int w = 0; w < NT / 64; ++w) {
+        const int xa = sh[w], xb = sh[NT / 64 + w];
+        if (w < wave) { ba += xa; bb += xb; }
+        sa += xa;
+        sb += xb;
+    }
+    *ea = ba + ia - a;
+    *eb = bb + ib - b;
+    if (ta) *ta = sa;
+    if (tb) *tb = sb;
+}
+
+// Called by every thread before the keys are staged: empties the histogram and the key range.
+template <int NT>
+__device__ __forceinline__ void lc_leaf_select_prepare(LcLeafSelSh& sh) {
+    for (int i = threadIdx.x; i < LC_LS_BINS; i += NT) { sh.hw[i] = 0; sh.hc[i] = 0; }
+    if (threadIdx.x == 0) { sh.res[0] = -1; sh.ncand = 0; sh.mm[0] = (int)0xffffffffu; sh.mm[1] = 0; }
+}
+// Called by every thread with the range of the candidate keys it staged (0xffffffff / 0 if none);
+// a barrier must follow before lc_leaf_select.
+__device__ __forceinline__ void lc_leaf_select_range(uint32_t kmin, uint32_t kmax, LcLeafSelSh& sh) {
+    kmin = min(kmin, lc_dpp_u<0xB1>(kmin)); kmin = min(kmin, lc_dpp_u<0x4E>(kmin));
+    kmin = min(kmin, lc_dpp_u<0x141>(kmin)); kmin = min(kmin, lc_dpp_u<0x140>(kmin));
+    kmax = max(kmax, lc_dpp_u<0xB1>(kmax)); kmax = max(kmax, lc_dpp_u<0x4E>(kmax));
+    kmax = max(kmax, lc_dpp_u<0x141>(kmax)); kmax = max(kmax, lc_dpp_u<0x140>(kmax));
+    if ((threadIdx.x & 15) == 0 && kmax != 0u) {
+        atomicMin(reinterpret_cast<unsigned int*>(&sh.mm[0]), kmin);
+        atomicMax(reinterpret_cast<unsigned int*>(&sh.mm[1]), kmax);
+    }
+}
+
+template <int NT>
+__device__ __forceinline__ uint32_t lc_leaf_select(int n, uint32_t* skey, const int* slen, long long W, long long C,
+                                                   LcLeafSelSh& sh) {
+    const int tid = threadIdx.x;
+    LC_SEL_STAMP(0);
+    const uint32_t kmin = (uint32_t)sh.mm[0], kmax = (uint32_t)sh.mm[1];
+    if (kmax == 0u) return 0u;                                   // no candidate at all
+    int remW = (int)(W > 0x7fffffffLL ? 0x7fffffffLL : (W < 0 ? 0 : W));
+    int remC = (int)(C > 0x7fffffffLL ? 0x7fffffffLL : (C < 0 ? 0 : C));
+    uint32_t lo = kmin, hi = kmax;
+    int pass = 0;
+    for (;;) {
+        LC_SEL_STAMP(1 + 4 * pass);
+        const uint32_t span = hi - lo;
+        const int bits = span ? 32 - __clz(span) : 0;
+        const int shift = bits > LC_LS_BITS ? bits - LC_LS_BITS : 0;     // (span >> shift) < LC_LS_BINS
+        if (pass > 0) {                                                  // the first pass was prepared by the caller
+            for (int i = tid; i < LC_LS_BINS; i += NT) { sh.hw[i] = 0; sh.hc[i] = 0; }
+            if (tid == 0) { sh.res[0] = -1; sh.ncand = 0; }
+            __syncthreads();
+        }
+#pragma unroll 4
+        for (int i = tid; i < n; i += NT) {
+            const uint32_t k = skey[i];
+            if (k >= lo && k <= hi) {
+                const int bin = (int)((k - lo) >> shift);
+                atomicAdd(&sh.hw[bin], slen[i]);
+                atomicAdd(&sh.hc[bin], 1);
+            }
+        }
+        __syncthreads();
+        LC_SEL_STAMP(2 + 4 * pass);
+        // descending scan: thread t looks at bin 1023 - t (at PER consecutive bins with fewer threads)
+        constexpr int PER = LC_LS_BINS / NT;
+        int w[PER], c[PER], sw = 0, sc = 0;
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            const int bin = LC_LS_BINS - 1 - (tid * PER + j);
+            w[j] = sh.hw[bin];
+            c[j] = sh.hc[bin];
+            sw += w[j];
+            sc += c[j];
+        }
+        int cw, cc;
+        lc_block_scan2<NT>(sw, sc, sh.scan, &cw, &cc);       // length / count of all higher bins
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            // the prefix ends in the first bin that no longer fits: everything above it fits, it does not
+            if (cw <= remW && cc <= remC && ((long long)cw + w[j] > remW || cc + c[j] > remC)) {
+                sh.res[0] = LC_LS_BINS - 1 - (tid * PER + j);
+                sh.res[1] = cw;
+                sh.res[2] = cc;
+                sh.res[3] = c[j];
+            }
+            cw += w[j];
+            cc += c[j];
+        }
+        __syncthreads();
+        LC_SEL_STAMP(3 + 4 * pass);
+        const int fb = sh.res[0];
+        if (fb < 0) return lo - 1u;                               // every candidate in scope fits
+        remW -= sh.res[1];
+        remC -= sh.res[2];
+        const int nc = sh.res[3];
+        const uint32_t blo = lo + ((uint32_t)fb << shift);
+        const unsigned long long bend = (unsigned long long)blo + ((1ull << shift) - 1ull);
+        const uint32_t bhi = bend < (unsigned long long)hi ? (uint32_t)bend : hi;
+        if (nc <= LC_LS_CAND) {
+            // ---- short list, ranked directly
+#pragma unroll 4
+            for (int i = tid; i < n; i += NT) {
+                const uint32_t k = skey[i];
+                if (k >= blo && k <= bhi) {
+                    const int pos = atomicAdd(&sh.ncand, 1);
+                    if (pos < LC_LS_CAND) { sh.ck[pos] = k; sh.cl[pos] = slen[i]; sh.ci[pos] = i; }
+                }
+            }
+            __syncthreads();
+            LC_SEL_STAMP(4 + 4 * pass);
+            const int part = tid & 15;
+            for (int c0 = 0; c0 < nc; c0 += NT / 16) {
+                const int me = c0 + (tid >> 4);
+                const bool valid = me < nc;
+                const uint32_t km = valid ? sh.ck[me] : 0u;
+                const int im = valid ? sh.ci[me] : 0;
+                const int lm = valid ? sh.cl[me] : 0;
+                int wb = 0, cb = 0;
+                for (int j = part; j < nc; j += 16) {
+                    const uint32_t kj = sh.ck[j];
+                    const bool before = kj > km || (kj == km && sh.ci[j] < im);
+                    wb += before ? sh.cl[j] : 0;
+                    cb += before ? 1 : 0;
+                }
+                wb = lc_sum16_i(wb);
+                cb = lc_sum16_i(cb);
+                if (valid && part == 0) skey[im] = ((long long)wb + lm <= remW && cb + 1 <= remC) ? 0xffffffffu : 0u;
+            }
+            __syncthreads();
+            return bhi;
+        }
+        if (blo == bhi) {
+            // ---- a tie group too large for the list: cut it in id order
+            int E = (n + NT - 1) / NT;
+            E |= 1;                                               // odd stride: no LDS bank conflicts
+            const int i0 = min(n, tid * E), i1 = min(n, i0 + E);
+            int my_w = 0, my_c = 0;
+            for (int i = i0; i < i1; ++i)
+                if (skey[i] == blo) { my_w += slen[i]; my_c += 1; }
+            int tw, tc;
+            lc_block_scan2<NT>(my_w, my_c, sh.scan, &tw, &tc);
+            long long rw = tw;
+            int rc = tc;
+            for (int i = i0; i < i1; ++i) {
+                if (skey[i] == blo) {
+                    rw += slen[i];
+                    rc += 1;
+                    skey[i] = (rw <= remW && rc <= remC) ? 0xffffffffu : 0u;
+                }
+            }
+            __syncthreads();
+            return bhi;
+        }
+        lo = blo;
+        hi = bhi;
+        ++pass;
+        __syncthreads();
+    }
+}
+

@@ -35,6 +35,7 @@ struct lc_index {
     std::vector<int> T;      // host mirror, per sequence
     std::vector<int> M;      // host mirror, per sequence
     std::vector<int> N;      // [B][LC_MAX_LEVELS] nodes per level (N[b][0] mirrors M)
+    hipEvent_t probe = nullptr;   // measurement aid: recorded between the kernels of lc_decode_step
 };
 
 // Layout of the index buffer: fills dev pointers from base; returns total bytes.
@@ -46,6 +47,8 @@ struct LcWs {
     uint32_t* keys;      // [B][H][cap0] order-preserving score keys of the chunks (0 = not a candidate)
     uint8_t* want;       // [B][H][cap0] 1 = this chunk's score is needed
     int* scratch;        // [B][H][4 * cap0] chunk-level staging when it does not fit in LDS
+    int32_t* ids_tmp;    // [B][H][cap0] chunk list of a decode step that has to run as two kernels
+    int32_t* counts_tmp; // [B][H]
     // decode
     float* part_acc;     // [B][H][S][G][d]
     float* part_ml;      // [B][H][S][G][2]
@@ -74,10 +77,16 @@ int lc_launch_build(const lc_index* idx, const LcWs& ws, const void* K, const in
                     int max_M, hipStream_t stream);
 int lc_launch_retrieve(const lc_index* idx, const LcWs& ws, const void* q, int G, int budget,
                        int32_t* ids, int32_t* counts, float* scores, int cap,
-                       int max_M, int max_upper, hipStream_t stream);
+                       int max_M, int max_upper, int score_only, hipStream_t stream);
 int lc_launch_decode(const lc_index* idx, const LcWs& ws, const void* q, const void* K, const void* V,
                      const int64_t ks[3], const int32_t* ids, const int32_t* counts, int cap, int G,
                      int splits, float* out, float* lse, hipStream_t stream);
+// Fused step: selection from ws.keys (written by lc_launch_retrieve with score_only) + attention.
+// lc_decode_fused_fits tells whether the staged chunk arrays of max_M chunks fit into LDS.
+bool lc_decode_fused_fits(int G, int max_M);
+int lc_launch_decode_fused(const lc_index* idx, const LcWs& ws, const void* q, const void* K, const void* V,
+                           const int64_t ks[3], int G, int splits, int budget, int32_t* ids_out,
+                           int32_t* counts_out, int cap, int max_M, float* out, float* lse, hipStream_t stream);
 int lc_launch_append(const lc_index* idx, void* K, void* V, const int64_t ks[3],
                      const void* k_new, const void* v_new, const uint8_t* close_dev_flags_or_null,
                      uint32_t close_mask_lo, hipStream_t stream);

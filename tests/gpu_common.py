@@ -155,6 +155,27 @@ def gpu_decode(case: Case, q_bits: np.ndarray, ids_per_bh):
     return out.cpu().numpy(), lse.cpu().numpy()
 
 
+def gpu_step(case: Case, q_bits: np.ndarray, budget: int, with_ids: bool = True):
+    """The fused entry point.  Returns (ids_per_bh or None, out, lse)."""
+    import torch
+    from paper_2603_08453_amd import binding as lc
+    w = case.w
+    q = to_bf16_tensor(q_bits)
+    ids = counts = None
+    if with_ids:
+        ids = torch.full((w.B, w.H_kv, case.cap), -1, dtype=torch.int32, device="cuda")
+        counts = torch.full((w.B, w.H_kv), -1, dtype=torch.int32, device="cuda")
+    out = torch.full((w.B, w.H_q, w.d), float("nan"), dtype=torch.float32, device="cuda")
+    lse = torch.full((w.B, w.H_q), float("nan"), dtype=torch.float32, device="cuda")
+    lc.lc_decode_step(case.idx, q, case.K, case.V, budget, out, case.ws, lse=lse, chunk_ids=ids, counts=counts)
+    torch.cuda.synchronize()
+    got = None
+    if with_ids:
+        ids_h, counts_h = ids.cpu().numpy(), counts.cpu().numpy()
+        got = [[ids_h[b, h, : counts_h[b, h]].copy() for h in range(w.H_kv)] for b in range(w.B)]
+    return got, out.cpu().numpy(), lse.cpu().numpy()
+
+
 def attention_errors(got: np.ndarray, ref: np.ndarray):
     """(max abs error, relative L2 error) over the whole output."""
     got = got.astype(np.float64)

@@ -36,6 +36,12 @@ def _check_step(G, case, qb, budget, heads=None, seqs=None, tag=""):
     w = case.w
     ids, scores, _ = G.gpu_retrieve(case, qb, budget, want_scores=False)
     out, lse = G.gpu_decode(case, qb, ids)
+    # the fused entry point (the one bench.py times) must give the same lists and the same bits
+    ids_f, out_f, lse_f = G.gpu_step(case, qb, budget)
+    for b in range(w.B):
+        for h in range(w.H_kv):
+            assert ids_f[b][h].tolist() == ids[b][h].tolist(), (tag, b, h)
+    assert np.array_equal(out_f, out) and np.array_equal(lse_f, lse), tag
     worst = (0.0, 0.0)
     n_band = 0
     for b in (range(w.B) if seqs is None else seqs):
@@ -81,6 +87,8 @@ def test_c3_headline_128k(G):
     M = case2.oidx[0][0].M
     assert all(ids[0][h].tolist() == list(range(M)) for h in range(8))
     out, lse = G.gpu_decode(case2, qb, ids)
+    _, out_f, lse_f = G.gpu_step(case2, qb, wl.C3.T, with_ids=False)
+    assert np.array_equal(out_f, out) and np.array_equal(lse_f, lse)
     h = 3
     ref, ref_lse = H.dense_attention_library(wl.bf16_bits_to_f64(qb[0, 12:16]), case2.Kf(0, h), case2.Vf(0, h))
     mx, rel = G.attention_errors(out[0, 12:16], ref)

@@ -100,6 +100,25 @@ def _check_decode(G, case, qbits, ids_per_bh, tag=""):
     return out
 
 
+def _check_step(G, case, qbits, budget, policy=orc.POLICY_EXACT, beam=None, sink=0, tag=""):
+    """The fused entry point against the two separate calls: same chunk lists, same attention, bit
+    for bit (the separate calls are checked against the oracle by the other helpers)."""
+    from paper_2603_08453_amd import binding as lc
+    w = case.w
+    lc.lc_set_policy(case.idx, policy, beam, sink)
+    ids, _, _ = G.gpu_retrieve(case, qbits, budget)
+    out, lse = G.gpu_decode(case, qbits, ids)
+    ids_f, out_f, lse_f = G.gpu_step(case, qbits, budget)
+    where = f"{tag} budget={budget} policy={policy} sink={sink}"
+    for b in range(w.B):
+        for h in range(w.H_kv):
+            assert ids_f[b][h].tolist() == ids[b][h].tolist(), f"{where} b={b} h={h}"
+    assert np.array_equal(out_f, out), where
+    assert np.array_equal(lse_f, lse), where
+    _, out_n, lse_n = G.gpu_step(case, qbits, budget, with_ids=False)
+    assert np.array_equal(out_n, out) and np.array_equal(lse_n, lse), where + " (no id output)"
+
+
 # ----------------------------------------------------------------- C1: the reference config
 
 @pytest.fixture(scope="module")
@@ -181,6 +200,45 @@ def test_c1_repeatable(G, c1):
     assert np.array_equal(o1, o2) and np.array_equal(l1, l2)
 
 
+def test_c1_fused_step_equals_separate_calls(G, c1):
+    from paper_2603_08453_amd import binding as lc
+    qb = _q_batch(c1, 0)
+    for budget in (0, 1, 200, 1024, 4096, 10 ** 6):
+        _check_step(G, c1, qb, budget, tag="C1 step")
+    _check_step(G, c1, np.zeros_like(qb), 200, tag="C1 step q=0")
+    _check_step(G, c1, qb, 512, sink=16, tag="C1 step sink")
+    _check_step(G, c1, qb, 512, sink=100, tag="C1 step sink100")
+    _check_step(G, c1, qb, 1024, policy=orc.POLICY_BEAM, beam=[0, 3], tag="C1 step beam top-3")
+    _check_step(G, c1, qb, 1024, policy=orc.POLICY_BEAM, beam=[12, 2], tag="C1 step beam leaf 12")
+    _check_step(G, c1, qb, 1024, policy=orc.POLICY_BEAM, beam=[0, 0], sink=40, tag="C1 step beam unbounded")
+    lc.lc_set_policy(c1.idx, lc.LC_POLICY_EXACT, None, 0)
+    for mode in (lc.LC_PRUNE_NEVER, lc.LC_PRUNE_AUTO, lc.LC_PRUNE_ALWAYS):
+        lc.lc_set_prune(c1.idx, mode)
+        _check_step(G, c1, qb, 777, tag=f"C1 step prune={mode}")
+    # and against the oracle directly, end to end
+    ids_f, out_f, _ = G.gpu_step(c1, qb, 1024)
+    for h in range(8):
+        oi = c1.oidx[0][h]
+        q = wl.bf16_bits_to_f64(qb[0, 4 * h:4 * h + 4])
+        H.accept_ids(ids_f[0][h], orc.node_scores(oi, 0, q), oi.lens(), 1024, pinned=orc.pinned_chunks(oi, 0))
+        ref, _ = orc.sparse_decode(q, c1.Kf(0, h), c1.Vf(0, h), oi.bounds, oi.T, ids_f[0][h])
+        mx, rel = G.attention_errors(out_f[0, 4 * h:4 * h + 4], ref)
+        assert mx <= ATTN_MAX_ABS and rel <= ATTN_REL_L2
+
+
+def test_fused_step_falls_back_when_the_chunks_do_not_fit_in_lds(G):
+    """About ten thousand chunks per sequence are more than the fused kernel stages: the call then
+    runs the two separate kernels and must give the same results."""
+    w = wl.tiny("many-chunks", levels=2, fanout=16, T=20000, chunk_lo=1, chunk_hi=3, H_q=4, H_kv=1, budget=500)
+    case = G.make_case(w)
+    assert case.oidx[0][0].M > 9500
+    qb = _q_batch(case, 0)
+    for budget in (0, 500, 10 ** 6):
+        _check_step(G, case, qb, budget, tag="many-chunks")
+    ids = _check_retrieve(G, case, qb, 500, tag="many-chunks")
+    _check_decode(G, case, qb, ids, tag="many-chunks")
+
+
 # ----------------------------------------------------------------- small, ragged, tails, deep trees
 
 @pytest.mark.parametrize("name,kw,tails", [
@@ -200,10 +258,13 @@ def test_small_cases(G, name, kw, tails):
     for budget in (0, 1, 50, w.budget, 10 ** 6):
         ids = _check_retrieve(G, case, qb, budget, tag=name)
         _check_decode(G, case, qb, ids, tag=f"{name} budget {budget}")
+        _check_step(G, case, qb, budget, tag=name + " step")
     if w.levels > 1:
         beam = [0] + [2] * (w.levels - 1)
         _check_retrieve(G, case, qb, w.budget, policy=orc.POLICY_BEAM, beam=beam, tag=name + " beam")
+        _check_step(G, case, qb, w.budget, policy=orc.POLICY_BEAM, beam=beam, tag=name + " step beam")
     _check_retrieve(G, case, qb, 64, sink=7, tag=name + " sink")
+    _check_step(G, case, qb, 64, sink=7, tag=name + " step sink")
 
 
 def test_pruning_happens_and_stays_exact(G):
@@ -237,6 +298,9 @@ def test_select_with_a_large_tie_group(G):
     ids = _check_retrieve(G, case, q0, 10 ** 6, policy=orc.POLICY_BEAM, beam=[300, 0], tag="ties beam")
     assert all(ids[0][h].tolist() == list(range(300)) for h in range(w.H_kv))
     ids = _check_retrieve(G, case, q0, 600, policy=orc.POLICY_BEAM, beam=[300, 0], sink=30, tag="ties beam sink")
+    _check_step(G, case, q0, 600, policy=orc.POLICY_BEAM, beam=[300, 0], sink=30, tag="ties step beam sink")
+    for budget in (7, 1000, 2500):
+        _check_step(G, case, q0, budget, tag="ties step")
     from paper_2603_08453_amd import binding as lc
     lc.lc_set_policy(case.idx, lc.LC_POLICY_EXACT, None, 0)
 
@@ -266,6 +330,7 @@ def test_select_with_a_crowded_score_range(G):
         lc.lc_set_prune(case.idx, prune)
         for budget in (3, 600, 5000, 10 ** 6):
             ids = _check_retrieve(G, case, qb, budget, tag=f"crowded prune={prune}")
+            _check_step(G, case, qb, budget, tag=f"crowded step prune={prune}")
         _check_decode(G, case, qb, ids, tag="crowded")
 
 
