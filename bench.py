@@ -173,6 +173,7 @@ def main():
     torch.cuda.synchronize()
     eager_s = timed(step, args.steps)
     if args.pmc_mode:
+        timed(step_separate if step is step_fused else step_fused, args.steps)     # the other entry points' kernels too
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
         dst = torch.empty_like(src)
         for _ in range(4):
@@ -250,21 +251,26 @@ def main():
         torch.cuda.synchronize()
         retrieve_us = float(np.mean([e0.elapsed_time(e1) for e0, e1 in ev])) * 1e3
 
-    # the two kernels of lc_decode_step, timed with an event the library records between them
-    n_ev = min(args.steps, 512)
-    evs = [tuple(torch.cuda.Event(enable_timing=True) for _ in range(3)) for _ in range(n_ev)]
-    for i, (e0, em, e1) in enumerate(evs):
+    # The second kernel of lc_decode_step (selection + attention) by itself: back-to-back launches from
+    # a graph with the scoring kernels switched off -- every replica's workspace still holds the score
+    # keys of the query it is paired with here (replica r with query r mod nq).
+    def step_fused_paired(i):
         rp = reps[i % R]
-        em.record()                     # creates the event (torch does that lazily); the library records it again
-        lc.lc_set_probe_event(rp["idx"], em)
-        e0.record()
-        step_fused(i)
-        e1.record()
-    torch.cuda.synchronize()
-    for rp in reps:
-        lc.lc_set_probe_event(rp["idx"], None)
-    score_us = float(np.mean([e0.elapsed_time(em) for e0, em, e1 in evs])) * 1e3
-    fused_us = float(np.mean([em.elapsed_time(e1) for e0, em, e1 in evs])) * 1e3
+        lc.lc_decode_step(rp["idx"], Qs[(i % R) % nq], rp["K"], rp["V"], w.budget, out, rp["ws"])
+
+    fused_us = None
+    if not args.separate and not args.no_graph:
+        for i in range(R):
+            step_fused_paired(i)
+        for rp in reps:
+            lc.lc_set_step_reuse_keys(rp["idx"], True)
+        try:
+            fused_us, _ = graph_us_per_launch(step_fused_paired, args.steps)
+        finally:
+            for rp in reps:
+                lc.lc_set_step_reuse_keys(rp["idx"], False)
+    if fused_us is None:
+        fused_us = attend_us
 
     # the same step with the level-by-level walk forced on (EXACT: same ids, more kernels), and with the
     # paper's per-level top-k (BEAM: 4 nodes kept at each internal level but 16 at level 1)
@@ -396,7 +402,6 @@ def main():
             "beam_policy_us": None if beam_us is None else round(beam_us, 2),
             "entry_points": "lc_retrieve + lc_sparse_decode" if args.separate else "lc_decode_step",
             "separate_calls_us": None if separate_s is None else round(separate_s * 1e6, 2),
-            "score_kernels_us_event": round(score_us, 2),
             "select_attend_kernel_us_event": round(fused_us, 2),
             "retrieve_us_event": round(retrieve_us, 2),
             "attend_us_event": round(attend_us, 2),

@@ -141,10 +141,12 @@ int lc_set_policy(lc_index* idx, int policy, const int32_t* beam /* host, LC_MAX
 /* Change the pruning mode (LC_PRUNE_*) of an existing index (host state only). */
 int lc_set_prune(lc_index* idx, int prune);
 
-/* Measurement aid (host state only): `event` is a hipEvent_t, or NULL to clear.  While set,
- * lc_decode_step records it on its stream between its two kernels, so that a caller who brackets
- * the call with events of its own can time each kernel.  Not for use under graph capture. */
-int lc_set_probe_event(lc_index* idx, void* event);
+/* Measurement aid (host state only).  While on, lc_decode_step launches only its second kernel
+ * (selection + attention) and takes the chunk score keys that the previous lc_decode_step with
+ * the same query, index and workspace left in the workspace; the results are the same.  It lets a
+ * benchmark time that kernel by itself.  A call that has to fall back to the kernels of
+ * lc_retrieve + lc_sparse_decode ignores the setting. */
+int lc_set_step_reuse_keys(lc_index* idx, int on);
 
 /*
  * lc_retrieve -- hierarchical retrieval for one decode step (Eq. 2, Algorithm 1

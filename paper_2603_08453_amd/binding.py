@@ -100,8 +100,8 @@ def lib() -> ctypes.CDLL:
     L.lc_decode_step.argtypes = [vp, vp, vp, vp, i64p, ctypes.c_int, ctypes.c_int, vp, vp, vp, vp, ctypes.c_int,
                                  vp, ctypes.c_size_t, vp]
     L.lc_decode_step.restype = ctypes.c_int
-    L.lc_set_probe_event.argtypes = [vp, vp]
-    L.lc_set_probe_event.restype = ctypes.c_int
+    L.lc_set_step_reuse_keys.argtypes = [vp, ctypes.c_int]
+    L.lc_set_step_reuse_keys.restype = ctypes.c_int
     L.lc_append.argtypes = [vp, vp, vp, i64p, vp, vp, u8p, vp, ctypes.c_size_t, vp]
     L.lc_append.restype = ctypes.c_int
     L.lc_index_info.argtypes = [vp, ctypes.c_int, i32p, i32p, i32p]
@@ -246,10 +246,8 @@ def lc_sparse_decode(idx: Index, q, K, V, chunk_ids, counts, out, ws, lse=None, 
     _check(rc, "lc_sparse_decode")
 
 
-def lc_set_probe_event(idx: Index, event) -> None:
-    """event: a recorded-capable torch.cuda.Event (timing enabled) or None."""
-    handle = None if event is None else int(event.cuda_event)
-    _check(lib().lc_set_probe_event(idx.handle, handle), "lc_set_probe_event")
+def lc_set_step_reuse_keys(idx: Index, on: bool) -> None:
+    _check(lib().lc_set_step_reuse_keys(idx.handle, 1 if on else 0), "lc_set_step_reuse_keys")
 
 
 def lc_decode_step(idx: Index, q, K, V, budget: int, out, ws, lse=None, chunk_ids=None, counts=None,

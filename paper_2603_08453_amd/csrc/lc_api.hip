@@ -293,9 +293,9 @@ int lc_set_prune(lc_index* idx, int prune) {
     return LC_OK;
 }
 
-int lc_set_probe_event(lc_index* idx, void* event) {
+int lc_set_step_reuse_keys(lc_index* idx, int on) {
     if (!idx) return LC_ERR_INVALID_ARG;
-    idx->probe = static_cast<hipEvent_t>(event);
+    idx->step_reuse_keys = on ? 1 : 0;
     return LC_OK;
 }
 
@@ -394,10 +394,11 @@ int lc_decode_step(const lc_index* idx, const void* q, const void* K, const void
     if (lc_decode_fused_fits(G, p.max_M)) {
         // kernel 1 (and the level walk before it) leaves the chunk score keys in the workspace;
         // kernel 2 selects from them in every workgroup and attends
-        rc = lc_launch_retrieve(idx, w, q, G, budget, nullptr, nullptr, nullptr, 1, p.max_M,
-                                p.walk ? p.max_upper : -1, 1, st);
-        if (rc) return rc;
-        if (idx->probe) LC_HIP_CHECK(hipEventRecord(idx->probe, st));
+        if (!idx->step_reuse_keys) {
+            rc = lc_launch_retrieve(idx, w, q, G, budget, nullptr, nullptr, nullptr, 1, p.max_M,
+                                    p.walk ? p.max_upper : -1, 1, st);
+            if (rc) return rc;
+        }
         return lc_launch_decode_fused(idx, w, q, K, V, kv_strides, G, splits, budget, chunk_ids, counts,
                                       want_ids ? cap : 0, p.max_M, out, lse, st);
     }
@@ -412,7 +413,6 @@ int lc_decode_step(const lc_index* idx, const void* q, const void* K, const void
     }
     rc = lc_launch_retrieve(idx, w, q, G, budget, ids, cnt, nullptr, icap, p.max_M, p.walk ? p.max_upper : -1, 0, st);
     if (rc) return rc;
-    if (idx->probe) LC_HIP_CHECK(hipEventRecord(idx->probe, st));
     return lc_launch_decode(idx, w, q, K, V, kv_strides, ids, cnt, icap, G, splits, out, lse, st);
 }
 

@@ -35,7 +35,7 @@ struct lc_index {
     std::vector<int> T;      // host mirror, per sequence
     std::vector<int> M;      // host mirror, per sequence
     std::vector<int> N;      // [B][LC_MAX_LEVELS] nodes per level (N[b][0] mirrors M)
-    hipEvent_t probe = nullptr;   // measurement aid: recorded between the kernels of lc_decode_step
+    int step_reuse_keys = 0;      // measurement aid: lc_decode_step skips the scoring kernels
 };
 
 // Layout of the index buffer: fills dev pointers from base; returns total bytes.
