@@ -21,6 +21,7 @@ import re
 import sys
 
 COPY_KERNEL = "__amd_rocclr_copyBuffer"
+CALIBRATION_COPIES = 4
 
 
 def _read_counter(dirname: str, counter: str):
@@ -28,11 +29,14 @@ def _read_counter(dirname: str, counter: str):
     if not files:
         raise SystemExit(f"no counter_collection.csv under {dirname}")
     per = collections.defaultdict(list)
+    copies = []                      # (dispatch id, value) of the plain device copies
     for f in files:
         for r in csv.DictReader(open(f)):
             if r["Counter_Name"] == counter:
                 per[r["Kernel_Name"]].append(float(r["Counter_Value"]))
-    return per
+                if COPY_KERNEL in r["Kernel_Name"]:
+                    copies.append((int(r["Dispatch_Id"]), float(r["Counter_Value"])))
+    return per, sorted(copies)
 
 
 def _short(name: str) -> str:
@@ -44,10 +48,9 @@ def traffic(fetch_dir: str, write_dir: str, copy_bytes: int):
     out = {}
     factors = {}
     for counter, d in (("FETCH_SIZE", fetch_dir), ("WRITE_SIZE", write_dir)):
-        per = _read_counter(d, counter)
-        copies = [v for k, vs in per.items() if COPY_KERNEL in k for v in vs]
-        big = [v for v in copies if v > 0.25 * max(copies)]        # the calibration copies are the large ones
-        factor = copy_bytes / (sum(big) / len(big))
+        per, copies = _read_counter(d, counter)
+        cal = [v for _, v in copies[-CALIBRATION_COPIES:]]         # bench.py --pmc-mode ends with them
+        factor = copy_bytes / (sum(cal) / len(cal))
         factors[counter] = factor
         for k, vs in per.items():
             if "lc_" not in k:
