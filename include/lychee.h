@@ -135,6 +135,17 @@ int lc_build_index(lc_index** out, const lc_config* cfg,
                    int B, int H_kv, int d,
                    void* index_buf, size_t index_bytes, void* ws, size_t ws_bytes, void* stream);
 
+/*
+ * lc_recluster -- global re-clustering against drift (the remedy the paper's limitations
+ * section proposes for long generations: the lazy update only ever attaches chunks to existing
+ * nodes and lets radii grow).  Keeps the chunk nodes (level 0) as they are and rebuilds every
+ * level above them exactly as lc_build_index does -- ceil(N/F) clusters per level for the
+ * current chunk counts, the same k-means -- so the result equals lc_build_index on the whole
+ * sequence as it now stands.  K and V are not read.  Synchronises the stream once (a small host
+ * to device copy of the level sizes).  Same workspace size as lc_build_index.
+ */
+int lc_recluster(lc_index* idx, void* ws, size_t ws_bytes, void* stream);
+
 /* Change the retrieval policy of an existing index (host state only). */
 int lc_set_policy(lc_index* idx, int policy, const int32_t* beam /* host, LC_MAX_LEVELS, may be NULL */,
                   int sink_tokens);

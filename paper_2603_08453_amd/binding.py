@@ -100,6 +100,8 @@ def lib() -> ctypes.CDLL:
     L.lc_decode_step.argtypes = [vp, vp, vp, vp, i64p, ctypes.c_int, ctypes.c_int, vp, vp, vp, vp, ctypes.c_int,
                                  vp, ctypes.c_size_t, vp]
     L.lc_decode_step.restype = ctypes.c_int
+    L.lc_recluster.argtypes = [vp, vp, ctypes.c_size_t, vp]
+    L.lc_recluster.restype = ctypes.c_int
     L.lc_set_step_reuse_keys.argtypes = [vp, ctypes.c_int]
     L.lc_set_step_reuse_keys.restype = ctypes.c_int
     L.lc_append.argtypes = [vp, vp, vp, i64p, vp, vp, u8p, vp, ctypes.c_size_t, vp]
@@ -244,6 +246,10 @@ def lc_sparse_decode(idx: Index, q, K, V, chunk_ids, counts, out, ws, lse=None, 
                                 cap, H_q, _ptr(out), _ptr(lse), _ptr(ws), ws.numel() * ws.element_size(),
                                 _stream(stream))
     _check(rc, "lc_sparse_decode")
+
+
+def lc_recluster(idx: Index, ws, stream=None) -> None:
+    _check(lib().lc_recluster(idx.handle, _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "lc_recluster")
 
 
 def lc_set_step_reuse_keys(idx: Index, on: bool) -> None:

@@ -276,6 +276,25 @@ int lc_build_index(lc_index** out, const lc_config* cfg, const void* K, const in
     return LC_OK;
 }
 
+int lc_recluster(lc_index* idx, void* ws, size_t ws_bytes, void* stream) {
+    if (!idx || !ws || (reinterpret_cast<uintptr_t>(ws) & 255u)) return LC_ERR_INVALID_ARG;
+    LcWs w;
+    if (ws_bytes < lc_layout_ws(&idx->cfg, idx->B, idx->H_kv, idx->H_kv, idx->d, 1, nullptr, nullptr))
+        return LC_ERR_WORKSPACE_TOO_SMALL;
+    lc_layout_ws(&idx->cfg, idx->B, idx->H_kv, idx->H_kv, idx->d, 1, ws, &w);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    fill_level_counts(idx);                       // nodes per level follow the current chunk counts
+    std::vector<int> nlev((size_t)idx->B * LC_MAX_LEVELS, 0);
+    for (size_t i = 0; i < nlev.size(); ++i) nlev[i] = idx->N[i];
+    LC_HIP_CHECK(hipMemcpyAsync(idx->dev.nlev, nlev.data(), nlev.size() * sizeof(int), hipMemcpyHostToDevice, s));
+    LC_HIP_CHECK(hipStreamSynchronize(s));        // the staging vector dies at return
+    int max_M = 0;
+    for (int b = 0; b < idx->B; ++b)
+        if (idx->M[b] > max_M) max_M = idx->M[b];
+    const int64_t no_strides[3] = {0, 0, 0};
+    return lc_launch_build(idx, w, nullptr, no_strides, max_M, s);
+}
+
 int lc_set_policy(lc_index* idx, int policy, const int32_t* beam, int sink_tokens) {
     if (!idx) return LC_ERR_INVALID_ARG;
     if (policy != LC_POLICY_EXACT && policy != LC_POLICY_BEAM) return LC_ERR_INVALID_ARG;

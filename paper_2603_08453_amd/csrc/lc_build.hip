@@ -144,6 +144,23 @@ lc_pool_kernel(LcDev ix, const uint16_t* K, long long ks_seq, long long ks_head,
     }
 }
 
+// Re-clustering starts from the chunk nodes already in the index: unit directions of their centers.
+__global__ void __launch_bounds__(LC_BT)
+lc_dirs_kernel(LcDev ix, float* dirs) {
+    const int h = blockIdx.y, b = blockIdx.z;
+    const int bh = b * ix.H + h;
+    const int M = ix.state[bh * 4 + 1];
+    const int sub = threadIdx.x & 15;
+    const int j = blockIdx.x * LC_BG + (threadIdx.x >> 4);
+    if (j >= M) return;
+    const size_t n = (size_t)bh * ix.cap[0] + j;
+    float mu[8], u[8];
+    lc_load8(ix.center[0] + n * LC_D + 8 * sub, mu);
+    lc_unit_frag(mu, sub, u);
+    lc_store8(dirs + n * LC_D + 8 * sub, u);
+    if (sub == 0) ix.parent[0][n] = -1;
+}
+
 // ---------------------------------------------------------------------------------
 // spherical k-means
 // ---------------------------------------------------------------------------------
@@ -331,15 +348,19 @@ lc_node_kernel(LcDev ix, int l, const int* anc, const float* cent, int cent_cap,
     }
 }
 
+// K == nullptr: keep the chunk nodes (level 0) as they are and rebuild only the levels above them.
 int lc_launch_build(const lc_index* idx, const LcWs& ws, const void* Kp, const int64_t ks[3],
                     int max_M, hipStream_t stream) {
     const LcDev& ix = idx->dev;
     const uint16_t* K = static_cast<const uint16_t*>(Kp);
     const int geometry = idx->cfg.geometry;
     const int B = ix.B, H = ix.H, L = ix.L;
-    if (max_M > 0) {
+    if (max_M > 0 && K != nullptr) {
         hipLaunchKernelGGL(lc_pool_kernel, dim3(max_M, H, B), dim3(LC_BT), 0, stream, ix, K,
                            (long long)ks[0], (long long)ks[1], (long long)ks[2], geometry, ws.dirs);
+        LC_HIP_CHECK(hipGetLastError());
+    } else if (max_M > 0) {
+        hipLaunchKernelGGL(lc_dirs_kernel, dim3((max_M + LC_BG - 1) / LC_BG, H, B), dim3(LC_BT), 0, stream, ix, ws.dirs);
         LC_HIP_CHECK(hipGetLastError());
     }
     // per-level maxima over the batch (host mirror)

@@ -499,6 +499,74 @@ def test_append_stream_matches_oracle(G, geometry, L):
             assert mx <= ATTN_MAX_ABS and rel <= ATTN_REL_L2
 
 
+def test_recluster_after_a_stream_equals_a_fresh_build(G):
+    """Drift control: after many lazy appends lc_recluster rebuilds the levels above the chunks;
+    the result must be what the oracle builds from scratch on the sequence as it stands."""
+    import torch
+    from paper_2603_08453_amd import binding as lc
+    steps, L, F = 400, 3, 4
+    w = wl.tiny("drift", B=2, levels=L, fanout=F, T=0, T_range=(300, 500), chunk_lo=3, chunk_hi=20,
+                stream_close_lo=3, stream_close_hi=17)
+    case = G.make_case(w, tails=[2, 0], extra_tokens=steps, extra_chunks=steps)
+    streams = [wl.make_stream(w, b, steps) for b in range(w.B)]
+    Kf = [[np.vstack([case.Kf(b, h), np.zeros((steps, w.d))]) for h in range(w.H_kv)] for b in range(w.B)]
+    for t in range(steps):
+        k_bits = np.stack([st.k[t] for st in streams])
+        v_bits = np.stack([st.v[t] for st in streams])
+        close = [int(st.close[t]) for st in streams]
+        lc.lc_append(case.idx, case.K, case.V, G.to_bf16_tensor(k_bits), G.to_bf16_tensor(v_bits), close, case.ws)
+        for b in range(w.B):
+            for h in range(w.H_kv):
+                oi = case.oidx[b][h]
+                Kf[b][h][oi.T] = wl.bf16_bits_to_f64(k_bits[b, h])
+                orc.append_token(oi)
+                if close[b]:
+                    orc.close_chunk(oi, Kf[b][h])
+    torch.cuda.synchronize()
+    before = lc.unpack_blob(lc.lc_index_export(case.idx))
+    lc.lc_recluster(case.idx, case.ws)
+    torch.cuda.synchronize()
+    after = lc.unpack_blob(lc.lc_index_export(case.idx))
+    same_topology = 0
+    for b in range(w.B):
+        sb, sa = before["seqs"][b], after["seqs"][b]
+        assert sa["T"] == sb["T"] and np.array_equal(sa["bounds"], sb["bounds"])
+        T, M, n_lev = case.idx.info(b)
+        for h in range(w.H_kv):
+            lazy = case.oidx[b][h]
+            assert (T, M) == (lazy.T, lazy.M)
+            fresh = orc.build_index(Kf[b][h][:T], lazy.bounds, T, L, F)
+            gi = G.levels_to_oracle_index(sa["heads"][h], sa["bounds"], sa["T"], F, orc.TOKEN_BALL)
+            gb = G.levels_to_oracle_index(sb["heads"][h], sb["bounds"], sb["T"], F, orc.TOKEN_BALL)
+            assert [gi.n(l) for l in range(L)] == [fresh.n(l) for l in range(L)] == list(n_lev[:L])
+            assert gi.n(1) > gb.n(1)                               # the tree grew with the sequence
+            # the chunk nodes are untouched
+            assert np.array_equal(gi.center[0], gb.center[0]) and np.array_equal(gi.radius[0], gb.radius[0])
+            H.check_covering_invariant(gi, Kf[b][h], slack=1e-6)
+            H.check_counts(gi)
+            if all(np.array_equal(gi.parent[l], fresh.parent[l]) for l in range(L - 1)):
+                same_topology += 1
+                for l in range(1, L):
+                    live = fresh.nchunk[l] > 0
+                    assert np.allclose(gi.center[l][live], fresh.center[l][live], rtol=1e-5, atol=1e-5)
+                    assert np.all(gi.radius[l][live] >= fresh.radius[l][live] * (1 - 1e-6))
+                    assert np.all(gi.radius[l][live] <= fresh.radius[l][live] * (1 + 5e-5) + 1e-6)
+            if b == 0 and h == 0:
+                _say(f"drift: mean level-1 radius {gb.radius[1][gb.nchunk[1] > 0].mean():.3f} over {gb.n(1)} nodes "
+                     f"before, {gi.radius[1].mean():.3f} over {gi.n(1)} nodes after re-clustering")
+    _say(f"recluster: {same_topology}/{w.B * w.H_kv} (seq, head) trees have the topology of the oracle's fresh build")
+    assert same_topology >= (w.B * w.H_kv) // 2
+    # retrieval and attention on the re-clustered index (level walk on) agree with the oracle on it
+    qb = np.stack([st.q[steps - 1] for st in streams])
+    ids, _, _ = G.gpu_retrieve(case, qb, 150)
+    for b in range(w.B):
+        sa = after["seqs"][b]
+        for h in range(w.H_kv):
+            gi = G.levels_to_oracle_index(sa["heads"][h], sa["bounds"], sa["T"], F, orc.TOKEN_BALL)
+            q = wl.bf16_bits_to_f64(qb[b, h * w.G:(h + 1) * w.G])
+            H.accept_ids(ids[b][h], orc.node_scores(gi, 0, q), gi.lens(), 150)
+
+
 def test_capacity_errors(G):
     from paper_2603_08453_amd import binding as lc
     w = wl.tiny("cap", levels=2, fanout=4, T=100)
