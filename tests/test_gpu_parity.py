@@ -582,3 +582,13 @@ def test_capacity_errors(G):
     with pytest.raises(lc.LycheeError) as e:
         lc.lc_retrieve(case.idx, q, 64, ids, counts, case.ws)
     assert e.value.code == lc.LC_ERR_CAPACITY
+    out = torch.zeros((1, w.H_q, w.d), dtype=torch.float32, device="cuda")
+    with pytest.raises(lc.LycheeError) as e:          # the same capacity rule when the fused step is asked for ids
+        lc.lc_decode_step(case.idx, q, case.K, case.V, 64, out, case.ws, chunk_ids=ids, counts=counts)
+    assert e.value.code == lc.LC_ERR_CAPACITY
+    with pytest.raises(lc.LycheeError) as e:          # ids and counts come together or not at all
+        lc.lc_decode_step(case.idx, q, case.K, case.V, 64, out, case.ws, chunk_ids=ids)
+    assert e.value.code == lc.LC_ERR_INVALID_ARG
+    lc.lc_decode_step(case.idx, q, case.K, case.V, 64, out, case.ws)        # without ids no capacity is needed
+    torch.cuda.synchronize()
+    assert torch.isfinite(out).all()

@@ -25,7 +25,8 @@ def test_header_symbols_are_exported(L):
     hdr = open(os.path.join(ROOT, "include", "lychee.h")).read()
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     names = set(re.findall(r"\b(lc_[a-z_0-9]+)\s*\(", hdr))
-    assert {"lc_build_index", "lc_retrieve", "lc_sparse_decode", "lc_append"} <= names
+    assert {"lc_build_index", "lc_retrieve", "lc_sparse_decode", "lc_append", "lc_decode_step", "lc_recluster",
+            "lc_chunk_tokens"} <= names
     for n in sorted(names):
         assert hasattr(L, n), f"{n} declared in lychee.h but not exported"
 
@@ -89,6 +90,10 @@ def test_argument_errors_before_any_gpu_work(L):
     assert L.lc_retrieve(None, fake, 32, 10, fake, fake, None, 16, fake, 1 << 20, None) == lc.LC_ERR_INVALID_ARG
     assert L.lc_sparse_decode(None, fake, fake, fake, strides, fake, fake, 16, 32, fake, None, fake, 1 << 20,
                               None) == lc.LC_ERR_INVALID_ARG
+    assert L.lc_decode_step(None, fake, fake, fake, strides, 32, 10, fake, None, None, None, 0, fake, 1 << 20,
+                            None) == lc.LC_ERR_INVALID_ARG
+    assert L.lc_recluster(None, fake, 1 << 20, None) == lc.LC_ERR_INVALID_ARG
+    assert L.lc_set_step_reuse_keys(None, 1) == lc.LC_ERR_INVALID_ARG
     assert L.lc_append(None, fake, fake, strides, fake, fake, None, fake, 0, None) == lc.LC_ERR_INVALID_ARG
     assert L.lc_set_policy(None, 0, None, 0) == lc.LC_ERR_INVALID_ARG
     assert L.lc_index_info(None, 0, None, None, None) == lc.LC_ERR_INVALID_ARG
