@@ -13,6 +13,7 @@
 //   V row (one 16-byte load), four rows make a full 1 KiB wavefront load.
 #include <type_traits>
 
+#define LC_SEL_STAMP_X (blockIdx.x == 0)
 #include "lc_device.h"
 #include "lc_internal.h"
 
@@ -31,6 +32,11 @@ typedef __bf16 lc_bf16x8 __attribute__((ext_vector_type(8)));
 typedef float lc_f32x4 __attribute__((ext_vector_type(4)));
 
 LC_STAMP_DECL(lc_dbg_decode)
+#ifdef LC_DBG_TIMES
+extern "C" int lc_dbg_sel2_read(unsigned long long* host) {
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(lc_dbg_sel), sizeof(lc_dbg_sel));
+}
+#endif
 
 struct LcDecodeArgs {
     LcDev ix;

@@ -15,7 +15,10 @@
     name[i] = wall_clock64(); } while (0)
 #define LC_STAMP(name, i) do { if (blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) name[i] = wall_clock64(); } while (0)
 static __device__ unsigned long long lc_dbg_sel[32];
-#define LC_SEL_STAMP(i) do { if (blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) lc_dbg_sel[i] = wall_clock64(); } while (0)
+#ifndef LC_SEL_STAMP_X
+#define LC_SEL_STAMP_X true
+#endif
+#define LC_SEL_STAMP(i) do { if ((LC_SEL_STAMP_X) && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) lc_dbg_sel[i] = wall_clock64(); } while (0)
 #else
 #define LC_SEL_STAMP(i)
 #define LC_STAMP_DECL(name)
@@ -487,6 +490,7 @@ __device__ __forceinline__ uint32_t lc_leaf_select(int n, uint32_t* skey, const 
     if (kmax == 0u) return 0u;                                   // no candidate at all
     int remW = (int)(W > 0x7fffffffLL ? 0x7fffffffLL : (W < 0 ? 0 : W));
     int remC = (int)(C > 0x7fffffffLL ? 0x7fffffffLL : (C < 0 ? 0 : C));
+    const bool count_c = C < 0x7fffffffLL;                       // chunk counts matter only with a count limit
     uint32_t lo = kmin, hi = kmax;
     int pass = 0;
     for (;;) {
@@ -505,7 +509,7 @@ __device__ __forceinline__ uint32_t lc_leaf_select(int n, uint32_t* skey, const 
             if (k >= lo && k <= hi) {
                 const int bin = (int)((k - lo) >> shift);
                 atomicAdd(&sh.hw[bin], slen[i]);
-                atomicAdd(&sh.hc[bin], 1);
+                if (count_c) atomicAdd(&sh.hc[bin], 1);
             }
         }
         __syncthreads();
@@ -517,12 +521,17 @@ __device__ __forceinline__ uint32_t lc_leaf_select(int n, uint32_t* skey, const 
         for (int j = 0; j < PER; ++j) {
             const int bin = LC_LS_BINS - 1 - (tid * PER + j);
             w[j] = sh.hw[bin];
-            c[j] = sh.hc[bin];
+            c[j] = count_c ? sh.hc[bin] : 0;
             sw += w[j];
             sc += c[j];
         }
-        int cw, cc;
-        lc_block_scan2<NT>(sw, sc, sh.scan, &cw, &cc);       // length / count of all higher bins
+        int cw, cc = 0;                                      // length / count of all higher bins
+        if (count_c) {
+            lc_block_scan2<NT>(sw, sc, sh.scan, &cw, &cc);
+        } else {
+            int total;
+            cw = lc_block_scan<NT>(sw, sh.scan, &total);
+        }
 #pragma unroll
         for (int j = 0; j < PER; ++j) {
             // the prefix ends in the first bin that no longer fits: everything above it fits, it does not
@@ -530,7 +539,6 @@ __device__ __forceinline__ uint32_t lc_leaf_select(int n, uint32_t* skey, const 
                 sh.res[0] = LC_LS_BINS - 1 - (tid * PER + j);
                 sh.res[1] = cw;
                 sh.res[2] = cc;
-                sh.res[3] = c[j];
             }
             cw += w[j];
             cc += c[j];
@@ -541,22 +549,23 @@ __device__ __forceinline__ uint32_t lc_leaf_select(int n, uint32_t* skey, const 
         if (fb < 0) return lo - 1u;                               // every candidate in scope fits
         remW -= sh.res[1];
         remC -= sh.res[2];
-        const int nc = sh.res[3];
         const uint32_t blo = lo + ((uint32_t)fb << shift);
         const unsigned long long bend = (unsigned long long)blo + ((1ull << shift) - 1ull);
         const uint32_t bhi = bend < (unsigned long long)hi ? (uint32_t)bend : hi;
-        if (nc <= LC_LS_CAND) {
-            // ---- short list, ranked directly
+        // the chunks of that bin go to the short list (as many as it holds; the counter tells how many there are)
 #pragma unroll 4
-            for (int i = tid; i < n; i += NT) {
-                const uint32_t k = skey[i];
-                if (k >= blo && k <= bhi) {
-                    const int pos = atomicAdd(&sh.ncand, 1);
-                    if (pos < LC_LS_CAND) { sh.ck[pos] = k; sh.cl[pos] = slen[i]; sh.ci[pos] = i; }
-                }
+        for (int i = tid; i < n; i += NT) {
+            const uint32_t k = skey[i];
+            if (k >= blo && k <= bhi) {
+                const int pos = atomicAdd(&sh.ncand, 1);
+                if (pos < LC_LS_CAND) { sh.ck[pos] = k; sh.cl[pos] = slen[i]; sh.ci[pos] = i; }
             }
-            __syncthreads();
-            LC_SEL_STAMP(4 + 4 * pass);
+        }
+        __syncthreads();
+        LC_SEL_STAMP(4 + 4 * pass);
+        const int nc = sh.ncand;
+        if (nc <= LC_LS_CAND) {
+            // ---- ranked directly
             const int part = tid & 15;
             for (int c0 = 0; c0 < nc; c0 += NT / 16) {
                 const int me = c0 + (tid >> 4);
@@ -603,7 +612,7 @@ __device__ __forceinline__ uint32_t lc_leaf_select(int n, uint32_t* skey, const 
         lo = blo;
         hi = bhi;
         ++pass;
-        __syncthreads();
+        __syncthreads();                                          // everyone has read the list counter
     }
 }
 
