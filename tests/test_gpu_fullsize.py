@@ -180,8 +180,12 @@ def test_c4_streaming_2048_steps(G):
     for t in range(steps):
         close = int(st.close[t])
         lc.lc_append(case.idx, case.K, case.V, k_dev[t:t + 1], v_dev[t:t + 1], [close], case.ws)
-        lc.lc_retrieve(case.idx, q_dev[t:t + 1], w.budget, ids, counts, case.ws)
-        lc.lc_sparse_decode(case.idx, q_dev[t:t + 1], case.K, case.V, ids, counts, out, case.ws)
+        if t % 2 == 0:                     # the two entry points take turns (the checks below do not care which ran)
+            lc.lc_retrieve(case.idx, q_dev[t:t + 1], w.budget, ids, counts, case.ws)
+            lc.lc_sparse_decode(case.idx, q_dev[t:t + 1], case.K, case.V, ids, counts, out, case.ws)
+        else:
+            lc.lc_decode_step(case.idx, q_dev[t:t + 1], case.K, case.V, w.budget, out, case.ws,
+                              chunk_ids=ids, counts=counts)
         n_closed += close
         if t % 4 == 0:                     # stability of the retrieved sets of head 0 (Appendix D metrics)
             cur = ids[0, 0, : int(counts[0, 0])].cpu().numpy().tolist()
