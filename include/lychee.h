@@ -231,6 +231,9 @@ int lc_decode_step(const lc_index* idx, const void* q, const void* K, const void
  *   close_chunk    host uint8[B] (the caller's boundary decision); NULL = none
  * Returns LC_ERR_CAPACITY (nothing enqueued) if a sequence is at max_tokens, or
  * would exceed max_chunks.
+ * The handle keeps host-side counts of tokens and chunks that every call updates: a captured
+ * graph that replays lc_append leaves them behind (the kernel itself never writes past the
+ * capacities), so append outside graphs or rebuild the handle's view with lc_index_export/import.
  */
 int lc_append(lc_index* idx, void* K, void* V, const int64_t kv_strides[3],
               const void* k_new, const void* v_new, const uint8_t* close_chunk,

@@ -407,7 +407,7 @@ struct LcCloseBits { uint32_t w[32]; };       // one bit per sequence (B <= 1024
 
 __global__ void __launch_bounds__(LC_BT)
 lc_append_kernel(LcDev ix, uint16_t* K, uint16_t* V, long long ks_seq, long long ks_head, long long ks_tok,
-                 const uint16_t* k_new, const uint16_t* v_new, LcCloseBits close, int geometry) {
+                 const uint16_t* k_new, const uint16_t* v_new, LcCloseBits close, int geometry, int max_tokens) {
     __shared__ float sh[LC_BG * LC_D + LC_BG];
     __shared__ float best_sim[LC_BG];
     __shared__ int best_arg[LC_BG];
@@ -416,6 +416,9 @@ lc_append_kernel(LcDev ix, uint16_t* K, uint16_t* V, long long ks_seq, long long
     const int tid = threadIdx.x, sub = tid & 15, grp = tid >> 4;
     const int T = ix.state[bh * 4 + 0];
     const int M = ix.state[bh * 4 + 1];
+    // The host checks the capacities against its own counts before it launches; these guards are for
+    // a caller who replays the launch from a captured graph, where the host is not asked again.
+    if (T >= max_tokens) return;
     uint16_t* Kbh = K + b * ks_seq + h * ks_head;
     uint16_t* Vbh = V + b * ks_seq + h * ks_head;
     if (tid < 16) {
@@ -425,7 +428,7 @@ lc_append_kernel(LcDev ix, uint16_t* K, uint16_t* V, long long ks_seq, long long
         *reinterpret_cast<uint4*>(Vbh + (long long)T * ks_tok + 8 * sub) =
             *reinterpret_cast<const uint4*>(v_new + (size_t)bh * LC_D + 8 * sub);
     }
-    const bool do_close = (close.w[b >> 5] >> (b & 31)) & 1u;
+    const bool do_close = ((close.w[b >> 5] >> (b & 31)) & 1u) && M < ix.cap[0];
     if (!do_close) {
         if (tid == 0) ix.state[bh * 4 + 0] = T + 1;
         return;
@@ -536,7 +539,7 @@ int lc_launch_append(const lc_index* idx, void* K, void* V, const int64_t ks[3],
                        static_cast<uint16_t*>(K), static_cast<uint16_t*>(V),
                        (long long)ks[0], (long long)ks[1], (long long)ks[2],
                        static_cast<const uint16_t*>(k_new), static_cast<const uint16_t*>(v_new), bits,
-                       idx->cfg.geometry);
+                       idx->cfg.geometry, idx->cfg.max_tokens);
     LC_HIP_CHECK(hipGetLastError());
     return LC_OK;
 }
