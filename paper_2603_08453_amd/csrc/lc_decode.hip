@@ -57,6 +57,7 @@ struct LcDecodeArgs {
     int32_t* counts_out;  // [B][H] or null
     int budget, sink, count_limit;   // token budget, pinned prefix, chunk-count limit (0 = none)
     int chunk_cap;        // LDS entries of the staged chunk arrays
+    int max_tokens;       // rows of one (sequence, head) slab of K and V
 };
 
 // Value of lane `src` (0..15) of the caller's 16-lane row, in every lane of the row.
@@ -266,9 +267,11 @@ lc_decode_kernel(const LcDecodeArgs a) {
         }
         // K and V of this (sequence, head) as buffer resources: one 32-bit byte offset per row
         // (the host has checked that the slab spans less than 2 GiB)
-        const __amdgpu_buffer_rsrc_t Kr = lc_buffer(a.K + (size_t)b * a.ks_seq + (size_t)h * a.ks_head);
-        const __amdgpu_buffer_rsrc_t Vr = lc_buffer(a.V + (size_t)b * a.ks_seq + (size_t)h * a.ks_head);
+        // (the resources end with the last row the index may ever hold, so a wrong row cannot fault)
         const int row_bytes = (int)a.ks_tok * 2;
+        const int slab_bytes = (a.max_tokens - 1) * row_bytes + LC_D * 2;
+        const __amdgpu_buffer_rsrc_t Kr = lc_buffer(a.K + (size_t)b * a.ks_seq + (size_t)h * a.ks_head, slab_bytes);
+        const __amdgpu_buffer_rsrc_t Vr = lc_buffer(a.V + (size_t)b * a.ks_seq + (size_t)h * a.ks_head, slab_bytes);
 
         // A lane loads K for token (sub & 3) of group (sub >> 2) of its wavefront -- row `sub` of the
         // MFMA A operand -- and V for the tokens of its own group.
@@ -594,6 +597,7 @@ static void fill_common(LcDecodeArgs& a, const lc_index* idx, const LcWs& ws, co
     a.sink = 0;
     a.count_limit = 0;
     a.chunk_cap = 0;
+    a.max_tokens = idx->cfg.max_tokens;
 }
 
 int lc_launch_decode(const lc_index* idx, const LcWs& ws, const void* q, const void* K, const void* V,

@@ -88,8 +88,9 @@ __device__ __forceinline__ uint32_t lc_load_agent(const uint32_t* p) {
 }
 // 16-byte versions through buffer instructions with the agent-scope cache policy (sc1).
 typedef int lc_v4i __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t lc_buffer(const void* base) {
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, 0x7fffffff, 0x00020000);
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t lc_buffer(const void* base, int bytes = 0x7fffffff) {
+    // `bytes` is the extent the hardware checks offsets against: a load past it returns 0, a store is dropped
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
 }
 __device__ __forceinline__ float4 lc_load_agent4(__amdgpu_buffer_rsrc_t r, int byte_offset) {
     const lc_v4i v = __builtin_amdgcn_raw_buffer_load_b128(r, byte_offset, 0, 16);
