@@ -239,6 +239,25 @@ def test_fused_step_falls_back_when_the_chunks_do_not_fit_in_lds(G):
     _check_decode(G, case, qb, ids, tag="many-chunks")
 
 
+def test_more_chunks_than_the_select_can_stage_in_lds(G):
+    """About twenty thousand chunks: the scoring kernel's last workgroup stages keys and lengths in
+    global scratch instead of LDS, and the fused step falls back to the separate kernels."""
+    from paper_2603_08453_amd import binding as lc
+    w = wl.tiny("huge-M", levels=3, fanout=16, T=40000, chunk_lo=1, chunk_hi=3, H_q=2, H_kv=1, budget=700)
+    case = G.make_case(w)
+    assert case.oidx[0][0].M > 19000
+    qb = _q_batch(case, 0)
+    for prune in (lc.LC_PRUNE_NEVER, lc.LC_PRUNE_ALWAYS):
+        lc.lc_set_prune(case.idx, prune)
+        for budget in (0, 700, 10 ** 6):
+            ids = _check_retrieve(G, case, qb, budget, tag=f"huge-M prune={prune}")
+            _check_step(G, case, qb, budget, tag=f"huge-M step prune={prune}")
+    _check_retrieve(G, case, np.zeros_like(qb), 5000, tag="huge-M q=0")        # one tie group of 20000 chunks
+    _check_retrieve(G, case, qb, 700, sink=50, tag="huge-M sink")
+    ids = _check_retrieve(G, case, qb, 700, tag="huge-M")
+    _check_decode(G, case, qb, ids, tag="huge-M")
+
+
 # ----------------------------------------------------------------- small, ragged, tails, deep trees
 
 @pytest.mark.parametrize("name,kw,tails", [
