@@ -65,11 +65,13 @@ enum { LC_POLICY_EXACT = 0, LC_POLICY_BEAM = 1 };
 
 /* EXACT only: whether the level-by-level pruning pass runs before the chunks are
  * scored.  The selection is the same either way (it is defined as the flat scan);
- * the pass costs a few dependent memory round trips and pays off only when the
- * chunk level is large.  AUTO runs it when the chunk-level index of the whole
- * batch exceeds LC_PRUNE_AUTO_BYTES.  BEAM always walks the levels. */
+ * the pass costs a chain of dependent memory round trips in one workgroup per
+ * (sequence, head) and pays off only when it removes most of a very large chunk
+ * level -- with an 8 TB/s memory the flat scan was faster in every case measured,
+ * up to 300 MB of chunk centers.  AUTO runs the pass when the chunk-level index
+ * of the whole batch exceeds LC_PRUNE_AUTO_BYTES.  BEAM always walks the levels. */
 enum { LC_PRUNE_AUTO = 0, LC_PRUNE_ALWAYS = 1, LC_PRUNE_NEVER = 2 };
-#define LC_PRUNE_AUTO_BYTES (32u << 20)
+#define LC_PRUNE_AUTO_BYTES (1u << 30)
 
 typedef struct lc_config {
     int32_t levels;                 /* L >= 1, counts the chunk level (paper: 3)            */
