@@ -207,9 +207,9 @@ int lc_sparse_decode(const lc_index* idx, const void* q, const void* K, const vo
  * from the scoring kernel to the attention kernel through the workspace; every
  * workgroup of the attention kernel repeats the selection of its (sequence,
  * head) from them, so no chunk list travels through memory on the critical path.
- * When a sequence has more chunks than the attention kernel can stage in LDS
- * (several thousand; depends on G) the call runs the kernels of the two separate
- * entry points instead.
+ * When a sequence has more than about three thousand chunks, repeating the
+ * selection stops paying and the call runs the kernels of the two separate
+ * entry points instead (through a chunk list in the workspace).
  *
  *   chunk_ids, counts  optional outputs as in lc_retrieve (both or neither); cap
  *                      is checked only when they are given

@@ -337,6 +337,8 @@ static int common_decode_checks(const lc_index* idx, const void* q, int H_q, int
     return LC_OK;
 }
 
+#define LC_STEP_FUSED_MAX_CHUNKS 3072
+
 namespace {
 // What a retrieval over the current index needs: sizes, the capacity check, walk or flat scan.
 struct RetrievePlan {
@@ -410,7 +412,10 @@ int lc_decode_step(const lc_index* idx, const void* q, const void* K, const void
     lc_layout_ws(&idx->cfg, idx->B, H_q, idx->H_kv, idx->d, splits, ws, &w);
     const int G = H_q / idx->H_kv;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (lc_decode_fused_fits(G, p.max_M)) {
+    // Every workgroup of the fused kernel repeats the selection with 256 threads: with a few thousand
+    // chunks that is cheaper than the hand-off through a chunk list, with more it is not (measured
+    // cross-over near 4096 chunks per sequence).
+    if (p.max_M <= LC_STEP_FUSED_MAX_CHUNKS && lc_decode_fused_fits(G, p.max_M)) {
         // kernel 1 (and the level walk before it) leaves the chunk score keys in the workspace;
         // kernel 2 selects from them in every workgroup and attends
         if (!idx->step_reuse_keys) {

@@ -226,9 +226,9 @@ def test_c1_fused_step_equals_separate_calls(G, c1):
         assert mx <= ATTN_MAX_ABS and rel <= ATTN_REL_L2
 
 
-def test_fused_step_falls_back_when_the_chunks_do_not_fit_in_lds(G):
-    """About ten thousand chunks per sequence are more than the fused kernel stages: the call then
-    runs the two separate kernels and must give the same results."""
+def test_fused_step_falls_back_with_many_chunks(G):
+    """About ten thousand chunks per sequence: the call runs the kernels of the two separate entry
+    points (repeating the selection per workgroup would cost more) and must give the same results."""
     w = wl.tiny("many-chunks", levels=2, fanout=16, T=20000, chunk_lo=1, chunk_hi=3, H_q=4, H_kv=1, budget=500)
     case = G.make_case(w)
     assert case.oidx[0][0].M > 9500
