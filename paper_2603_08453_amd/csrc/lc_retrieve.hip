@@ -34,7 +34,8 @@ struct LcRetrieveArgs {
     LcDev ix;
     const uint16_t* q;       // [B][H_q][d]
     uint32_t* keys;          // [B][H][cap0]
-    uint8_t* want;           // [B][H][cap0] 1 = score this chunk
+    uint8_t* want;           // [B][H][cap0], first N_1 entries used: 1 = this level-1 node was kept, i.e. the
+                             // chunks below it are to be scored (the chunk kernel looks its chunks' parents up)
     float* scores;           // [B][H][cap0] or null
     int32_t* ids;            // [B][H][cap]
     int32_t* counts;         // [B][H]
@@ -184,6 +185,111 @@ lc_upper_kernel(const LcRetrieveArgs a) {
         while (l + 1 < L && u >= off_sh[l + 1]) ++l;
         return l;
     };
+    if (a.policy == LC_POLICY_BEAM) {
+        // ---- top-k per level (Algorithm 1): only the children of the kept nodes are ever scored.
+        // Candidates of a level sit in a compact list in ascending node order (so that equal scores
+        // fall to the lower id); per level: score the list, rank it, flag the kept nodes, gather
+        // their children.
+        uint8_t* want_b = a.want + (size_t)bh * ix.cap[0];
+        const int o1b = off_sh[1];
+        const int n_1b = off_sh[2 < L ? 2 : L] - o1b;
+        if (a.budget <= 0) {
+            for (int i = tid; i < n_1b; i += LC_UP_THREADS) want_b[i] = 0;
+            return;
+        }
+        for (int u = tid; u < NU; u += LC_UP_THREADS) {
+            const int l = level_of(u);
+            upar[u] = ix.parent[l][(size_t)bh * ix.cap[l] + (u - off_sh[l])];
+            kp[u] = 0;
+        }
+        int* cid = reinterpret_cast<int*>(ekB);              // candidate node ids (within their level)
+        int* cid_next = ewB;
+        uint8_t* cflag = reinterpret_cast<uint8_t*>(untok);  // kept flag per list position
+        int n_c = off_sh[L] - off_sh[L - 1];
+        for (int i = tid; i < n_c; i += LC_UP_THREADS) cid[i] = i;
+        __syncthreads();
+        for (int l = L - 1; l >= 1; --l) {
+            const int o = off_sh[l];
+            if (n_c <= LC_UP_GROUPS) {            // a short list: one node per group, nothing to batch
+                if (grp < n_c) {
+                    const size_t n = (size_t)bh * ix.cap[l] + cid[grp];
+                    const LcNodeFrag f = lc_load_node(ix.center[l] + n * LC_D, sub);
+                    const float R = ix.radius[l][n];
+                    const int nc = ix.nchunk[l][n];
+                    float sc = lc_score_frag<G>(f, R, qf, qn);
+                    if (nc <= 0) sc = LC_NEG_INF;
+                    if (sub == 0) { ekA[grp] = lc_score_key(sc); ewA[grp] = 0; }
+                }
+            } else {
+                for (int i0 = grp; i0 < n_c; i0 += NB * LC_UP_GROUPS) {
+                    LcNodeFrag f[NB];
+                    float R[NB];
+                    int nc[NB];
+#pragma unroll
+                    for (int k = 0; k < NB; ++k) {
+                        const size_t n = (size_t)bh * ix.cap[l] + cid[min(i0 + k * LC_UP_GROUPS, n_c - 1)];
+                        f[k] = lc_load_node(ix.center[l] + n * LC_D, sub);
+                        R[k] = ix.radius[l][n];
+                        nc[k] = ix.nchunk[l][n];
+                    }
+#pragma unroll
+                    for (int k = 0; k < NB; ++k) {
+                        const int i = i0 + k * LC_UP_GROUPS;
+                        float sc = lc_score_frag<G>(f[k], R[k], qf, qn);
+                        if (nc[k] <= 0) sc = LC_NEG_INF;
+                        if (sub == 0 && i < n_c) { ekA[i] = lc_score_key(sc); ewA[i] = 0; }
+                    }
+                }
+            }
+            if (tid < 4 && n_c + tid < ((n_c + 3) & ~3)) { ekA[n_c + tid] = 0u; ewA[n_c + tid] = 0; }
+            __syncthreads();
+            LC_STAMP0(lc_dbg_upper, 8 + 3 * (L - 1 - l));
+            const long long C = a.beam[l] > 0 ? a.beam[l] : 0x7fffffffLL;
+            if (n_c <= LC_COUNT_SELECT_MAX) {
+                uint32_t mk;
+                int reached;
+                lc_small_select<LC_UP_THREADS, false>(n_c, 0, 0x7fffffffffffLL, C, ekA, ewA, cflag, sel_sh, &mk, &reached);
+            } else {
+                auto keyf = [&](int i) -> uint32_t { return ekA[i]; };
+                auto wf = [&](int) -> int { return 0; };
+                const LcSel r = lc_block_select<LC_UP_THREADS>(n_c, 0x7fffffffffffLL, C, keyf, wf, sel_sh);
+                int tie_c = 0;
+                for (int t0 = 0; t0 < n_c; t0 += LC_UP_THREADS) {
+                    const int i = t0 + tid;
+                    const uint32_t k = (i < n_c) ? ekA[i] : 0u;
+                    const int eq = (!r.all && k != 0u && k == r.kstar) ? 1 : 0;
+                    int tot;
+                    const int ex = lc_block_scan<LC_UP_THREADS>(eq, sel_sh, &tot);
+                    if (i < n_c) cflag[i] = (k != 0u && (k > r.kstar || (eq && tie_c + ex + 1 <= r.remC))) ? 1 : 0;
+                    tie_c += tot;
+                }
+            }
+            __syncthreads();
+            for (int i = tid; i < n_c; i += LC_UP_THREADS)
+                if (cflag[i]) kp[o + cid[i]] = 1;
+            __syncthreads();
+            LC_STAMP0(lc_dbg_upper, 9 + 3 * (L - 1 - l));
+            if (l >= 2) {                     // the kept nodes' children, in ascending order
+                const int ob = off_sh[l - 1], n_b = off_sh[l] - ob;
+                int n_new = 0;
+                for (int base = 0; base < n_b; base += LC_UP_THREADS) {
+                    const int i = base + tid;
+                    const int in = (i < n_b && kp[o + upar[ob + i]]) ? 1 : 0;
+                    int tot;
+                    const int ex = lc_block_scan<LC_UP_THREADS>(in, sel_sh, &tot);
+                    if (in) cid_next[n_new + ex] = i;
+                    n_new += tot;
+                }
+                __syncthreads();
+                int* t = cid; cid = cid_next; cid_next = t;
+                n_c = n_new;
+                if (n_c == 0) break;          // nothing below the kept nodes: no chunk is wanted
+            }
+        }
+        for (int i = tid; i < n_1b; i += LC_UP_THREADS) want_b[i] = kp[o1b + i];
+        LC_STAMP0(lc_dbg_upper, 7);
+        return;
+    }
     for (int u = tid; u < NU; u += LC_UP_THREADS) {
         const int l = level_of(u);
         const size_t n = (size_t)bh * ix.cap[l] + (u - off_sh[l]);
@@ -217,34 +323,16 @@ lc_upper_kernel(const LcRetrieveArgs a) {
     uint8_t* want = a.want + (size_t)bh * ix.cap[0];
     const int* bnd = ix.bounds + (size_t)b * (ix.cap[0] + 1);
     const int* par0 = ix.parent[0] + (size_t)bh * ix.cap[0];
+    const int o1 = off_sh[1];
+    const int n_1 = (L > 2 ? off_sh[2] : off_sh[L]) - o1;
     if (a.budget <= 0) {
-        for (int j = tid; j < M; j += LC_UP_THREADS) want[j] = 0;
+        for (int i = tid; i < n_1; i += LC_UP_THREADS) want[i] = 0;
         return;
     }
-    const int o1 = off_sh[1];
 
-    // want[j] = (level-1 parent kept) and not pinned; streamed, loads batched
+    // the outcome of the walk: which level-1 nodes were kept (the chunk kernel maps chunks to them)
     auto write_want = [&]() {
-        const bool word_ok = (reinterpret_cast<uintptr_t>(want) & 3u) == 0;
-        for (int j0 = tid * LC_UP_PER_THREAD; j0 < M; j0 += LC_UP_THREADS * LC_UP_PER_THREAD) {
-            int p[LC_UP_PER_THREAD], s0[LC_UP_PER_THREAD];
-#pragma unroll
-            for (int k = 0; k < LC_UP_PER_THREAD; ++k) {
-                const int j = min(j0 + k, M - 1);
-                p[k] = par0[j];
-                s0[k] = a.sink > 0 ? bnd[j] : 0;
-            }
-            uint32_t packed = 0u;
-#pragma unroll
-            for (int k = 0; k < LC_UP_PER_THREAD; ++k)
-                packed |= (uint32_t)((s0[k] >= a.sink && kp[o1 + p[k]]) ? 1u : 0u) << (8 * k);
-            if (j0 + LC_UP_PER_THREAD <= M && word_ok) {
-                *reinterpret_cast<uint32_t*>(want + j0) = packed;          // j0 is a multiple of 4
-            } else {
-                for (int k = 0; k < LC_UP_PER_THREAD && j0 + k < M; ++k)
-                    want[j0 + k] = (uint8_t)((packed >> (8 * k)) & 1u);
-            }
-        }
+        for (int i = tid; i < n_1; i += LC_UP_THREADS) want[i] = kp[o1 + i];
     };
     // Per-level selection.  The candidates of a level (frontier nodes: key, weight; others: 0) sit in
     // one staging buffer; the select writes kept flags; the children of the kept nodes are staged into
@@ -443,6 +531,7 @@ lc_leaf_kernel(const LcRetrieveArgs a) {
     uint32_t* keys = a.keys + cb;
     float* scores = a.scores ? a.scores + cb : nullptr;
     const uint8_t* want = a.want + cb;
+    const int* par0 = ix.parent[0] + cb;
     const bool have_want = a.walk != 0;
 
     LC_STAMP0(lc_dbg_leaf, 0);
@@ -455,7 +544,8 @@ lc_leaf_kernel(const LcRetrieveArgs a) {
     for (int r = 0; r < R; ++r) {
         const int j = min(j_lo + r * LC_LF_GROUPS + grp, ix.cap[0] - 1);
         jj[r] = j;
-        wv[r] = have_want ? (int)want[j] : (bnd[j] >= a.sink ? 1 : 0);
+        // (rows past the chunk count hold whatever the buffer held: the parent is clamped, the result unused)
+        wv[r] = (bnd[j] >= a.sink ? 1 : 0) & (have_want ? (int)want[min(max(par0[j], 0), ix.cap[0] - 1)] : 1);
         rv[r] = ix.radius[0][cb + j];
     }
     // Without a level walk every chunk below M is scored, so its center can be fetched right away
