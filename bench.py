@@ -405,6 +405,7 @@ def main():
             "select_attend_kernel_us_event": round(fused_us, 2),
             "retrieve_us_event": round(retrieve_us, 2),
             "attend_us_event": round(attend_us, 2),
+            "attend_kernel_alone_frac_of_hbm_peak": round(attend_bytes / (attend_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
             "append_us": round(append_us, 2),
             "build_ms": round(float(np.median(build_ms)), 2),
             "step_bytes": round(step_bytes),
