@@ -611,3 +611,55 @@ def test_capacity_errors(G):
     lc.lc_decode_step(case.idx, q, case.K, case.V, 64, out, case.ws)        # without ids no capacity is needed
     torch.cuda.synchronize()
     assert torch.isfinite(out).all()
+
+
+def test_index_with_no_closed_chunk_yet(G):
+    """A stream's very beginning: every token is still in the open tail.  Retrieval returns nothing,
+    attention is dense attention over the tail (checked with library routines), and the first closed
+    chunk is grafted into the empty tree."""
+    import torch
+    from paper_2603_08453_amd import binding as lc
+    w = wl.tiny("empty", levels=3, fanout=4, T=50, H_q=4, H_kv=2)
+    s = wl.make_sequence(w, 0, 50)
+    cfg = lc.lc_config_default(levels=3, fanout=4, max_chunks=8, max_tokens=80)
+    K = torch.zeros((1, 2, 80, w.d), dtype=torch.bfloat16, device="cuda")
+    V = torch.zeros_like(K)
+    K[0, :, :50] = G.to_bf16_tensor(s.K)
+    V[0, :, :50] = G.to_bf16_tensor(s.V)
+    ib = torch.zeros(lc.lc_index_bytes(cfg, 1, 2), dtype=torch.uint8, device="cuda")
+    ws = torch.zeros(lc.lc_workspace_bytes(cfg, 1, 4, 2), dtype=torch.uint8, device="cuda")
+    idx = lc.lc_build_index(cfg, K, [50], [[0]], ib, ws)
+    assert idx.info(0)[:2] == (50, 0)
+    q = G.to_bf16_tensor(s.Q[0][None])
+    ids = torch.full((1, 2, 8), -1, dtype=torch.int32, device="cuda")
+    counts = torch.full((1, 2), -1, dtype=torch.int32, device="cuda")
+    out = torch.zeros((1, 4, w.d), dtype=torch.float32, device="cuda")
+    lse = torch.zeros((1, 4), dtype=torch.float32, device="cuda")
+    for fused in (False, True):
+        out.fill_(float("nan"))
+        if fused:
+            lc.lc_decode_step(idx, q, K, V, 64, out, ws, lse=lse, chunk_ids=ids, counts=counts)
+        else:
+            lc.lc_retrieve(idx, q, 64, ids, counts, ws)
+            lc.lc_sparse_decode(idx, q, K, V, ids, counts, out, ws, lse=lse)
+        torch.cuda.synchronize()
+        assert counts.cpu().numpy().tolist() == [[0, 0]]
+        for h in range(2):
+            ref, ref_lse = H.dense_attention_library(wl.bf16_bits_to_f64(s.Q[0][2 * h:2 * h + 2]),
+                                                     wl.bf16_bits_to_f64(s.K[h]), wl.bf16_bits_to_f64(s.V[h]))
+            mx, rel = G.attention_errors(out[0, 2 * h:2 * h + 2].cpu().numpy(), ref)
+            assert mx <= ATTN_MAX_ABS and rel <= ATTN_REL_L2, (fused, h, mx, rel)
+            assert np.all(np.abs(lse[0, 2 * h:2 * h + 2].cpu().numpy() - ref_lse) <= 1e-3)
+    # the first chunk closes: 51 tokens become chunk 0, and it can be retrieved
+    st = wl.make_stream(w, 0, 2)
+    lc.lc_append(idx, K, V, G.to_bf16_tensor(st.k[0][None]), G.to_bf16_tensor(st.v[0][None]), [1], ws)
+    lc.lc_append(idx, K, V, G.to_bf16_tensor(st.k[1][None]), G.to_bf16_tensor(st.v[1][None]), [0], ws)
+    torch.cuda.synchronize()
+    assert idx.info(0)[:2] == (52, 1)
+    lc.lc_decode_step(idx, q, K, V, 64, out, ws, lse=lse, chunk_ids=ids, counts=counts)
+    torch.cuda.synchronize()
+    assert counts.cpu().numpy().tolist() == [[1, 1]] and ids[0, :, 0].cpu().numpy().tolist() == [0, 0]
+    assert torch.isfinite(out).all()
+    lc.lc_retrieve(idx, q, 40, ids, counts, ws)                      # the only chunk is longer than this budget
+    torch.cuda.synchronize()
+    assert counts.cpu().numpy().tolist() == [[0, 0]]
