@@ -77,9 +77,20 @@ def test_c3_headline_128k(G):
     beam = [0, 16, 4, 0]
     lc.lc_set_policy(case.idx, lc.LC_POLICY_BEAM, beam, 0)
     ids, _, _ = G.gpu_retrieve(case, qb, wl.C3.budget, want_scores=False)
+    from paper_2603_08453_amd import diagnostics as D
+    rec_exact, rec_beam, tok_exact, tok_beam = [], [], [], []
     for h in range(8):
         q = wl.bf16_bits_to_f64(qb[0, h * 4:(h + 1) * 4])
-        assert ids[0][h].tolist() == orc.retrieve_beam(case.oidx[0][h], q, wl.C3.budget, beam).tolist(), h
+        oi = case.oidx[0][h]
+        assert ids[0][h].tolist() == orc.retrieve_beam(oi, q, wl.C3.budget, beam).tolist(), h
+        # retrieval quality of the two policies under the same budget: recall of the true top-256 tokens
+        logits = case.Kf(0, h)[:oi.T] @ q[0]
+        for got, rec, tok in ((ids_auto[0][h], rec_exact, tok_exact), (ids[0][h], rec_beam, tok_beam)):
+            sel = D.selected_tokens(oi.bounds, oi.T, got)
+            rec.append(D.recall_rate(logits, sel, 256))
+            tok.append(len(sel))
+    _say(f"C3 recall of the true top-256 tokens (first query head of each KV head): EXACT {np.mean(rec_exact):.3f} "
+         f"with {np.mean(tok_exact):.0f} tokens attended, top-k per level {np.mean(rec_beam):.3f} with {np.mean(tok_beam):.0f}")
     # dense degenerate case at full size: budget >= context attends everything (properties only)
     lc.lc_set_policy(case.idx, lc.LC_POLICY_EXACT, None, 0)
     case2 = G.make_case(wl.C3, prune=lc.LC_PRUNE_AUTO)                 # cap = all chunks
