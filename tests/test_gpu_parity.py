@@ -663,3 +663,36 @@ def test_index_with_no_closed_chunk_yet(G):
     lc.lc_retrieve(idx, q, 40, ids, counts, ws)                      # the only chunk is longer than this budget
     torch.cuda.synchronize()
     assert counts.cpu().numpy().tolist() == [[0, 0]]
+
+
+def test_chunker_bounds_feed_the_index(G):
+    """The host chunker's boundaries are a valid chunk_bounds argument: build on them, and one decode
+    step over everything equals dense attention."""
+    import torch
+    from paper_2603_08453_amd import binding as lc
+    r = np.random.default_rng(5)
+    vocab = ["the", " cat", ".", ",", "\n", "\n\n", "}", " ", "x", "foo ", ":", "y", " sat", " on", " mat"]
+    T = 600
+    toks = [vocab[i] for i in r.integers(0, len(vocab), size=T)]
+    bounds = lc.lc_chunk_tokens(toks, 8, 16)
+    lens = np.diff(bounds)
+    assert bounds[0] == 0 and bounds[-1] == T and lens.max() <= 16 and lens[:-1].min() >= 8
+    w = wl.tiny("chunked", levels=2, fanout=4, T=T, H_q=4, H_kv=2)
+    s = wl.make_sequence(w, 0, T)
+    cfg = lc.lc_config_default(levels=2, fanout=4, max_chunks=len(lens) + 4, max_tokens=T + 8)
+    K = torch.zeros((1, 2, T + 8, w.d), dtype=torch.bfloat16, device="cuda")
+    V = torch.zeros_like(K)
+    K[0, :, :T] = G.to_bf16_tensor(s.K)
+    V[0, :, :T] = G.to_bf16_tensor(s.V)
+    ib = torch.zeros(lc.lc_index_bytes(cfg, 1, 2), dtype=torch.uint8, device="cuda")
+    ws = torch.zeros(lc.lc_workspace_bytes(cfg, 1, 4, 2), dtype=torch.uint8, device="cuda")
+    idx = lc.lc_build_index(cfg, K, [T], [bounds], ib, ws)
+    assert idx.info(0)[:2] == (T, len(lens))
+    out = torch.zeros((1, 4, w.d), dtype=torch.float32, device="cuda")
+    lc.lc_decode_step(idx, G.to_bf16_tensor(s.Q[0][None]), K, V, T, out, ws)
+    torch.cuda.synchronize()
+    for h in range(2):
+        ref, _ = H.dense_attention_library(wl.bf16_bits_to_f64(s.Q[0][2 * h:2 * h + 2]),
+                                           wl.bf16_bits_to_f64(s.K[h]), wl.bf16_bits_to_f64(s.V[h]))
+        mx, rel = G.attention_errors(out[0, 2 * h:2 * h + 2].cpu().numpy(), ref)
+        assert mx <= ATTN_MAX_ABS and rel <= ATTN_REL_L2
