@@ -696,3 +696,37 @@ def test_chunker_bounds_feed_the_index(G):
                                            wl.bf16_bits_to_f64(s.K[h]), wl.bf16_bits_to_f64(s.V[h]))
         mx, rel = G.attention_errors(out[0, 2 * h:2 * h + 2].cpu().numpy(), ref)
         assert mx <= ATTN_MAX_ABS and rel <= ATTN_REL_L2
+
+
+@pytest.mark.parametrize("seed", list(range(24)))
+def test_random_small_configurations(G, seed):
+    """Seeded random shapes: group size 1..8, 1..4 levels, odd fan-outs, ragged batches, open tails,
+    sinks, both policies -- retrieval, attention and the fused step against the oracle."""
+    from paper_2603_08453_amd import binding as lc
+    r = np.random.default_rng(1000 + seed)
+    g = int(r.integers(1, 9))
+    h_kv = int(r.integers(1, 4))
+    B = int(r.integers(1, 4))
+    levels = int(r.integers(1, 5))
+    fanout = int(r.integers(2, 9))
+    lo = int(r.integers(1, 9))
+    hi = lo + int(r.integers(0, 40))
+    t_lo = int(r.integers(40, 600))
+    w = wl.tiny(f"rand{seed}", B=B, H_q=g * h_kv, H_kv=h_kv, levels=levels, fanout=fanout, T=0,
+                T_range=(t_lo, t_lo + int(r.integers(1, 1500))), chunk_lo=lo, chunk_hi=hi)
+    tails = [int(x) for x in r.integers(0, 30, size=B)]
+    geometry = orc.TOKEN_BALL if r.random() < 0.7 else orc.PAPER_UNIT
+    _say(f"seed {seed}: G={g} H_kv={h_kv} B={B} L={levels} F={fanout} chunks {lo}..{hi} tails {tails} geometry {geometry}")
+    case = G.make_case(w, tails=tails, geometry=geometry, prune=int(r.integers(0, 3)))
+    qb = _q_batch(case, 0)
+    for budget in (int(r.integers(0, 40)), int(r.integers(40, 400)), int(r.integers(400, 3000))):
+        sink = int(r.integers(0, 30)) if r.random() < 0.4 else 0
+        ids = _check_retrieve(G, case, qb, budget, sink=sink, tag=f"rand{seed}")
+        _check_decode(G, case, qb, ids, tag=f"rand{seed} budget {budget}")
+        _check_step(G, case, qb, budget, sink=sink, tag=f"rand{seed} step")
+    if levels > 1:
+        beam = [int(r.integers(0, 12))] + [int(r.integers(1, 6)) for _ in range(levels - 1)]
+        budget = int(r.integers(50, 2000))
+        _check_retrieve(G, case, qb, budget, policy=orc.POLICY_BEAM, beam=beam, tag=f"rand{seed} beam {beam}")
+        _check_step(G, case, qb, budget, policy=orc.POLICY_BEAM, beam=beam, tag=f"rand{seed} step beam")
+    lc.lc_set_policy(case.idx, lc.LC_POLICY_EXACT, None, 0)
