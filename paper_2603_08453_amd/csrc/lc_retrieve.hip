@@ -49,7 +49,7 @@ struct LcRetrieveArgs {
     int walk;                // 1 = the internal levels were walked and `want` is valid
     int chunk_cap;           // upper kernel: LDS entries of the probe list; leaf kernel: LDS entries for
                              // the select's staging, 0 = stage in `scratch` (global memory)
-    int score_only;          // 1 = the leaf kernel only writes the score keys (the fused decode step selects)
+    int score_only;          // 1 = only the score keys are wanted (lc_score_kernel; the fused decode step selects)
 };
 
 // Selection among n <= LC_COUNT_SELECT_MAX candidates whose keys / weights sit in 16-byte aligned,
@@ -592,7 +592,6 @@ lc_leaf_kernel(const LcRetrieveArgs a) {
 
     LC_STAMP0(lc_dbg_leaf, 2);
     // ---- last workgroup of this (sequence, head) selects
-    if (a.score_only) return;
     // (every workgroup empties its select histogram on the way: whichever turns out to be the last
     // finds it ready behind the barriers of the arrival)
     lc_leaf_select_prepare<LC_LF_THREADS>(sel_sh);
@@ -665,6 +664,68 @@ lc_leaf_kernel(const LcRetrieveArgs a) {
 // ---------------------------------------------------------------------------------
 // launcher
 // ---------------------------------------------------------------------------------
+// ---------------------------------------------------------------------------------
+// kernel 2': chunk scoring only (the fused decode step selects by itself)
+// ---------------------------------------------------------------------------------
+// The same scoring as lc_leaf_kernel without the selection behind it, so without its LDS and its
+// 1024-thread workgroups: NT threads = NT/16 groups, R chunks per group.
+#define LC_SC_THREADS 256
+#define LC_SCORE_MAX_WGS 1024          // measured flat between 512 and 2048 workgroups
+template <int G, int R>
+__global__ void __launch_bounds__(LC_SC_THREADS)
+lc_score_kernel(const LcRetrieveArgs a) {
+    constexpr int GROUPS = LC_SC_THREADS / 16;
+    const LcDev& ix = a.ix;
+    const int h = blockIdx.y, b = blockIdx.z;
+    const int bh = b * ix.H + h;
+    const int tid = threadIdx.x;
+    const int sub = tid & 15, grp = tid >> 4;
+    const size_t cb = (size_t)bh * ix.cap[0];
+    const int* bnd = ix.bounds + (size_t)b * (ix.cap[0] + 1);
+    uint32_t* keys = a.keys + cb;
+    const uint8_t* want = a.want + cb;
+    const int* par0 = ix.parent[0] + cb;
+    const bool have_want = a.walk != 0;
+    const int j_lo = blockIdx.x * (R * GROUPS);
+    int jj[R], wv[R];
+    float rv[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int j = min(j_lo + r * GROUPS + grp, ix.cap[0] - 1);
+        jj[r] = j;
+        wv[r] = (bnd[j] >= a.sink ? 1 : 0) & (have_want ? (int)want[min(max(par0[j], 0), ix.cap[0] - 1)] : 1);
+        rv[r] = ix.radius[0][cb + j];
+    }
+    LcNodeFrag pre[R];
+    if (!have_want) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) pre[r] = lc_load_node(ix.center[0] + (cb + jj[r]) * LC_D, sub);
+    }
+    float qf[G][8], qn[G];
+    lc_load_query_frags<G>(a.q + (size_t)b * ix.H * G * LC_D, h, sub, qf, qn);
+    const int M = ix.state[bh * 4 + 1];
+    if (j_lo >= M) return;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int j = j_lo + r * GROUPS + grp;
+        float sv = LC_NEG_INF;
+        if (a.budget > 0 && j < M && wv[r]) {
+            if (!have_want) sv = lc_score_frag<G>(pre[r], rv[r], qf, qn);
+            else sv = lc_score_node<G>(ix.center[0] + (cb + jj[r]) * LC_D, rv[r], sub, qf, qn);
+        }
+        if (j < M && sub == 0) keys[j] = lc_score_key(sv);
+    }
+}
+
+template <int G, int R>
+static int launch_score(const LcRetrieveArgs& a, int max_M, hipStream_t stream) {
+    const int per = R * (LC_SC_THREADS / 16);
+    const int nblk = max_M > 0 ? (max_M + per - 1) / per : 1;
+    hipLaunchKernelGGL((lc_score_kernel<G, R>), dim3(nblk, a.ix.H, a.ix.B), dim3(LC_SC_THREADS), 0, stream, a);
+    LC_HIP_CHECK(hipGetLastError());
+    return LC_OK;
+}
+
 template <int G, int R>
 static int launch_leaf(const LcRetrieveArgs& a, int max_M, size_t lds, hipStream_t stream) {
     if (lds > 48 * 1024)
@@ -695,8 +756,15 @@ static int launch_retrieve_g(LcRetrieveArgs& a, int max_M, hipStream_t stream) {
         hipLaunchKernelGGL(lc_upper_kernel<G>, dim3(ix.H, ix.B), dim3(LC_UP_THREADS), lds, stream, a);
         LC_HIP_CHECK(hipGetLastError());
     }
+    if (a.score_only) {
+        // chunks per group: enough work per workgroup without leaving compute units idle
+        int rs = 1;
+        while (rs < 4 && (long long)((max_M + 16 * rs - 1) / (16 * rs)) * ix.H * ix.B > LC_SCORE_MAX_WGS) rs *= 2;
+        if (rs == 1) return launch_score<G, 1>(a, max_M, stream);
+        if (rs == 2) return launch_score<G, 2>(a, max_M, stream);
+        return launch_score<G, 4>(a, max_M, stream);
+    }
     a.chunk_cap = ((size_t)mc * 8 + sizeof(LcLeafSelSh) + 1024 <= lds_limit) ? mc : 0;
-    if (a.score_only) a.chunk_cap = 0;
     const size_t lds2 = (size_t)a.chunk_cap * 8;
     // chunks per group: the fewest for which there is at most one workgroup per compute unit
     // (measured: beyond that the kernel gets slower, not faster)
