@@ -730,3 +730,60 @@ def test_random_small_configurations(G, seed):
         _check_retrieve(G, case, qb, budget, policy=orc.POLICY_BEAM, beam=beam, tag=f"rand{seed} beam {beam}")
         _check_step(G, case, qb, budget, policy=orc.POLICY_BEAM, beam=beam, tag=f"rand{seed} step beam")
     lc.lc_set_policy(case.idx, lc.LC_POLICY_EXACT, None, 0)
+
+
+def test_graph_replays_equal_eager(G, c1):
+    """The retrieval + attention calls captured in a HIP graph: every replay, with eager work and
+    synchronisations in between, reproduces the eager results bit for bit (nothing in the kernels'
+    cross-workgroup hand-off may depend on state left by an earlier launch)."""
+    import torch
+    from paper_2603_08453_amd import binding as lc
+    w = c1.w
+    lc.lc_set_policy(c1.idx, lc.LC_POLICY_EXACT, None, 0)
+    lc.lc_set_prune(c1.idx, lc.LC_PRUNE_ALWAYS)
+    qs = [G.to_bf16_tensor(np.stack([wl.make_queries(w, b, c1.seqs[b].offsets, 1, stream=200 + i)[0][0]
+                                     for b in range(w.B)])) for i in range(3)]
+    ids = [torch.zeros((w.B, w.H_kv, c1.cap), dtype=torch.int32, device="cuda") for _ in range(3)]
+    counts = [torch.zeros((w.B, w.H_kv), dtype=torch.int32, device="cuda") for _ in range(3)]
+    outs = [torch.zeros((w.B, w.H_q, w.d), dtype=torch.float32, device="cuda") for _ in range(6)]
+
+    def work():
+        for i in range(3):
+            lc.lc_retrieve(c1.idx, qs[i], 700, ids[i], counts[i], c1.ws)
+            lc.lc_sparse_decode(c1.idx, qs[i], c1.K, c1.V, ids[i], counts[i], outs[i], c1.ws)
+            lc.lc_decode_step(c1.idx, qs[i], c1.K, c1.V, 700, outs[3 + i], c1.ws)
+
+    work()
+    torch.cuda.synchronize()
+    want = [o.clone() for o in outs]
+    want_ids = [(a.clone(), c.clone()) for a, c in zip(ids, counts)]
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        work()
+        side.synchronize()
+        with torch.cuda.graph(g, stream=side):
+            work()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        for o in outs:
+            o.fill_(float("nan"))
+        for a in ids:
+            a.fill_(-7)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for o, ref in zip(outs, want):
+            assert torch.equal(o, ref), rep
+        for (a, c), (ra, rc) in zip(zip(ids, counts), want_ids):
+            assert torch.equal(c, rc)
+            for b in range(w.B):
+                for h in range(w.H_kv):
+                    n = int(c[b, h])
+                    assert torch.equal(a[b, h, :n], ra[b, h, :n])
+        # eager work of the same kind between the replays
+        lc.lc_decode_step(c1.idx, qs[rep % 3], c1.K, c1.V, 300 + rep, outs[0], c1.ws)
+        torch.cuda.synchronize()
+    lc.lc_set_prune(c1.idx, lc.LC_PRUNE_ALWAYS)
