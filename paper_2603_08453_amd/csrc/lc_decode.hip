@@ -660,7 +660,7 @@ bool lc_decode_fused_fits(int G, int max_M) {
 template <int G>
 static int launch_fused_g(const LcDecodeArgs& a, int splits, hipStream_t stream) {
     const size_t lds = (size_t)a.chunk_cap * 12;
-    if (lds > 16 * 1024)
+    if (lds > 0 && fused_static_lds<G>() + lds > 48 * 1024)          // beyond the default per-workgroup allowance
         LC_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&lc_decode_kernel<G, true>),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     hipLaunchKernelGGL((lc_decode_kernel<G, true>), dim3(splits, a.ix.H, a.ix.B), dim3(LC_DEC_THREADS), lds, stream, a);

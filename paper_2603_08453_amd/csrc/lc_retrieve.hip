@@ -728,7 +728,7 @@ static int launch_score(const LcRetrieveArgs& a, int max_M, hipStream_t stream) 
 
 template <int G, int R>
 static int launch_leaf(const LcRetrieveArgs& a, int max_M, size_t lds, hipStream_t stream) {
-    if (lds > 48 * 1024)
+    if (lds + sizeof(LcLeafSelSh) + 1024 > 48 * 1024)             // static + dynamic beyond the default allowance
         LC_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&lc_leaf_kernel<G, R>),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     const int per = R * LC_LF_GROUPS;
