@@ -321,6 +321,19 @@ def main():
     torch.cuda.synchronize()
     append_us = (time.perf_counter() - ta) / n_app * 1e6
 
+    # what a plain device copy reaches on this machine (read + written bytes per second), as context for the 8 TB/s figure
+    cp_src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+    cp_dst = torch.empty_like(cp_src)
+    cp_dst.copy_(cp_src)
+    ce0, ce1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ce0.record()
+    for _ in range(5):
+        cp_dst.copy_(cp_src)
+    ce1.record()
+    torch.cuda.synchronize()
+    copy_gbps = 5 * 2 * (1 << 30) / (ce0.elapsed_time(ce1) * 1e-3) / 1e9
+    del cp_src, cp_dst
+
     best_s = graph_s if (graph_s is not None and graph_s < eager_s) else eager_s
     step_bytes = attend_bytes + retrieve_bytes
 
@@ -408,6 +421,7 @@ def main():
             "attend_kernel_alone_frac_of_hbm_peak": round(attend_bytes / (attend_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
             "append_us": round(append_us, 2),
             "build_ms": round(float(np.median(build_ms)), 2),
+            "device_copy_GBps": round(copy_gbps, 1),
             "step_bytes": round(step_bytes),
             "retrieve_bytes": round(retrieve_bytes),
             "attend_bytes": round(attend_bytes),
