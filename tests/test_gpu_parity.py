@@ -712,12 +712,13 @@ def test_random_small_configurations(G, seed):
     lo = int(r.integers(1, 9))
     hi = lo + int(r.integers(0, 40))
     t_lo = int(r.integers(40, 600))
-    w = wl.tiny(f"rand{seed}", B=B, H_q=g * h_kv, H_kv=h_kv, levels=levels, fanout=fanout, T=0,
+    w = wl.tiny(f"rand{seed}", cfg_id=1000 + seed, B=B, H_q=g * h_kv, H_kv=h_kv, levels=levels, fanout=fanout, T=0,
                 T_range=(t_lo, t_lo + int(r.integers(1, 1500))), chunk_lo=lo, chunk_hi=hi)
     tails = [int(x) for x in r.integers(0, 30, size=B)]
     geometry = orc.TOKEN_BALL if r.random() < 0.7 else orc.PAPER_UNIT
     _say(f"seed {seed}: G={g} H_kv={h_kv} B={B} L={levels} F={fanout} chunks {lo}..{hi} tails {tails} geometry {geometry}")
-    case = G.make_case(w, tails=tails, geometry=geometry, prune=int(r.integers(0, 3)))
+    splits = int(np.random.default_rng(7000 + seed).choice([0, 0, 1, 2, 7]))   # 0 = the library's choice
+    case = G.make_case(w, tails=tails, geometry=geometry, prune=int(r.integers(0, 3)), decode_splits=splits)
     qb = _q_batch(case, 0)
     for budget in (int(r.integers(0, 40)), int(r.integers(40, 400)), int(r.integers(400, 3000))):
         sink = int(r.integers(0, 30)) if r.random() < 0.4 else 0
@@ -729,6 +730,41 @@ def test_random_small_configurations(G, seed):
         budget = int(r.integers(50, 2000))
         _check_retrieve(G, case, qb, budget, policy=orc.POLICY_BEAM, beam=beam, tag=f"rand{seed} beam {beam}")
         _check_step(G, case, qb, budget, policy=orc.POLICY_BEAM, beam=beam, tag=f"rand{seed} step beam")
+    lc.lc_set_policy(case.idx, lc.LC_POLICY_EXACT, None, 0)
+
+
+@pytest.mark.parametrize("seed", list(range(int(__import__("os").environ.get("LC_RANDOM_MEDIUM_CONFIGS", "4")))))
+def test_random_medium_configurations(G, seed):
+    """Seeded random shapes with tens of thousands of tokens and hundreds to thousands of chunks per
+    head (both sides of the chunk count at which lc_decode_step changes its kernels), forced small
+    split counts (several tiles per split) and budgets of thousands of tokens."""
+    from paper_2603_08453_amd import binding as lc
+    r = np.random.default_rng(3000 + seed)
+    g = int(r.integers(1, 9))
+    h_kv = int(r.integers(1, 3))
+    B = int(r.integers(1, 3))
+    levels = int(r.integers(2, 5))
+    fanout = int(r.integers(8, 33))
+    lo = int(r.integers(4, 17))
+    hi = lo + int(r.integers(0, 49))
+    t_lo = int(r.integers(20000, 60000))
+    w = wl.tiny(f"med{seed}", cfg_id=3000 + seed, B=B, H_q=g * h_kv, H_kv=h_kv, levels=levels, fanout=fanout, T=0,
+                T_range=(t_lo, t_lo + int(r.integers(1, 30000))), chunk_lo=lo, chunk_hi=hi)
+    tails = [int(x) for x in r.integers(0, 70, size=B)]
+    splits = int(r.choice([0, 0, 1, 3, 8]))
+    _say(f"medium seed {seed}: G={g} H_kv={h_kv} B={B} L={levels} F={fanout} chunks {lo}..{hi} tails {tails} splits {splits}")
+    case = G.make_case(w, tails=tails, prune=int(r.integers(0, 3)), decode_splits=splits)
+    _say(f"  chunks per sequence {[len(s.bounds) - 1 for s in case.seqs]}, tokens {[s.T for s in case.seqs]}")
+    qb = _q_batch(case, 0)
+    for budget in (int(r.integers(500, 3000)), int(r.integers(3000, 9000))):
+        sink = int(r.integers(0, 40)) if r.random() < 0.4 else 0
+        ids = _check_retrieve(G, case, qb, budget, sink=sink, tag=f"med{seed}")
+        _check_decode(G, case, qb, ids, tag=f"med{seed} budget {budget}")
+        _check_step(G, case, qb, budget, sink=sink, tag=f"med{seed} step")
+    beam = [int(r.integers(0, 200))] + [int(r.integers(2, 20)) for _ in range(levels - 1)]
+    budget = int(r.integers(1000, 5000))
+    _check_retrieve(G, case, qb, budget, policy=orc.POLICY_BEAM, beam=beam, tag=f"med{seed} beam {beam}")
+    _check_step(G, case, qb, budget, policy=orc.POLICY_BEAM, beam=beam, tag=f"med{seed} step beam")
     lc.lc_set_policy(case.idx, lc.LC_POLICY_EXACT, None, 0)
 
 
