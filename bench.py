@@ -332,7 +332,18 @@ def main():
     ce1.record()
     torch.cuda.synchronize()
     copy_gbps = 5 * 2 * (1 << 30) / (ce0.elapsed_time(ce1) * 1e-3) / 1e9
-    del cp_src, cp_dst
+    # and a plain streaming read of 2 GiB (the decode path only reads)
+    del cp_dst
+    rd_src = torch.empty(2 << 30, dtype=torch.uint8, device=dev).fill_(1)
+    rd_sink = torch.zeros(2048, dtype=torch.int32, device=dev)
+    lc.lc_read_sweep(rd_src, rd_sink)
+    ce0.record()
+    for _ in range(5):
+        lc.lc_read_sweep(rd_src, rd_sink)
+    ce1.record()
+    torch.cuda.synchronize()
+    read_gbps = 5 * (2 << 30) / (ce0.elapsed_time(ce1) * 1e-3) / 1e9
+    del cp_src, rd_src
 
     best_s = graph_s if (graph_s is not None and graph_s < eager_s) else eager_s
     step_bytes = attend_bytes + retrieve_bytes
@@ -422,6 +433,7 @@ def main():
             "append_us": round(append_us, 2),
             "build_ms": round(float(np.median(build_ms)), 2),
             "device_copy_GBps": round(copy_gbps, 1),
+            "device_read_GBps": round(read_gbps, 1),
             "step_bytes": round(step_bytes),
             "retrieve_bytes": round(retrieve_bytes),
             "attend_bytes": round(attend_bytes),

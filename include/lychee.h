@@ -161,6 +161,14 @@ int lc_set_prune(lc_index* idx, int prune);
  * lc_retrieve + lc_sparse_decode ignores the setting. */
 int lc_set_step_reuse_keys(lc_index* idx, int on);
 
+/* Measurement aid, not part of the decode path: reads `bytes` bytes (a multiple of 16, from a
+ * 16-byte aligned device pointer) once with plain streaming loads, so that a benchmark can quote
+ * the read bandwidth this GPU reaches beside its published peak.  `sink` (device, at least 2048
+ * words; `sink_words` says how many there are) receives one folded word per workgroup.
+ * LC_ERR_INVALID_ARG for a null or misaligned pointer or a size that is 0 or not a multiple of 16,
+ * LC_ERR_WORKSPACE_TOO_SMALL for a short sink. */
+int lc_read_sweep(const void* src, size_t bytes, uint32_t* sink, size_t sink_words, void* stream);
+
 /*
  * lc_retrieve -- hierarchical retrieval for one decode step (Eq. 2, Algorithm 1
  * steps 1-2).  Per (sequence, KV head) every node u gets the group score

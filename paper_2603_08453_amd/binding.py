@@ -104,6 +104,8 @@ def lib() -> ctypes.CDLL:
     L.lc_recluster.restype = ctypes.c_int
     L.lc_set_step_reuse_keys.argtypes = [vp, ctypes.c_int]
     L.lc_set_step_reuse_keys.restype = ctypes.c_int
+    L.lc_read_sweep.argtypes = [vp, ctypes.c_size_t, vp, ctypes.c_size_t, vp]
+    L.lc_read_sweep.restype = ctypes.c_int
     L.lc_append.argtypes = [vp, vp, vp, i64p, vp, vp, u8p, vp, ctypes.c_size_t, vp]
     L.lc_append.restype = ctypes.c_int
     L.lc_index_info.argtypes = [vp, ctypes.c_int, i32p, i32p, i32p]
@@ -254,6 +256,12 @@ def lc_recluster(idx: Index, ws, stream=None) -> None:
 
 def lc_set_step_reuse_keys(idx: Index, on: bool) -> None:
     _check(lib().lc_set_step_reuse_keys(idx.handle, 1 if on else 0), "lc_set_step_reuse_keys")
+
+
+def lc_read_sweep(src, sink, stream=None) -> None:
+    """Reads the device tensor `src` once; `sink` is an int32/uint32 device tensor of >= 2048 words."""
+    _check(lib().lc_read_sweep(_ptr(src), src.numel() * src.element_size(), _ptr(sink), sink.numel(),
+                               _stream(stream)), "lc_read_sweep")
 
 
 def lc_decode_step(idx: Index, q, K, V, budget: int, out, ws, lse=None, chunk_ids=None, counts=None,

@@ -768,6 +768,20 @@ def test_random_medium_configurations(G, seed):
     lc.lc_set_policy(case.idx, lc.LC_POLICY_EXACT, None, 0)
 
 
+def test_read_sweep_reads_every_word_once(G):
+    """The bandwidth probe folds (xor) exactly the words of the buffer, whatever its length."""
+    import torch
+    from paper_2603_08453_amd import binding as lc
+    r = np.random.default_rng(11)
+    for n_words in (4, 4 * 1000, 4 * (256 * 2048 * 4 + 77), 4 * 3_000_001):
+        host = r.integers(0, 2 ** 31, size=n_words, dtype=np.int64).astype(np.int32)
+        src = torch.from_numpy(host).cuda()
+        sink = torch.full((2048,), 123, dtype=torch.int32, device="cuda")
+        lc.lc_read_sweep(src, sink)
+        torch.cuda.synchronize()
+        assert int(np.bitwise_xor.reduce(sink.cpu().numpy())) == int(np.bitwise_xor.reduce(host)), n_words
+
+
 def test_graph_replays_equal_eager(G, c1):
     """The retrieval + attention calls captured in a HIP graph: every replay, with eager work and
     synchronisations in between, reproduces the eager results bit for bit (nothing in the kernels'

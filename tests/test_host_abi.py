@@ -94,6 +94,10 @@ def test_argument_errors_before_any_gpu_work(L):
                             None) == lc.LC_ERR_INVALID_ARG
     assert L.lc_recluster(None, fake, 1 << 20, None) == lc.LC_ERR_INVALID_ARG
     assert L.lc_set_step_reuse_keys(None, 1) == lc.LC_ERR_INVALID_ARG
+    assert L.lc_read_sweep(None, 1 << 20, fake, 2048, None) == lc.LC_ERR_INVALID_ARG
+    assert L.lc_read_sweep(fake, 100, fake, 2048, None) == lc.LC_ERR_INVALID_ARG          # not a multiple of 16
+    assert L.lc_read_sweep(ctypes.c_void_p(0x10008), 1 << 20, fake, 2048, None) == lc.LC_ERR_INVALID_ARG
+    assert L.lc_read_sweep(fake, 1 << 20, fake, 100, None) == lc.LC_ERR_WORKSPACE_TOO_SMALL
     assert L.lc_append(None, fake, fake, strides, fake, fake, None, fake, 0, None) == lc.LC_ERR_INVALID_ARG
     assert L.lc_set_policy(None, 0, None, 0) == lc.LC_ERR_INVALID_ARG
     assert L.lc_index_info(None, 0, None, None, None) == lc.LC_ERR_INVALID_ARG
