@@ -38,10 +38,10 @@ Readings taken where the paper is silent (each is listed in the design notes):
     float32 and measured against the stored (rounded) centers.
 
 Parity status: every function below is pinned by tests/test_oracle_*.py
-(brute force, closed forms, library routines, a hand-worked example), except
-the *topology* produced by spherical k-means (initialisation and rounding can
-change assignments): "parity unpinned" for that topology; it is constrained
-only by invariants (objective monotone, k = N, separated clusters recovered).
+(brute force, closed forms, library routines, a hand-worked example).  The
+clustering is pinned by iterating a library's nearest-codeword search (which
+on the unit sphere is the inner-product assignment) from the same start, and
+by invariants (objective monotone, k = N, separated clusters recovered).
 """
 from __future__ import annotations
 

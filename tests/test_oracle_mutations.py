@@ -119,3 +119,33 @@ def test_kmeans_argmin_is_caught(monkeypatch):
     monkeypatch.setattr(orc, "spherical_kmeans", bad_kmeans)
     assert _fails(P.test_kmeans_k_equals_n_and_separated_clusters)
     assert _fails(P.test_hand_example_index)
+
+
+def test_kmeans_unnormalised_update_and_wrong_start_are_caught(monkeypatch):
+    """Mistakes that keep the objective monotone and still separate clear clusters: only the
+    comparison with the library's nearest-codeword iterations sees them."""
+    def mean_update(X, k, iters, trace=None):
+        N = X.shape[0]
+        m = np.stack([X[(c * N) // k] for c in range(k)]).astype(np.float64)
+        labels = np.zeros(N, dtype=np.int64)
+        for _ in range(iters):
+            labels = np.argmax(X @ m.T, axis=1)
+            for c in range(k):
+                if np.any(labels == c):
+                    m[c] = X[labels == c].mean(axis=0)          # wrong: not projected back onto the sphere
+        return labels, m
+
+    def first_k_start(X, k, iters, trace=None):
+        m = X[:k].astype(np.float64).copy()                     # wrong: first k points instead of strided
+        labels = np.zeros(X.shape[0], dtype=np.int64)
+        for _ in range(iters):
+            labels = np.argmax(X @ m.T, axis=1)
+            for c in range(k):
+                if np.any(labels == c):
+                    m[c] = orc.unit(X[labels == c].sum(axis=0))
+        return labels, m
+
+    for bad in (mean_update, first_k_start):
+        monkeypatch.setattr(orc, "spherical_kmeans", bad)
+        assert _fails(P.test_kmeans_equals_library_nearest_codeword_iterations, 1, 200, 128, 13) or \
+            _fails(P.test_kmeans_equals_library_nearest_codeword_iterations, 3, 500, 32, 32), bad.__name__

@@ -340,6 +340,30 @@ def test_kmeans_objective_monotone_and_unit_centroids():
     assert labels.min() >= 0 and labels.max() < 7
 
 
+@pytest.mark.parametrize("seed,N,d,k", [(0, 60, 8, 5), (1, 200, 128, 13), (2, 33, 16, 33), (3, 500, 32, 32)])
+def test_kmeans_equals_library_nearest_codeword_iterations(seed, N, d, k):
+    """On the unit sphere |x - m|^2 = 2 - 2<x, m>, so the assignment step is the nearest-codeword
+    search of a vector-quantisation library (Euclidean) and of a cosine-distance argmin; iterating
+    those with a normalised-sum update from the same strided start must reproduce the labels and
+    centroids (generic data: no exact ties, no empty clusters by construction of the check)."""
+    from scipy.cluster.vq import vq
+    from sklearn.metrics import pairwise_distances_argmin
+    r = np.random.default_rng(100 + seed)
+    n_src = max(2, k // 2)
+    X = orc.unit_rows(r.standard_normal((N, d)) + 2.0 * r.standard_normal((n_src, d))[r.integers(0, n_src, size=N)])
+    m = np.stack([X[(c * N) // k] for c in range(k)])
+    for _ in range(10):
+        lab = vq(X, m)[0]
+        assert np.array_equal(lab, pairwise_distances_argmin(X, m, metric="cosine"))
+        sums = np.zeros_like(m)
+        np.add.at(sums, lab, X)
+        hit = np.linalg.norm(sums, axis=1) > 0
+        m = np.where(hit[:, None], sums / np.maximum(np.linalg.norm(sums, axis=1), 1e-300)[:, None], m)
+    labels, cent = orc.spherical_kmeans(X, k, 10)
+    assert np.array_equal(labels, lab)
+    assert np.allclose(cent, m, rtol=0, atol=1e-12)
+
+
 def test_kmeans_k_equals_n_and_separated_clusters():
     r = np.random.default_rng(9)
     X = orc.unit_rows(r.standard_normal((9, 5)))
