@@ -40,6 +40,7 @@ def parse():
     ap.add_argument("--queries", type=int, default=16)
     ap.add_argument("--policy", default="exact", choices=["exact", "beam"])
     ap.add_argument("--splits", type=int, default=0)
+    ap.add_argument("--centers", default="f32", choices=["f32", "bf16"], help="storage of the chunk-level centers")
     ap.add_argument("--separate", action="store_true", help="time lc_retrieve + lc_sparse_decode instead of lc_decode_step")
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -72,7 +73,8 @@ def main():
     Mmax = max(len(s.bounds) - 1 for s in seqs)
     extra = 64
     cfg = lc.lc_config_default(levels=w.levels, fanout=w.fanout, max_chunks=Mmax + extra, max_tokens=Tmax + extra,
-                               decode_splits=args.splits)
+                               decode_splits=args.splits,
+                               center_dtype=lc.LC_CENTER_BF16 if args.centers == "bf16" else lc.LC_CENTER_F32)
     if args.policy == "beam":
         cfg.policy = lc.LC_POLICY_BEAM
         beam = [0] * lc.LC_MAX_LEVELS
@@ -156,7 +158,8 @@ def main():
     attend_bytes = float(np.mean(tok_per_q)) * 4 * w.d + io_small
     n_upper = sum(sum(reps[0]["idx"].info(b)[2][1:]) for b in range(w.B)) * w.H_kv
     node_bytes = w.d * 4 + 4 + 4
-    retrieve_bytes = (float(np.mean(scored_per_q)) + n_upper) * node_bytes \
+    chunk_node_bytes = w.d * (2 if args.centers == "bf16" else 4) + 4 + 4
+    retrieve_bytes = float(np.mean(scored_per_q)) * chunk_node_bytes + n_upper * node_bytes \
         + sum(len(bn) - 1 for bn in bounds_np) * w.H_kv * 8 + w.B * w.H_q * w.d * 2 + float(np.mean(chunks_per_q)) * 4
 
     # ------------------------------------------------------------- timing
@@ -296,6 +299,27 @@ def main():
                 retrieve(i)
             torch.cuda.synchronize()
 
+    # the same step on indices whose chunk-level centers are stored as bfloat16 (half the index bytes)
+    half_us = None
+    if graph_s is not None and args.centers == "f32" and args.policy == "exact":
+        cfg_half = lc.lc_config_default(levels=w.levels, fanout=w.fanout, max_chunks=Mmax + extra,
+                                        max_tokens=Tmax + extra, decode_splits=args.splits,
+                                        center_dtype=lc.LC_CENTER_BF16)
+        half = []
+        for rp in reps:
+            ibh = torch.zeros(lc.lc_index_bytes(cfg_half, w.B, w.H_kv), dtype=torch.uint8, device=dev)
+            half.append((ibh, lc.lc_build_index(cfg_half, rp["K"], [s.T for s in seqs], [s.bounds for s in seqs],
+                                               ibh, rp["ws"])))
+        torch.cuda.synchronize()
+
+        def step_half(i):
+            rp = reps[i % R]
+            lc.lc_decode_step(half[i % R][1], Qs[i % nq], rp["K"], rp["V"], w.budget, out, rp["ws"])
+
+        _, t_half = graph_us_per_launch(step_half, args.steps)
+        half_us = t_half * 1e6
+        del half
+
     # warm (cache-resident) figure: one replica, one query
     def step_warm(i):
         rp = reps[0]
@@ -365,7 +389,8 @@ def main():
         for h in heads:
             Kf[h] = wl.bf16_bits_to_f64(s0.K[h])
             Vf[h] = wl.bf16_bits_to_f64(s0.V[h])
-            oidx[h] = orc.build_index(Kf[h], s0.bounds, s0.T, w.levels, w.fanout)
+            oidx[h] = orc.build_index(Kf[h], s0.bounds, s0.T, w.levels, w.fanout,
+                                      center_dtype=orc.CENTER_BF16 if args.centers == "bf16" else orc.CENTER_F32)
             if time.perf_counter() - tb > 60 and len(oidx) >= 2:
                 break
         heads = sorted(oidx)
@@ -409,7 +434,7 @@ def main():
         "data": "synthetic (seeded; clustered keys, queries biased to 3 chunks)",
         "config": {"workload": w.name, "batch": w.B, "q_heads": w.H_q, "kv_heads": w.H_kv, "head_dim": w.d,
                    "context": Tmax, "chunks": Mmax, "levels": w.levels, "fanout": w.fanout, "budget": w.budget,
-                   "policy": args.policy, "replicas": R, "queries": nq,
+                   "policy": args.policy, "chunk_centers": args.centers, "replicas": R, "queries": nq,
                    "entry": "lc_retrieve+lc_sparse_decode" if args.separate else "lc_decode_step",
                    "launch": "hip-graph" if best_s == graph_s else "eager"},
         "roofline": {"bound": "hbm", "achieved": round(dom_bytes / (dom_us * 1e-6) / 1e9, 1),
@@ -424,6 +449,7 @@ def main():
             "warm_cache_us": round(warm_s * 1e6, 2),
             "level_walk_forced_us": None if walk_us is None else round(walk_us, 2),
             "beam_policy_us": None if beam_us is None else round(beam_us, 2),
+            "bf16_chunk_centers_us": None if half_us is None else round(half_us, 2),
             "entry_points": "lc_retrieve + lc_sparse_decode" if args.separate else "lc_decode_step",
             "separate_calls_us": None if separate_s is None else round(separate_s * 1e6, 2),
             "select_attend_kernel_us_event": round(fused_us, 2),

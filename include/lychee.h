@@ -73,6 +73,16 @@ enum { LC_POLICY_EXACT = 0, LC_POLICY_BEAM = 1 };
 enum { LC_PRUNE_AUTO = 0, LC_PRUNE_ALWAYS = 1, LC_PRUNE_NEVER = 2 };
 #define LC_PRUNE_AUTO_BYTES (1u << 30)
 
+/* How the centers of the chunk level (level 0) are stored.  The chunk level is almost the whole
+ * index (N_0 nodes against N_0 / F above it) and every decode step reads all of it.
+ * F32: float32 values.
+ * BF16: rounded to the nearest bfloat16 (ties to even) when the chunk is pooled; its radius, the
+ *   direction used for clustering and everything above it are then computed from the rounded
+ *   center, so the covering property of the radii (and with it Eq. 2) holds for the stored
+ *   values.  Halves the bytes of the chunk level.  The levels above keep float32: their centers
+ *   are running means that the lazy update (Section 4.4) moves by small steps. */
+enum { LC_CENTER_F32 = 0, LC_CENTER_BF16 = 1 };
+
 typedef struct lc_config {
     int32_t levels;                 /* L >= 1, counts the chunk level (paper: 3)            */
     int32_t fanout;                 /* F >= 1                                               */
@@ -87,12 +97,14 @@ typedef struct lc_config {
     int32_t max_tokens;             /* capacity: tokens per sequence (rows of K and V)      */
     int32_t decode_splits;          /* split-K factor of the attention kernel; 0 = auto     */
     int32_t prune;                  /* LC_PRUNE_*                                           */
+    int32_t center_dtype;           /* LC_CENTER_*: storage of the chunk-level centers      */
 } lc_config;
 
 typedef struct lc_index lc_index;   /* opaque host-side handle */
 
 /* Fill *cfg with defaults: levels 3, fanout 16, kmeans_iters 10, TOKEN_BALL,
- * EXACT, no beam limits, sink 0, prune AUTO, capacities 0 (the caller must set them). */
+ * EXACT, no beam limits, sink 0, prune AUTO, float32 centers, capacities 0 (the caller must
+ * set them). */
 void lc_config_default(lc_config* cfg /* host */);
 
 /* Text for an error code (static storage). */
@@ -256,10 +268,12 @@ int lc_index_info(const lc_index* idx, int b, int32_t* T, int32_t* M, int32_t* n
 /*
  * Export / import of the stored index as a flat little-endian host blob, so that
  * a CPU reference and the GPU can run on the identical stored values.
- *   int32 header[16] = {magic 'LCIX', version 1, B, H_kv, d, L, F, geometry, 0...}
+ *   int32 header[16] = {magic 'LCIX', version 1, B, H_kv, d, L, F, geometry, center_dtype, 0...}
  *   per sequence b:    int32 T_b, M_b, N_1..N_{L-1};  int32 bounds[M_b+1]
  *   per (b, h, level): float32 center[N_l][d], float32 radius[N_l],
  *                      int32 parent[N_l], int32 ntok[N_l], int32 nchunk[N_l]
+ * Centers are float32 in the blob whatever center_dtype says (bfloat16 values widened); import
+ * requires the blob's L, F, geometry and center_dtype to equal the configuration's.
  * lc_index_export synchronises the stream.  With blob == NULL it only stores the
  * required size in *bytes.
  */

@@ -34,8 +34,9 @@ Readings taken where the paper is silent (each is listed in the design notes):
     top-k per level.
   * lazy update: count-weighted cumulative mean; the radius also grows by the
     centroid shift so that old members stay covered.
-  * stored centers are float32 values, stored radii are rounded *up* to
-    float32 and measured against the stored (rounded) centers.
+  * stored centers are float32 values (chunk-level centers optionally
+    bfloat16 values), stored radii are rounded *up* to float32 and measured
+    against the stored (rounded) centers.
 
 Parity status: every function below is pinned by tests/test_oracle_*.py
 (brute force, closed forms, library routines, a hand-worked example).  The
@@ -58,6 +59,9 @@ PAPER_UNIT = 1
 POLICY_EXACT = 0
 POLICY_BEAM = 1
 
+CENTER_F32 = 0      # chunk-level centers stored as float32
+CENTER_BF16 = 1     # chunk-level centers stored as bfloat16 (the levels above stay float32)
+
 NEG_INF = -math.inf
 
 
@@ -68,6 +72,18 @@ NEG_INF = -math.inf
 def store_f32(x) -> np.ndarray:
     """Round to the nearest float32 and return as float64 (a stored value)."""
     return np.asarray(x, dtype=np.float64).astype(np.float32).astype(np.float64)
+
+
+def store_bf16(x) -> np.ndarray:
+    """Round to the nearest bfloat16 (8 significant bits, ties to even; normal range) and return as
+    float64: x = m 2^e with 0.5 <= |m| < 1, and m is rounded to a multiple of 2^-8."""
+    m, e = np.frexp(np.asarray(x, dtype=np.float64))
+    return np.ldexp(np.round(m * 256.0) / 256.0, e)
+
+
+def store_center0(x, center_dtype: int) -> np.ndarray:
+    """A chunk-level center as it is stored."""
+    return store_bf16(x) if center_dtype == CENTER_BF16 else store_f32(x)
 
 
 def round_up_f32(x) -> np.ndarray:
@@ -102,7 +118,8 @@ def unit_rows(X: np.ndarray) -> np.ndarray:
 class Index:
     """Stored hierarchical index.  Level 0 = chunks, level L-1 = top.
 
-    center[l]  [N_l, d]  float64 holding float32-representable values
+    center[l]  [N_l, d]  float64 holding float32-representable values (level 0: bfloat16-
+                         representable ones when center_dtype is CENTER_BF16)
     radius[l]  [N_l]     float64 holding float32-representable values (-inf: empty node)
     parent[l]  [N_l]     int64, index into level l+1 (-1 at the top level)
     ntok[l]    [N_l]     tokens in the subtree
@@ -121,6 +138,7 @@ class Index:
     parent: List[np.ndarray]
     ntok: List[np.ndarray]
     nchunk: List[np.ndarray]
+    center_dtype: int = CENTER_F32
 
     @property
     def M(self) -> int:
@@ -148,21 +166,23 @@ class Index:
 # index construction (prefill)  -- Section 4.3
 # --------------------------------------------------------------------------
 
-def chunk_node(keys: np.ndarray, geometry: int) -> Tuple[np.ndarray, float, np.ndarray]:
+def chunk_node(keys: np.ndarray, geometry: int,
+               center_dtype: int = CENTER_F32) -> Tuple[np.ndarray, float, np.ndarray]:
     """(stored center, stored radius, mean key) of one chunk from its token keys [n, d].
 
     The representative is the mean-pooled key (Section 4.1).  TOKEN_BALL stores
-    the mean itself and the radius that covers the chunk's token keys;
-    PAPER_UNIT stores the unit-norm representative with radius 0.
+    the mean itself and the radius that covers the chunk's token keys -- measured
+    from the center as stored, whatever its storage rounding; PAPER_UNIT stores
+    the unit-norm representative with radius 0.
     """
     keys = np.asarray(keys, dtype=np.float64)
     c = keys.sum(axis=0) / keys.shape[0]
     if geometry == TOKEN_BALL:
-        mu = store_f32(c)
+        mu = store_center0(c, center_dtype)
         diff = keys - mu[None, :]
         r = float(round_up_f32(np.sqrt((diff * diff).sum(axis=1)).max()))
     else:
-        mu = store_f32(unit(c))
+        mu = store_center0(unit(c), center_dtype)
         r = 0.0
     return mu, r, c
 
@@ -205,7 +225,7 @@ def spherical_kmeans(X: np.ndarray, k: int, iters: int,
 
 
 def build_index(K: np.ndarray, bounds: Sequence[int], T: int, L: int, F: int,
-                iters: int = 10, geometry: int = TOKEN_BALL) -> Index:
+                iters: int = 10, geometry: int = TOKEN_BALL, center_dtype: int = CENTER_F32) -> Index:
     """Build the index of one (sequence, KV head).
 
     K [>=T, d] float64 keys; bounds[0..M] boundaries of the closed chunks
@@ -222,8 +242,8 @@ def build_index(K: np.ndarray, bounds: Sequence[int], T: int, L: int, F: int,
     center0 = np.zeros((M, d))
     radius0 = np.zeros(M)
     for j in range(M):
-        center0[j], radius0[j], _ = chunk_node(K[bounds[j]:bounds[j + 1]], geometry)
-    idx = Index(d=d, L=L, F=F, geometry=geometry, bounds=bounds.copy(), T=int(T),
+        center0[j], radius0[j], _ = chunk_node(K[bounds[j]:bounds[j + 1]], geometry, center_dtype)
+    idx = Index(d=d, L=L, F=F, geometry=geometry, center_dtype=center_dtype, bounds=bounds.copy(), T=int(T),
                 center=[center0], radius=[radius0],
                 parent=[np.full(M, -1, dtype=np.int64)],
                 ntok=[np.diff(bounds).astype(np.int64)],
@@ -569,7 +589,7 @@ def close_chunk(idx: Index, K: np.ndarray) -> int:
     K = np.asarray(K, dtype=np.float64)
     lo, hi = int(idx.bounds[-1]), idx.T
     assert hi > lo, "no open tokens to close"
-    mu_x, r_x, _ = chunk_node(K[lo:hi], idx.geometry)
+    mu_x, r_x, _ = chunk_node(K[lo:hi], idx.geometry, idx.center_dtype)
     n_x = hi - lo
     p = -1
     if idx.L > 1:

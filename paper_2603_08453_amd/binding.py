@@ -31,6 +31,8 @@ LC_POLICY_BEAM = 1
 LC_PRUNE_AUTO = 0
 LC_PRUNE_ALWAYS = 1
 LC_PRUNE_NEVER = 2
+LC_CENTER_F32 = 0
+LC_CENTER_BF16 = 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("LYCHEE_LIB", os.path.join(_HERE, "liblychee.so"))
@@ -49,6 +51,7 @@ class LcConfig(ctypes.Structure):
         ("max_tokens", ctypes.c_int32),
         ("decode_splits", ctypes.c_int32),
         ("prune", ctypes.c_int32),
+        ("center_dtype", ctypes.c_int32),
     ]
 
 
@@ -326,11 +329,12 @@ def lc_chunk_tokens(tokens: Sequence[str], min_len: int, max_len: int) -> List[i
 _MAGIC = 0x5849434C
 
 
-def pack_blob(B: int, H_kv: int, d: int, L: int, F: int, geometry: int, seqs: List[Dict]) -> bytes:
+def pack_blob(B: int, H_kv: int, d: int, L: int, F: int, geometry: int, seqs: List[Dict],
+              center_dtype: int = LC_CENTER_F32) -> bytes:
     """seqs[b] = {"T": int, "bounds": int array [M+1],
                   "heads": [ per head: [ per level: dict(center, radius, parent, ntok, nchunk) ] ]}"""
     hdr = np.zeros(16, dtype=np.int32)
-    hdr[:8] = [_MAGIC, 1, B, H_kv, d, L, F, geometry]
+    hdr[:9] = [_MAGIC, 1, B, H_kv, d, L, F, geometry, center_dtype]
     parts = [hdr.tobytes()]
     for s in seqs:
         M = len(s["bounds"]) - 1
@@ -378,4 +382,5 @@ def unpack_blob(blob: bytes) -> Dict:
                 levels.append(lv)
             s["heads"].append(levels)
     assert off == len(blob), (off, len(blob))
-    return {"B": B, "H_kv": H_kv, "d": d, "L": L, "F": F, "geometry": geometry, "seqs": seqs}
+    return {"B": B, "H_kv": H_kv, "d": d, "L": L, "F": F, "geometry": geometry, "center_dtype": int(hdr[8]),
+            "seqs": seqs}

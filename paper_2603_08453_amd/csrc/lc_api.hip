@@ -26,6 +26,7 @@ bool config_ok(const lc_config* c) {
     if (c->max_tokens > (1 << 30)) return false;
     if (c->decode_splits < 0 || c->decode_splits > 256) return false;
     if (c->prune != LC_PRUNE_AUTO && c->prune != LC_PRUNE_ALWAYS && c->prune != LC_PRUNE_NEVER) return false;
+    if (c->center_dtype != LC_CENTER_F32 && c->center_dtype != LC_CENTER_BF16) return false;
     return true;
 }
 
@@ -58,6 +59,7 @@ size_t lc_layout_index(const lc_config* cfg, int B, int H, int d, void* base, Lc
     LcDev* D = dev ? dev : &tmp;
     memset(D, 0, sizeof(LcDev));
     D->B = B; D->H = H; D->d = d; D->L = cfg->levels; D->F = cfg->fanout;
+    D->c0_bf16 = cfg->center_dtype == LC_CENTER_BF16 ? 1 : 0;
     level_caps(cfg, D->cap);
     Carver c{static_cast<char*>(base), 0};
     const size_t BH = (size_t)B * H;
@@ -67,7 +69,8 @@ size_t lc_layout_index(const lc_config* cfg, int B, int H, int d, void* base, Lc
     D->bounds = c.take<int>((size_t)B * (D->cap[0] + 1));
     for (int l = 0; l < cfg->levels; ++l) {
         const size_t n = BH * D->cap[l];
-        D->center[l] = c.take<float>(n * d);
+        if (l == 0 && D->c0_bf16) D->center[l] = reinterpret_cast<float*>(c.take<uint16_t>(n * d));   // rows of d bfloat16
+        else D->center[l] = c.take<float>(n * d);
         D->radius[l] = c.take<float>(n);
         D->parent[l] = c.take<int>(n);
         D->ntok[l] = c.take<int>(n);
@@ -351,7 +354,7 @@ int plan_retrieve(const lc_index* idx, int budget, int cap, bool check_cap, Retr
     for (int b = 0; b < idx->B; ++b) {
         const int M = idx->M[b];
         if (M > p->max_M) p->max_M = M;
-        leaf_bytes += (long long)M * idx->H_kv * (idx->d * 4 + 8);
+        leaf_bytes += (long long)M * idx->H_kv * (idx->d * (idx->dev.c0_bf16 ? 2 : 4) + 8);
         // every chunk holds >= 1 token: at most `budget` chunks fit, plus the pinned ones
         long long need = (long long)budget + idx->cfg.sink_tokens;
         if (need > M) need = M;
@@ -511,7 +514,8 @@ int lc_index_export(const lc_index* idx, void* blob, size_t* bytes, void* stream
     hipStream_t s = static_cast<hipStream_t>(stream);
     LC_HIP_CHECK(hipStreamSynchronize(s));
     char* p = static_cast<char*>(blob);
-    int32_t hdr[16] = {kMagic, 1, idx->B, idx->H_kv, idx->d, idx->cfg.levels, idx->cfg.fanout, idx->cfg.geometry};
+    int32_t hdr[16] = {kMagic, 1, idx->B, idx->H_kv, idx->d, idx->cfg.levels, idx->cfg.fanout, idx->cfg.geometry,
+                       idx->cfg.center_dtype};
     memcpy(p, hdr, sizeof(hdr));
     p += sizeof(hdr);
     const int L = idx->cfg.levels;
@@ -533,7 +537,18 @@ int lc_index_export(const lc_index* idx, void* blob, size_t* bytes, void* stream
                 const size_t nl = idx->N[(size_t)b * LC_MAX_LEVELS + l];
                 const size_t base = ((size_t)b * idx->H_kv + h) * D.cap[l];
                 if (nl == 0) continue;
-                LC_HIP_CHECK(hipMemcpy(p, D.center[l] + base * idx->d, nl * idx->d * 4, hipMemcpyDeviceToHost));
+                if (l == 0 && D.c0_bf16) {
+                    // the blob always carries float32 centers: widen the stored bfloat16 values
+                    std::vector<uint16_t> half(nl * idx->d);
+                    LC_HIP_CHECK(hipMemcpy(half.data(), reinterpret_cast<const uint16_t*>(D.center[0]) + base * idx->d,
+                                           nl * idx->d * 2, hipMemcpyDeviceToHost));
+                    for (size_t i = 0; i < half.size(); ++i) {
+                        const uint32_t w = (uint32_t)half[i] << 16;
+                        memcpy(p + 4 * i, &w, 4);
+                    }
+                } else {
+                    LC_HIP_CHECK(hipMemcpy(p, D.center[l] + base * idx->d, nl * idx->d * 4, hipMemcpyDeviceToHost));
+                }
                 p += nl * idx->d * 4;
                 LC_HIP_CHECK(hipMemcpy(p, D.radius[l] + base, nl * 4, hipMemcpyDeviceToHost)); p += nl * 4;
                 LC_HIP_CHECK(hipMemcpy(p, D.parent[l] + base, nl * 4, hipMemcpyDeviceToHost)); p += nl * 4;
@@ -559,6 +574,7 @@ int lc_index_import(lc_index** out, const lc_config* cfg, const void* blob, size
     if (B < 1 || H < 1) return LC_ERR_BAD_BLOB;
     if (d != LC_HEAD_DIM) return LC_ERR_BAD_SHAPE;
     if (L != cfg->levels || F != cfg->fanout || geo != cfg->geometry) return LC_ERR_BAD_BLOB;
+    if (hdr[8] != cfg->center_dtype) return LC_ERR_BAD_BLOB;     // radii are only valid for the centers they were measured against
     if (index_bytes < lc_layout_index(cfg, B, H, d, nullptr, nullptr)) return LC_ERR_WORKSPACE_TOO_SMALL;
 
     lc_index* h = new_handle(cfg, B, H, d, index_buf, index_bytes);
@@ -625,7 +641,20 @@ int lc_index_import(lc_index** out, const lc_config* cfg, const void* blob, size
                     const size_t nl = h->N[(size_t)b * LC_MAX_LEVELS + l];
                     if (nl == 0) continue;
                     const size_t base = ((size_t)b * H + hh) * D.cap[l];
-                    hipError_t e = hipMemcpy(D.center[l] + base * d, p, nl * d * 4, hipMemcpyHostToDevice);
+                    hipError_t e;
+                    if (l == 0 && D.c0_bf16) {
+                        // values of a bfloat16 index are bfloat16-representable; anything else is rounded to nearest even
+                        std::vector<uint16_t> half(nl * d);
+                        for (size_t i = 0; i < half.size(); ++i) {
+                            uint32_t w;
+                            memcpy(&w, p + 4 * i, 4);
+                            half[i] = (uint16_t)((w + 0x7fffu + ((w >> 16) & 1u)) >> 16);
+                        }
+                        e = hipMemcpy(reinterpret_cast<uint16_t*>(D.center[0]) + base * d, half.data(), nl * d * 2,
+                                      hipMemcpyHostToDevice);
+                    } else {
+                        e = hipMemcpy(D.center[l] + base * d, p, nl * d * 4, hipMemcpyHostToDevice);
+                    }
                     p += nl * d * 4;
                     if (e == hipSuccess) e = hipMemcpy(D.radius[l] + base, p, nl * 4, hipMemcpyHostToDevice);
                     p += nl * 4;

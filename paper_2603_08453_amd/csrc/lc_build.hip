@@ -23,10 +23,12 @@ __device__ __forceinline__ float lc_pad_radius(float r) { return r > 0.f ? r * (
 // ---------------------------------------------------------------------------------
 // pooling of rows [lo, hi) of one (sequence, head) key cache; block-wide.
 // On return every lane holds, for its 8 columns [8 sub, 8 sub + 8), the stored center
-// `mu`, and all threads hold the stored radius.  sh: LC_BG * 128 + LC_BG floats.
+// `mu` (rounded to bfloat16 first if the chunk level is stored that way, so that the radius
+// covers the tokens around the value that is stored), and all threads hold the stored radius.
+// sh: LC_BG * 128 + LC_BG floats.
 // ---------------------------------------------------------------------------------
 __device__ __forceinline__ void lc_pool_rows(const uint16_t* __restrict__ Kbh, long long ks_tok, int lo, int hi,
-                                             int geometry, float* sh, float (&mu)[8], float* radius) {
+                                             int geometry, bool round_bf16, float* sh, float (&mu)[8], float* radius) {
     const int tid = threadIdx.x, sub = tid & 15, grp = tid >> 4;
     float sum[8];
 #pragma unroll
@@ -62,9 +64,17 @@ __device__ __forceinline__ void lc_pool_rows(const uint16_t* __restrict__ Kbh, l
 #pragma unroll
             for (int i = 0; i < 8; ++i) mu[i] = (sub == 0 && i == 0) ? 1.f : 0.f;
         }
+        if (round_bf16) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) mu[i] = lc_round_bf16(mu[i]);
+        }
         *radius = 0.f;
         __syncthreads();
         return;
+    }
+    if (round_bf16) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) mu[i] = lc_round_bf16(mu[i]);
     }
     float far2 = 0.f;
     for (int r = lo + grp; r < hi; r += LC_BG) {
@@ -113,6 +123,29 @@ __device__ __forceinline__ void lc_load8(const float* p, float (&v)[8]) {
     v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
 }
 
+// Chunk-level center of node n, columns [8 sub, 8 sub + 8), in the index's storage format.
+// (`v` already holds bfloat16-representable values when the level is stored as bfloat16.)
+__device__ __forceinline__ void lc_c0_store8(const LcDev& ix, size_t n, int sub, const float (&v)[8]) {
+    if (ix.c0_bf16) {
+        uint4 w;
+        w.x = (__float_as_uint(v[0]) >> 16) | (__float_as_uint(v[1]) & 0xffff0000u);
+        w.y = (__float_as_uint(v[2]) >> 16) | (__float_as_uint(v[3]) & 0xffff0000u);
+        w.z = (__float_as_uint(v[4]) >> 16) | (__float_as_uint(v[5]) & 0xffff0000u);
+        w.w = (__float_as_uint(v[6]) >> 16) | (__float_as_uint(v[7]) & 0xffff0000u);
+        *reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(ix.center[0]) + n * LC_D + 8 * sub) = w;
+    } else {
+        lc_store8(ix.center[0] + n * LC_D + 8 * sub, v);
+    }
+}
+__device__ __forceinline__ void lc_c0_load8(const LcDev& ix, size_t n, int sub, float (&v)[8]) {
+    if (ix.c0_bf16) {
+        const uint4 w = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(ix.center[0]) + n * LC_D + 8 * sub);
+        lc_unpack8(w, v);
+    } else {
+        lc_load8(ix.center[0] + n * LC_D + 8 * sub, v);
+    }
+}
+
 // ---------------------------------------------------------------------------------
 // level 0: one block per chunk
 // ---------------------------------------------------------------------------------
@@ -128,10 +161,10 @@ lc_pool_kernel(LcDev ix, const uint16_t* K, long long ks_seq, long long ks_head,
     const int lo = bnd[j], hi = bnd[j + 1];
     const int sub = threadIdx.x & 15;
     float mu[8], radius;
-    lc_pool_rows(K + b * ks_seq + h * ks_head, ks_tok, lo, hi, geometry, sh, mu, &radius);
+    lc_pool_rows(K + b * ks_seq + h * ks_head, ks_tok, lo, hi, geometry, ix.c0_bf16 != 0, sh, mu, &radius);
     const size_t n = (size_t)bh * ix.cap[0] + j;
     if (threadIdx.x < 16) {
-        lc_store8(ix.center[0] + n * LC_D + 8 * sub, mu);
+        lc_c0_store8(ix, n, sub, mu);
         float u[8];
         lc_unit_frag(mu, sub, u);
         lc_store8(dirs + n * LC_D + 8 * sub, u);
@@ -155,7 +188,7 @@ lc_dirs_kernel(LcDev ix, float* dirs) {
     if (j >= M) return;
     const size_t n = (size_t)bh * ix.cap[0] + j;
     float mu[8], u[8];
-    lc_load8(ix.center[0] + n * LC_D + 8 * sub, mu);
+    lc_c0_load8(ix, n, sub, mu);
     lc_unit_frag(mu, sub, u);
     lc_store8(dirs + n * LC_D + 8 * sub, u);
     if (sub == 0) ix.parent[0][n] = -1;
@@ -291,7 +324,7 @@ lc_node_kernel(LcDev ix, int l, const int* anc, const float* cent, int cent_cap,
     for (int j = grp; j < M; j += LC_BG) {
         if (a[j] == u) {
             float c[8];
-            lc_load8(ix.center[0] + (cb + j) * LC_D + 8 * sub, c);
+            lc_c0_load8(ix, cb + j, sub, c);
 #pragma unroll
             for (int t = 0; t < 8; ++t) sum[t] += c[t];
             cnt += 1;
@@ -321,7 +354,7 @@ lc_node_kernel(LcDev ix, int l, const int* anc, const float* cent, int cent_cap,
     for (int j = grp; j < M; j += LC_BG) {
         if (a[j] == u) {
             float c[8];
-            lc_load8(ix.center[0] + (cb + j) * LC_D + 8 * sub, c);
+            lc_c0_load8(ix, cb + j, sub, c);
             float d2 = 0.f;
 #pragma unroll
             for (int t = 0; t < 8; ++t) { const float e = c[t] - mu[t]; d2 = fmaf(e, e, d2); }
@@ -439,7 +472,7 @@ lc_append_kernel(LcDev ix, uint16_t* K, uint16_t* V, long long ks_seq, long long
     int* bnd = ix.bounds + (size_t)b * (ix.cap[0] + 1);
     const int lo = bnd[M], hi = T + 1;
     float mu_x[8], r_x;
-    lc_pool_rows(Kbh, ks_tok, lo, hi, geometry, sh, mu_x, &r_x);
+    lc_pool_rows(Kbh, ks_tok, lo, hi, geometry, ix.c0_bf16 != 0, sh, mu_x, &r_x);
     const int n_x = hi - lo;
     int p = -1;
     if (ix.L > 1) {
@@ -513,7 +546,7 @@ lc_append_kernel(LcDev ix, uint16_t* K, uint16_t* V, long long ks_seq, long long
     }
     const size_t n0 = (size_t)bh * ix.cap[0] + M;
     if (tid < 16) {
-        lc_store8(ix.center[0] + n0 * LC_D + 8 * sub, mu_x);
+        lc_c0_store8(ix, n0, sub, mu_x);
         if (sub == 0) {
             ix.radius[0][n0] = r_x;
             ix.parent[0][n0] = p;

@@ -151,6 +151,35 @@ __device__ __forceinline__ LcNodeFrag lc_load_node(const float* __restrict__ cen
     f.b = *reinterpret_cast<const float4*>(center + 64 + 4 * sub);
     return f;
 }
+// Chunk-level centers may be stored as bfloat16.  Loading and widening are separate steps so that a
+// kernel can issue the loads early and touch the data only where it scores: the loaded fragment
+// holds the raw words (float32 storage: the eight values; bfloat16 storage: four packed pairs in
+// a.x, a.y, b.x, b.y) and lc_score_chunk_frag widens them.  Same columns per lane either way.
+__device__ __forceinline__ LcNodeFrag lc_load_chunk_node(const float* center0, bool bf16, size_t n, int sub) {
+    if (!bf16) return lc_load_node(center0 + n * LC_D, sub);
+    const uint16_t* row = reinterpret_cast<const uint16_t*>(center0) + n * LC_D;
+    const uint2 a = *reinterpret_cast<const uint2*>(row + 4 * sub);
+    const uint2 b = *reinterpret_cast<const uint2*>(row + 64 + 4 * sub);
+    LcNodeFrag f;
+    f.a = make_float4(__uint_as_float(a.x), __uint_as_float(a.y), 0.f, 0.f);
+    f.b = make_float4(__uint_as_float(b.x), __uint_as_float(b.y), 0.f, 0.f);
+    return f;
+}
+__device__ __forceinline__ LcNodeFrag lc_widen_chunk_frag(const LcNodeFrag& r) {
+    const uint32_t a0 = __float_as_uint(r.a.x), a1 = __float_as_uint(r.a.y);
+    const uint32_t b0 = __float_as_uint(r.b.x), b1 = __float_as_uint(r.b.y);
+    LcNodeFrag f;
+    f.a = make_float4(lc_bf16_lo(a0), lc_bf16_hi(a0), lc_bf16_lo(a1), lc_bf16_hi(a1));
+    f.b = make_float4(lc_bf16_lo(b0), lc_bf16_hi(b0), lc_bf16_lo(b1), lc_bf16_hi(b1));
+    return f;
+}
+// float -> nearest bfloat16, ties to even (finite inputs)
+__device__ __forceinline__ uint32_t lc_f32_to_bf16_bits(float f) {
+    const uint32_t u = __float_as_uint(f);
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+__device__ __forceinline__ float lc_round_bf16(float f) { return __uint_as_float(lc_f32_to_bf16_bits(f) << 16); }
+
 template <int G>
 __device__ __forceinline__ float lc_score_frag(const LcNodeFrag& f, float R, const float (&qf)[G][8],
                                                const float (&qn)[G]) {
@@ -175,6 +204,12 @@ template <int G>
 __device__ __forceinline__ float lc_score_node(const float* __restrict__ center, float R, int sub,
                                                const float (&qf)[G][8], const float (&qn)[G]) {
     return lc_score_frag<G>(lc_load_node(center, sub), R, qf, qn);
+}
+// Eq. 2 for a chunk node from its loaded fragment (see lc_load_chunk_node).
+template <int G>
+__device__ __forceinline__ float lc_score_chunk_frag(const LcNodeFrag& raw, bool bf16, float R,
+                                                     const float (&qf)[G][8], const float (&qn)[G]) {
+    return lc_score_frag<G>(bf16 ? lc_widen_chunk_frag(raw) : raw, R, qf, qn);
 }
 
 // Load the query group of KV head h into registers (fragments as above) and

@@ -10,9 +10,11 @@
 #include "lychee.h"
 
 // Device-side view of an index, passed to kernels by value.
-// Per-level arrays are indexed [(b * H + h) * cap[l] + n]; centers carry d floats per node.
+// Per-level arrays are indexed [(b * H + h) * cap[l] + n]; centers carry d floats per node, except that
+// center[0] points at rows of d bfloat16 values when c0_bf16 is set (read it through lc_c0_*).
 struct LcDev {
     int B, H, d, L, F;
+    int c0_bf16;
     int cap[LC_MAX_LEVELS];
     int* state;      // [B][H][4]: {T, M, 0, 0}: tokens written, closed chunks (one copy per head)
     int* nlev;       // [B][LC_MAX_LEVELS]: nodes per level (entry 0 unused: level 0 has M nodes)

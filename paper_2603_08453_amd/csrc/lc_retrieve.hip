@@ -446,19 +446,20 @@ lc_upper_kernel(const LcRetrieveArgs a) {
     // ---- score them
     {
         const size_t cb = (size_t)bh * ix.cap[0];
+        const bool c0b = ix.c0_bf16 != 0;
         for (int i0 = grp; i0 < n_probe; i0 += NB * LC_UP_GROUPS) {
             LcNodeFrag f[NB];
             float R[NB];
 #pragma unroll
             for (int k = 0; k < NB; ++k) {
                 const int j = plist[min(i0 + k * LC_UP_GROUPS, n_probe - 1)];
-                f[k] = lc_load_node(ix.center[0] + (cb + j) * LC_D, sub);
+                f[k] = lc_load_chunk_node(ix.center[0], c0b, cb + j, sub);
                 R[k] = ix.radius[0][cb + j];
             }
 #pragma unroll
             for (int k = 0; k < NB; ++k) {
                 const int i = i0 + k * LC_UP_GROUPS;
-                const float s = lc_score_frag<G>(f[k], R[k], qf, qn);
+                const float s = lc_score_chunk_frag<G>(f[k], c0b, R[k], qf, qn);
                 if (sub == 0 && i < n_probe) pkey[i] = lc_score_key(s);
             }
         }
@@ -514,7 +515,8 @@ lc_upper_kernel(const LcRetrieveArgs a) {
 // ---------------------------------------------------------------------------------
 // kernel 2: chunk scoring + budget selection by the last workgroup
 // ---------------------------------------------------------------------------------
-template <int G, int R>
+// BF16: how the chunk-level centers are stored (a compile-time copy of the index's flag).
+template <int G, int R, bool BF16>
 __global__ void __launch_bounds__(LC_LF_THREADS)
 lc_leaf_kernel(const LcRetrieveArgs a) {
     extern __shared__ int lds_dyn[];
@@ -527,6 +529,7 @@ lc_leaf_kernel(const LcRetrieveArgs a) {
     const int tid = threadIdx.x;
     const int sub = tid & 15, grp = tid >> 4;
     const size_t cb = (size_t)bh * ix.cap[0];
+    constexpr bool c0b = BF16;
     const int* bnd = ix.bounds + (size_t)b * (ix.cap[0] + 1);
     uint32_t* keys = a.keys + cb;
     float* scores = a.scores ? a.scores + cb : nullptr;
@@ -555,7 +558,7 @@ lc_leaf_kernel(const LcRetrieveArgs a) {
     LcNodeFrag pre[kSpec ? R : 1];
     if (kSpec && !have_want) {
 #pragma unroll
-        for (int r = 0; r < (kSpec ? R : 1); ++r) pre[r] = lc_load_node(ix.center[0] + (cb + jj[r]) * LC_D, sub);
+        for (int r = 0; r < (kSpec ? R : 1); ++r) pre[r] = lc_load_chunk_node(ix.center[0], c0b, cb + jj[r], sub);
     }
     float qf[G][8], qn[G];
     lc_load_query_frags<G>(a.q + (size_t)b * ix.H * G * LC_D, h, sub, qf, qn);
@@ -570,8 +573,8 @@ lc_leaf_kernel(const LcRetrieveArgs a) {
                 const int j = j_lo + r * LC_LF_GROUPS + grp;
                 sv[r] = LC_NEG_INF;
                 if (j < M && wv[r]) {
-                    if (kSpec && !have_want) sv[r] = lc_score_frag<G>(pre[kSpec ? r : 0], rv[r], qf, qn);
-                    else sv[r] = lc_score_node<G>(ix.center[0] + (cb + jj[r]) * LC_D, rv[r], sub, qf, qn);
+                    if (kSpec && !have_want) sv[r] = lc_score_chunk_frag<G>(pre[kSpec ? r : 0], c0b, rv[r], qf, qn);
+                    else sv[r] = lc_score_chunk_frag<G>(lc_load_chunk_node(ix.center[0], c0b, cb + jj[r], sub), c0b, rv[r], qf, qn);
                 }
             }
 #pragma unroll
@@ -671,7 +674,8 @@ lc_leaf_kernel(const LcRetrieveArgs a) {
 // 1024-thread workgroups: NT threads = NT/16 groups, R chunks per group.
 #define LC_SC_THREADS 256
 #define LC_SCORE_MAX_WGS 1024          // measured flat between 512 and 2048 workgroups
-template <int G, int R>
+// BF16: how the chunk-level centers are stored (a compile-time copy of the index's flag).
+template <int G, int R, bool BF16>
 __global__ void __launch_bounds__(LC_SC_THREADS)
 lc_score_kernel(const LcRetrieveArgs a) {
     constexpr int GROUPS = LC_SC_THREADS / 16;
@@ -681,6 +685,7 @@ lc_score_kernel(const LcRetrieveArgs a) {
     const int tid = threadIdx.x;
     const int sub = tid & 15, grp = tid >> 4;
     const size_t cb = (size_t)bh * ix.cap[0];
+    constexpr bool c0b = BF16;
     const int* bnd = ix.bounds + (size_t)b * (ix.cap[0] + 1);
     uint32_t* keys = a.keys + cb;
     const uint8_t* want = a.want + cb;
@@ -699,7 +704,7 @@ lc_score_kernel(const LcRetrieveArgs a) {
     LcNodeFrag pre[R];
     if (!have_want) {
 #pragma unroll
-        for (int r = 0; r < R; ++r) pre[r] = lc_load_node(ix.center[0] + (cb + jj[r]) * LC_D, sub);
+        for (int r = 0; r < R; ++r) pre[r] = lc_load_chunk_node(ix.center[0], c0b, cb + jj[r], sub);
     }
     float qf[G][8], qn[G];
     lc_load_query_frags<G>(a.q + (size_t)b * ix.H * G * LC_D, h, sub, qf, qn);
@@ -710,8 +715,8 @@ lc_score_kernel(const LcRetrieveArgs a) {
         const int j = j_lo + r * GROUPS + grp;
         float sv = LC_NEG_INF;
         if (a.budget > 0 && j < M && wv[r]) {
-            if (!have_want) sv = lc_score_frag<G>(pre[r], rv[r], qf, qn);
-            else sv = lc_score_node<G>(ix.center[0] + (cb + jj[r]) * LC_D, rv[r], sub, qf, qn);
+            if (!have_want) sv = lc_score_chunk_frag<G>(pre[r], c0b, rv[r], qf, qn);
+            else sv = lc_score_chunk_frag<G>(lc_load_chunk_node(ix.center[0], c0b, cb + jj[r], sub), c0b, rv[r], qf, qn);
         }
         if (j < M && sub == 0) keys[j] = lc_score_key(sv);
     }
@@ -721,21 +726,28 @@ template <int G, int R>
 static int launch_score(const LcRetrieveArgs& a, int max_M, hipStream_t stream) {
     const int per = R * (LC_SC_THREADS / 16);
     const int nblk = max_M > 0 ? (max_M + per - 1) / per : 1;
-    hipLaunchKernelGGL((lc_score_kernel<G, R>), dim3(nblk, a.ix.H, a.ix.B), dim3(LC_SC_THREADS), 0, stream, a);
+    if (a.ix.c0_bf16)
+        hipLaunchKernelGGL((lc_score_kernel<G, R, true>), dim3(nblk, a.ix.H, a.ix.B), dim3(LC_SC_THREADS), 0, stream, a);
+    else
+        hipLaunchKernelGGL((lc_score_kernel<G, R, false>), dim3(nblk, a.ix.H, a.ix.B), dim3(LC_SC_THREADS), 0, stream, a);
     LC_HIP_CHECK(hipGetLastError());
     return LC_OK;
 }
 
-template <int G, int R>
-static int launch_leaf(const LcRetrieveArgs& a, int max_M, size_t lds, hipStream_t stream) {
+template <int G, int R, bool BF16>
+static int launch_leaf_t(const LcRetrieveArgs& a, int max_M, size_t lds, hipStream_t stream) {
     if (lds + sizeof(LcLeafSelSh) + 1024 > 48 * 1024)             // static + dynamic beyond the default allowance
-        LC_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&lc_leaf_kernel<G, R>),
+        LC_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&lc_leaf_kernel<G, R, BF16>),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     const int per = R * LC_LF_GROUPS;
     const int nblk = max_M > 0 ? (max_M + per - 1) / per : 1;
-    hipLaunchKernelGGL((lc_leaf_kernel<G, R>), dim3(nblk, a.ix.H, a.ix.B), dim3(LC_LF_THREADS), lds, stream, a);
+    hipLaunchKernelGGL((lc_leaf_kernel<G, R, BF16>), dim3(nblk, a.ix.H, a.ix.B), dim3(LC_LF_THREADS), lds, stream, a);
     LC_HIP_CHECK(hipGetLastError());
     return LC_OK;
+}
+template <int G, int R>
+static int launch_leaf(const LcRetrieveArgs& a, int max_M, size_t lds, hipStream_t stream) {
+    return a.ix.c0_bf16 ? launch_leaf_t<G, R, true>(a, max_M, lds, stream) : launch_leaf_t<G, R, false>(a, max_M, lds, stream);
 }
 
 template <int G>

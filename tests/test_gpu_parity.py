@@ -446,6 +446,159 @@ def test_build_index_matches_oracle(G, geometry):
             H.accept_ids(ids[b][h], orc.node_scores(gi, 0, q), gi.lens(), w.budget)
 
 
+def _bf16_ulp(x):
+    """Spacing of bfloat16 values at |x| (8 significant bits)."""
+    _, e = np.frexp(np.abs(x))
+    return np.ldexp(1.0, e - 8)
+
+
+def test_bf16_chunk_centers_imported_index(G):
+    """An index whose chunk centers are stored as bfloat16: import/export keeps every value, and
+    retrieval (flat, level walk, top-k per level), attention and the fused step match the oracle
+    on the same stored values."""
+    from paper_2603_08453_amd import binding as lc
+    w = wl.tiny("half", B=2, H_q=8, H_kv=2, levels=3, fanout=4, T=0, T_range=(1500, 2500), chunk_lo=3, chunk_hi=30)
+    case = G.make_case(w, tails=[6, 0], center_dtype=lc.LC_CENTER_BF16)
+    blob = lc.unpack_blob(lc.lc_index_export(case.idx))
+    assert blob["center_dtype"] == lc.LC_CENTER_BF16
+    for b in range(w.B):
+        for h in range(w.H_kv):
+            oi = case.oidx[b][h]
+            for l in range(w.levels):
+                assert np.array_equal(blob["seqs"][b]["heads"][h][l]["center"].astype(np.float64), oi.center[l]), (b, h, l)
+            assert np.array_equal(orc.store_bf16(oi.center[0]), oi.center[0])
+    qb = _q_batch(case, 0)
+    for prune in (lc.LC_PRUNE_NEVER, lc.LC_PRUNE_ALWAYS):
+        lc.lc_set_prune(case.idx, prune)
+        for budget in (0, 90, 700, 10 ** 6):
+            ids = _check_retrieve(G, case, qb, budget, tag=f"half prune={prune}")
+            _check_decode(G, case, qb, ids, tag=f"half budget {budget}")
+            _check_step(G, case, qb, budget, tag=f"half step prune={prune}")
+    _check_retrieve(G, case, qb, 500, sink=20, tag="half sink")
+    beam = [0, 6, 2]
+    _check_retrieve(G, case, qb, 600, policy=orc.POLICY_BEAM, beam=beam, tag="half beam")
+    _check_step(G, case, qb, 600, policy=orc.POLICY_BEAM, beam=beam, tag="half step beam")
+    lc.lc_set_policy(case.idx, lc.LC_POLICY_EXACT, None, 0)
+    # a blob written for float32 centers is refused: its radii were measured from other centers
+    f32_cfg = lc.lc_config_default(levels=w.levels, fanout=w.fanout, max_chunks=case.cfg.max_chunks,
+                                   max_tokens=case.cfg.max_tokens)
+    import torch
+    buf = torch.zeros(lc.lc_index_bytes(f32_cfg, w.B, w.H_kv), dtype=torch.uint8, device="cuda")
+    with pytest.raises(lc.LycheeError) as e:
+        lc.lc_index_import(f32_cfg, lc.lc_index_export(case.idx), buf)
+    assert e.value.code == lc.LC_ERR_BAD_BLOB
+
+
+@pytest.mark.parametrize("geometry", [orc.TOKEN_BALL, orc.PAPER_UNIT])
+def test_bf16_chunk_centers_built_on_gpu(G, geometry):
+    """lc_build_index with bfloat16 chunk centers: the stored centers are bfloat16 values, equal to the
+    oracle's except where the float32 mean falls on the other side of a rounding boundary (then one
+    bfloat16 step away); the radii cover the tokens around the stored centers; retrieval on the
+    built index is exact with respect to its own stored values."""
+    from paper_2603_08453_amd import binding as lc
+    w = wl.tiny("halfbuild", B=2, levels=3, fanout=4, T=0, T_range=(800, 1600), chunk_lo=3, chunk_hi=30)
+    case = G.make_case(w, tails=[4, 0], geometry=geometry, build_on="gpu", center_dtype=lc.LC_CENTER_BF16)
+    blob = lc.unpack_blob(lc.lc_index_export(case.idx))
+    n_el = n_diff = same_topology = 0
+    for b in range(w.B):
+        s = blob["seqs"][b]
+        for h in range(w.H_kv):
+            oi = case.oidx[b][h]
+            gi = G.levels_to_oracle_index(s["heads"][h], s["bounds"], s["T"], w.fanout, geometry)
+            assert [gi.n(l) for l in range(w.levels)] == [oi.n(l) for l in range(w.levels)]
+            assert np.array_equal(orc.store_bf16(gi.center[0]), gi.center[0])
+            diff = np.abs(gi.center[0] - oi.center[0])
+            assert np.all(diff <= _bf16_ulp(oi.center[0]) * 1.0000001)
+            n_el += diff.size
+            n_diff += int((diff > 0).sum())
+            exact_rows = np.all(diff == 0, axis=1)
+            assert np.all(gi.radius[0][exact_rows] >= oi.radius[0][exact_rows] * (1 - 1e-6))
+            assert np.all(gi.radius[0][exact_rows] <= oi.radius[0][exact_rows] * (1 + 2e-5) + 1e-7)
+            H.check_covering_invariant(gi, case.Kf(b, h), slack=1e-6)
+            H.check_counts(gi)
+            same_topology += int(all(np.array_equal(gi.parent[l], oi.parent[l]) for l in range(w.levels - 1)))
+    _say(f"bf16 build geometry={geometry}: {n_diff} of {n_el} chunk-center elements one bfloat16 step from the "
+         f"oracle's; {same_topology}/{w.B * w.H_kv} trees have the oracle's topology")
+    assert n_diff <= 0.002 * n_el
+    assert same_topology >= (w.B * w.H_kv) // 2
+    qb = _q_batch(case, 0)
+    ids, scores, _ = G.gpu_retrieve(case, qb, w.budget)
+    ids_f, out_f, _ = G.gpu_step(case, qb, w.budget)
+    out, _ = G.gpu_decode(case, qb, ids)
+    assert np.array_equal(out, out_f)
+    for b in range(w.B):
+        s = blob["seqs"][b]
+        for h in range(w.H_kv):
+            gi = G.levels_to_oracle_index(s["heads"][h], s["bounds"], s["T"], w.fanout, geometry)
+            q = wl.bf16_bits_to_f64(qb[b, h * w.G:(h + 1) * w.G])
+            H.accept_ids(ids[b][h], orc.node_scores(gi, 0, q), gi.lens(), w.budget)
+            assert ids_f[b][h].tolist() == ids[b][h].tolist()
+
+
+def test_bf16_chunk_centers_append_stream(G):
+    """Lazy update with bfloat16 chunk centers: every new chunk's stored center is a bfloat16 value, its
+    radius covers its tokens, the path above it is updated as in the oracle, and re-clustering
+    afterwards starts from the stored (rounded) chunk centers."""
+    import torch
+    from paper_2603_08453_amd import binding as lc
+    steps, L = 120, 3
+    w = wl.tiny("halfstream", B=2, levels=L, fanout=4, T=0, T_range=(300, 500), chunk_lo=3, chunk_hi=20,
+                stream_close_lo=3, stream_close_hi=17)
+    case = G.make_case(w, tails=[2, 0], extra_tokens=steps, extra_chunks=steps, center_dtype=lc.LC_CENTER_BF16)
+    streams = [wl.make_stream(w, b, steps) for b in range(w.B)]
+    Kf = [[np.vstack([case.Kf(b, h), np.zeros((steps, w.d))]) for h in range(w.H_kv)] for b in range(w.B)]
+    for t in range(steps):
+        k_bits = np.stack([st.k[t] for st in streams])
+        v_bits = np.stack([st.v[t] for st in streams])
+        close = [int(st.close[t]) for st in streams]
+        lc.lc_append(case.idx, case.K, case.V, G.to_bf16_tensor(k_bits), G.to_bf16_tensor(v_bits), close, case.ws)
+        for b in range(w.B):
+            for h in range(w.H_kv):
+                oi = case.oidx[b][h]
+                Kf[b][h][oi.T] = wl.bf16_bits_to_f64(k_bits[b, h])
+                orc.append_token(oi)
+                if close[b]:
+                    orc.close_chunk(oi, Kf[b][h])
+    torch.cuda.synchronize()
+    blob = lc.unpack_blob(lc.lc_index_export(case.idx))
+    n_el = n_diff = 0
+    for b in range(w.B):
+        s = blob["seqs"][b]
+        for h in range(w.H_kv):
+            oi = case.oidx[b][h]
+            gi = G.levels_to_oracle_index(s["heads"][h], s["bounds"], s["T"], w.fanout, orc.TOKEN_BALL)
+            assert gi.M == oi.M and gi.M > len(case.seqs[b].bounds) - 1
+            assert np.array_equal(orc.store_bf16(gi.center[0]), gi.center[0])
+            diff = np.abs(gi.center[0] - oi.center[0])
+            assert np.all(diff <= _bf16_ulp(oi.center[0]) * 1.0000001)
+            n_el += diff.size
+            n_diff += int((diff > 0).sum())
+            H.check_covering_invariant(gi, Kf[b][h], slack=1e-6)
+            H.check_counts(gi)
+            assert np.array_equal(gi.parent[0], oi.parent[0])
+            if np.all(diff == 0):
+                for l in range(1, L):
+                    live = oi.nchunk[l] > 0
+                    assert np.allclose(gi.center[l][live], oi.center[l][live], rtol=2e-5, atol=2e-5)
+                    assert np.all(gi.radius[l][live] >= oi.radius[l][live] * (1 - 1e-6))
+                    assert np.all(gi.radius[l][live] <= oi.radius[l][live] * (1 + 1e-3) + 1e-5)
+    _say(f"bf16 append: {n_diff} of {n_el} chunk-center elements one bfloat16 step from the oracle's")
+    assert n_diff <= 0.002 * n_el
+    lc.lc_recluster(case.idx, case.ws)
+    torch.cuda.synchronize()
+    after = lc.unpack_blob(lc.lc_index_export(case.idx))
+    qb = np.stack([st.q[steps - 1] for st in streams])
+    ids, _, _ = G.gpu_retrieve(case, qb, 150)
+    for b in range(w.B):
+        sa = after["seqs"][b]
+        for h in range(w.H_kv):
+            gi = G.levels_to_oracle_index(sa["heads"][h], sa["bounds"], sa["T"], w.fanout, orc.TOKEN_BALL)
+            assert np.array_equal(gi.center[0].astype(np.float32), blob["seqs"][b]["heads"][h][0]["center"])
+            H.check_covering_invariant(gi, Kf[b][h], slack=1e-6)
+            q = wl.bf16_bits_to_f64(qb[b, h * w.G:(h + 1) * w.G])
+            H.accept_ids(ids[b][h], orc.node_scores(gi, 0, q), gi.lens(), 150)
+
+
 # ----------------------------------------------------------------- lazy update
 
 @pytest.mark.parametrize("geometry,L", [(orc.TOKEN_BALL, 3), (orc.TOKEN_BALL, 1), (orc.PAPER_UNIT, 2)])
@@ -717,8 +870,11 @@ def test_random_small_configurations(G, seed):
     tails = [int(x) for x in r.integers(0, 30, size=B)]
     geometry = orc.TOKEN_BALL if r.random() < 0.7 else orc.PAPER_UNIT
     _say(f"seed {seed}: G={g} H_kv={h_kv} B={B} L={levels} F={fanout} chunks {lo}..{hi} tails {tails} geometry {geometry}")
-    splits = int(np.random.default_rng(7000 + seed).choice([0, 0, 1, 2, 7]))   # 0 = the library's choice
-    case = G.make_case(w, tails=tails, geometry=geometry, prune=int(r.integers(0, 3)), decode_splits=splits)
+    r2 = np.random.default_rng(7000 + seed)
+    splits = int(r2.choice([0, 0, 1, 2, 7]))                      # 0 = the library's choice
+    center_dtype = int(r2.integers(0, 2))                          # float32 / bfloat16 chunk centers
+    case = G.make_case(w, tails=tails, geometry=geometry, prune=int(r.integers(0, 3)), decode_splits=splits,
+                       center_dtype=center_dtype)
     qb = _q_batch(case, 0)
     for budget in (int(r.integers(0, 40)), int(r.integers(40, 400)), int(r.integers(400, 3000))):
         sink = int(r.integers(0, 30)) if r.random() < 0.4 else 0
@@ -753,7 +909,7 @@ def test_random_medium_configurations(G, seed):
     tails = [int(x) for x in r.integers(0, 70, size=B)]
     splits = int(r.choice([0, 0, 1, 3, 8]))
     _say(f"medium seed {seed}: G={g} H_kv={h_kv} B={B} L={levels} F={fanout} chunks {lo}..{hi} tails {tails} splits {splits}")
-    case = G.make_case(w, tails=tails, prune=int(r.integers(0, 3)), decode_splits=splits)
+    case = G.make_case(w, tails=tails, prune=int(r.integers(0, 3)), decode_splits=splits, center_dtype=seed % 2)
     _say(f"  chunks per sequence {[len(s.bounds) - 1 for s in case.seqs]}, tokens {[s.T for s in case.seqs]}")
     qb = _q_batch(case, 0)
     for budget in (int(r.integers(500, 3000)), int(r.integers(3000, 9000))):

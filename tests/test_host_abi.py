@@ -35,7 +35,8 @@ def test_config_struct_matches_header(L):
     cfg = lc.lc_config_default()
     assert (cfg.levels, cfg.fanout, cfg.kmeans_iters) == (3, 16, 10)
     assert cfg.geometry == lc.LC_GEOMETRY_TOKEN_BALL and cfg.policy == lc.LC_POLICY_EXACT
-    assert ctypes.sizeof(lc.LcConfig) == 4 * (5 + lc.LC_MAX_LEVELS + 5)
+    assert ctypes.sizeof(lc.LcConfig) == 4 * (5 + lc.LC_MAX_LEVELS + 6)
+    assert cfg.center_dtype == lc.LC_CENTER_F32
     hdr = open(os.path.join(ROOT, "include", "lychee.h")).read()
     assert f"#define LC_MAX_LEVELS {lc.LC_MAX_LEVELS}" in hdr
     assert f"#define LC_MAX_GROUP {lc.LC_MAX_GROUP}" in hdr
@@ -49,6 +50,11 @@ def test_size_queries(L):
     # dominated by the float32 chunk centers: 4096 chunks x 128 x 4 B x 8 heads
     assert 4096 * 512 * 8 <= n1 <= 4096 * 512 * 8 * 1.25
     assert lc.lc_workspace_bytes(cfg, 1, 32, 8) > 0
+    # bfloat16 chunk centers: half of that, the small upper levels stay float32
+    half = lc.lc_config_default(levels=4, fanout=16, max_chunks=4096, max_tokens=140000, center_dtype=lc.LC_CENTER_BF16)
+    nh = lc.lc_index_bytes(half, 1, 8)
+    assert 4096 * 256 * 8 <= nh <= 4096 * 256 * 8 * 1.4 and nh < 0.62 * n1
+    assert lc.lc_index_bytes(lc.lc_config_default(max_chunks=64, max_tokens=1024, center_dtype=2), 1, 8) == 0
     # invalid: d != 128, capacities unset, G too large, H_q not a multiple
     assert lc.lc_index_bytes(cfg, 1, 8, 64) == 0
     assert lc.lc_index_bytes(lc.lc_config_default(), 1, 8) == 0

@@ -508,3 +508,75 @@ def test_append_into_empty_cluster():
     assert p == 0
     H.check_covering_invariant(idx, K)
     H.check_counts(idx)
+
+
+# ---------------------------------------------------------------- bfloat16 chunk centers
+
+def test_store_bf16_is_round_to_nearest_even_with_8_significant_bits():
+    import torch
+    # exact cases: ties go to the even neighbour, everything else to the nearer one
+    x = np.array([1.0, 1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -8 + 2.0 ** -20, -(1.0 + 2.0 ** -8),
+                  0.0, 255.5, 256.5 * 2.0 ** 10, 0.1])
+    want = np.array([1.0, 1.0, 1.0 + 2.0 ** -6, 1.0 + 2.0 ** -7, -1.0,
+                     0.0, 256.0, 256.0 * 2.0 ** 10, 0.10009765625])
+    assert np.array_equal(orc.store_bf16(x), want)
+    # a library conversion of float32 inputs (no second rounding on the way) agrees bit for bit
+    r = np.random.default_rng(3)
+    f = (r.standard_normal(200000) * np.exp(r.uniform(-30, 30, 200000))).astype(np.float32)
+    lib = torch.from_numpy(f).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(orc.store_bf16(f.astype(np.float64)), lib)
+    # stored values are fixed points, and the error is at most half a unit in the 8th bit
+    assert np.array_equal(orc.store_bf16(lib), lib)
+    assert np.all(np.abs(lib - f.astype(np.float64)) <= np.abs(f.astype(np.float64)) * 2.0 ** -8)
+
+
+@pytest.mark.parametrize("geometry", [orc.TOKEN_BALL, orc.PAPER_UNIT])
+def test_bf16_chunk_centers_keep_the_index_sound(geometry):
+    """With chunk centers rounded to bfloat16 the radii are measured from the rounded centers, so the
+    covering invariant, the bound and the equality of hierarchical and flat retrieval all still hold;
+    the stored chunk centers are bfloat16 values next to the float32-mode ones."""
+    c = H.rand_case(21, T=260, d=16, G=3)
+    a = orc.build_index(c["K"], c["bounds"], c["T"], 3, 3, geometry=geometry)
+    b = orc.build_index(c["K"], c["bounds"], c["T"], 3, 3, geometry=geometry, center_dtype=orc.CENTER_BF16)
+    assert b.center_dtype == orc.CENTER_BF16
+    assert np.array_equal(orc.store_bf16(b.center[0]), b.center[0])
+    assert np.array_equal(b.center[0], orc.store_bf16(a.center[0])) or \
+        np.max(np.abs(b.center[0] - a.center[0])) <= 2.0 ** -8 * np.max(np.abs(a.center[0]))
+    assert not np.array_equal(a.center[0], b.center[0])
+    H.check_covering_invariant(b, c["K"])
+    H.check_counts(b)
+    if geometry == orc.TOKEN_BALL:
+        # radii grow by no more than the rounding moved the centers
+        shift = np.sqrt(((a.center[0] - b.center[0]) ** 2).sum(axis=1))
+        assert np.all(b.radius[0] <= a.radius[0] + shift + 1e-6) and np.all(b.radius[0] >= a.radius[0] - shift - 1e-6)
+        true_max = np.array([(c["K"][b.bounds[j]:b.bounds[j + 1]] @ c["q"].T).max() / math.sqrt(16)
+                             for j in range(b.M)])
+        assert np.all(orc.node_scores(b, 0, c["q"]) >= true_max - 1e-9)
+    for budget in (0, 17, 60, 150, 10 ** 6):
+        flat = orc.retrieve_flat(b, c["q"], budget).tolist()
+        assert orc.retrieve_best_first(b, c["q"], budget).tolist() == flat
+        assert orc.retrieve_level_sync(b, c["q"], budget).tolist() == flat
+
+
+def test_bf16_chunk_centers_survive_appends():
+    import lc_workloads as wl
+    r = np.random.default_rng(33)
+    c = H.rand_case(33, T=150, d=8, G=2, tail=3)
+    K = np.vstack([c["K"], r.standard_normal((60, 8))])
+    K = wl.bf16_bits_to_f64(wl.f32_to_bf16_bits(K.astype(np.float32)))
+    idx = orc.build_index(K, c["bounds"], c["T"], 3, 3, center_dtype=orc.CENTER_BF16)
+    open_len = idx.T - int(idx.bounds[-1])
+    closed = 0
+    for _ in range(60):
+        orc.append_token(idx)
+        open_len += 1
+        if open_len >= 4 and r.random() < 0.4:
+            orc.close_chunk(idx, K)
+            open_len = 0
+            closed += 1
+            assert np.array_equal(orc.store_bf16(idx.center[0][-1]), idx.center[0][-1])
+            H.check_covering_invariant(idx, K)
+            H.check_counts(idx)
+    assert closed >= 5
+    flat = orc.retrieve_flat(idx, c["q"], 70).tolist()
+    assert orc.retrieve_best_first(idx, c["q"], 70).tolist() == flat
