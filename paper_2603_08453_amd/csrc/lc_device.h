@@ -212,6 +212,51 @@ __device__ __forceinline__ float lc_score_chunk_frag(const LcNodeFrag& raw, bool
     return lc_score_frag<G>(bf16 ? lc_widen_chunk_frag(raw) : raw, R, qf, qn);
 }
 
+// The same with the query fragments kept as the packed bfloat16 words they arrive in (half the
+// registers; the widening is redone per node).  Same operands in the same order: same bits.
+template <int G>
+__device__ __forceinline__ float lc_score_frag_packed(const LcNodeFrag& f, float R, const uint32_t (&qp)[G][4],
+                                                      const float (&qn)[G]) {
+    float best = LC_NEG_INF;
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        // (the empty asm makes the words opaque here, so that the widening is not hoisted out of the
+        // caller's loops and kept in registers after all)
+        uint32_t w0 = qp[g][0], w1 = qp[g][1], w2 = qp[g][2], w3 = qp[g][3];
+        asm volatile("" : "+v"(w0), "+v"(w1), "+v"(w2), "+v"(w3));
+        float p = f.a.x * lc_bf16_lo(w0);
+        p = fmaf(f.a.y, lc_bf16_hi(w0), p);
+        p = fmaf(f.a.z, lc_bf16_lo(w1), p);
+        p = fmaf(f.a.w, lc_bf16_hi(w1), p);
+        p = fmaf(f.b.x, lc_bf16_lo(w2), p);
+        p = fmaf(f.b.y, lc_bf16_hi(w2), p);
+        p = fmaf(f.b.z, lc_bf16_lo(w3), p);
+        p = fmaf(f.b.w, lc_bf16_hi(w3), p);
+        p = lc_sum16(p);
+        const float ub = fmaf(qn[g], R, p) * 0.08838834764831845f;      // 1/sqrt(128)
+        best = fmaxf(best, ub);
+    }
+    return best;
+}
+template <int G>
+__device__ __forceinline__ void lc_load_query_packed(const uint16_t* __restrict__ q, int h, int sub,
+                                                     uint32_t (&qp)[G][4], float (&qn)[G]) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        const uint16_t* row = q + (size_t)(h * G + g) * LC_D;
+        const uint2 a = *reinterpret_cast<const uint2*>(row + 4 * sub);
+        const uint2 b = *reinterpret_cast<const uint2*>(row + 64 + 4 * sub);
+        qp[g][0] = a.x; qp[g][1] = a.y; qp[g][2] = b.x; qp[g][3] = b.y;
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            s = fmaf(lc_bf16_lo(qp[g][i]), lc_bf16_lo(qp[g][i]), s);
+            s = fmaf(lc_bf16_hi(qp[g][i]), lc_bf16_hi(qp[g][i]), s);
+        }
+        qn[g] = sqrtf(lc_sum16(s));
+    }
+}
+
 // Load the query group of KV head h into registers (fragments as above) and
 // compute the norms.  q: bf16 [H_q][d] of this sequence.
 template <int G>

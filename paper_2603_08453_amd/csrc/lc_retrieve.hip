@@ -161,8 +161,17 @@ lc_upper_kernel(const LcRetrieveArgs a) {
     int* plen = plist + PC;
     uint32_t* pkey = reinterpret_cast<uint32_t*>(plen + PC);
 
-    float qf[G][8], qn[G];
-    lc_load_query_frags<G>(a.q + (size_t)b * ix.H * G * LC_D, h, sub, qf, qn);
+    // Query fragments: widened once for small groups; for large ones kept as packed bfloat16 words
+    // and widened per node, which keeps this 1024-thread kernel within its 128 registers per lane.
+    constexpr bool QP = G > 4;
+    float qf[QP ? 1 : G][8], qn[G];
+    uint32_t qp[QP ? G : 1][4];
+    if constexpr (QP) lc_load_query_packed<G>(a.q + (size_t)b * ix.H * G * LC_D, h, sub, qp, qn);
+    else lc_load_query_frags<G>(a.q + (size_t)b * ix.H * G * LC_D, h, sub, qf, qn);
+    auto score_node = [&](const LcNodeFrag& f, float R) -> float {
+        if constexpr (QP) return lc_score_frag_packed<G>(f, R, qp, qn);
+        else return lc_score_frag<G>(f, R, qf, qn);
+    };
     // prefetch what the chunk pass will need much later (parents and boundaries of this thread's
     // first LC_UP_PER_THREAD chunks): the arrays are cap[0] long, so no count is needed to load them
     int pf_p[LC_UP_PER_THREAD], pf_s[LC_UP_PER_THREAD + 1];
@@ -216,7 +225,7 @@ lc_upper_kernel(const LcRetrieveArgs a) {
                     const LcNodeFrag f = lc_load_node(ix.center[l] + n * LC_D, sub);
                     const float R = ix.radius[l][n];
                     const int nc = ix.nchunk[l][n];
-                    float sc = lc_score_frag<G>(f, R, qf, qn);
+                    float sc = score_node(f, R);
                     if (nc <= 0) sc = LC_NEG_INF;
                     if (sub == 0) { ekA[grp] = lc_score_key(sc); ewA[grp] = 0; }
                 }
@@ -235,7 +244,7 @@ lc_upper_kernel(const LcRetrieveArgs a) {
 #pragma unroll
                     for (int k = 0; k < NB; ++k) {
                         const int i = i0 + k * LC_UP_GROUPS;
-                        float sc = lc_score_frag<G>(f[k], R[k], qf, qn);
+                        float sc = score_node(f[k], R[k]);
                         if (nc[k] <= 0) sc = LC_NEG_INF;
                         if (sub == 0 && i < n_c) { ekA[i] = lc_score_key(sc); ewA[i] = 0; }
                     }
@@ -312,7 +321,7 @@ lc_upper_kernel(const LcRetrieveArgs a) {
 #pragma unroll
         for (int k = 0; k < NB; ++k) {
             const int u = u0 + k * LC_UP_GROUPS;
-            float s = lc_score_frag<G>(f[k], R[k], qf, qn);
+            float s = score_node(f[k], R[k]);
             if (nc[k] <= 0) s = LC_NEG_INF;
             if (sub == 0 && u < NU) ukey[u] = lc_score_key(s);
         }
@@ -459,7 +468,7 @@ lc_upper_kernel(const LcRetrieveArgs a) {
 #pragma unroll
             for (int k = 0; k < NB; ++k) {
                 const int i = i0 + k * LC_UP_GROUPS;
-                const float s = lc_score_chunk_frag<G>(f[k], c0b, R[k], qf, qn);
+                const float s = score_node(c0b ? lc_widen_chunk_frag(f[k]) : f[k], R[k]);
                 if (sub == 0 && i < n_probe) pkey[i] = lc_score_key(s);
             }
         }
@@ -560,8 +569,16 @@ lc_leaf_kernel(const LcRetrieveArgs a) {
 #pragma unroll
         for (int r = 0; r < (kSpec ? R : 1); ++r) pre[r] = lc_load_chunk_node(ix.center[0], c0b, cb + jj[r], sub);
     }
-    float qf[G][8], qn[G];
-    lc_load_query_frags<G>(a.q + (size_t)b * ix.H * G * LC_D, h, sub, qf, qn);
+    // (group size 7 with four speculative centers per group: the query stays packed, see lc_upper_kernel)
+    constexpr bool QP = kSpec && R == 4 && G >= 7;
+    float qf[QP ? 1 : G][8], qn[G];
+    uint32_t qp[QP ? G : 1][4];
+    if constexpr (QP) lc_load_query_packed<G>(a.q + (size_t)b * ix.H * G * LC_D, h, sub, qp, qn);
+    else lc_load_query_frags<G>(a.q + (size_t)b * ix.H * G * LC_D, h, sub, qf, qn);
+    auto score_chunk = [&](const LcNodeFrag& raw, float Rv) -> float {
+        if constexpr (QP) return lc_score_frag_packed<G>(c0b ? lc_widen_chunk_frag(raw) : raw, Rv, qp, qn);
+        else return lc_score_chunk_frag<G>(raw, c0b, Rv, qf, qn);
+    };
     const int M = ix.state[bh * 4 + 1];
 
     LC_STAMP0(lc_dbg_leaf, 1);
@@ -573,8 +590,8 @@ lc_leaf_kernel(const LcRetrieveArgs a) {
                 const int j = j_lo + r * LC_LF_GROUPS + grp;
                 sv[r] = LC_NEG_INF;
                 if (j < M && wv[r]) {
-                    if (kSpec && !have_want) sv[r] = lc_score_chunk_frag<G>(pre[kSpec ? r : 0], c0b, rv[r], qf, qn);
-                    else sv[r] = lc_score_chunk_frag<G>(lc_load_chunk_node(ix.center[0], c0b, cb + jj[r], sub), c0b, rv[r], qf, qn);
+                    if (kSpec && !have_want) sv[r] = score_chunk(pre[kSpec ? r : 0], rv[r]);
+                    else sv[r] = score_chunk(lc_load_chunk_node(ix.center[0], c0b, cb + jj[r], sub), rv[r]);
                 }
             }
 #pragma unroll
