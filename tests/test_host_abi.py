@@ -141,3 +141,21 @@ def test_blob_roundtrip_python_side():
             for a, b in zip(hs, ht):
                 for k in a:
                     assert np.array_equal(a[k], b[k])
+
+
+def test_build_reports_and_rejects_register_spills():
+    """The build parses the compiler's per-kernel resource remarks; a kernel with scratch memory
+    (spilled registers) must make it fail."""
+    from paper_2603_08453_amd import build as B
+    remarks = """\
+a.hip:5:1: remark: Function Name: _Z3fooPf [-Rpass-analysis=kernel-resource-usage]
+    5 | foo(float* p) {
+      | ^
+a.hip:5:1: remark:     VGPRs: 26 [-Rpass-analysis=kernel-resource-usage]
+a.hip:5:1: remark:     ScratchSize [bytes/lane]: 0 [-Rpass-analysis=kernel-resource-usage]
+a.hip:9:1: remark: Function Name: _Z3barPf [-Rpass-analysis=kernel-resource-usage]
+a.hip:9:1: remark:     VGPRs: 128 [-Rpass-analysis=kernel-resource-usage]
+a.hip:9:1: remark:     ScratchSize [bytes/lane]: 56 [-Rpass-analysis=kernel-resource-usage]
+"""
+    k = B.kernel_resources(remarks)
+    assert k == {"_Z3fooPf": {"vgprs": 26, "scratch": 0}, "_Z3barPf": {"vgprs": 128, "scratch": 56}}
