@@ -143,6 +143,7 @@ def main():
     scores = torch.zeros((w.B, w.H_kv, cfg.max_chunks), dtype=torch.float32, device=dev)
     bounds_np = [s.bounds.astype(np.int64) for s in seqs]
     for i in range(nq):
+        scores.fill_(float("nan"))          # entries past a sequence's last chunk are never written: not "scored"
         lc.lc_retrieve(reps[0]["idx"], Qs[i], w.budget, ids_q[i], counts_q[i], reps[0]["ws"], scores=scores)
         torch.cuda.synchronize()
         ih, ch, sh = ids_q[i].cpu().numpy(), counts_q[i].cpu().numpy(), scores.cpu().numpy()
