@@ -13,7 +13,7 @@
 //   V row (one 16-byte load), four rows make a full 1 KiB wavefront load.
 #include <type_traits>
 
-#define LC_SEL_STAMP_X (blockIdx.x == 0)
+#define LC_SEL_STAMP_X false          // (the selection's own stamps are for the chunk kernel)
 #include "lc_device.h"
 #include "lc_internal.h"
 
@@ -112,7 +112,8 @@ lc_decode_kernel(const LcDecodeArgs a) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int sub = tid & 15, grp = tid >> 4, q4 = lane >> 4;
 
-    LC_STAMP0(lc_dbg_decode, 0);
+    LC_LSTAMP_INIT();
+    LC_LSTAMP0(0);
     const int* bnd = ix.bounds + (size_t)b * (ix.cap[0] + 1);
     // the query block in MFMA B layout (lane (q4, n): head n, columns 8 q4 + 32 j + [0, 8))
     uint4 qb[4];
@@ -203,6 +204,7 @@ lc_decode_kernel(const LcDecodeArgs a) {
         M = min(M_all, a.chunk_cap);
         tail_st = bnd[M_all];
         __syncthreads();
+        LC_LSTAMP0(15);
         // stage every chunk: key (pinned chunks get the always-selected mark), length, first row
         uint32_t kmin = 0xffffffffu, kmax = 0u;
         auto stage = [&](int j, uint32_t k, int s0, int s1) {
@@ -222,11 +224,11 @@ lc_decode_kernel(const LcDecodeArgs a) {
         for (int j = tid + LC_DEC_SPEC * LC_DEC_THREADS; j < M; j += LC_DEC_THREADS) stage(j, keys[j], bnd[j], bnd[j + 1]);
         lc_leaf_select_range(kmin, kmax, sel_sh);
         __syncthreads();
-        LC_STAMP0(lc_dbg_decode, 11);
+        LC_LSTAMP0(11);
         const long long C = a.count_limit > 0 ? (long long)a.count_limit : 0x7fffffffLL;
         thr = lc_leaf_select<LC_DEC_THREADS>(M, skey, slen, a.budget > 0 ? (long long)a.budget : 0LL, C, sel_sh);
         __syncthreads();
-        LC_STAMP0(lc_dbg_decode, 12);
+        LC_LSTAMP0(12);
         // tokens and chunks selected before this thread's run of chunks
         int Ec = (M + LC_DEC_THREADS - 1) / LC_DEC_THREADS;
         Ec |= 1;                                                    // odd stride: no LDS bank conflicts
@@ -248,7 +250,7 @@ lc_decode_kernel(const LcDecodeArgs a) {
             if (tid == 0 && a.counts_out != nullptr) a.counts_out[bh] = min(n_sel, a.cap);
         }
     }
-    LC_STAMP0(lc_dbg_decode, 1);
+    LC_LSTAMP0(1);
 
     int S_eff = (n_tok + LC_DEC_MIN_TOKENS_PER_SPLIT - 1) / LC_DEC_MIN_TOKENS_PER_SPLIT;
     S_eff = max(1, min(S, S_eff));
@@ -345,7 +347,7 @@ lc_decode_kernel(const LcDecodeArgs a) {
             }
         };
 
-        LC_STAMP0(lc_dbg_decode, 8);
+        LC_LSTAMP0(8);
         // The split's tokens are handled in tiles; for each tile the workgroup first writes the cache
         // row of every token into LDS (the few entries that overlap the tile go into a window, then
         // one small binary search per token, in parallel), then every group streams a contiguous
@@ -397,6 +399,7 @@ lc_decode_kernel(const LcDecodeArgs a) {
                 }
             }
             __syncthreads();
+            LC_LSTAMP0(13);
             {
                 const int w_first = win_hd[0], w_last = win_hd[1];
                 const int row_max = max(T - 1, 0);
@@ -412,7 +415,7 @@ lc_decode_kernel(const LcDecodeArgs a) {
                 }
             }
             __syncthreads();
-            LC_STAMP0(lc_dbg_decode, 9);
+            LC_LSTAMP0(9);
             const int per = (tl + LC_DEC_GROUPS - 1) / LC_DEC_GROUPS;
             const int n_it = (per + U - 1) / U;            // the same for every wavefront: the MFMA needs all lanes
             tv = min(tl, grp * per);
@@ -424,14 +427,14 @@ lc_decode_kernel(const LcDecodeArgs a) {
             for (int it = 0; it < n_it; it += 2) {
                 if (it + 1 < n_it) issue(it + 1, kB, vB);
                 consume(it, kA, vA);
-                LC_STAMP0(lc_dbg_decode, 10);
+                LC_LSTAMP0(10);
                 if (it + 1 >= n_it) break;
                 if (it + 2 < n_it) issue(it + 2, kA, vA);
                 consume(it + 1, kB, vB);
             }
         }
 
-        LC_STAMP0(lc_dbg_decode, 2);
+        LC_LSTAMP0(2);
         // ---- combine the 4 groups of a wave (xor 16, 32), then the waves through LDS
 #pragma unroll
         for (int off = 16; off < 64; off <<= 1) {
@@ -462,6 +465,7 @@ lc_decode_kernel(const LcDecodeArgs a) {
             }
         }
         __syncthreads();
+        LC_LSTAMP0(14);
         // one float4 slot of the split's partial per thread, stored at agent scope
         float* pml = a.part_ml + ((size_t)bh * S + s) * G * 2;
         const __amdgpu_buffer_rsrc_t pacc_w = lc_buffer(a.part_acc + ((size_t)bh * S + s) * G * LC_D);
@@ -486,11 +490,14 @@ lc_decode_kernel(const LcDecodeArgs a) {
         }
     }
 
-    LC_STAMP0(lc_dbg_decode, 3);
+    LC_LSTAMP0(3);
     // ---- the last split to arrive merges (log-sum-exp merge of the partial results)
-    if (!lc_arrive_last(&ix.sync[bh * 4 + 1], S, &last_sh)) return;
+    if (!lc_arrive_last(&ix.sync[bh * 4 + 1], S, &last_sh)) {
+        LC_LSTAMP_FLUSH(lc_dbg_decode);
+        return;
+    }
 
-    LC_STAMP(lc_dbg_decode, 4);
+    LC_LSTAMP(4);
     // The accumulator partials do not depend on the scales, so their loads go out first and fly
     // while the (m, l) pairs are fetched and turned into per-split scales.
     const __amdgpu_buffer_rsrc_t pacc_r = lc_buffer(a.part_acc + (size_t)bh * S * G * LC_D);
@@ -531,7 +538,7 @@ lc_decode_kernel(const LcDecodeArgs a) {
         if (lane == 0) { mrg_hd[2 * gg] = mx; mrg_hd[2 * gg + 1] = den; }
     }
     __syncthreads();
-    LC_STAMP(lc_dbg_decode, 5);
+    LC_LSTAMP(5);
     float4 acc4 = make_float4(0.f, 0.f, 0.f, 0.f);
     if (wy < WAYS) {
         for (int sp0 = wy; sp0 < n_part; sp0 += MR * WAYS) {
@@ -549,7 +556,7 @@ lc_decode_kernel(const LcDecodeArgs a) {
         if (WAYS > 1 && wy > 0) mrg_red[(wy - 1) * NV + v] = acc4;
     }
     __syncthreads();
-    LC_STAMP(lc_dbg_decode, 6);
+    LC_LSTAMP(6);
     if (wy == 0) {
 #pragma unroll
         for (int k = 1; k < WAYS; ++k) {
@@ -563,7 +570,8 @@ lc_decode_kernel(const LcDecodeArgs a) {
             make_float4(acc4.x * inv, acc4.y * inv, acc4.z * inv, acc4.w * inv);
         if (a.lse && c4 == 0) a.lse[o] = den > 0.f ? (mx + log2f(den)) * LC_LN2 : LC_NEG_INF;
     }
-    LC_STAMP(lc_dbg_decode, 7);
+    LC_LSTAMP(7);
+    LC_LSTAMP_FLUSH(lc_dbg_decode);
     if (tid == 0) ix.sync[bh * 4 + 1] = 0;
 }
 

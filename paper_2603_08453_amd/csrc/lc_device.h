@@ -19,11 +19,25 @@ static __device__ unsigned long long lc_dbg_sel[32];
 #define LC_SEL_STAMP_X true
 #endif
 #define LC_SEL_STAMP(i) do { if ((LC_SEL_STAMP_X) && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) lc_dbg_sel[i] = wall_clock64(); } while (0)
+// The same, parked in LDS and written out when the workgroup leaves: a global store at the stamp
+// would be waited for by the next barrier (a barrier drains the vector memory counter) and so
+// lengthen the very phase it is meant to time.
+static __shared__ unsigned long long lc_stamp_lds[32];
+#define LC_LSTAMP_INIT() do { if (threadIdx.x == 0) for (int i_ = 0; i_ < 32; ++i_) lc_stamp_lds[i_] = 0ull; } while (0)
+#define LC_LSTAMP0(i) do { if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) \
+    lc_stamp_lds[i] = wall_clock64(); } while (0)
+#define LC_LSTAMP(i) do { if (blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) lc_stamp_lds[i] = wall_clock64(); } while (0)
+#define LC_LSTAMP_FLUSH(name) do { if (blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) \
+    for (int i_ = 0; i_ < 32; ++i_) if (lc_stamp_lds[i_] != 0ull) name[i_] = lc_stamp_lds[i_]; } while (0)
 #else
 #define LC_SEL_STAMP(i)
 #define LC_STAMP_DECL(name)
 #define LC_STAMP0(name, i)
 #define LC_STAMP(name, i)
+#define LC_LSTAMP_INIT()
+#define LC_LSTAMP0(i)
+#define LC_LSTAMP(i)
+#define LC_LSTAMP_FLUSH(name)
 #endif
 #define LC_NEG_INF (-__builtin_huge_valf())
 
