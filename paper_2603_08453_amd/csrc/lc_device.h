@@ -295,15 +295,24 @@ __device__ __forceinline__ void lc_load_query_frags(const uint16_t* __restrict__
 // ---------------------------------------------------------------- block scan
 // Exclusive prefix sum of one int per thread over a block of NT threads.
 // `sh` needs NT/64 + 1 ints.  Returns the exclusive prefix; *total = block sum.
+// Inclusive prefix sum over the 64 lanes of a wavefront (all of them active), on the vector ALU:
+// four shifted adds inside each 16-lane row, then the row totals are carried over by the two
+// row-broadcast adds (last lane of row 0 -> row 1 and of row 2 -> row 3; last lane of row 1 ->
+// rows 2 and 3).  A generic shuffle would take a trip through the LDS crossbar per step.
+__device__ __forceinline__ int lc_wave_scan_incl(int v) {
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xF, 0xF, true);   // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xF, 0xF, true);   // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xF, 0xF, true);   // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xF, 0xF, true);   // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xA, 0xF, true);   // row_bcast:15 -> rows 1, 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xC, 0xF, true);   // row_bcast:31 -> rows 2, 3
+    return v;
+}
+
 template <int NT>
 __device__ __forceinline__ int lc_block_scan(int v, int* sh, int* total) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    int inc = v;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const int t = __shfl_up(inc, off);
-        if (lane >= off) inc += t;
-    }
+    const int inc = lc_wave_scan_incl(v);
     __syncthreads();                 // protect sh from the previous use
     if (lane == 63) sh[wave] = inc;
     __syncthreads();
@@ -534,12 +543,7 @@ template <int NT>
 __device__ __forceinline__ void lc_block_scan2(int a, int b, int* sh, int* ea, int* eb, int* ta = nullptr,
                                                int* tb = nullptr) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    int ia = a, ib = b;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const int ta = __shfl_up(ia, off), tb = __shfl_up(ib, off);
-        if (lane >= off) { ia += ta; ib += tb; }
-    }
+    const int ia = lc_wave_scan_incl(a), ib = lc_wave_scan_incl(b);
     __syncthreads();                 // protect sh from the previous use
     if (lane == 63) { sh[wave] = ia; sh[NT / 64 + wave] = ib; }
     __syncthreads();
