@@ -14,6 +14,7 @@
 #include <type_traits>
 
 #define LC_SEL_STAMP_X false          // (the selection's own stamps are for the chunk kernel)
+#define LC_SEL_LSTAMP(i) LC_LSTAMP0(20 + (i))
 #include "lc_device.h"
 #include "lc_internal.h"
 
@@ -222,7 +223,9 @@ lc_decode_kernel(const LcDecodeArgs a) {
         }
 #pragma unroll 4
         for (int j = tid + LC_DEC_SPEC * LC_DEC_THREADS; j < M; j += LC_DEC_THREADS) stage(j, keys[j], bnd[j], bnd[j + 1]);
+        LC_LSTAMP0(18);
         lc_leaf_select_range(kmin, kmax, sel_sh);
+        LC_LSTAMP0(19);
         __syncthreads();
         LC_LSTAMP0(11);
         const long long C = a.count_limit > 0 ? (long long)a.count_limit : 0x7fffffffLL;
@@ -358,6 +361,7 @@ lc_decode_kernel(const LcDecodeArgs a) {
             // size) -- overlapping entries are consecutive and fewer than the window is long -- and the
             // entries that hold the tile's first and last token leave their indices.
             __syncthreads();
+            LC_LSTAMP0(16);
             {
                 auto entry = [&](int i, int off, int st, int ln) {
                     if (ln > 0 && off < tile0 + tl && tile0 < off + ln) {
@@ -398,6 +402,7 @@ lc_decode_kernel(const LcDecodeArgs a) {
                     if (tid == LC_DEC_THREADS - 1) entry(n_sel, n_sel_tok, tail_st, tail_ln);
                 }
             }
+            LC_LSTAMP0(17);
             __syncthreads();
             LC_LSTAMP0(13);
             {

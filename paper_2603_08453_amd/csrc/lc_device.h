@@ -39,6 +39,9 @@ static __shared__ unsigned long long lc_stamp_lds[32];
 #define LC_LSTAMP(i)
 #define LC_LSTAMP_FLUSH(name)
 #endif
+#ifndef LC_SEL_LSTAMP
+#define LC_SEL_LSTAMP(i)
+#endif
 #define LC_NEG_INF (-__builtin_huge_valf())
 
 // ---------------------------------------------------------------- bf16 unpacking
@@ -380,7 +383,7 @@ __device__ __forceinline__ LcSel lc_block_select(int n, long long W, long long C
     out.kstar = 0u;
     out.remW = 0;
     out.remC = 0;
-    LC_SEL_STAMP(0);
+    LC_SEL_STAMP(0); LC_SEL_LSTAMP(0);
     // ---- range of the candidate keys
     if (!have_range) {
         for (int i = threadIdx.x; i < n; i += NT) {
@@ -394,7 +397,7 @@ __device__ __forceinline__ LcSel lc_block_select(int n, long long W, long long C
     __syncthreads();
 #pragma unroll
     for (int w = 0; w < NT / 64; ++w) { kmin = min(kmin, (uint32_t)mm[w]); kmax = max(kmax, (uint32_t)mm[32 + w]); }
-    LC_SEL_STAMP(1);
+    LC_SEL_STAMP(1); LC_SEL_LSTAMP(1);
     if (kmax == 0u) { out.all = 1; __syncthreads(); return out; }            // no candidate at all
     const uint32_t diff = kmin ^ kmax;
     int top = diff ? 32 - __clz(diff) : 0;                   // bits [0, top) may differ
@@ -408,7 +411,7 @@ __device__ __forceinline__ LcSel lc_block_select(int n, long long W, long long C
     while (top > 0) {
         const int width = top >= 8 ? 8 : top;
         const int shift = top - width;
-        LC_SEL_STAMP(2 + 3 * npass);
+        LC_SEL_STAMP(2 + 3 * npass); LC_SEL_LSTAMP(2 + 3 * npass);
         for (int i = threadIdx.x; i < 256; i += NT) { hw[i] = 0; hc[i] = 0; }
         __syncthreads();
         for (int i = threadIdx.x; i < n; i += NT) {
@@ -420,7 +423,7 @@ __device__ __forceinline__ LcSel lc_block_select(int n, long long W, long long C
             }
         }
         __syncthreads();
-        LC_SEL_STAMP(3 + 3 * npass);
+        LC_SEL_STAMP(3 + 3 * npass); LC_SEL_LSTAMP(3 + 3 * npass);
         if (threadIdx.x < 64) {
             const int l = threadIdx.x;
             int w[4], c[4];
@@ -453,7 +456,7 @@ __device__ __forceinline__ LcSel lc_block_select(int n, long long W, long long C
             }
         }
         __syncthreads();
-        LC_SEL_STAMP(4 + 3 * npass);
+        LC_SEL_STAMP(4 + 3 * npass); LC_SEL_LSTAMP(4 + 3 * npass);
         ++npass;
         const int found = res[0];
         if (found < 0) {            // everything in scope fits: only possible in the first pass
@@ -584,7 +587,7 @@ template <int NT>
 __device__ __forceinline__ uint32_t lc_leaf_select(int n, uint32_t* skey, const int* slen, long long W, long long C,
                                                    LcLeafSelSh& sh) {
     const int tid = threadIdx.x;
-    LC_SEL_STAMP(0);
+    LC_SEL_STAMP(0); LC_SEL_LSTAMP(0);
     const uint32_t kmin = (uint32_t)sh.mm[0], kmax = (uint32_t)sh.mm[1];
     if (kmax == 0u) return 0u;                                   // no candidate at all
     int remW = (int)(W > 0x7fffffffLL ? 0x7fffffffLL : (W < 0 ? 0 : W));
@@ -593,7 +596,7 @@ __device__ __forceinline__ uint32_t lc_leaf_select(int n, uint32_t* skey, const 
     uint32_t lo = kmin, hi = kmax;
     int pass = 0;
     for (;;) {
-        LC_SEL_STAMP(1 + 4 * pass);
+        LC_SEL_STAMP(1 + 4 * pass); LC_SEL_LSTAMP(1 + 4 * pass);
         const uint32_t span = hi - lo;
         const int bits = span ? 32 - __clz(span) : 0;
         const int shift = bits > LC_LS_BITS ? bits - LC_LS_BITS : 0;     // (span >> shift) < LC_LS_BINS
@@ -612,7 +615,7 @@ __device__ __forceinline__ uint32_t lc_leaf_select(int n, uint32_t* skey, const 
             }
         }
         __syncthreads();
-        LC_SEL_STAMP(2 + 4 * pass);
+        LC_SEL_STAMP(2 + 4 * pass); LC_SEL_LSTAMP(2 + 4 * pass);
         // descending scan: thread t looks at bin 1023 - t (at PER consecutive bins with fewer threads)
         constexpr int PER = LC_LS_BINS / NT;
         int w[PER], c[PER], sw = 0, sc = 0;
@@ -643,7 +646,7 @@ __device__ __forceinline__ uint32_t lc_leaf_select(int n, uint32_t* skey, const 
             cc += c[j];
         }
         __syncthreads();
-        LC_SEL_STAMP(3 + 4 * pass);
+        LC_SEL_STAMP(3 + 4 * pass); LC_SEL_LSTAMP(3 + 4 * pass);
         const int fb = sh.res[0];
         if (fb < 0) return lo - 1u;                               // every candidate in scope fits
         remW -= sh.res[1];
@@ -661,7 +664,7 @@ __device__ __forceinline__ uint32_t lc_leaf_select(int n, uint32_t* skey, const 
             }
         }
         __syncthreads();
-        LC_SEL_STAMP(4 + 4 * pass);
+        LC_SEL_STAMP(4 + 4 * pass); LC_SEL_LSTAMP(4 + 4 * pass);
         const int nc = sh.ncand;
         if (nc <= LC_LS_CAND) {
             // ---- ranked directly
