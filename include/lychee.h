@@ -98,6 +98,11 @@ typedef struct lc_config {
     int32_t decode_splits;          /* split-K factor of the attention kernel; 0 = auto     */
     int32_t prune;                  /* LC_PRUNE_*                                           */
     int32_t center_dtype;           /* LC_CENTER_*: storage of the chunk-level centers      */
+    int32_t fanouts[LC_MAX_LEVELS]; /* fanouts[l], l >= 1: average children of a level-l node,
+                                       i.e. level l has ceil(N_{l-1} / fanouts[l]) nodes;
+                                       0 = use `fanout`.  The paper's three tiers are e.g.
+                                       {0, 2, 22}: 2 chunks per fine cluster, 22 fine
+                                       clusters per coarse unit (Appendix B)                */
 } lc_config;
 
 typedef struct lc_index lc_index;   /* opaque host-side handle */
@@ -268,12 +273,13 @@ int lc_index_info(const lc_index* idx, int b, int32_t* T, int32_t* M, int32_t* n
 /*
  * Export / import of the stored index as a flat little-endian host blob, so that
  * a CPU reference and the GPU can run on the identical stored values.
- *   int32 header[16] = {magic 'LCIX', version 1, B, H_kv, d, L, F, geometry, center_dtype, 0...}
+ *   int32 header[16] = {magic 'LCIX', version 1, B, H_kv, d, L, F, geometry, center_dtype,
+ *                       fanouts[1..5] (0 = F), 0...}
  *   per sequence b:    int32 T_b, M_b, N_1..N_{L-1};  int32 bounds[M_b+1]
  *   per (b, h, level): float32 center[N_l][d], float32 radius[N_l],
  *                      int32 parent[N_l], int32 ntok[N_l], int32 nchunk[N_l]
  * Centers are float32 in the blob whatever center_dtype says (bfloat16 values widened); import
- * requires the blob's L, F, geometry and center_dtype to equal the configuration's.
+ * requires the blob's L, fan-outs, geometry and center_dtype to equal the configuration's.
  * lc_index_export synchronises the stream.  With blob == NULL it only stores the
  * required size in *bytes.
  */

@@ -129,7 +129,7 @@ class Index:
     """
     d: int
     L: int
-    F: int
+    F: object                      # int, or per-level sequence (see level_fanout)
     geometry: int
     bounds: np.ndarray
     T: int
@@ -224,14 +224,24 @@ def spherical_kmeans(X: np.ndarray, k: int, iters: int,
     return labels, m
 
 
-def build_index(K: np.ndarray, bounds: Sequence[int], T: int, L: int, F: int,
+def level_fanout(F, level: int) -> int:
+    """Average number of children of a node at `level` (>= 1): F itself, or F[level] when the levels
+    have fan-outs of their own (the paper's tiers: 2 chunks per fine cluster, at most 64 coarse units;
+    Appendix B)."""
+    if isinstance(F, (int, np.integer)):
+        return int(F)
+    return int(F[level])
+
+
+def build_index(K: np.ndarray, bounds: Sequence[int], T: int, L: int, F,
                 iters: int = 10, geometry: int = TOKEN_BALL, center_dtype: int = CENTER_F32) -> Index:
     """Build the index of one (sequence, KV head).
 
     K [>=T, d] float64 keys; bounds[0..M] boundaries of the closed chunks
     (bounds[0] = 0, bounds[M] <= T); tokens [bounds[M], T) are the open tail.
     Levels: 0 = chunks, then L-1 rounds of spherical k-means with
-    k = ceil(N/F) clusters on the unit directions of the level below.
+    k = ceil(N/F) clusters on the unit directions of the level below (F an int,
+    or a sequence with F[level] for the level being formed).
     """
     K = np.asarray(K, dtype=np.float64)
     bounds = np.asarray(bounds, dtype=np.int64)
@@ -253,7 +263,7 @@ def build_index(K: np.ndarray, bounds: Sequence[int], T: int, L: int, F: int,
     for level in range(1, L):
         below = idx.center[level - 1]
         N = below.shape[0]
-        k = max(1, -(-N // F))
+        k = max(1, -(-N // level_fanout(F, level)))
         X = np.stack([direction_of(c) for c in below]) if N else np.zeros((0, d))
         if N:
             labels, m = spherical_kmeans(X, k, iters)

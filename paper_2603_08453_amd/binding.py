@@ -52,6 +52,7 @@ class LcConfig(ctypes.Structure):
         ("decode_splits", ctypes.c_int32),
         ("prune", ctypes.c_int32),
         ("center_dtype", ctypes.c_int32),
+        ("fanouts", ctypes.c_int32 * LC_MAX_LEVELS),
     ]
 
 
@@ -159,9 +160,10 @@ def lc_config_default(**overrides) -> LcConfig:
     cfg = LcConfig()
     lib().lc_config_default(ctypes.byref(cfg))
     for k, v in overrides.items():
-        if k == "beam":
+        if k in ("beam", "fanouts"):
+            arr = getattr(cfg, k)
             for i in range(LC_MAX_LEVELS):
-                cfg.beam[i] = int(v[i]) if i < len(v) else 0
+                arr[i] = int(v[i]) if i < len(v) else 0
         else:
             setattr(cfg, k, int(v))
     return cfg
@@ -330,11 +332,13 @@ _MAGIC = 0x5849434C
 
 
 def pack_blob(B: int, H_kv: int, d: int, L: int, F: int, geometry: int, seqs: List[Dict],
-              center_dtype: int = LC_CENTER_F32) -> bytes:
+              center_dtype: int = LC_CENTER_F32, fanouts: Optional[Sequence[int]] = None) -> bytes:
     """seqs[b] = {"T": int, "bounds": int array [M+1],
                   "heads": [ per head: [ per level: dict(center, radius, parent, ntok, nchunk) ] ]}"""
     hdr = np.zeros(16, dtype=np.int32)
     hdr[:9] = [_MAGIC, 1, B, H_kv, d, L, F, geometry, center_dtype]
+    for l in range(1, LC_MAX_LEVELS):
+        hdr[8 + l] = int(fanouts[l]) if fanouts is not None and l < len(fanouts) else 0
     parts = [hdr.tobytes()]
     for s in seqs:
         M = len(s["bounds"]) - 1
@@ -383,4 +387,4 @@ def unpack_blob(blob: bytes) -> Dict:
             s["heads"].append(levels)
     assert off == len(blob), (off, len(blob))
     return {"B": B, "H_kv": H_kv, "d": d, "L": L, "F": F, "geometry": geometry, "center_dtype": int(hdr[8]),
-            "seqs": seqs}
+            "fanouts": [0] + [int(x) for x in hdr[9:9 + LC_MAX_LEVELS - 1]], "seqs": seqs}

@@ -27,13 +27,18 @@ bool config_ok(const lc_config* c) {
     if (c->decode_splits < 0 || c->decode_splits > 256) return false;
     if (c->prune != LC_PRUNE_AUTO && c->prune != LC_PRUNE_ALWAYS && c->prune != LC_PRUNE_NEVER) return false;
     if (c->center_dtype != LC_CENTER_F32 && c->center_dtype != LC_CENTER_BF16) return false;
+    for (int l = 0; l < LC_MAX_LEVELS; ++l)
+        if (c->fanouts[l] < 0) return false;
     return true;
 }
+
+// average children of a level-l node (l >= 1)
+int level_fanout(const lc_config* c, int l) { return c->fanouts[l] > 0 ? c->fanouts[l] : c->fanout; }
 
 void level_caps(const lc_config* c, int* cap) {
     cap[0] = c->max_chunks;
     for (int l = 1; l < LC_MAX_LEVELS; ++l) {
-        cap[l] = l < c->levels ? (cap[l - 1] + c->fanout - 1) / c->fanout : 0;
+        cap[l] = l < c->levels ? (cap[l - 1] + level_fanout(c, l) - 1) / level_fanout(c, l) : 0;
         if (l < c->levels && cap[l] < 1) cap[l] = 1;
     }
 }
@@ -190,7 +195,7 @@ void fill_level_counts(lc_index* h) {
         int n = h->M[b];
         h->N[(size_t)b * LC_MAX_LEVELS + 0] = n;
         for (int l = 1; l < h->cfg.levels; ++l) {
-            n = (n + h->cfg.fanout - 1) / h->cfg.fanout;
+            n = (n + level_fanout(&h->cfg, l) - 1) / level_fanout(&h->cfg, l);
             if (n < 1) n = 1;
             h->N[(size_t)b * LC_MAX_LEVELS + l] = n;
         }
@@ -516,6 +521,7 @@ int lc_index_export(const lc_index* idx, void* blob, size_t* bytes, void* stream
     char* p = static_cast<char*>(blob);
     int32_t hdr[16] = {kMagic, 1, idx->B, idx->H_kv, idx->d, idx->cfg.levels, idx->cfg.fanout, idx->cfg.geometry,
                        idx->cfg.center_dtype};
+    for (int l = 1; l < LC_MAX_LEVELS; ++l) hdr[8 + l] = idx->cfg.fanouts[l];
     memcpy(p, hdr, sizeof(hdr));
     p += sizeof(hdr);
     const int L = idx->cfg.levels;
@@ -574,6 +580,8 @@ int lc_index_import(lc_index** out, const lc_config* cfg, const void* blob, size
     if (B < 1 || H < 1) return LC_ERR_BAD_BLOB;
     if (d != LC_HEAD_DIM) return LC_ERR_BAD_SHAPE;
     if (L != cfg->levels || F != cfg->fanout || geo != cfg->geometry) return LC_ERR_BAD_BLOB;
+    for (int l = 1; l < L; ++l)
+        if ((hdr[8 + l] > 0 ? hdr[8 + l] : F) != level_fanout(cfg, l)) return LC_ERR_BAD_BLOB;
     if (hdr[8] != cfg->center_dtype) return LC_ERR_BAD_BLOB;     // radii are only valid for the centers they were measured against
     if (index_bytes < lc_layout_index(cfg, B, H, d, nullptr, nullptr)) return LC_ERR_WORKSPACE_TOO_SMALL;
 

@@ -63,7 +63,8 @@ class Case:
 def make_case(w: wl.Workload, tails: Optional[Sequence[int]] = None, extra_tokens: int = 0,
               extra_chunks: int = 0, geometry: int = orc.TOKEN_BALL, build_on: str = "oracle",
               offset_std: float = 0.5, noise_std: float = 1.0, cap: Optional[int] = None,
-              decode_splits: int = 0, prune: int = 1, mutate=None, center_dtype: int = 0) -> Case:
+              decode_splits: int = 0, prune: int = 1, mutate=None, center_dtype: int = 0,
+              fanouts: Optional[Sequence[int]] = None) -> Case:
     """build_on = "oracle": the oracle builds the index and the GPU imports it (identical
     stored values on both sides); "gpu": lc_build_index builds it (the oracle index is still
     built for comparison).  `mutate(seqs)` may edit the drawn sequences in place before anything
@@ -88,8 +89,10 @@ def make_case(w: wl.Workload, tails: Optional[Sequence[int]] = None, extra_token
     Tcap = Tmax + extra_tokens
     cfg = lc.lc_config_default(levels=w.levels, fanout=w.fanout, geometry=geometry,
                                max_chunks=Mmax + extra_chunks, max_tokens=Tcap, decode_splits=decode_splits,
-                               prune=prune, center_dtype=center_dtype)      # default 1 = always walk the levels, so the pruning path is what is tested
-    oidx = [[orc.build_index(wl.bf16_bits_to_f64(s.K[h]), s.bounds, s.T, w.levels, w.fanout, geometry=geometry,
+                               prune=prune, center_dtype=center_dtype,
+                               **({} if fanouts is None else {"fanouts": list(fanouts)}))      # default 1 = always walk the levels, so the pruning path is what is tested
+    F_or = w.fanout if fanouts is None else [f if f > 0 else w.fanout for f in fanouts]
+    oidx = [[orc.build_index(wl.bf16_bits_to_f64(s.K[h]), s.bounds, s.T, w.levels, F_or, geometry=geometry,
                              center_dtype=center_dtype)
              for h in range(w.H_kv)] for s in seqs]
 
@@ -104,7 +107,7 @@ def make_case(w: wl.Workload, tails: Optional[Sequence[int]] = None, extra_token
         blob = lc.pack_blob(w.B, w.H_kv, w.d, w.levels, w.fanout, geometry,
                             [dict(T=s.T, bounds=s.bounds, heads=[oracle_index_to_levels(oidx[b][h])
                                                                  for h in range(w.H_kv)])
-                             for b, s in enumerate(seqs)], center_dtype=center_dtype)
+                             for b, s in enumerate(seqs)], center_dtype=center_dtype, fanouts=fanouts)
         idx = lc.lc_index_import(cfg, blob, index_buf)
     else:
         idx = lc.lc_build_index(cfg, Kt, [s.T for s in seqs], [s.bounds for s in seqs], index_buf, ws)

@@ -599,6 +599,51 @@ def test_bf16_chunk_centers_append_stream(G):
             H.accept_ids(ids[b][h], orc.node_scores(gi, 0, q), gi.lens(), 150)
 
 
+def test_per_level_fanouts_built_on_gpu(G):
+    """The paper's tiers (Appendix B): 2 chunks per fine cluster, many fine clusters per coarse unit.
+    lc_build_index sizes every level by its own fan-out; the tree matches the oracle's and retrieval
+    (level walk and top-k per level) works on it."""
+    from paper_2603_08453_amd import binding as lc
+    w = wl.tiny("tiers", B=2, H_q=8, H_kv=2, levels=3, fanout=16, T=0, T_range=(1500, 2500), chunk_lo=8, chunk_hi=16)
+    fan = [0, 2, 22]
+    case = G.make_case(w, tails=[5, 0], build_on="gpu", fanouts=fan)
+    blob = lc.unpack_blob(lc.lc_index_export(case.idx))
+    assert blob["fanouts"][:3] == fan
+    same_topology = 0
+    for b in range(w.B):
+        s = blob["seqs"][b]
+        T, M, n_lev = case.idx.info(b)
+        assert list(n_lev[:3]) == [M, -(-M // 2), -(-(-(-M // 2)) // 22)]
+        for h in range(w.H_kv):
+            oi = case.oidx[b][h]
+            gi = G.levels_to_oracle_index(s["heads"][h], s["bounds"], s["T"], w.fanout, orc.TOKEN_BALL)
+            assert [gi.n(l) for l in range(3)] == [oi.n(l) for l in range(3)]
+            H.check_covering_invariant(gi, case.Kf(b, h), slack=1e-6)
+            H.check_counts(gi)
+            same_topology += int(all(np.array_equal(gi.parent[l], oi.parent[l]) for l in range(2)))
+    _say(f"tiers: {same_topology}/{w.B * w.H_kv} trees have the oracle's topology")
+    assert same_topology >= (w.B * w.H_kv) // 2
+    # a blob of this index is refused by a configuration with other fan-outs
+    import torch
+    other = lc.lc_config_default(levels=3, fanout=16, fanouts=[0, 2, 8], max_chunks=case.cfg.max_chunks,
+                                 max_tokens=case.cfg.max_tokens)
+    buf = torch.zeros(lc.lc_index_bytes(other, w.B, w.H_kv), dtype=torch.uint8, device="cuda")
+    with pytest.raises(lc.LycheeError) as e:
+        lc.lc_index_import(other, lc.lc_index_export(case.idx), buf)
+    assert e.value.code == lc.LC_ERR_BAD_BLOB
+    # retrieval on the imported oracle index of the same shape: exact policy and top-k per level
+    case2 = G.make_case(w, tails=[5, 0], fanouts=fan)
+    qb = _q_batch(case2, 0)
+    for budget in (100, 700):
+        ids = _check_retrieve(G, case2, qb, budget, tag="tiers")
+        _check_decode(G, case2, qb, ids, tag=f"tiers budget {budget}")
+        _check_step(G, case2, qb, budget, tag="tiers step")
+    beam = [0, 20, 3]
+    _check_retrieve(G, case2, qb, 10 ** 9, policy=orc.POLICY_BEAM, beam=beam, sink=16, tag="tiers beam")
+    _check_step(G, case2, qb, 10 ** 9, policy=orc.POLICY_BEAM, beam=beam, sink=16, tag="tiers step beam")
+    lc.lc_set_policy(case2.idx, lc.LC_POLICY_EXACT, None, 0)
+
+
 # ----------------------------------------------------------------- lazy update
 
 @pytest.mark.parametrize("geometry,L", [(orc.TOKEN_BALL, 3), (orc.TOKEN_BALL, 1), (orc.PAPER_UNIT, 2)])

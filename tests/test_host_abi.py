@@ -35,7 +35,7 @@ def test_config_struct_matches_header(L):
     cfg = lc.lc_config_default()
     assert (cfg.levels, cfg.fanout, cfg.kmeans_iters) == (3, 16, 10)
     assert cfg.geometry == lc.LC_GEOMETRY_TOKEN_BALL and cfg.policy == lc.LC_POLICY_EXACT
-    assert ctypes.sizeof(lc.LcConfig) == 4 * (5 + lc.LC_MAX_LEVELS + 6)
+    assert ctypes.sizeof(lc.LcConfig) == 4 * (5 + lc.LC_MAX_LEVELS + 6 + lc.LC_MAX_LEVELS)
     assert cfg.center_dtype == lc.LC_CENTER_F32
     hdr = open(os.path.join(ROOT, "include", "lychee.h")).read()
     assert f"#define LC_MAX_LEVELS {lc.LC_MAX_LEVELS}" in hdr
@@ -55,6 +55,11 @@ def test_size_queries(L):
     nh = lc.lc_index_bytes(half, 1, 8)
     assert 4096 * 256 * 8 <= nh <= 4096 * 256 * 8 * 1.4 and nh < 0.62 * n1
     assert lc.lc_index_bytes(lc.lc_config_default(max_chunks=64, max_tokens=1024, center_dtype=2), 1, 8) == 0
+    # fan-outs of their own per level: 4096 chunks -> 2048 fine clusters -> 94 coarse units
+    tiers = lc.lc_config_default(levels=3, fanout=16, fanouts=[0, 2, 22], max_chunks=4096, max_tokens=140000)
+    flat = lc.lc_config_default(levels=3, fanout=16, max_chunks=4096, max_tokens=140000)
+    assert lc.lc_index_bytes(tiers, 1, 1) > lc.lc_index_bytes(flat, 1, 1) + 2048 * 512 - 256 * 512
+    assert lc.lc_index_bytes(lc.lc_config_default(max_chunks=64, max_tokens=1024, fanouts=[0, -1]), 1, 8) == 0
     # invalid: d != 128, capacities unset, G too large, H_q not a multiple
     assert lc.lc_index_bytes(cfg, 1, 8, 64) == 0
     assert lc.lc_index_bytes(lc.lc_config_default(), 1, 8) == 0

@@ -580,3 +580,27 @@ def test_bf16_chunk_centers_survive_appends():
     assert closed >= 5
     flat = orc.retrieve_flat(idx, c["q"], 70).tolist()
     assert orc.retrieve_best_first(idx, c["q"], 70).tolist() == flat
+
+
+# ---------------------------------------------------------------- per-level fan-outs
+
+def test_per_level_fanouts_give_the_papers_tiers():
+    """Fan-outs of their own per level (2 chunks per fine cluster, then 8 fine clusters per coarse
+    unit here): level sizes are ceil(N / F_level), and everything that holds for one fan-out holds."""
+    c = H.rand_case(55, T=400, d=8, G=2)
+    F = [0, 2, 8]
+    idx = orc.build_index(c["K"], c["bounds"], c["T"], 3, F)
+    M = idx.M
+    assert idx.n(1) == -(-M // 2) and idx.n(2) == -(-idx.n(1) // 8)
+    same = orc.build_index(c["K"], c["bounds"], c["T"], 3, 2)
+    assert np.array_equal(idx.parent[0], same.parent[0]) and np.array_equal(idx.center[1], same.center[1])
+    assert same.n(2) == -(-same.n(1) // 2) and idx.n(2) < same.n(2)
+    H.check_covering_invariant(idx, c["K"])
+    H.check_counts(idx)
+    for budget in (0, 30, 120, 10 ** 6):
+        flat = orc.retrieve_flat(idx, c["q"], budget).tolist()
+        assert orc.retrieve_best_first(idx, c["q"], budget).tolist() == flat
+        assert orc.retrieve_level_sync(idx, c["q"], budget).tolist() == flat
+    beam = [0, 6, 2]
+    got = orc.retrieve_beam(idx, c["q"], 10 ** 6, beam)
+    assert len(set(idx.parent[0][got].tolist())) <= 6
