@@ -254,3 +254,69 @@ def test_c4_streaming_2048_steps(G):
     _say(f"C4 stream diagnostics (head 0): mean Jaccard of consecutive sampled sets {np.mean(jac):.3f}, "
          f"mean window hit (w=32) {np.mean(hit):.3f}, recall of the true top-256 tokens {np.mean(rec):.3f}")
     assert 0.0 <= np.mean(jac) <= 1.0 and 0.0 <= np.mean(hit) <= 1.0 and 0.0 <= np.mean(rec) <= 1.0
+
+
+def test_paper_literal_mode_against_the_default_32k(G):
+    """The paper's own configuration against this build's default, at one context and (about) one token
+    count: 32768 tokens in chunks of 8..16, the paper's tiers (2 chunks per fine cluster, 22 fine
+    clusters per coarse unit: 63 coarse units), 32 query / 8 KV heads.
+      default:        token-covering balls, exact selection under a 1024-token budget;
+      paper-literal:  unit-norm representatives with radius 0, top-8 coarse units then top-43 fine
+                      clusters, all chunks of the kept clusters attended, attention sink of 16 tokens.
+    Both are checked against the oracle (ids and attention); cost per step and recall of the true
+    top-64 tokens of the first query head of every KV head are reported."""
+    import time
+    import torch
+    from paper_2603_08453_amd import binding as lc
+    from paper_2603_08453_amd import diagnostics as D
+    w = wl.tiny("paper32k", cfg_id=77, B=1, H_q=32, H_kv=8, levels=3, fanout=16, T=32768, chunk_lo=8, chunk_hi=16,
+                budget=1024)
+    fan = [0, 2, 22]
+    report = {}
+    for mode in ("default", "paper-literal"):
+        literal = mode == "paper-literal"
+        _say(f"building the 32K index ({mode})")
+        case = G.make_case(w, geometry=orc.PAPER_UNIT if literal else orc.TOKEN_BALL, fanouts=fan,
+                           prune=lc.LC_PRUNE_AUTO)
+        assert [case.oidx[0][0].n(l) for l in (1, 2)] == [-(-case.oidx[0][0].M // 2), -(-(-(-case.oidx[0][0].M // 2)) // 22)]
+        qb = np.stack([s.Q[0] for s in case.seqs])
+        if literal:
+            beam, budget, sink = [0, 43, 8], 10 ** 9, 16
+            lc.lc_set_policy(case.idx, lc.LC_POLICY_BEAM, beam, sink)
+        else:
+            beam, budget, sink = None, w.budget, 0
+            lc.lc_set_policy(case.idx, lc.LC_POLICY_EXACT, None, 0)
+        ids, _, _ = G.gpu_retrieve(case, qb, budget, want_scores=False)
+        out, lse = G.gpu_decode(case, qb, ids)
+        ids_f, out_f, _ = G.gpu_step(case, qb, budget)
+        assert np.array_equal(out_f, out)
+        rec, tok = [], []
+        for h in range(w.H_kv):
+            oi = case.oidx[0][h]
+            q = wl.bf16_bits_to_f64(qb[0, h * w.G:(h + 1) * w.G])
+            assert ids_f[0][h].tolist() == ids[0][h].tolist()
+            if literal:
+                assert ids[0][h].tolist() == orc.retrieve_beam(oi, q, budget, beam, sink).tolist(), h
+            else:
+                H.accept_ids(ids[0][h], orc.node_scores(oi, 0, q), oi.lens(), budget)
+            ref, ref_lse = orc.sparse_decode(q, case.Kf(0, h), case.Vf(0, h), oi.bounds, oi.T, ids[0][h])
+            mx, rel = G.attention_errors(out[0, h * w.G:(h + 1) * w.G], ref)
+            assert mx <= ATTN_MAX_ABS and rel <= ATTN_REL_L2, (mode, h, mx, rel)
+            sel = D.selected_tokens(oi.bounds, oi.T, ids[0][h])
+            rec.append(D.recall_rate(case.Kf(0, h)[:oi.T] @ q[0], sel, 64))
+            tok.append(len(sel))
+        # cost of the step (one index, rows mostly in cache: a comparison of the two modes, not a headline)
+        qd = G.to_bf16_tensor(qb)
+        o = torch.zeros((1, w.H_q, w.d), dtype=torch.float32, device="cuda")
+        for _ in range(20):
+            lc.lc_decode_step(case.idx, qd, case.K, case.V, budget, o, case.ws)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(300):
+            lc.lc_decode_step(case.idx, qd, case.K, case.V, budget, o, case.ws)
+        torch.cuda.synchronize()
+        report[mode] = ((time.perf_counter() - t0) / 300 * 1e6, float(np.mean(rec)), float(np.mean(tok)))
+        lc.lc_set_policy(case.idx, lc.LC_POLICY_EXACT, None, 0)
+    for mode, (us, r, t) in report.items():
+        _say(f"32K, {mode}: {us:.1f} us per step, {t:.0f} tokens attended, recall of the true top-64 tokens {r:.3f}")
+    assert report["default"][2] <= w.budget + 64 and report["paper-literal"][2] > 0
