@@ -44,6 +44,14 @@ def _short(name: str) -> str:
     return m.group(1) if m else name[:48]
 
 
+def _label(name: str) -> str:
+    """Kernel name with its template arguments, without the parameter list."""
+    head = name.split("(")[0]
+    if "lc_" not in head:
+        return _short(name)
+    return _short(head) + (head[head.index("<"):head.rindex(">") + 1] if "<" in head and ">" in head else "")
+
+
 def traffic(fetch_dir: str, write_dir: str, copy_bytes: int):
     out = {}
     factors = {}
@@ -55,7 +63,7 @@ def traffic(fetch_dir: str, write_dir: str, copy_bytes: int):
         for k, vs in per.items():
             if "lc_" not in k:
                 continue
-            e = out.setdefault(_short(k) + ("" if "<" not in k else k[k.index("<"):k.index(">") + 1]), {})
+            e = out.setdefault(_label(k), {})
             e[counter] = (sum(vs) / len(vs), len(vs))
     return out, factors
 
@@ -80,7 +88,7 @@ def main():
         rows = list(csv.DictReader(open(files[0])))
         lines += ["| kernel | calls | avg us | min us | max us | % of GPU time |", "|---|---|---|---|---|---|"]
         for r in rows[:14]:
-            lines.append(f"| {_short(r['Name'])}{'' if '<' not in r['Name'] else r['Name'][r['Name'].index('<'):r['Name'].index('>') + 1]} | {r['Calls']} | "
+            lines.append(f"| {_label(r['Name'])} | {r['Calls']} | "
                          f"{float(r['AverageNs']) / 1e3:.2f} | {float(r['MinNs']) / 1e3:.2f} | "
                          f"{float(r['MaxNs']) / 1e3:.2f} | {float(r['Percentage']):.1f} |")
         lines.append("")
