@@ -78,7 +78,12 @@ __device__ __forceinline__ float lc_sum64(float v) {
     return v;
 }
 __device__ __forceinline__ float lc_max64(float v) {
-    for (int m = 1; m < 64; m <<= 1) v = fmaxf(v, __shfl_xor(v, m));
+    v = fmaxf(v, lc_dpp<0xB1>(v));
+    v = fmaxf(v, lc_dpp<0x4E>(v));
+    v = fmaxf(v, lc_dpp<0x141>(v));
+    v = fmaxf(v, lc_dpp<0x140>(v));
+    v = fmaxf(v, __shfl_xor(v, 16));
+    v = fmaxf(v, __shfl_xor(v, 32));
     return v;
 }
 
