@@ -436,12 +436,8 @@ __device__ __forceinline__ LcSel lc_block_select(int n, long long W, long long C
             for (int j = 0; j < 4; ++j) { w[j] = hw[255 - (4 * l + j)]; c[j] = hc[255 - (4 * l + j)]; }
             long long sw = (long long)w[0] + w[1] + w[2] + w[3];
             long long sc = (long long)c[0] + c[1] + c[2] + c[3];
-            long long iw = sw, ic = sc;
-#pragma unroll
-            for (int off = 1; off < 64; off <<= 1) {
-                const long long tw = __shfl_up(iw, off), tc = __shfl_up(ic, off);
-                if (l >= off) { iw += tw; ic += tc; }
-            }
+            // (the histogram holds ints: the sums of a pass fit 32 bits, so the scan can run on the vector ALU)
+            const long long iw = lc_wave_scan_incl((int)sw), ic = lc_wave_scan_incl((int)sc);
             long long cw = iw - sw, cc = ic - sc;           // weight / count of all higher bins
             int found = -1;
             long long fw = 0, fc = 0;

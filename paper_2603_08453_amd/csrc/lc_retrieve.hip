@@ -87,11 +87,8 @@ __device__ __forceinline__ void lc_small_select(int n, int mode, long long W, lo
         *reached = 0;
         return;
     }
-#pragma unroll
-    for (int m = 1; m < 64; m <<= 1) {
-        mk = min(mk, (uint32_t)__shfl_xor((int)mk, m));
-        hit |= __shfl_xor(hit, m);
-    }
+    mk = lc_wave_min_u(mk);
+    hit = (int)lc_wave_max_u((uint32_t)(hit != 0));
     __syncthreads();
     if ((threadIdx.x & 63) == 0) { sh[threadIdx.x >> 6] = (int)mk; sh[32 + (threadIdx.x >> 6)] = hit; }
     __syncthreads();
