@@ -246,6 +246,31 @@ int lc_decode_step(const lc_index* idx, const void* q, const void* K, const void
                    void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * lc_decode_step_static -- lc_decode_step for callers that cannot allocate device memory or
+ * pass a workspace: code that runs under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, checks, kernels and results as lc_decode_step, except that
+ * the step's workspace (chunk score keys, kept flags, select staging, chunk list, split-K
+ * partials) lives in a device array of LC_STATIC_SCRATCH_BYTES that is part of the library image:
+ * every GPU the library runs on holds one copy until the process ends.  The call allocates and
+ * frees nothing.  LC_ERR_CAPACITY (nothing enqueued) if the step needs more than that, i.e. if
+ * lc_decode_workspace_bytes(cfg, B, H_q, H_kv, d) > LC_STATIC_SCRATCH_BYTES.
+ * All calls on one GPU share that GPU's array: two calls that overlap on one GPU (different
+ * streams, or different indices) race; stream-ordered calls are fine, nothing in the array has to
+ * survive from one call to the next and nothing in it has to be cleared by the caller.
+ */
+#define LC_STATIC_SCRATCH_BYTES (16u << 20)
+int lc_decode_step_static(const lc_index* idx, const void* q, const void* K, const void* V,
+                          const int64_t kv_strides[3], int H_q, int budget,
+                          float* out, float* lse, int32_t* chunk_ids, int32_t* counts, int cap,
+                          void* stream);
+/* Bytes of workspace one decode step (lc_retrieve, lc_sparse_decode, lc_decode_step) uses: the
+ * part of lc_workspace_bytes() without the scratch of lc_build_index / lc_recluster (pure host
+ * function; 0 on invalid arguments). */
+size_t lc_decode_workspace_bytes(const lc_config* cfg /* host */, int B, int H_q, int H_kv, int d);
+/* LC_STATIC_SCRATCH_BYTES as the loaded library was built with. */
+size_t lc_static_workspace_bytes(void);
+
+/*
  * lc_append -- lazy update for one streamed token per sequence (Section 4.4,
  * Algorithm 1 step 4).  Writes k_new/v_new at row T_b of K and V and advances
  * T_b.  Where close_chunk[b] != 0 the open tail (including the new token) becomes

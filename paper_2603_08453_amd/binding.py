@@ -104,6 +104,12 @@ def lib() -> ctypes.CDLL:
     L.lc_decode_step.argtypes = [vp, vp, vp, vp, i64p, ctypes.c_int, ctypes.c_int, vp, vp, vp, vp, ctypes.c_int,
                                  vp, ctypes.c_size_t, vp]
     L.lc_decode_step.restype = ctypes.c_int
+    L.lc_decode_step_static.argtypes = [vp, vp, vp, vp, i64p, ctypes.c_int, ctypes.c_int, vp, vp, vp, vp, ctypes.c_int, vp]
+    L.lc_decode_step_static.restype = ctypes.c_int
+    L.lc_decode_workspace_bytes.argtypes = [cfgp, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int]
+    L.lc_decode_workspace_bytes.restype = ctypes.c_size_t
+    L.lc_static_workspace_bytes.argtypes = []
+    L.lc_static_workspace_bytes.restype = ctypes.c_size_t
     L.lc_recluster.argtypes = [vp, vp, ctypes.c_size_t, vp]
     L.lc_recluster.restype = ctypes.c_int
     L.lc_set_step_reuse_keys.argtypes = [vp, ctypes.c_int]
@@ -278,6 +284,25 @@ def lc_decode_step(idx: Index, q, K, V, budget: int, out, ws, lse=None, chunk_id
     _check(lib().lc_decode_step(idx.handle, _ptr(q), _ptr(K), _ptr(V), _strides3(K), H_q, int(budget), _ptr(out),
                                 _ptr(lse), _ptr(chunk_ids), _ptr(counts), cap, _ptr(ws),
                                 ws.numel() * ws.element_size(), _stream(stream)), "lc_decode_step")
+
+
+def lc_decode_step_static(idx: Index, q, K, V, budget: int, out, lse=None, chunk_ids=None, counts=None,
+                          stream=None) -> None:
+    """lc_decode_step on the library's own static scratch array (no workspace argument)."""
+    assert K.shape == V.shape and K.stride() == V.stride()
+    H_q = int(q.shape[1])
+    cap = int(chunk_ids.shape[-1]) if chunk_ids is not None else 0
+    _check(lib().lc_decode_step_static(idx.handle, _ptr(q), _ptr(K), _ptr(V), _strides3(K), H_q, int(budget),
+                                       _ptr(out), _ptr(lse), _ptr(chunk_ids), _ptr(counts), cap,
+                                       _stream(stream)), "lc_decode_step_static")
+
+
+def lc_decode_workspace_bytes(cfg: LcConfig, B: int, H_q: int, H_kv: int, d: int = LC_HEAD_DIM) -> int:
+    return int(lib().lc_decode_workspace_bytes(ctypes.byref(cfg), B, H_q, H_kv, d))
+
+
+def lc_static_workspace_bytes() -> int:
+    return int(lib().lc_static_workspace_bytes())
 
 
 def lc_append(idx: Index, K, V, k_new, v_new, close_chunk: Optional[Sequence[int]], ws, stream=None) -> None:

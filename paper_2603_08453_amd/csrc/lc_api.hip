@@ -2,6 +2,7 @@
 // All checks that do not need the GPU happen before the first HIP call.
 #include <string.h>
 
+#include <mutex>
 #include <new>
 #include <string>
 
@@ -94,7 +95,8 @@ int lc_auto_splits(const lc_config* cfg, int B, int H) {
     return s;
 }
 
-size_t lc_layout_ws(const lc_config* cfg, int B, int H_q, int H, int d, int splits, void* base, LcWs* ws) {
+size_t lc_layout_ws(const lc_config* cfg, int B, int H_q, int H, int d, int splits, void* base, LcWs* ws,
+                    bool with_build) {
     LcWs tmp;
     LcWs* W = ws ? ws : &tmp;
     int cap[LC_MAX_LEVELS];
@@ -109,10 +111,14 @@ size_t lc_layout_ws(const lc_config* cfg, int B, int H_q, int H, int d, int spli
     W->counts_tmp = c.take<int32_t>(BH);
     W->part_acc = c.take<float>((size_t)B * H_q * splits * d);
     W->part_ml = c.take<float>((size_t)B * H_q * splits * 2);
-    W->dirs = c.take<float>(BH * cap[0] * d);
-    W->cent_a = c.take<float>(BH * cap1 * d);
-    W->cent_b = c.take<float>(BH * cap1 * d);
-    W->anc = c.take<int>(BH * cap[0]);
+    W->dirs = W->cent_a = W->cent_b = nullptr;
+    W->anc = nullptr;
+    if (with_build) {
+        W->dirs = c.take<float>(BH * cap[0] * d);
+        W->cent_a = c.take<float>(BH * cap1 * d);
+        W->cent_b = c.take<float>(BH * cap1 * d);
+        W->anc = c.take<int>(BH * cap[0]);
+    }
     W->total = align_up(c.off);
     return W->total;
 }
@@ -398,31 +404,31 @@ int lc_retrieve(const lc_index* idx, const void* q, int H_q, int budget, int32_t
                               p.walk ? p.max_upper : -1, 0, static_cast<hipStream_t>(stream));
 }
 
-int lc_decode_step(const lc_index* idx, const void* q, const void* K, const void* V, const int64_t kv_strides[3],
-                   int H_q, int budget, float* out, float* lse, int32_t* chunk_ids, int32_t* counts, int cap,
-                   void* ws, size_t ws_bytes, void* stream) {
+namespace {
+// Argument checks of a decode step that need neither the workspace nor the GPU.
+int decode_step_checks(const lc_index* idx, const void* q, const void* K, const void* V, const int64_t kv_strides[3],
+                       int H_q, int budget, float* out, int32_t* chunk_ids, int32_t* counts, int cap) {
     const bool want_ids = chunk_ids != nullptr;
     int rc = common_decode_checks(idx, q, H_q, want_ids ? cap : 1);
     if (rc) return rc;
-    if (!K || !V || !out || !ws || budget < 0) return LC_ERR_INVALID_ARG;
+    if (!K || !V || !out || budget < 0) return LC_ERR_INVALID_ARG;
     if (want_ids != (counts != nullptr)) return LC_ERR_INVALID_ARG;
     rc = check_strides(kv_strides);
     if (rc) return rc;
-    if (!aligned16(K) || !aligned16(V) || (reinterpret_cast<uintptr_t>(ws) & 255u)) return LC_ERR_INVALID_ARG;
+    if (!aligned16(K) || !aligned16(V)) return LC_ERR_INVALID_ARG;
     if ((long long)idx->cfg.max_tokens * kv_strides[2] * 2 >= (1LL << 31)) return LC_ERR_BAD_SHAPE;
-    const int splits = lc_auto_splits(&idx->cfg, idx->B, idx->H_kv);
-    if (ws_bytes < lc_layout_ws(&idx->cfg, idx->B, H_q, idx->H_kv, idx->d, splits, nullptr, nullptr))
-        return LC_ERR_WORKSPACE_TOO_SMALL;
-    RetrievePlan p;
-    rc = plan_retrieve(idx, budget, cap, want_ids, &p);
-    if (rc) return rc;
-    LcWs w;
-    lc_layout_ws(&idx->cfg, idx->B, H_q, idx->H_kv, idx->d, splits, ws, &w);
+    return LC_OK;
+}
+
+// The step itself on a laid-out workspace (every check has passed).
+int decode_step_run(const lc_index* idx, const LcWs& w, const RetrievePlan& p, int splits, const void* q,
+                    const void* K, const void* V, const int64_t kv_strides[3], int H_q, int budget, float* out,
+                    float* lse, int32_t* chunk_ids, int32_t* counts, int cap, hipStream_t st) {
+    const bool want_ids = chunk_ids != nullptr;
     const int G = H_q / idx->H_kv;
-    hipStream_t st = static_cast<hipStream_t>(stream);
+    int rc;
     // Every workgroup of the fused kernel repeats the selection with 256 threads: with a few thousand
-    // chunks that is cheaper than the hand-off through a chunk list, with more it is not (measured
-    // cross-over near 4096 chunks per sequence).
+    // chunks that is cheaper than the hand-off through a chunk list, with more it is not.
     if (p.max_M <= LC_STEP_FUSED_MAX_CHUNKS && lc_decode_fused_fits(G, p.max_M)) {
         // kernel 1 (and the level walk before it) leaves the chunk score keys in the workspace;
         // kernel 2 selects from them in every workgroup and attends
@@ -446,6 +452,85 @@ int lc_decode_step(const lc_index* idx, const void* q, const void* K, const void
     rc = lc_launch_retrieve(idx, w, q, G, budget, ids, cnt, nullptr, icap, p.max_M, p.walk ? p.max_upper : -1, 0, st);
     if (rc) return rc;
     return lc_launch_decode(idx, w, q, K, V, kv_strides, ids, cnt, icap, G, splits, out, lse, st);
+}
+}  // namespace
+
+int lc_decode_step(const lc_index* idx, const void* q, const void* K, const void* V, const int64_t kv_strides[3],
+                   int H_q, int budget, float* out, float* lse, int32_t* chunk_ids, int32_t* counts, int cap,
+                   void* ws, size_t ws_bytes, void* stream) {
+    int rc = decode_step_checks(idx, q, K, V, kv_strides, H_q, budget, out, chunk_ids, counts, cap);
+    if (rc) return rc;
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u)) return LC_ERR_INVALID_ARG;
+    const int splits = lc_auto_splits(&idx->cfg, idx->B, idx->H_kv);
+    if (ws_bytes < lc_layout_ws(&idx->cfg, idx->B, H_q, idx->H_kv, idx->d, splits, nullptr, nullptr))
+        return LC_ERR_WORKSPACE_TOO_SMALL;
+    RetrievePlan p;
+    rc = plan_retrieve(idx, budget, cap, chunk_ids != nullptr, &p);
+    if (rc) return rc;
+    LcWs w;
+    lc_layout_ws(&idx->cfg, idx->B, H_q, idx->H_kv, idx->d, splits, ws, &w);
+    return decode_step_run(idx, w, p, splits, q, K, V, kv_strides, H_q, budget, out, lse, chunk_ids, counts, cap,
+                           static_cast<hipStream_t>(stream));
+}
+
+// ---------------------------------------------------------------------------------
+// decode step without a caller workspace
+// ---------------------------------------------------------------------------------
+// The workspace of a decode step (score keys, kept flags, select staging, chunk list, split-K
+// partials) in a file-scope device array instead of a caller buffer, for callers that cannot
+// allocate.  In host code the array's name is only a stand-in: its device address is asked for
+// once per device and kept; kernels and layout code only ever see that address.
+static __device__ __align__(256) unsigned char lc_static_scratch[LC_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+// Device address of the static scratch array on the current device (asked for on first use).
+int static_scratch(void** out) {
+    int dev = -1;
+    LC_HIP_CHECK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return LC_ERR_CAPACITY;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* ptr = nullptr;
+        LC_HIP_CHECK(hipGetSymbolAddress(&ptr, HIP_SYMBOL(lc_static_scratch)));
+        if (ptr == nullptr || (reinterpret_cast<uintptr_t>(ptr) & 255u)) return LC_ERR_HIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return LC_OK;
+}
+}  // namespace
+
+size_t lc_static_workspace_bytes(void) { return (size_t)LC_STATIC_SCRATCH_BYTES; }
+
+size_t lc_decode_workspace_bytes(const lc_config* cfg, int B, int H_q, int H_kv, int d) {
+    if (!config_ok(cfg) || B < 1 || H_kv < 1 || H_q < H_kv || H_q % H_kv != 0 || d != LC_HEAD_DIM) return 0;
+    if (H_q / H_kv > LC_MAX_GROUP) return 0;
+    return lc_layout_ws(cfg, B, H_q, H_kv, d, lc_auto_splits(cfg, B, H_kv), nullptr, nullptr, false);
+}
+
+int lc_decode_step_static(const lc_index* idx, const void* q, const void* K, const void* V,
+                          const int64_t kv_strides[3], int H_q, int budget, float* out, float* lse,
+                          int32_t* chunk_ids, int32_t* counts, int cap, void* stream) {
+    int rc = decode_step_checks(idx, q, K, V, kv_strides, H_q, budget, out, chunk_ids, counts, cap);
+    if (rc) return rc;
+    const int splits = lc_auto_splits(&idx->cfg, idx->B, idx->H_kv);
+    if (lc_layout_ws(&idx->cfg, idx->B, H_q, idx->H_kv, idx->d, splits, nullptr, nullptr, false) >
+        (size_t)LC_STATIC_SCRATCH_BYTES)
+        return LC_ERR_CAPACITY;
+    RetrievePlan p;
+    rc = plan_retrieve(idx, budget, cap, chunk_ids != nullptr, &p);
+    if (rc) return rc;
+    void* base = nullptr;
+    rc = static_scratch(&base);
+    if (rc) return rc;
+    LcWs w;
+    lc_layout_ws(&idx->cfg, idx->B, H_q, idx->H_kv, idx->d, splits, base, &w, false);
+    return decode_step_run(idx, w, p, splits, q, K, V, kv_strides, H_q, budget, out, lse, chunk_ids, counts, cap,
+                           static_cast<hipStream_t>(stream));
 }
 
 int lc_sparse_decode(const lc_index* idx, const void* q, const void* K, const void* V, const int64_t kv_strides[3],

@@ -61,7 +61,9 @@ struct LcWs {
     int* anc;            // [B][H][cap0] chunk -> ancestor at the level being built
     size_t total;
 };
-size_t lc_layout_ws(const lc_config* cfg, int B, int H_q, int H, int d, int splits, void* base, LcWs* ws);
+// with_build = false leaves out the build scratch (dirs, centroids, ancestors): what a decode step needs.
+size_t lc_layout_ws(const lc_config* cfg, int B, int H_q, int H, int d, int splits, void* base, LcWs* ws,
+                    bool with_build = true);
 int lc_auto_splits(const lc_config* cfg, int B, int H);
 
 void lc_set_hip_error(hipError_t e);
