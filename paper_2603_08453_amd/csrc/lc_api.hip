@@ -351,7 +351,7 @@ static int common_decode_checks(const lc_index* idx, const void* q, int H_q, int
     return LC_OK;
 }
 
-#define LC_STEP_FUSED_MAX_CHUNKS 3072
+#define LC_STEP_FUSED_MAX_CHUNKS 4096
 
 namespace {
 // What a retrieval over the current index needs: sizes, the capacity check, walk or flat scan.

@@ -24,8 +24,9 @@
 #define LC_DEC_MAX_SPLITS 256
 #define LC_DEC_TILE 1024          // tokens of a split whose cache rows are resolved into LDS at a time
 #define LC_DEC_WIN 2048           // slots of the entry window of a tile: a power of two above LC_DEC_TILE + 2
-#define LC_DEC_SPEC 12            // fused step: chunks per thread staged before the chunk count has arrived
 #define LC_DEC_E 2                // selected ids per thread and pass of the row resolution
+#define LC_DEC_CAND 64            // fused step: chunks of the cutoff bin that are ranked directly
+#define LC_DEC_BINS_MAX 1024      // fused step: most bins of the selection histogram
 #define LC_LOG2E 1.4426950408889634f
 #define LC_LN2 0.6931471805599453f
 
@@ -57,7 +58,7 @@ struct LcDecodeArgs {
     int32_t* ids_out;     // [B][H][cap] selected ids, ascending, or null
     int32_t* counts_out;  // [B][H] or null
     int budget, sink, count_limit;   // token budget, pinned prefix, chunk-count limit (0 = none)
-    int chunk_cap;        // LDS entries of the staged chunk arrays
+    int ew;               // fused step: rows of 64 chunks per wavefront that hold the longest sequence (host side: picks EC)
     int max_tokens;       // rows of one (sequence, head) slab of K and V
 };
 
@@ -81,19 +82,78 @@ __device__ __forceinline__ float lc_row_bcast_n(float v, int src) {      // src 
 // exp2 of (x - ref) where x may be -inf (gives 0); ref is finite.
 __device__ __forceinline__ float lc_exp2_rel(float x, float ref) { return exp2f(x - ref); }
 
+// Workgroup barrier that orders LDS accesses only: global loads issued before it stay in flight
+// (a plain __syncthreads() also waits for every outstanding global load of the wavefront).
+__device__ __forceinline__ void lc_barrier_lds() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+__device__ __forceinline__ int lc_readlane(int v, int l) { return __builtin_amdgcn_readlane(v, l); }
+__device__ __forceinline__ int lc_wave_sum_i(int v) {                       // all 64 lanes active
+    return lc_readlane(lc_wave_scan_incl(v), 63);
+}
+
+// LDS of the fused step's selection (the general select routine, used when the cutoff bin
+// overflows its short list, has its own block)
+struct LcFusedSh {
+    int hw[LC_DEC_BINS_MAX + 4];     // chunk lengths per bin; the slot after the last bin takes what is no candidate
+    int hc[LC_DEC_BINS_MAX + 4];     // chunk counts per bin (with a count limit only)
+    int4 cand[LC_DEC_CAND];          // chunks of the cutoff bin: key, length, id
+    int n_cand;
+    uint32_t kmin[LC_DEC_THREADS / 64], kmax[LC_DEC_THREADS / 64];
+    int wtok[LC_DEC_THREADS / 64], wcnt[LC_DEC_THREADS / 64];
+};
+// min / max over a wavefront, uniform result: DPP within the four 16-lane rows, then the rows' values by lane reads
+__device__ __forceinline__ uint32_t lc_wave_min_uniform(uint32_t v) {
+    v = min(v, lc_dpp_u<0xB1>(v)); v = min(v, lc_dpp_u<0x4E>(v));
+    v = min(v, lc_dpp_u<0x141>(v)); v = min(v, lc_dpp_u<0x140>(v));
+    const uint32_t r0 = (uint32_t)lc_readlane((int)v, 0), r1 = (uint32_t)lc_readlane((int)v, 16);
+    const uint32_t r2 = (uint32_t)lc_readlane((int)v, 32), r3 = (uint32_t)lc_readlane((int)v, 48);
+    return min(min(r0, r1), min(r2, r3));
+}
+__device__ __forceinline__ uint32_t lc_wave_max_uniform(uint32_t v) {
+    v = max(v, lc_dpp_u<0xB1>(v)); v = max(v, lc_dpp_u<0x4E>(v));
+    v = max(v, lc_dpp_u<0x141>(v)); v = max(v, lc_dpp_u<0x140>(v));
+    const uint32_t r0 = (uint32_t)lc_readlane((int)v, 0), r1 = (uint32_t)lc_readlane((int)v, 16);
+    const uint32_t r2 = (uint32_t)lc_readlane((int)v, 32), r3 = (uint32_t)lc_readlane((int)v, 48);
+    return max(max(r0, r1), max(r2, r3));
+}
+// number of set bits of `mask` below this lane
+__device__ __forceinline__ int lc_mbcnt(unsigned long long mask) {
+    return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
+
 // FUSED = false: the chunk list comes from a.ids / a.counts.  FUSED = true: every workgroup first
 // repeats the budget selection of its (sequence, head) from the chunk score keys -- the same
 // deterministic routine on the same keys, so all splits agree -- and never reads a chunk list.
-template <int G, bool FUSED>
+//
+// The fused selection keeps the chunks in registers: wavefront w owns the chunks
+// [64 EC w, 64 EC (w + 1)), lane l of it the chunks (EC w + e) * 64 + l for e < EC, so every load is
+// coalesced and the id order is (wavefront, e, lane): prefix sums in id order are EC independent
+// wavefront scans on the vector ALU plus one exchange of four totals.  The loops over e carry no
+// branches, so that the EC copies of each step overlap in the pipeline (one wavefront per SIMD has
+// nothing else to hide a dependent instruction's latency behind).
+//   1. range of the candidate keys (one exchange), 1024-bin histogram of chunk lengths over it
+//      (LDS atomics), every wavefront scans all bins from the top: cutoff bin, budget left for it;
+//   2. chunks in bins above the cutoff bin are selected; the few in the cutoff bin go to a short
+//      list and their owners rank them against each other (key descending, id ascending) -- or,
+//      if the list overflows (a crowded or tied bin), the general select routine runs on them;
+//   3. token offsets of the selected chunks by the scans above; the wavefronts write the cache
+//      row of every token of the split's tile into LDS, 64 lanes per overlapping chunk.
+template <int G, bool FUSED, int EC>
 __global__ void __launch_bounds__(LC_DEC_THREADS)
 lc_decode_kernel(const LcDecodeArgs a) {
-    extern __shared__ int lds_dyn[];             // FUSED: staged key, length, first row of every chunk
+    extern __shared__ int lds_dyn[];             // FUSED: key and length of every chunk, for the overflow path only
     using SelStore = typename std::conditional<FUSED, LcLeafSelSh, int>::type;
-    __shared__ SelStore sel_store;
+    using FusedStore = typename std::conditional<FUSED, LcFusedSh, int>::type;
+    constexpr int WIN = FUSED ? 1 : LC_DEC_WIN;
+    __shared__ __attribute__((aligned(16))) SelStore sel_store;
+    __shared__ __attribute__((aligned(16))) FusedStore fused_store;
     __shared__ int scan_sh[8];
     __shared__ int rows[LC_DEC_TILE];
-    __shared__ int win_off[LC_DEC_WIN];           // first token position of the entries that overlap the tile
-    __shared__ int win_st[LC_DEC_WIN];            // and their first cache row
+    __shared__ int win_off[WIN];                  // first token position of the entries that overlap the tile
+    __shared__ int win_st[WIN];                   // and their first cache row
     __shared__ int win_hd[2];                     // indices of the entries holding the tile's first / last token
     __shared__ int last_sh;
     __shared__ float comb_ml[LC_DEC_THREADS / 64][G][2];
@@ -126,19 +186,17 @@ lc_decode_kernel(const LcDecodeArgs a) {
 
     // ---- the attended tokens are the selected chunks in ascending id order, then the open tail.
     // Entry i of that list is (first cache row, length).  Both variants end up with: n_runs entries,
-    // n_tok tokens, and a way for each thread to walk the entries it owns with their token offsets.
+    // n_tok tokens, and a way to find the cache row of every token of a tile.
     int n_runs, n_tok, T;
     // FUSED = false: thread t of a pass owns entries [E t, E t + E); the first pass stays in registers
     const int32_t* ids = nullptr;
     int n_ids = 0, M = 0;
     int idv[E], st0[E], ln0[E];
     int ex0 = 0, tot0 = 0;
-    // FUSED = true: thread t owns the chunks [c0, c1), of which those with skey > thr are selected
-    uint32_t* skey = nullptr;
-    int* slen = nullptr;
-    int* sstart = nullptr;
-    uint32_t thr = 0u;
-    int c0 = 0, c1 = 0, tok_off = 0, cnt_off = 0, my_tok = 0, n_sel = 0, n_sel_tok = 0, tail_st = 0, tail_ln = 0;
+    // FUSED = true: this lane's chunks (see above): first row, length (0 unless selected), token
+    // offset among the wavefront's selected tokens
+    int cst[EC], stok[EC], coff[EC];
+    int base_tok = 0, n_sel = 0, n_sel_tok = 0, tail_st = 0, tail_ln = 0;
 
     auto entries = [&](int base, bool preloaded, int (&st)[E], int (&ln)[E]) -> int {
         int sum = 0;
@@ -179,82 +237,274 @@ lc_decode_kernel(const LcDecodeArgs a) {
         }
     } else {
         LcLeafSelSh& sel_sh = sel_store;
-        skey = reinterpret_cast<uint32_t*>(lds_dyn);
-        slen = lds_dyn + a.chunk_cap;
-        sstart = lds_dyn + 2 * a.chunk_cap;
-        const uint32_t* keys = a.keys + (size_t)bh * ix.cap[0];
-        lc_leaf_select_prepare<LC_DEC_THREADS>(sel_sh);
-        // the first LC_DEC_SPEC chunks of every thread are fetched before the chunk count is known
-        // (the arrays are as long as the index's capacity), the rest in a loop afterwards
+        LcFusedSh& fs = fused_store;
+        // bins of the histogram: about one per four chunks, so that the cutoff bin holds a handful
+        constexpr int BITS = EC <= 4 ? 8 : (EC <= 10 ? 9 : 10);
+        constexpr int BINS = 1 << BITS;
         const int cap0 = ix.cap[0];
-        uint32_t kq[LC_DEC_SPEC];
-        int b0[LC_DEC_SPEC], b1[LC_DEC_SPEC];
+        // ---- every load of the selection goes out at once, before the chunk count is known (reads
+        // past the arrays' ends return 0; what lies past the count is masked below)
+        const __amdgpu_buffer_rsrc_t keys_r = lc_buffer(a.keys + (size_t)bh * cap0, cap0 * 4);
+        const __amdgpu_buffer_rsrc_t bnd_r = lc_buffer(bnd, (cap0 + 1) * 4);
+        const int j0 = wave * (EC * 64) + lane;                      // this lane's chunk e is j0 + 64 e
+        uint32_t ck[EC];
+        int cend[EC];
 #pragma unroll
-        for (int u = 0; u < LC_DEC_SPEC; ++u) {
-            kq[u] = 0u;
-            b0[u] = b1[u] = 0;
-            if (u * LC_DEC_THREADS < a.chunk_cap) {            // none of the sequences has more chunks than that
-                const int j = min(tid + u * LC_DEC_THREADS, cap0 - 1);
-                kq[u] = keys[j];
-                b0[u] = bnd[j];
-                b1[u] = bnd[j + 1];
-            }
+        for (int e = 0; e < EC; ++e) {
+            ck[e] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(keys_r, j0 * 4, e * 256, 0);
+            cst[e] = __builtin_amdgcn_raw_buffer_load_b32(bnd_r, j0 * 4, e * 256, 0);
+            cend[e] = __builtin_amdgcn_raw_buffer_load_b32(bnd_r, j0 * 4, e * 256 + 4, 0);
         }
         T = ix.state[bh * 4 + 0];
         const int M_all = ix.state[bh * 4 + 1];
-        M = min(M_all, a.chunk_cap);
-        tail_st = bnd[M_all];
-        __syncthreads();
-        LC_LSTAMP0(15);
-        // stage every chunk: key (pinned chunks get the always-selected mark), length, first row
-        uint32_t kmin = 0xffffffffu, kmax = 0u;
-        auto stage = [&](int j, uint32_t k, int s0, int s1) {
-            if (k == 0xffffffffu) k = 0xfffffffeu;                 // the mark is reserved
-            const bool pinned = s0 < a.sink;
-            skey[j] = pinned ? 0xffffffffu : k;
-            slen[j] = max(0, s1 - s0);
-            sstart[j] = s0;
-            if (!pinned && k != 0u) { kmin = min(kmin, k); kmax = max(kmax, k); }
-        };
-#pragma unroll
-        for (int u = 0; u < LC_DEC_SPEC; ++u) {
-            const int j = tid + u * LC_DEC_THREADS;
-            if (j < M) stage(j, kq[u], b0[u], b1[u]);
+        // meanwhile: empty histograms and list (their first use is behind the barrier of the key range)
+        const bool count_c = a.count_limit > 0;                     // chunk counts matter only with a count limit
+        for (int i = tid; i < BINS + 4; i += LC_DEC_THREADS) {
+            fs.hw[i] = 0;
+            if (count_c) fs.hc[i] = 0;
         }
-#pragma unroll 4
-        for (int j = tid + LC_DEC_SPEC * LC_DEC_THREADS; j < M; j += LC_DEC_THREADS) stage(j, keys[j], bnd[j], bnd[j + 1]);
+        if (tid < LC_DEC_CAND) fs.cand[tid] = make_int4(0, 0, 0, 0);
+        if (tid == 0) fs.n_cand = 0;
+        M = min(M_all, EC * LC_DEC_THREADS);
+        tail_st = bnd[M_all];
+        const int W = a.budget > 0 ? a.budget : 0;
+        const int C = count_c ? a.count_limit : 0x7fffffff;
+        LC_LSTAMP0(15);
+        // ---- lengths; what is past the count or pinned is no candidate (key 0), pinned chunks are selected
+        int cln[EC];
+        uint32_t kmin1 = 0xffffffffu, kmax = 0u;                    // (lowest candidate key) - 1, highest
+#pragma unroll
+        for (int e = 0; e < EC; ++e) {
+            const bool valid = j0 + 64 * e < M;
+            cln[e] = valid ? max(0, cend[e] - cst[e]) : 0;
+            const bool pinned = valid && cst[e] < a.sink;
+            const int len_p = cln[e];
+            stok[e] = pinned ? len_p : 0;
+            ck[e] = (valid && !pinned) ? ck[e] : 0u;
+            kmin1 = min(kmin1, ck[e] - 1u);                         // key 0 wraps to the largest value: ignored
+            kmax = max(kmax, ck[e]);
+        }
+        {
+            const uint32_t wmin = lc_wave_min_uniform(kmin1), wmax = lc_wave_max_uniform(kmax);
+            if (lane == 0) { fs.kmin[wave] = wmin; fs.kmax[wave] = wmax; }
+        }
+        lc_barrier_lds();
+        kmin1 = min(min(fs.kmin[0], fs.kmin[1]), min(fs.kmin[2], fs.kmin[3]));
+        kmax = max(max(fs.kmax[0], fs.kmax[1]), max(fs.kmax[2], fs.kmax[3]));
         LC_LSTAMP0(18);
-        lc_leaf_select_range(kmin, kmax, sel_sh);
-        LC_LSTAMP0(19);
-        __syncthreads();
-        LC_LSTAMP0(11);
-        const long long C = a.count_limit > 0 ? (long long)a.count_limit : 0x7fffffffLL;
-        thr = lc_leaf_select<LC_DEC_THREADS>(M, skey, slen, a.budget > 0 ? (long long)a.budget : 0LL, C, sel_sh);
-        __syncthreads();
+        if (kmax != 0u) {                                           // (uniform) there are candidates
+            const uint32_t kmin = kmin1 + 1u;
+            const uint32_t span = kmax - kmin;
+            const int bits = span ? 32 - __clz(span) : 0;
+            const int shift = bits > BITS ? bits - BITS : 0;        // (span >> shift) < BINS
+            // bin of every chunk: -1 = no candidate (those add their length to a slot nobody reads)
+            int cbin[EC];
+#pragma unroll
+            for (int e = 0; e < EC; ++e) {
+                const int bin = (int)((ck[e] - kmin) >> shift);
+                cbin[e] = ck[e] != 0u ? bin : -1;
+                const int slot = (int)min((uint32_t)cbin[e], (uint32_t)BINS);
+                atomicAdd(&fs.hw[slot], cln[e]);
+                if (count_c) atomicAdd(&fs.hc[slot], 1);
+            }
+            lc_barrier_lds();
+            LC_LSTAMP0(19);
+            // ---- every wavefront scans all bins from the top: lane l holds bins BINS - 1 - PER l - i, i < PER
+            constexpr int PER = BINS / 64;
+            int fb = -1, remW = W, remC = C;                        // cutoff bin (-1: every candidate fits), what is left for it
+            {
+                int pw[PER];                                        // inclusive prefix sums within the lane, bins descending
+                const int4* hw4 = reinterpret_cast<const int4*>(fs.hw + BINS - PER * (lane + 1));
+#pragma unroll
+                for (int v = 0; v < PER / 4; ++v) {
+                    const int4 x = hw4[PER / 4 - 1 - v];
+                    pw[4 * v + 0] = x.w; pw[4 * v + 1] = x.z; pw[4 * v + 2] = x.y; pw[4 * v + 3] = x.x;
+                }
+#pragma unroll
+                for (int i = 1; i < PER; ++i) pw[i] += pw[i - 1];
+                const int cw = lc_wave_scan_incl(pw[PER - 1]) - pw[PER - 1];      // length of all higher lanes' bins
+                // bins of this lane that still fit (prefix sums grow, so they are the first `fit` ones) and their total
+                int fit = 0, fitw = 0, cc = 0, fitc = 0;
+                if (!count_c) {
+#pragma unroll
+                    for (int i = 0; i < PER; ++i) {
+                        const bool ok = cw + pw[i] <= W;
+                        fit += ok ? 1 : 0;
+                        fitw = ok ? pw[i] : fitw;
+                    }
+                } else {
+                    int pc[PER];
+                    const int4* hc4 = reinterpret_cast<const int4*>(fs.hc + BINS - PER * (lane + 1));
+#pragma unroll
+                    for (int v = 0; v < PER / 4; ++v) {
+                        const int4 y = hc4[PER / 4 - 1 - v];
+                        pc[4 * v + 0] = y.w; pc[4 * v + 1] = y.z; pc[4 * v + 2] = y.y; pc[4 * v + 3] = y.x;
+                    }
+#pragma unroll
+                    for (int i = 1; i < PER; ++i) pc[i] += pc[i - 1];
+                    cc = lc_wave_scan_incl(pc[PER - 1]) - pc[PER - 1];
+#pragma unroll
+                    for (int i = 0; i < PER; ++i) {
+                        const bool ok = cw + pw[i] <= W && cc + pc[i] <= C;
+                        fit += ok ? 1 : 0;
+                        fitw = ok ? pw[i] : fitw;
+                        fitc = ok ? pc[i] : fitc;
+                    }
+                }
+                const unsigned long long bal = __ballot(fit < PER); // the prefix ends in the first bin that no longer fits
+                if (bal != 0ull) {
+                    const int fl = __ffsll((long long)bal) - 1;     // lowest lane = highest bins
+                    fb = BINS - 1 - (PER * fl + lc_readlane(fit, fl));
+                    remW = W - (lc_readlane(cw, fl) + lc_readlane(fitw, fl));
+                    if (count_c) remC = C - (lc_readlane(cc, fl) + lc_readlane(fitc, fl));
+                }
+            }
+            // ---- chunks above the cutoff bin are in; those in it go to the short list
+            unsigned long long cutm[EC];
+            unsigned long long anycut = 0ull;
+#pragma unroll
+            for (int e = 0; e < EC; ++e) {
+                const int len_e = cln[e], old_e = stok[e];          // (values first: a select of two array slots keeps both arrays in memory)
+                stok[e] = cbin[e] > fb ? len_e : old_e;
+                cutm[e] = __ballot(fb >= 0 && cbin[e] == fb);
+                anycut |= cutm[e];
+            }
+            int cpos[EC];
+            if (anycut != 0ull) {                                   // (uniform per wavefront)
+                int n_mine = 0;
+#pragma unroll
+                for (int e = 0; e < EC; ++e) {
+                    cpos[e] = n_mine + lc_mbcnt(cutm[e]);
+                    n_mine += __popcll(cutm[e]);
+                }
+                int base = 0;
+                if (lane == 0) base = atomicAdd(&fs.n_cand, n_mine);
+                base = lc_readlane(base, 0);
+#pragma unroll
+                for (int e = 0; e < EC; ++e) {
+                    cpos[e] += base;
+                    if (((cutm[e] >> lane) & 1ull) && cpos[e] < LC_DEC_CAND)
+                        fs.cand[cpos[e]] = make_int4((int)ck[e], cln[e], j0 + 64 * e, 0);
+                }
+            }
+            lc_barrier_lds();
+            LC_LSTAMP0(11);
+            const int nc = fs.n_cand;
+            if (nc <= LC_DEC_CAND) {
+                // ---- each owner ranks its chunk against the list: length and number of the chunks before it
+                // (the list is padded with key 0 entries, which come before nothing)
+                if (anycut != 0ull) {
+#pragma unroll
+                    for (int e = 0; e < EC; ++e) {
+                        if (cutm[e] != 0ull) {                      // (uniform per wavefront)
+                            const uint32_t km = ck[e];
+                            const int im = j0 + 64 * e;
+                            int wb = 0, cb = 0;
+                            for (int t = 0; t < nc; t += 4) {
+#pragma unroll
+                                for (int u = 0; u < 4; ++u) {
+                                    const int4 o = fs.cand[t + u];
+                                    const bool before = (uint32_t)o.x > km || ((uint32_t)o.x == km && o.z < im);
+                                    wb += before ? o.y : 0;
+                                    cb += before ? 1 : 0;
+                                }
+                            }
+                            const int len_e = cln[e], old_e = stok[e];
+                            const bool in = ((cutm[e] >> lane) & 1ull) && wb + len_e <= remW && cb + 1 <= remC;
+                            stok[e] = in ? len_e : old_e;
+                        }
+                    }
+                }
+            } else {
+                // ---- a crowded or tied cutoff bin: the general select routine on its chunks alone
+                uint32_t* skey = reinterpret_cast<uint32_t*>(lds_dyn);
+                int* slen = lds_dyn + EC * LC_DEC_THREADS;
+                lc_leaf_select_prepare<LC_DEC_THREADS>(sel_sh);
+                lc_barrier_lds();
+                uint32_t bmin = 0xffffffffu, bmax = 0u;
+#pragma unroll
+                for (int e = 0; e < EC; ++e) {
+                    const int j = j0 + 64 * e;
+                    const bool cnd = (cutm[e] >> lane) & 1ull;
+                    const uint32_t k = cnd ? (ck[e] == 0xffffffffu ? 0xfffffffeu : ck[e]) : 0u;     // the mark is reserved
+                    skey[j] = k;
+                    slen[j] = cln[e];
+                    if (cnd) { bmin = min(bmin, k); bmax = max(bmax, k); }
+                }
+                lc_leaf_select_range(bmin, bmax, sel_sh);
+                lc_barrier_lds();
+                const uint32_t thr = lc_leaf_select<LC_DEC_THREADS>(M, skey, slen, (long long)remW,
+                                                                    count_c ? (long long)remC : 0x7fffffffLL, sel_sh);
+                __syncthreads();
+#pragma unroll
+                for (int e = 0; e < EC; ++e) {
+                    const int len_e = cln[e], old_e = stok[e];
+                    const bool in = ((cutm[e] >> lane) & 1ull) && skey[j0 + 64 * e] > thr;
+                    stok[e] = in ? len_e : old_e;
+                }
+            }
+        }
         LC_LSTAMP0(12);
-        // tokens and chunks selected before this thread's run of chunks
-        int Ec = (M + LC_DEC_THREADS - 1) / LC_DEC_THREADS;
-        Ec |= 1;                                                    // odd stride: no LDS bank conflicts
-        c0 = min(M, tid * Ec);
-        c1 = min(M, c0 + Ec);
-        int my_cnt = 0;
-#pragma unroll 4
-        for (int c = c0; c < c1; ++c)
-            if (skey[c] > thr) { my_tok += slen[c]; my_cnt += 1; }
-        lc_block_scan2<LC_DEC_THREADS>(my_tok, my_cnt, sel_sh.scan, &tok_off, &cnt_off, &n_sel_tok, &n_sel);
+        // ---- token offsets in id order: EC independent wavefront scans, their totals chained, then
+        // the four wavefront totals
+        {
+            int inc[EC], tot[EC];
+#pragma unroll
+            for (int e = 0; e < EC; ++e) inc[e] = lc_wave_scan_incl(stok[e]);
+#pragma unroll
+            for (int e = 0; e < EC; ++e) tot[e] = lc_readlane(inc[e], 63);
+            int run = 0;
+#pragma unroll
+            for (int e = 0; e < EC; ++e) {
+                coff[e] = run + inc[e] - stok[e];
+                run += tot[e];
+            }
+            if (lane == 0) fs.wtok[wave] = run;
+        }
+        const bool want_ids = a.ids_out != nullptr && s == 0;
+        int crank[EC];
+        if (want_ids) {                                             // (uniform) the same for the chunk counts
+            int inc[EC], tot[EC];
+#pragma unroll
+            for (int e = 0; e < EC; ++e) inc[e] = lc_wave_scan_incl(stok[e] > 0 ? 1 : 0);
+#pragma unroll
+            for (int e = 0; e < EC; ++e) tot[e] = lc_readlane(inc[e], 63);
+            int run = 0;
+#pragma unroll
+            for (int e = 0; e < EC; ++e) {
+                crank[e] = run + inc[e] - (stok[e] > 0 ? 1 : 0);
+                run += tot[e];
+            }
+            if (lane == 0) fs.wcnt[wave] = run;
+        }
+        lc_barrier_lds();
+#pragma unroll
+        for (int w = 0; w < LC_DEC_THREADS / 64; ++w) {
+            const int wt = fs.wtok[w];
+            if (w < wave) base_tok += wt;
+            n_sel_tok += wt;
+        }
         tail_ln = max(0, T - tail_st);
         n_tok = n_sel_tok + tail_ln;
-        n_runs = n_sel + 1;
-        if (a.ids_out != nullptr && s == 0) {                       // the chunk list, for callers that want it
+        if (want_ids) {                                             // the chunk list, for callers that want it
+            int base_cnt = 0;
+#pragma unroll
+            for (int w = 0; w < LC_DEC_THREADS / 64; ++w) {
+                const int wc = fs.wcnt[w];
+                if (w < wave) base_cnt += wc;
+                n_sel += wc;
+            }
             int32_t* io = a.ids_out + (size_t)bh * a.cap;
-            int r = cnt_off;
-            for (int c = c0; c < c1; ++c)
-                if (skey[c] > thr) { if (r < a.cap) io[r] = c; ++r; }
+#pragma unroll
+            for (int e = 0; e < EC; ++e) {
+                const int r = base_cnt + crank[e];
+                if (stok[e] > 0 && r < a.cap) io[r] = j0 + 64 * e;
+            }
             if (tid == 0 && a.counts_out != nullptr) a.counts_out[bh] = min(n_sel, a.cap);
         }
+        n_runs = n_sel + 1;
     }
     LC_LSTAMP0(1);
-
     int S_eff = (n_tok + LC_DEC_MIN_TOKENS_PER_SPLIT - 1) / LC_DEC_MIN_TOKENS_PER_SPLIT;
     S_eff = max(1, min(S, S_eff));
 
@@ -352,26 +602,47 @@ lc_decode_kernel(const LcDecodeArgs a) {
 
         LC_LSTAMP0(8);
         // The split's tokens are handled in tiles; for each tile the workgroup first writes the cache
-        // row of every token into LDS (the few entries that overlap the tile go into a window, then
-        // one small binary search per token, in parallel), then every group streams a contiguous
-        // slice of the tile.
+        // row of every token into LDS, then every group streams a contiguous slice of the tile.
         for (int tile0 = lo; tile0 < hi; tile0 += LC_DEC_TILE) {
             const int tl = min(LC_DEC_TILE, hi - tile0);
-            // Every entry that overlaps the tile goes into the window at slot (entry index mod window
-            // size) -- overlapping entries are consecutive and fewer than the window is long -- and the
-            // entries that hold the tile's first and last token leave their indices.
-            __syncthreads();
-            LC_LSTAMP0(16);
-            {
-                auto entry = [&](int i, int off, int st, int ln) {
-                    if (ln > 0 && off < tile0 + tl && tile0 < off + ln) {
-                        win_off[i & (LC_DEC_WIN - 1)] = off;
-                        win_st[i & (LC_DEC_WIN - 1)] = st;
-                        if (off <= tile0) win_hd[0] = i;
-                        if (tile0 + tl <= off + ln) win_hd[1] = i;
-                    }
+            const int row_max = max(T - 1, 0);
+            if constexpr (FUSED) {
+                // 64 lanes per selected chunk that overlaps the tile (its owner's values are read by lane)
+                if (tile0 != lo) lc_barrier_lds();                  // the previous tile's rows have been used
+                auto fill = [&](int o, int st, int ln) {
+                    const int k0 = max(o, tile0), k1 = min(o + ln, tile0 + tl);
+                    for (int k = k0 + lane; k < k1; k += 64) rows[k - tile0] = max(0, min(st + (k - o), row_max));
                 };
-                if constexpr (!FUSED) {
+#pragma unroll
+                for (int e = 0; e < EC; ++e) {
+                    const int off = base_tok + coff[e];
+                    unsigned long long mask = __ballot(stok[e] > 0 && off < tile0 + tl && tile0 < off + stok[e]);
+                    while (mask != 0ull) {
+                        const int l = __ffsll((long long)mask) - 1;
+                        mask &= mask - 1ull;
+                        fill(lc_readlane(off, l), lc_readlane(cst[e], l), lc_readlane(stok[e], l));
+                    }
+                }
+                if (wave == 0 && tail_ln > 0 && n_sel_tok < tile0 + tl && tile0 < n_sel_tok + tail_ln)
+                    fill(n_sel_tok, tail_st, tail_ln);
+                LC_LSTAMP0(17);
+                lc_barrier_lds();
+            } else {
+                // The few entries that overlap the tile go into a window at slot (entry index mod window
+                // size) -- overlapping entries are consecutive and fewer than the window is long -- and the
+                // entries that hold the tile's first and last token leave their indices; then one small
+                // binary search per token, in parallel.
+                __syncthreads();
+                LC_LSTAMP0(16);
+                {
+                    auto entry = [&](int i, int off, int st, int ln) {
+                        if (ln > 0 && off < tile0 + tl && tile0 < off + ln) {
+                            win_off[i & (LC_DEC_WIN - 1)] = off;
+                            win_st[i & (LC_DEC_WIN - 1)] = st;
+                            if (off <= tile0) win_hd[0] = i;
+                            if (tile0 + tl <= off + ln) win_hd[1] = i;
+                        }
+                    };
                     auto visit = [&](int base, int off, const int (&st)[E], const int (&ln)[E]) {
 #pragma unroll
                         for (int e = 0; e < E; ++e) {
@@ -387,39 +658,25 @@ lc_decode_kernel(const LcDecodeArgs a) {
                         visit(base, carry + ex, st, ln);
                         carry += tot;
                     }
-                } else {
-                    // only a thread whose run of chunks overlaps the tile has anything to add
-                    if (tok_off < tile0 + tl && tile0 < tok_off + my_tok) {
-                        int off = tok_off, r = cnt_off;
-                        for (int c = c0; c < c1; ++c) {
-                            if (skey[c] > thr) {
-                                entry(r, off, sstart[c], slen[c]);
-                                off += slen[c];
-                                ++r;
-                            }
+                }
+                LC_LSTAMP0(17);
+                __syncthreads();
+                LC_LSTAMP0(13);
+                {
+                    const int w_first = win_hd[0], w_last = win_hd[1];
+                    for (int i = tid; i < tl; i += LC_DEC_THREADS) {
+                        const int tok = tile0 + i;
+                        int lo_w = w_first, hi_w = w_last + 1;   // off[lo_w] <= tok < off[hi_w]
+                        while (hi_w - lo_w > 1) {
+                            const int mid = (lo_w + hi_w) >> 1;
+                            if (win_off[mid & (LC_DEC_WIN - 1)] <= tok) lo_w = mid; else hi_w = mid;
                         }
+                        const int sl = lo_w & (LC_DEC_WIN - 1);
+                        rows[i] = max(0, min(win_st[sl] + (tok - win_off[sl]), row_max));
                     }
-                    if (tid == LC_DEC_THREADS - 1) entry(n_sel, n_sel_tok, tail_st, tail_ln);
                 }
+                __syncthreads();
             }
-            LC_LSTAMP0(17);
-            __syncthreads();
-            LC_LSTAMP0(13);
-            {
-                const int w_first = win_hd[0], w_last = win_hd[1];
-                const int row_max = max(T - 1, 0);
-                for (int i = tid; i < tl; i += LC_DEC_THREADS) {
-                    const int tok = tile0 + i;
-                    int lo_w = w_first, hi_w = w_last + 1;   // off[lo_w] <= tok < off[hi_w]
-                    while (hi_w - lo_w > 1) {
-                        const int mid = (lo_w + hi_w) >> 1;
-                        if (win_off[mid & (LC_DEC_WIN - 1)] <= tok) lo_w = mid; else hi_w = mid;
-                    }
-                    const int sl = lo_w & (LC_DEC_WIN - 1);
-                    rows[i] = max(0, min(win_st[sl] + (tok - win_off[sl]), row_max));
-                }
-            }
-            __syncthreads();
             LC_LSTAMP0(9);
             const int per = (tl + LC_DEC_GROUPS - 1) / LC_DEC_GROUPS;
             const int n_it = (per + U - 1) / U;            // the same for every wavefront: the MFMA needs all lanes
@@ -582,7 +839,7 @@ lc_decode_kernel(const LcDecodeArgs a) {
 
 template <int G>
 static int launch_decode_g(const LcDecodeArgs& a, int splits, hipStream_t stream) {
-    hipLaunchKernelGGL((lc_decode_kernel<G, false>), dim3(splits, a.ix.H, a.ix.B), dim3(LC_DEC_THREADS), 0, stream, a);
+    hipLaunchKernelGGL((lc_decode_kernel<G, false, 1>), dim3(splits, a.ix.H, a.ix.B), dim3(LC_DEC_THREADS), 0, stream, a);
     LC_HIP_CHECK(hipGetLastError());
     return LC_OK;
 }
@@ -609,7 +866,7 @@ static void fill_common(LcDecodeArgs& a, const lc_index* idx, const LcWs& ws, co
     a.budget = 0;
     a.sink = 0;
     a.count_limit = 0;
-    a.chunk_cap = 0;
+    a.ew = 0;
     a.max_tokens = idx->cfg.max_tokens;
 }
 
@@ -635,50 +892,29 @@ int lc_launch_decode(const lc_index* idx, const LcWs& ws, const void* q, const v
 }
 
 // ---- fused step
-#define LC_DEC_LDS_TOTAL (150 * 1024)      // static + dynamic LDS a fused workgroup may take
+// Rows of 64 chunks per wavefront that the kernel instances hold in registers: a (sequence, head)
+// with up to 256 * EC chunks runs in the smallest instance that holds it.
+#define LC_DEC_EC_MAX 16
 
-template <int G>
-static size_t fused_static_lds() {
-    static size_t cached = 0;
-    if (cached == 0) {
-        hipFuncAttributes attr;
-        if (hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(&lc_decode_kernel<G, true>)) != hipSuccess) {
-            (void)hipGetLastError();
-            return (size_t)LC_DEC_LDS_TOTAL;       // unknown: report "does not fit"
-        }
-        cached = attr.sharedSizeBytes;
-    }
-    return cached;
-}
-static int fused_chunk_cap(int max_M) { return ((max_M > 0 ? max_M : 1) + 63) / 64 * 64; }
-
-template <int G>
-static bool fused_fits_g(int max_M) {
-    return fused_static_lds<G>() + (size_t)fused_chunk_cap(max_M) * 12 <= (size_t)LC_DEC_LDS_TOTAL;
-}
 bool lc_decode_fused_fits(int G, int max_M) {
-    switch (G) {
-        case 1: return fused_fits_g<1>(max_M);
-        case 2: return fused_fits_g<2>(max_M);
-        case 3: return fused_fits_g<3>(max_M);
-        case 4: return fused_fits_g<4>(max_M);
-        case 5: return fused_fits_g<5>(max_M);
-        case 6: return fused_fits_g<6>(max_M);
-        case 7: return fused_fits_g<7>(max_M);
-        case 8: return fused_fits_g<8>(max_M);
-    }
-    return false;
+    return G >= 1 && G <= LC_MAX_GROUP && max_M <= LC_DEC_THREADS * LC_DEC_EC_MAX;
 }
 
-template <int G>
-static int launch_fused_g(const LcDecodeArgs& a, int splits, hipStream_t stream) {
-    const size_t lds = (size_t)a.chunk_cap * 12;
-    if (lds > 0 && fused_static_lds<G>() + lds > 48 * 1024)          // beyond the default per-workgroup allowance
-        LC_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&lc_decode_kernel<G, true>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    hipLaunchKernelGGL((lc_decode_kernel<G, true>), dim3(splits, a.ix.H, a.ix.B), dim3(LC_DEC_THREADS), lds, stream, a);
+template <int G, int EC>
+static int launch_fused_ge(const LcDecodeArgs& a, int splits, hipStream_t stream) {
+    // key and length of every chunk, touched only when the cutoff bin overflows its short list
+    const size_t lds = (size_t)EC * LC_DEC_THREADS * 8;
+    hipLaunchKernelGGL((lc_decode_kernel<G, true, EC>), dim3(splits, a.ix.H, a.ix.B), dim3(LC_DEC_THREADS), lds, stream, a);
     LC_HIP_CHECK(hipGetLastError());
     return LC_OK;
+}
+template <int G>
+static int launch_fused_g(const LcDecodeArgs& a, int splits, hipStream_t stream) {
+    if (a.ew <= 2) return launch_fused_ge<G, 2>(a, splits, stream);
+    if (a.ew <= 4) return launch_fused_ge<G, 4>(a, splits, stream);
+    if (a.ew <= 6) return launch_fused_ge<G, 6>(a, splits, stream);
+    if (a.ew <= 10) return launch_fused_ge<G, 10>(a, splits, stream);
+    return launch_fused_ge<G, LC_DEC_EC_MAX>(a, splits, stream);
 }
 
 int lc_launch_decode_fused(const lc_index* idx, const LcWs& ws, const void* q, const void* K, const void* V,
@@ -693,7 +929,8 @@ int lc_launch_decode_fused(const lc_index* idx, const LcWs& ws, const void* q, c
     a.budget = budget;
     a.sink = idx->cfg.sink_tokens;
     a.count_limit = (idx->cfg.policy == LC_POLICY_BEAM && idx->cfg.beam[0] > 0) ? idx->cfg.beam[0] : 0;
-    a.chunk_cap = fused_chunk_cap(max_M);
+    a.ew = ((max_M > 0 ? max_M : 1) + LC_DEC_THREADS - 1) / LC_DEC_THREADS;
+    if (a.ew > LC_DEC_EC_MAX) return LC_ERR_CAPACITY;
     switch (G) {
         case 1: return launch_fused_g<1>(a, splits, stream);
         case 2: return launch_fused_g<2>(a, splits, stream);
