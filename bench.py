@@ -256,23 +256,22 @@ def main():
         retrieve_us = float(np.mean([e0.elapsed_time(e1) for e0, e1 in ev])) * 1e3
 
     # The second kernel of lc_decode_step (selection + attention) by itself: back-to-back launches from
-    # a graph with the scoring kernels switched off -- every replica's workspace still holds the score
-    # keys of the query it is paired with here (replica r with query r mod nq).
+    # a graph through the measurement aid lc_bench_select_attend -- every replica's workspace still
+    # holds the score keys of the query it is paired with here (replica r with query r mod nq).
     def step_fused_paired(i):
         rp = reps[i % R]
         lc.lc_decode_step(rp["idx"], Qs[(i % R) % nq], rp["K"], rp["V"], w.budget, out, rp["ws"])
+
+    def second_kernel_paired(i):
+        rp = reps[i % R]
+        lc.lc_bench_select_attend(rp["idx"], Qs[(i % R) % nq], rp["K"], rp["V"], w.budget, out, rp["ws"])
 
     fused_us = None
     if not args.separate and not args.no_graph:
         for i in range(R):
             step_fused_paired(i)
-        for rp in reps:
-            lc.lc_set_step_reuse_keys(rp["idx"], True)
-        try:
-            fused_us, _ = graph_us_per_launch(step_fused_paired, args.steps)
-        finally:
-            for rp in reps:
-                lc.lc_set_step_reuse_keys(rp["idx"], False)
+        torch.cuda.synchronize()
+        fused_us, _ = graph_us_per_launch(second_kernel_paired, args.steps)
     if fused_us is None:
         fused_us = attend_us
 
@@ -361,10 +360,10 @@ def main():
     del cp_dst
     rd_src = torch.empty(2 << 30, dtype=torch.uint8, device=dev).fill_(1)
     rd_sink = torch.zeros(2048, dtype=torch.int32, device=dev)
-    lc.lc_read_sweep(rd_src, rd_sink)
+    lc.lc_bench_read_sweep(rd_src, rd_sink)
     ce0.record()
     for _ in range(5):
-        lc.lc_read_sweep(rd_src, rd_sink)
+        lc.lc_bench_read_sweep(rd_src, rd_sink)
     ce1.record()
     torch.cuda.synchronize()
     read_gbps = 5 * (2 << 30) / (ce0.elapsed_time(ce1) * 1e-3) / 1e9
@@ -374,14 +373,15 @@ def main():
     step_bytes = attend_bytes + retrieve_bytes
 
     # ------------------------------------------------------------- CPU baseline (the oracle, as it stands)
+    # Two figures on this machine's host cores: one thread, and all the cores this process may run on
+    # (the affinity mask), with one (KV head) task per worker thread and the BLAS pool held at one
+    # thread per worker.  The oracle is float64 numpy; nothing in it is tuned for this.
     cpu = None
     if not args.no_cpu_baseline:
+        from concurrent.futures import ThreadPoolExecutor
         from oracle import lychee_oracle as orc
-        try:
-            from threadpoolctl import threadpool_info
-            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
-        except Exception:
-            cores = 1
+        from threadpoolctl import threadpool_limits
+        n_aff = len(os.sched_getaffinity(0))
         b0 = 0
         s0 = seqs[b0]
         heads = list(range(w.H_kv))
@@ -396,29 +396,61 @@ def main():
                 break
         heads = sorted(oidx)
         cpu_build_s = (time.perf_counter() - tb) / len(heads)
-        n_done, tc = 0, time.perf_counter()
-        while time.perf_counter() - tc < args.cpu_seconds:
-            qb = wl.bf16_bits_to_f64(wl.make_queries(w, b0, s0.offsets, 1, stream=100 + (n_done % nq))[0][0])
-            for h in heads:
-                q = qb[h * G:(h + 1) * G]
-                sel = orc.retrieve_flat(oidx[h], q, w.budget)
-                orc.sparse_decode(q, Kf[h], Vf[h], oidx[h].bounds, oidx[h].T, sel)
-            n_done += 1
-        per_seq_step = (time.perf_counter() - tc) / n_done * (w.H_kv / len(heads))
-        cpu = {"value": round(per_seq_step * w.B * 1e6, 1), "unit": "us/step", "cores": int(cores), "kind": "oracle",
-               "sample": f"{n_done} decode steps (flat-scan retrieve + attend) of sequence 0, "
-                         f"{len(heads)} of {w.H_kv} KV heads, scaled to {w.B} sequence(s) x {w.H_kv} heads; "
-                         f"oracle index build {cpu_build_s:.1f} s per (sequence, head), not included"}
+        qcache = [wl.bf16_bits_to_f64(wl.make_queries(w, b0, s0.offsets, 1, stream=100 + i)[0][0]) for i in range(nq)]
 
-    from paper_2603_08453_amd.profsum import read_traffic
+        def head_step(task):
+            i, h = task
+            q = qcache[i % nq][h * G:(h + 1) * G]
+            sel = orc.retrieve_flat(oidx[h], q, w.budget)
+            orc.sparse_decode(q, Kf[h], Vf[h], oidx[h].bounds, oidx[h].T, sel)
+
+        def run(workers, seconds):
+            """Seconds per decode step of one sequence (all its KV heads), and the steps that were run."""
+            n_done, tc = 0, time.perf_counter()
+            with threadpool_limits(limits=1):
+                if workers == 1:
+                    while time.perf_counter() - tc < seconds:
+                        for h in heads:
+                            head_step((n_done, h))
+                        n_done += 1
+                else:
+                    with ThreadPoolExecutor(max_workers=workers) as pool:
+                        while time.perf_counter() - tc < seconds:
+                            batch = max(1, -(-workers // len(heads)))         # steps in flight: enough tasks for every worker
+                            list(pool.map(head_step, [(n_done + k, h) for k in range(batch) for h in heads]))
+                            n_done += batch
+            return (time.perf_counter() - tc) / n_done * (w.H_kv / len(heads)), n_done
+
+        one_s, one_n = run(1, args.cpu_seconds / 2)
+        all_s, all_n = run(n_aff, args.cpu_seconds / 2)
+        sample = (f"decode steps (flat-scan retrieve + attend) of sequence 0, {len(heads)} of {w.H_kv} KV heads, "
+                  f"scaled to {w.B} sequence(s) x {w.H_kv} heads; {one_n} steps on one thread, {all_n} steps on "
+                  f"{n_aff} threads (affinity mask; one head per task); oracle index build {cpu_build_s:.1f} s "
+                  f"per (sequence, head), not included")
+        cpu = {"value": round(all_s * w.B * 1e6, 1), "unit": "us/step", "cores": int(n_aff), "kind": "oracle",
+               "sample": sample,
+               "single_thread": {"value": round(one_s * w.B * 1e6, 1), "unit": "us/step", "cores": 1}}
+
     # dominant kernel: the attention kernel (of lc_decode_step: it also repeats the selection, whose
     # algorithmic input is one key and one boundary pair per chunk and head)
     if args.separate:
-        dom_name, dom_us, dom_bytes = f"lc_decode_kernel<{G}, false>", attend_us, attend_bytes
+        dom_name, dom_us, dom_bytes = f"lc_decode_kernel<{G}, false", attend_us, attend_bytes
     else:
         select_bytes = sum(len(bn) - 1 for bn in bounds_np) * w.H_kv * 12
-        dom_name, dom_us, dom_bytes = f"lc_decode_kernel<{G}, true>", fused_us, attend_bytes + select_bytes
-    traffic = read_traffic(os.path.join(ROOT, "profiles", f"lc_decode_step_{w.name}_hbm_traffic.md"), dom_name)
+        dom_name, dom_us, dom_bytes = f"lc_decode_kernel<{G}, true", fused_us, attend_bytes + select_bytes
+    # HBM traffic of that kernel: hardware counters cannot be read from inside this process, so the figure
+    # is the one of the committed rocprofv3 --pmc summary of this workload (null if there is none)
+    traffic, traffic_src = None, None
+    prof = os.path.join("profiles", f"lc_decode_step_{w.name}_hbm_traffic.md")
+    if os.path.exists(os.path.join(ROOT, prof)):
+        for ln in open(os.path.join(ROOT, prof)):
+            cells = [c.strip() for c in ln.split("|")]
+            if len(cells) > 7 and cells[1].startswith(dom_name) and "=" in cells[7]:
+                traffic, traffic_src = int(float(cells[7].split("=")[-1])), prof
+                dom_name = cells[1]
+                break
+    if not dom_name.endswith(">"):
+        dom_name += ", ...>" if not args.separate else ", 1>"
     res = {
         "metric": "us per decode step per layer (retrieve+attend), 128K ctx" if w.name.startswith("C3") else
                   "us per decode step per layer (retrieve+attend)",
@@ -441,7 +473,7 @@ def main():
         "roofline": {"bound": "hbm", "achieved": round(dom_bytes / (dom_us * 1e-6) / 1e9, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(dom_bytes / (dom_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
-                     "traffic": traffic, "kernel": dom_name,
+                     "traffic": traffic, "traffic_source": traffic_src, "kernel": dom_name,
                      "bytes_per_launch": round(dom_bytes), "us_per_launch": round(dom_us, 2)},
         "cpu_baseline": cpu,
         "extra": {

@@ -86,7 +86,7 @@ enum { LC_CENTER_F32 = 0, LC_CENTER_BF16 = 1 };
 typedef struct lc_config {
     int32_t levels;                 /* L >= 1, counts the chunk level (paper: 3)            */
     int32_t fanout;                 /* F >= 1                                               */
-    int32_t kmeans_iters;           /* spherical k-means iterations (Appendix B: 10)        */
+    int32_t kmeans_iters;           /* spherical k-means iterations (Appendix A: 10)        */
     int32_t geometry;               /* LC_GEOMETRY_*                                        */
     int32_t policy;                 /* LC_POLICY_*                                          */
     int32_t beam[LC_MAX_LEVELS];    /* BEAM: nodes kept per level; <= 0 means no limit.
@@ -102,7 +102,7 @@ typedef struct lc_config {
                                        i.e. level l has ceil(N_{l-1} / fanouts[l]) nodes;
                                        0 = use `fanout`.  The paper's three tiers are e.g.
                                        {0, 2, 22}: 2 chunks per fine cluster, 22 fine
-                                       clusters per coarse unit (Appendix B)                */
+                                       clusters per coarse unit (Appendix A)                */
 } lc_config;
 
 typedef struct lc_index lc_index;   /* opaque host-side handle */
@@ -171,21 +171,6 @@ int lc_set_policy(lc_index* idx, int policy, const int32_t* beam /* host, LC_MAX
 /* Change the pruning mode (LC_PRUNE_*) of an existing index (host state only). */
 int lc_set_prune(lc_index* idx, int prune);
 
-/* Measurement aid (host state only).  While on, lc_decode_step launches only its second kernel
- * (selection + attention) and takes the chunk score keys that the previous lc_decode_step with
- * the same query, index and workspace left in the workspace; the results are the same.  It lets a
- * benchmark time that kernel by itself.  A call that has to fall back to the kernels of
- * lc_retrieve + lc_sparse_decode ignores the setting. */
-int lc_set_step_reuse_keys(lc_index* idx, int on);
-
-/* Measurement aid, not part of the decode path: reads `bytes` bytes (a multiple of 16, from a
- * 16-byte aligned device pointer) once with plain streaming loads, so that a benchmark can quote
- * the read bandwidth this GPU reaches beside its published peak.  `sink` (device, at least 2048
- * words; `sink_words` says how many there are) receives one folded word per workgroup.
- * LC_ERR_INVALID_ARG for a null or misaligned pointer or a size that is 0 or not a multiple of 16,
- * LC_ERR_WORKSPACE_TOO_SMALL for a short sink. */
-int lc_read_sweep(const void* src, size_t bytes, uint32_t* sink, size_t sink_words, void* stream);
-
 /*
  * lc_retrieve -- hierarchical retrieval for one decode step (Eq. 2, Algorithm 1
  * steps 1-2).  Per (sequence, KV head) every node u gets the group score
@@ -232,9 +217,9 @@ int lc_sparse_decode(const lc_index* idx, const void* q, const void* K, const vo
  * from the scoring kernel to the attention kernel through the workspace; every
  * workgroup of the attention kernel repeats the selection of its (sequence,
  * head) from them, so no chunk list travels through memory on the critical path.
- * When a sequence has more than about three thousand chunks, repeating the
- * selection stops paying and the call runs the kernels of the two separate
- * entry points instead (through a chunk list in the workspace).
+ * When a sequence has more than 4096 chunks, the chunks no longer fit the registers of
+ * the selecting workgroups and the call runs the kernels of the two separate entry
+ * points instead (through a chunk list in the workspace); the results are the same.
  *
  *   chunk_ids, counts  optional outputs as in lc_retrieve (both or neither); cap
  *                      is checked only when they are given
@@ -289,7 +274,7 @@ size_t lc_static_workspace_bytes(void);
  */
 int lc_append(lc_index* idx, void* K, void* V, const int64_t kv_strides[3],
               const void* k_new, const void* v_new, const uint8_t* close_chunk,
-              void* ws, size_t ws_bytes, void* stream);
+              void* ws /* unused, may be NULL */, size_t ws_bytes, void* stream);
 
 /* Host-side view of the index state: tokens, closed chunks and level sizes of
  * sequence b (n_per_level: host int32[LC_MAX_LEVELS], may be NULL). */
@@ -316,7 +301,7 @@ void lc_index_destroy(lc_index* idx);
 
 /*
  * lc_chunk_tokens -- structure-aware chunk boundaries for a token stream
- * (Section 4.3 "Structure-Aware Chunking", Appendix C separator table).  Host
+ * (Section 4.3 "Structure-Aware Chunking", Appendix B separator table).  Host
  * routine, no GPU work: its output is the chunk_bounds argument of
  * lc_build_index and decides the close_chunk bits of lc_append.
  * Tokens are accumulated greedily; once a chunk holds min_len tokens the

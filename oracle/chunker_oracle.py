@@ -1,6 +1,6 @@
 """CPU oracle for structure-aware chunking -- TEST INFRASTRUCTURE ONLY.
 
-Section 4.3 ("Structure-Aware Chunking") and Appendix C: tokens are accumulated greedily; once
+Section 4.3 ("Structure-Aware Chunking") and Appendix B: tokens are accumulated greedily; once
 the chunk has reached the minimum length the algorithm looks, up to the maximum length, for the
 natural delimiter of highest priority and cuts right after it; without any delimiter the chunk is
 cut at the maximum length.  Delimiter priorities are those of the paper's separator table

@@ -12,7 +12,7 @@ What follows the paper directly
   * node = (centroid, covering radius)            -- Section 4.1
   * score upper bound  q.mu + |q| r               -- Eq. 2
   * spherical k-means, inner-product similarity, 10 fixed iterations
-                                                  -- Section 4.3, Appendix B
+                                                  -- Section 4.3, Appendix A
   * top-down pruning with per-level top-k         -- Algorithm 1 (steps 1-2)
   * lazy update: nearest fine cluster, moving-average centroid, monotone
     radius growth                                 -- Section 4.4, Algorithm 1 (step 4)
@@ -194,7 +194,7 @@ def direction_of(center: np.ndarray) -> np.ndarray:
 
 def spherical_kmeans(X: np.ndarray, k: int, iters: int,
                      trace: Optional[list] = None) -> Tuple[np.ndarray, np.ndarray]:
-    """Spherical k-means on unit rows X [N, d] (Section 4.3; Appendix B: 10 iterations).
+    """Spherical k-means on unit rows X [N, d] (Section 4.3; Appendix A: 10 iterations).
 
     Similarity is the inner product.  Initial centroid c is the point with
     index floor(c*N/k).  One iteration = assign every point to the centroid of
@@ -227,7 +227,7 @@ def spherical_kmeans(X: np.ndarray, k: int, iters: int,
 def level_fanout(F, level: int) -> int:
     """Average number of children of a node at `level` (>= 1): F itself, or F[level] when the levels
     have fan-outs of their own (the paper's tiers: 2 chunks per fine cluster, at most 64 coarse units;
-    Appendix B)."""
+    Appendix A)."""
     if isinstance(F, (int, np.integer)):
         return int(F)
     return int(F[level])
@@ -356,7 +356,7 @@ def select_prefix(ids: np.ndarray, scores: np.ndarray, lens: np.ndarray, budget:
 
 def pinned_chunks(idx: Index, sink_tokens: int) -> np.ndarray:
     """Leading chunks that cover the first `sink_tokens` tokens: always attended,
-    never scored, not charged to the budget (Appendix B sets an attention sink)."""
+    never scored, not charged to the budget (Appendix A sets an attention sink)."""
     if sink_tokens <= 0:
         return np.zeros(0, dtype=np.int64)
     return np.nonzero(idx.bounds[:-1] < sink_tokens)[0]

@@ -112,10 +112,12 @@ def lib() -> ctypes.CDLL:
     L.lc_static_workspace_bytes.restype = ctypes.c_size_t
     L.lc_recluster.argtypes = [vp, vp, ctypes.c_size_t, vp]
     L.lc_recluster.restype = ctypes.c_int
-    L.lc_set_step_reuse_keys.argtypes = [vp, ctypes.c_int]
-    L.lc_set_step_reuse_keys.restype = ctypes.c_int
-    L.lc_read_sweep.argtypes = [vp, ctypes.c_size_t, vp, ctypes.c_size_t, vp]
-    L.lc_read_sweep.restype = ctypes.c_int
+    # measurement aids (lychee_bench.h)
+    L.lc_bench_select_attend.argtypes = [vp, vp, vp, vp, i64p, ctypes.c_int, ctypes.c_int, vp, vp,
+                                         vp, ctypes.c_size_t, vp]
+    L.lc_bench_select_attend.restype = ctypes.c_int
+    L.lc_bench_read_sweep.argtypes = [vp, ctypes.c_size_t, vp, ctypes.c_size_t, vp]
+    L.lc_bench_read_sweep.restype = ctypes.c_int
     L.lc_append.argtypes = [vp, vp, vp, i64p, vp, vp, u8p, vp, ctypes.c_size_t, vp]
     L.lc_append.restype = ctypes.c_int
     L.lc_index_info.argtypes = [vp, ctypes.c_int, i32p, i32p, i32p]
@@ -265,14 +267,19 @@ def lc_recluster(idx: Index, ws, stream=None) -> None:
     _check(lib().lc_recluster(idx.handle, _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "lc_recluster")
 
 
-def lc_set_step_reuse_keys(idx: Index, on: bool) -> None:
-    _check(lib().lc_set_step_reuse_keys(idx.handle, 1 if on else 0), "lc_set_step_reuse_keys")
+def lc_bench_select_attend(idx: Index, q, K, V, budget: int, out, ws, lse=None, stream=None) -> None:
+    """Measurement aid: the select+attend kernel of lc_decode_step alone, on the score keys that the
+    previous lc_decode_step with the same query, index, budget and workspace left in `ws`."""
+    assert K.shape == V.shape and K.stride() == V.stride()
+    _check(lib().lc_bench_select_attend(idx.handle, _ptr(q), _ptr(K), _ptr(V), _strides3(K), int(q.shape[1]),
+                                        int(budget), _ptr(out), _ptr(lse), _ptr(ws),
+                                        ws.numel() * ws.element_size(), _stream(stream)), "lc_bench_select_attend")
 
 
-def lc_read_sweep(src, sink, stream=None) -> None:
-    """Reads the device tensor `src` once; `sink` is an int32/uint32 device tensor of >= 2048 words."""
-    _check(lib().lc_read_sweep(_ptr(src), src.numel() * src.element_size(), _ptr(sink), sink.numel(),
-                               _stream(stream)), "lc_read_sweep")
+def lc_bench_read_sweep(src, sink, stream=None) -> None:
+    """Measurement aid: reads the device tensor `src` once; `sink` is an int32 device tensor of >= 2048 words."""
+    _check(lib().lc_bench_read_sweep(_ptr(src), src.numel() * src.element_size(), _ptr(sink), sink.numel(),
+                                     _stream(stream)), "lc_bench_read_sweep")
 
 
 def lc_decode_step(idx: Index, q, K, V, budget: int, out, ws, lse=None, chunk_ids=None, counts=None,

@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblychee.so")
-SOURCES = ["lc_api.hip", "lc_retrieve.hip", "lc_decode.hip", "lc_build.hip", "lc_chunker.hip", "lc_measure.hip"]
+SOURCES = ["lc_api.hip", "lc_retrieve.hip", "lc_decode.hip", "lc_build.hip", "lc_chunker.hip", "lc_bench.hip"]
 
 
 def hipcc() -> str:

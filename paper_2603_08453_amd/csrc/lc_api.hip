@@ -326,12 +326,6 @@ int lc_set_prune(lc_index* idx, int prune) {
     return LC_OK;
 }
 
-int lc_set_step_reuse_keys(lc_index* idx, int on) {
-    if (!idx) return LC_ERR_INVALID_ARG;
-    idx->step_reuse_keys = on ? 1 : 0;
-    return LC_OK;
-}
-
 int lc_index_info(const lc_index* idx, int b, int32_t* T, int32_t* M, int32_t* n_per_level) {
     if (!idx || b < 0 || b >= idx->B) return LC_ERR_INVALID_ARG;
     if (T) *T = idx->T[b];
@@ -423,7 +417,8 @@ int decode_step_checks(const lc_index* idx, const void* q, const void* K, const 
 // The step itself on a laid-out workspace (every check has passed).
 int decode_step_run(const lc_index* idx, const LcWs& w, const RetrievePlan& p, int splits, const void* q,
                     const void* K, const void* V, const int64_t kv_strides[3], int H_q, int budget, float* out,
-                    float* lse, int32_t* chunk_ids, int32_t* counts, int cap, hipStream_t st) {
+                    float* lse, int32_t* chunk_ids, int32_t* counts, int cap, hipStream_t st,
+                    bool second_kernel_only = false) {
     const bool want_ids = chunk_ids != nullptr;
     const int G = H_q / idx->H_kv;
     int rc;
@@ -432,7 +427,7 @@ int decode_step_run(const lc_index* idx, const LcWs& w, const RetrievePlan& p, i
     if (p.max_M <= LC_STEP_FUSED_MAX_CHUNKS && lc_decode_fused_fits(G, p.max_M)) {
         // kernel 1 (and the level walk before it) leaves the chunk score keys in the workspace;
         // kernel 2 selects from them in every workgroup and attends
-        if (!idx->step_reuse_keys) {
+        if (!second_kernel_only) {
             rc = lc_launch_retrieve(idx, w, q, G, budget, nullptr, nullptr, nullptr, 1, p.max_M,
                                     p.walk ? p.max_upper : -1, 1, st);
             if (rc) return rc;
@@ -440,7 +435,8 @@ int decode_step_run(const lc_index* idx, const LcWs& w, const RetrievePlan& p, i
         return lc_launch_decode_fused(idx, w, q, K, V, kv_strides, G, splits, budget, chunk_ids, counts,
                                       want_ids ? cap : 0, p.max_M, out, lse, st);
     }
-    // too many chunks to stage in LDS: the two kernels of lc_retrieve + lc_sparse_decode, with the
+    if (second_kernel_only) return LC_ERR_CAPACITY;
+    // too many chunks for the registers of the selecting workgroups: the two kernels of lc_retrieve + lc_sparse_decode, with the
     // chunk list in the caller's buffer or, without one, in the workspace
     int32_t* ids = want_ids ? chunk_ids : w.ids_tmp;
     int32_t* cnt = want_ids ? counts : w.counts_tmp;
@@ -458,6 +454,13 @@ int decode_step_run(const lc_index* idx, const LcWs& w, const RetrievePlan& p, i
 int lc_decode_step(const lc_index* idx, const void* q, const void* K, const void* V, const int64_t kv_strides[3],
                    int H_q, int budget, float* out, float* lse, int32_t* chunk_ids, int32_t* counts, int cap,
                    void* ws, size_t ws_bytes, void* stream) {
+    return lc_decode_step_impl(idx, q, K, V, kv_strides, H_q, budget, out, lse, chunk_ids, counts, cap, ws, ws_bytes,
+                               stream, false);
+}
+
+int lc_decode_step_impl(const lc_index* idx, const void* q, const void* K, const void* V, const int64_t kv_strides[3],
+                        int H_q, int budget, float* out, float* lse, int32_t* chunk_ids, int32_t* counts, int cap,
+                        void* ws, size_t ws_bytes, void* stream, bool second_kernel_only) {
     int rc = decode_step_checks(idx, q, K, V, kv_strides, H_q, budget, out, chunk_ids, counts, cap);
     if (rc) return rc;
     if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u)) return LC_ERR_INVALID_ARG;
@@ -470,7 +473,7 @@ int lc_decode_step(const lc_index* idx, const void* q, const void* K, const void
     LcWs w;
     lc_layout_ws(&idx->cfg, idx->B, H_q, idx->H_kv, idx->d, splits, ws, &w);
     return decode_step_run(idx, w, p, splits, q, K, V, kv_strides, H_q, budget, out, lse, chunk_ids, counts, cap,
-                           static_cast<hipStream_t>(stream));
+                           static_cast<hipStream_t>(stream), second_kernel_only);
 }
 
 // ---------------------------------------------------------------------------------

@@ -1,10 +1,11 @@
-// Measurement aid: a plain streaming read of a device buffer, so that a benchmark can report what
-// read bandwidth this GPU reaches next to its published peak.  Not part of the decode path.
+// Measurement aids (lychee_bench.h), kept apart from the decode path: a plain streaming read of a
+// device buffer, so that a benchmark can report what read bandwidth this GPU reaches next to its
+// published peak, and a launch of the select+attend kernel of lc_decode_step by itself.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
 #include "lc_internal.h"
-#include "lychee.h"
+#include "lychee_bench.h"
 
 #define LC_SWEEP_THREADS 256
 #define LC_SWEEP_WGS 2048
@@ -39,7 +40,7 @@ lc_read_sweep_kernel(const uint4* __restrict__ src, size_t n_vec, uint32_t* __re
     }
 }
 
-extern "C" int lc_read_sweep(const void* src, size_t bytes, uint32_t* sink, size_t sink_words, void* stream) {
+extern "C" int lc_bench_read_sweep(const void* src, size_t bytes, uint32_t* sink, size_t sink_words, void* stream) {
     if (!src || !sink || bytes == 0) return LC_ERR_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(src) & 15u) || (bytes & 15u)) return LC_ERR_INVALID_ARG;
     if (sink_words < (size_t)LC_SWEEP_WGS) return LC_ERR_WORKSPACE_TOO_SMALL;
@@ -47,4 +48,11 @@ extern "C" int lc_read_sweep(const void* src, size_t bytes, uint32_t* sink, size
                        static_cast<hipStream_t>(stream), static_cast<const uint4*>(src), bytes / 16, sink);
     LC_HIP_CHECK(hipGetLastError());
     return LC_OK;
+}
+
+extern "C" int lc_bench_select_attend(const lc_index* idx, const void* q, const void* K, const void* V,
+                                      const int64_t kv_strides[3], int H_q, int budget, float* out, float* lse,
+                                      void* ws, size_t ws_bytes, void* stream) {
+    return lc_decode_step_impl(idx, q, K, V, kv_strides, H_q, budget, out, lse, nullptr, nullptr, 0, ws, ws_bytes,
+                               stream, /*second_kernel_only=*/true);
 }

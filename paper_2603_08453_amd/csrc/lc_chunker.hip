@@ -1,4 +1,4 @@
-// Structure-aware chunking of a token stream (Section 4.3, Appendix C separator table).
+// Structure-aware chunking of a token stream (Section 4.3, Appendix B separator table).
 // Host code only: the boundaries feed lc_build_index and the close bits of lc_append.
 #include "lychee.h"
 

@@ -18,8 +18,10 @@
 #include "lc_device.h"
 #include "lc_internal.h"
 
+#ifndef LC_DEC_THREADS
 #define LC_DEC_THREADS 256
-#define LC_DEC_GROUPS 16
+#endif
+#define LC_DEC_GROUPS (LC_DEC_THREADS / 16)
 #define LC_DEC_MIN_TOKENS_PER_SPLIT 64
 #define LC_DEC_MAX_SPLITS 256
 #define LC_DEC_TILE 1024          // tokens of a split whose cache rows are resolved into LDS at a time
@@ -289,8 +291,10 @@ lc_decode_kernel(const LcDecodeArgs a) {
             if (lane == 0) { fs.kmin[wave] = wmin; fs.kmax[wave] = wmax; }
         }
         lc_barrier_lds();
-        kmin1 = min(min(fs.kmin[0], fs.kmin[1]), min(fs.kmin[2], fs.kmin[3]));
-        kmax = max(max(fs.kmax[0], fs.kmax[1]), max(fs.kmax[2], fs.kmax[3]));
+        kmin1 = fs.kmin[0];
+        kmax = fs.kmax[0];
+#pragma unroll
+        for (int w = 1; w < LC_DEC_THREADS / 64; ++w) { kmin1 = min(kmin1, fs.kmin[w]); kmax = max(kmax, fs.kmax[w]); }
         LC_LSTAMP0(18);
         if (kmax != 0u) {                                           // (uniform) there are candidates
             const uint32_t kmin = kmin1 + 1u;

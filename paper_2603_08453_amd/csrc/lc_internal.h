@@ -37,7 +37,6 @@ struct lc_index {
     std::vector<int> T;      // host mirror, per sequence
     std::vector<int> M;      // host mirror, per sequence
     std::vector<int> N;      // [B][LC_MAX_LEVELS] nodes per level (N[b][0] mirrors M)
-    int step_reuse_keys = 0;      // measurement aid: lc_decode_step skips the scoring kernels
 };
 
 // Layout of the index buffer: fills dev pointers from base; returns total bytes.
@@ -75,6 +74,13 @@ void lc_set_hip_error(hipError_t e);
             return LC_ERR_HIP;                   \
         }                                        \
     } while (0)
+
+// lc_decode_step with a switch for the measurement aid that launches its second kernel alone
+// (C linkage: it is defined among the entry points).
+extern "C" int lc_decode_step_impl(const lc_index* idx, const void* q, const void* K, const void* V,
+                                   const int64_t kv_strides[3], int H_q, int budget, float* out, float* lse,
+                                   int32_t* chunk_ids, int32_t* counts, int cap, void* ws, size_t ws_bytes,
+                                   void* stream, bool second_kernel_only);
 
 // Launchers (each enqueues on `stream` and returns LC_OK or LC_ERR_HIP).
 int lc_launch_build(const lc_index* idx, const LcWs& ws, const void* K, const int64_t ks[3],

@@ -263,9 +263,8 @@ def test_paper_literal_mode_against_the_default_32k(G):
       default:        token-covering balls, exact selection under a 1024-token budget;
       paper-literal:  unit-norm representatives with radius 0, top-8 coarse units then top-43 fine
                       clusters, all chunks of the kept clusters attended, attention sink of 16 tokens.
-    Both are checked against the oracle (ids and attention); cost per step and recall of the true
-    top-64 tokens of the first query head of every KV head are reported."""
-    import time
+    Both are checked against the oracle (ids and attention); the recall of the true top-64 tokens of
+    the first query head of every KV head is reported."""
     import torch
     from paper_2603_08453_amd import binding as lc
     from paper_2603_08453_amd import diagnostics as D
@@ -305,18 +304,8 @@ def test_paper_literal_mode_against_the_default_32k(G):
             sel = D.selected_tokens(oi.bounds, oi.T, ids[0][h])
             rec.append(D.recall_rate(case.Kf(0, h)[:oi.T] @ q[0], sel, 64))
             tok.append(len(sel))
-        # cost of the step (one index, rows mostly in cache: a comparison of the two modes, not a headline)
-        qd = G.to_bf16_tensor(qb)
-        o = torch.zeros((1, w.H_q, w.d), dtype=torch.float32, device="cuda")
-        for _ in range(20):
-            lc.lc_decode_step(case.idx, qd, case.K, case.V, budget, o, case.ws)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(300):
-            lc.lc_decode_step(case.idx, qd, case.K, case.V, budget, o, case.ws)
-        torch.cuda.synchronize()
-        report[mode] = ((time.perf_counter() - t0) / 300 * 1e6, float(np.mean(rec)), float(np.mean(tok)))
+        report[mode] = (float(np.mean(rec)), float(np.mean(tok)))
         lc.lc_set_policy(case.idx, lc.LC_POLICY_EXACT, None, 0)
-    for mode, (us, r, t) in report.items():
-        _say(f"32K, {mode}: {us:.1f} us per step, {t:.0f} tokens attended, recall of the true top-64 tokens {r:.3f}")
-    assert report["default"][2] <= w.budget + 64 and report["paper-literal"][2] > 0
+    for mode, (r, t) in report.items():
+        _say(f"32K, {mode}: {t:.0f} tokens attended, recall of the true top-64 tokens {r:.3f}")
+    assert report["default"][1] <= w.budget + 64 and report["paper-literal"][1] > 0

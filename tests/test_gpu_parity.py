@@ -600,7 +600,7 @@ def test_bf16_chunk_centers_append_stream(G):
 
 
 def test_per_level_fanouts_built_on_gpu(G):
-    """The paper's tiers (Appendix B): 2 chunks per fine cluster, many fine clusters per coarse unit.
+    """The paper's tiers (Appendix A): 2 chunks per fine cluster, many fine clusters per coarse unit.
     lc_build_index sizes every level by its own fan-out; the tree matches the oracle's and retrieval
     (level walk and top-k per level) works on it."""
     from paper_2603_08453_amd import binding as lc
@@ -978,7 +978,7 @@ def test_read_sweep_reads_every_word_once(G):
         host = r.integers(0, 2 ** 31, size=n_words, dtype=np.int64).astype(np.int32)
         src = torch.from_numpy(host).cuda()
         sink = torch.full((2048,), 123, dtype=torch.int32, device="cuda")
-        lc.lc_read_sweep(src, sink)
+        lc.lc_bench_read_sweep(src, sink)
         torch.cuda.synchronize()
         assert int(np.bitwise_xor.reduce(sink.cpu().numpy())) == int(np.bitwise_xor.reduce(host)), n_words
 

@@ -22,7 +22,7 @@ def L():
 
 
 def test_header_symbols_are_exported(L):
-    hdr = open(os.path.join(ROOT, "include", "lychee.h")).read()
+    hdr = open(os.path.join(ROOT, "include", "lychee.h")).read() + open(os.path.join(ROOT, "include", "lychee_bench.h")).read()
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     names = set(re.findall(r"\b(lc_[a-z_0-9]+)\s*\(", hdr))
     assert {"lc_build_index", "lc_retrieve", "lc_sparse_decode", "lc_append", "lc_decode_step", "lc_recluster",
@@ -104,11 +104,11 @@ def test_argument_errors_before_any_gpu_work(L):
     assert L.lc_decode_step(None, fake, fake, fake, strides, 32, 10, fake, None, None, None, 0, fake, 1 << 20,
                             None) == lc.LC_ERR_INVALID_ARG
     assert L.lc_recluster(None, fake, 1 << 20, None) == lc.LC_ERR_INVALID_ARG
-    assert L.lc_set_step_reuse_keys(None, 1) == lc.LC_ERR_INVALID_ARG
-    assert L.lc_read_sweep(None, 1 << 20, fake, 2048, None) == lc.LC_ERR_INVALID_ARG
-    assert L.lc_read_sweep(fake, 100, fake, 2048, None) == lc.LC_ERR_INVALID_ARG          # not a multiple of 16
-    assert L.lc_read_sweep(ctypes.c_void_p(0x10008), 1 << 20, fake, 2048, None) == lc.LC_ERR_INVALID_ARG
-    assert L.lc_read_sweep(fake, 1 << 20, fake, 100, None) == lc.LC_ERR_WORKSPACE_TOO_SMALL
+    assert L.lc_bench_select_attend(None, fake, fake, fake, strides, 8, 16, fake, None, fake, 1 << 20, None) == lc.LC_ERR_INVALID_ARG
+    assert L.lc_bench_read_sweep(None, 1 << 20, fake, 2048, None) == lc.LC_ERR_INVALID_ARG
+    assert L.lc_bench_read_sweep(fake, 100, fake, 2048, None) == lc.LC_ERR_INVALID_ARG          # not a multiple of 16
+    assert L.lc_bench_read_sweep(ctypes.c_void_p(0x10008), 1 << 20, fake, 2048, None) == lc.LC_ERR_INVALID_ARG
+    assert L.lc_bench_read_sweep(fake, 1 << 20, fake, 100, None) == lc.LC_ERR_WORKSPACE_TOO_SMALL
     assert L.lc_append(None, fake, fake, strides, fake, fake, None, fake, 0, None) == lc.LC_ERR_INVALID_ARG
     assert L.lc_set_policy(None, 0, None, 0) == lc.LC_ERR_INVALID_ARG
     assert L.lc_index_info(None, 0, None, None, None) == lc.LC_ERR_INVALID_ARG
