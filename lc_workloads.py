@@ -81,6 +81,8 @@ class Workload:
     stream_close_lo: int = 16
     stream_close_hi: int = 64
     stream_drift: float = 0.02
+    fanouts: Optional[Tuple[int, ...]] = None      # per-level fan-outs (entry l >= 1: children per level-l node), None = fanout
+    beam: Optional[Tuple[int, ...]] = None         # nodes kept per level under the top-k policy (entry 0: chunks, 0 = no limit)
 
     @property
     def G(self) -> int:
@@ -95,7 +97,14 @@ C4 = Workload("C4-stream", 4, 1, 32, 8, 128, 32768, "uniform", 16, 64, 3, 16, 20
 C5 = Workload("C5-ragged16", 5, 16, 28, 4, 128, 0, "uniform", 8, 128, 3, 32, 2048,
               T_range=(16384, 65536))
 
-WORKLOADS = {w.name: w for w in (C1, C2, C3, C4, C5)}
+# The paper's own tiers at the headline context (Appendix A: chunks of 8 to 16 tokens, 2 chunks per fine
+# cluster, budget 1024; 22 fine clusters per coarse unit gives about 250 coarse units): not one of the
+# five configurations, used to compare the top-k policy of Algorithm 1 with the flat scan where the
+# index is large.
+P3 = Workload("P3-128K-paper-tiers", 6, 1, 32, 8, 128, 131072, "uniform", 8, 16, 3, 16, 1024,
+              fanouts=(0, 2, 22), beam=(0, 43, 8))
+
+WORKLOADS = {w.name: w for w in (C1, C2, C3, C4, C5, P3)}
 
 
 def tiny(name: str = "tiny", **kw) -> Workload:

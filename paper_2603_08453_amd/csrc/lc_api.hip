@@ -351,7 +351,8 @@ namespace {
 // What a retrieval over the current index needs: sizes, the capacity check, walk or flat scan.
 struct RetrievePlan {
     int max_M = 0;
-    int max_upper = 0;
+    int max_upper = 0;          // internal nodes of one (sequence, head), all levels together
+    int max_level = 0;          // nodes of one internal level
     bool walk = false;
 };
 int plan_retrieve(const lc_index* idx, int budget, int cap, bool check_cap, RetrievePlan* p) {
@@ -365,15 +366,28 @@ int plan_retrieve(const lc_index* idx, int budget, int cap, bool check_cap, Retr
         if (need > M) need = M;
         if (check_cap && cap < need) return LC_ERR_CAPACITY;
         int up = 0;
-        for (int l = 1; l < idx->cfg.levels; ++l) up += idx->N[(size_t)b * LC_MAX_LEVELS + l];
+        for (int l = 1; l < idx->cfg.levels; ++l) {
+            const int n = idx->N[(size_t)b * LC_MAX_LEVELS + l];
+            up += n;
+            if (n > p->max_level) p->max_level = n;
+        }
         if (up > p->max_upper) p->max_upper = up;
     }
-    if (p->max_upper > 8192) return LC_ERR_CAPACITY;       // internal nodes of one (sequence, head) live in LDS
     // walk the internal levels?  BEAM: always.  EXACT: by mode; the result does not depend on it.
     p->walk = idx->cfg.levels > 1;
     if (p->walk && idx->cfg.policy == LC_POLICY_EXACT) {
         if (idx->cfg.prune == LC_PRUNE_NEVER) p->walk = false;
         else if (idx->cfg.prune == LC_PRUNE_AUTO) p->walk = leaf_bytes > (long long)LC_PRUNE_AUTO_BYTES;
+    }
+    // What the walks hold on chip: the exact walk keeps every internal node of a (sequence, head) in
+    // LDS; top-k per level keeps a kept-bit per node of a level.  A flat scan reads no internal node.
+    if (idx->cfg.policy == LC_POLICY_BEAM) {
+        if (p->max_level > lc_beam_max_level_nodes()) return LC_ERR_CAPACITY;
+    } else if (p->walk) {
+        if (p->max_upper > lc_walk_max_internal_nodes()) {
+            if (idx->cfg.prune == LC_PRUNE_ALWAYS) return LC_ERR_CAPACITY;
+            p->walk = false;                      // AUTO: the flat scan gives the same selection
+        }
     }
     return LC_OK;
 }
@@ -424,7 +438,7 @@ int decode_step_run(const lc_index* idx, const LcWs& w, const RetrievePlan& p, i
     int rc;
     // Every workgroup of the fused kernel repeats the selection with 256 threads: with a few thousand
     // chunks that is cheaper than the hand-off through a chunk list, with more it is not.
-    if (p.max_M <= LC_STEP_FUSED_MAX_CHUNKS && lc_decode_fused_fits(G, p.max_M)) {
+    if (idx->cfg.policy != LC_POLICY_BEAM && p.max_M <= LC_STEP_FUSED_MAX_CHUNKS && lc_decode_fused_fits(G, p.max_M)) {
         // kernel 1 (and the level walk before it) leaves the chunk score keys in the workspace;
         // kernel 2 selects from them in every workgroup and attends
         if (!second_kernel_only) {

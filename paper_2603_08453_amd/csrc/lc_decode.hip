@@ -17,6 +17,7 @@
 #define LC_SEL_LSTAMP(i) LC_LSTAMP0(20 + (i))
 #include "lc_device.h"
 #include "lc_internal.h"
+#include "lc_select.h"
 
 #ifndef LC_DEC_THREADS
 #define LC_DEC_THREADS 256
@@ -27,8 +28,6 @@
 #define LC_DEC_TILE 1024          // tokens of a split whose cache rows are resolved into LDS at a time
 #define LC_DEC_WIN 2048           // slots of the entry window of a tile: a power of two above LC_DEC_TILE + 2
 #define LC_DEC_E 2                // selected ids per thread and pass of the row resolution
-#define LC_DEC_CAND 64            // fused step: chunks of the cutoff bin that are ranked directly
-#define LC_DEC_BINS_MAX 1024      // fused step: most bins of the selection histogram
 #define LC_LOG2E 1.4426950408889634f
 #define LC_LN2 0.6931471805599453f
 
@@ -59,7 +58,7 @@ struct LcDecodeArgs {
     const uint32_t* keys; // [B][H][cap0] score keys of the chunks (0 = not a candidate)
     int32_t* ids_out;     // [B][H][cap] selected ids, ascending, or null
     int32_t* counts_out;  // [B][H] or null
-    int budget, sink, count_limit;   // token budget, pinned prefix, chunk-count limit (0 = none)
+    int budget, sink;     // token budget, tokens of the pinned prefix
     int ew;               // fused step: rows of 64 chunks per wavefront that hold the longest sequence (host side: picks EC)
     int max_tokens;       // rows of one (sequence, head) slab of K and V
 };
@@ -84,71 +83,19 @@ __device__ __forceinline__ float lc_row_bcast_n(float v, int src) {      // src 
 // exp2 of (x - ref) where x may be -inf (gives 0); ref is finite.
 __device__ __forceinline__ float lc_exp2_rel(float x, float ref) { return exp2f(x - ref); }
 
-// Workgroup barrier that orders LDS accesses only: global loads issued before it stay in flight
-// (a plain __syncthreads() also waits for every outstanding global load of the wavefront).
-__device__ __forceinline__ void lc_barrier_lds() {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-}
-__device__ __forceinline__ int lc_readlane(int v, int l) { return __builtin_amdgcn_readlane(v, l); }
-__device__ __forceinline__ int lc_wave_sum_i(int v) {                       // all 64 lanes active
-    return lc_readlane(lc_wave_scan_incl(v), 63);
-}
-
-// LDS of the fused step's selection (the general select routine, used when the cutoff bin
-// overflows its short list, has its own block)
-struct LcFusedSh {
-    int hw[LC_DEC_BINS_MAX + 4];     // chunk lengths per bin; the slot after the last bin takes what is no candidate
-    int hc[LC_DEC_BINS_MAX + 4];     // chunk counts per bin (with a count limit only)
-    int4 cand[LC_DEC_CAND];          // chunks of the cutoff bin: key, length, id
-    int n_cand;
-    uint32_t kmin[LC_DEC_THREADS / 64], kmax[LC_DEC_THREADS / 64];
-    int wtok[LC_DEC_THREADS / 64], wcnt[LC_DEC_THREADS / 64];
-};
-// min / max over a wavefront, uniform result: DPP within the four 16-lane rows, then the rows' values by lane reads
-__device__ __forceinline__ uint32_t lc_wave_min_uniform(uint32_t v) {
-    v = min(v, lc_dpp_u<0xB1>(v)); v = min(v, lc_dpp_u<0x4E>(v));
-    v = min(v, lc_dpp_u<0x141>(v)); v = min(v, lc_dpp_u<0x140>(v));
-    const uint32_t r0 = (uint32_t)lc_readlane((int)v, 0), r1 = (uint32_t)lc_readlane((int)v, 16);
-    const uint32_t r2 = (uint32_t)lc_readlane((int)v, 32), r3 = (uint32_t)lc_readlane((int)v, 48);
-    return min(min(r0, r1), min(r2, r3));
-}
-__device__ __forceinline__ uint32_t lc_wave_max_uniform(uint32_t v) {
-    v = max(v, lc_dpp_u<0xB1>(v)); v = max(v, lc_dpp_u<0x4E>(v));
-    v = max(v, lc_dpp_u<0x141>(v)); v = max(v, lc_dpp_u<0x140>(v));
-    const uint32_t r0 = (uint32_t)lc_readlane((int)v, 0), r1 = (uint32_t)lc_readlane((int)v, 16);
-    const uint32_t r2 = (uint32_t)lc_readlane((int)v, 32), r3 = (uint32_t)lc_readlane((int)v, 48);
-    return max(max(r0, r1), max(r2, r3));
-}
-// number of set bits of `mask` below this lane
-__device__ __forceinline__ int lc_mbcnt(unsigned long long mask) {
-    return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
-}
-
 // FUSED = false: the chunk list comes from a.ids / a.counts.  FUSED = true: every workgroup first
 // repeats the budget selection of its (sequence, head) from the chunk score keys -- the same
 // deterministic routine on the same keys, so all splits agree -- and never reads a chunk list.
 //
-// The fused selection keeps the chunks in registers: wavefront w owns the chunks
-// [64 EC w, 64 EC (w + 1)), lane l of it the chunks (EC w + e) * 64 + l for e < EC, so every load is
-// coalesced and the id order is (wavefront, e, lane): prefix sums in id order are EC independent
-// wavefront scans on the vector ALU plus one exchange of four totals.  The loops over e carry no
-// branches, so that the EC copies of each step overlap in the pipeline (one wavefront per SIMD has
-// nothing else to hide a dependent instruction's latency behind).
-//   1. range of the candidate keys (one exchange), 1024-bin histogram of chunk lengths over it
-//      (LDS atomics), every wavefront scans all bins from the top: cutoff bin, budget left for it;
-//   2. chunks in bins above the cutoff bin are selected; the few in the cutoff bin go to a short
-//      list and their owners rank them against each other (key descending, id ascending) -- or,
-//      if the list overflows (a crowded or tied bin), the general select routine runs on them;
-//   3. token offsets of the selected chunks by the scans above; the wavefronts write the cache
-//      row of every token of the split's tile into LDS, 64 lanes per overlapping chunk.
+// The fused selection (lc_select_chunks) keeps the chunks in registers and leaves every lane with
+// the first rows, lengths and token offsets of its selected chunks; the wavefronts then write the
+// cache row of every token of the split's tile into LDS, 64 lanes per overlapping chunk.
 template <int G, bool FUSED, int EC>
 __global__ void __launch_bounds__(LC_DEC_THREADS)
 lc_decode_kernel(const LcDecodeArgs a) {
     extern __shared__ int lds_dyn[];             // FUSED: key and length of every chunk, for the overflow path only
     using SelStore = typename std::conditional<FUSED, LcLeafSelSh, int>::type;
-    using FusedStore = typename std::conditional<FUSED, LcFusedSh, int>::type;
+    using FusedStore = typename std::conditional<FUSED, LcFusedSh<LC_DEC_THREADS>, int>::type;
     constexpr int WIN = FUSED ? 1 : LC_DEC_WIN;
     __shared__ __attribute__((aligned(16))) SelStore sel_store;
     __shared__ __attribute__((aligned(16))) FusedStore fused_store;
@@ -195,10 +142,8 @@ lc_decode_kernel(const LcDecodeArgs a) {
     int n_ids = 0, M = 0;
     int idv[E], st0[E], ln0[E];
     int ex0 = 0, tot0 = 0;
-    // FUSED = true: this lane's chunks (see above): first row, length (0 unless selected), token
-    // offset among the wavefront's selected tokens
-    int cst[EC], stok[EC], coff[EC];
-    int base_tok = 0, n_sel = 0, n_sel_tok = 0, tail_st = 0, tail_ln = 0;
+    // FUSED = true: this lane's chunks and the totals of the selection
+    LcChunkSel<EC> cs;
 
     auto entries = [&](int base, bool preloaded, int (&st)[E], int (&ln)[E]) -> int {
         int sum = 0;
@@ -238,275 +183,12 @@ lc_decode_kernel(const LcDecodeArgs a) {
             n_tok += tot;
         }
     } else {
-        LcLeafSelSh& sel_sh = sel_store;
-        LcFusedSh& fs = fused_store;
-        // bins of the histogram: about one per four chunks, so that the cutoff bin holds a handful
-        constexpr int BITS = EC <= 4 ? 8 : (EC <= 10 ? 9 : 10);
-        constexpr int BINS = 1 << BITS;
-        const int cap0 = ix.cap[0];
-        // ---- every load of the selection goes out at once, before the chunk count is known (reads
-        // past the arrays' ends return 0; what lies past the count is masked below)
-        const __amdgpu_buffer_rsrc_t keys_r = lc_buffer(a.keys + (size_t)bh * cap0, cap0 * 4);
-        const __amdgpu_buffer_rsrc_t bnd_r = lc_buffer(bnd, (cap0 + 1) * 4);
-        const int j0 = wave * (EC * 64) + lane;                      // this lane's chunk e is j0 + 64 e
-        uint32_t ck[EC];
-        int cend[EC];
-#pragma unroll
-        for (int e = 0; e < EC; ++e) {
-            ck[e] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(keys_r, j0 * 4, e * 256, 0);
-            cst[e] = __builtin_amdgcn_raw_buffer_load_b32(bnd_r, j0 * 4, e * 256, 0);
-            cend[e] = __builtin_amdgcn_raw_buffer_load_b32(bnd_r, j0 * 4, e * 256 + 4, 0);
-        }
-        T = ix.state[bh * 4 + 0];
-        const int M_all = ix.state[bh * 4 + 1];
-        // meanwhile: empty histograms and list (their first use is behind the barrier of the key range)
-        const bool count_c = a.count_limit > 0;                     // chunk counts matter only with a count limit
-        for (int i = tid; i < BINS + 4; i += LC_DEC_THREADS) {
-            fs.hw[i] = 0;
-            if (count_c) fs.hc[i] = 0;
-        }
-        if (tid < LC_DEC_CAND) fs.cand[tid] = make_int4(0, 0, 0, 0);
-        if (tid == 0) fs.n_cand = 0;
-        M = min(M_all, EC * LC_DEC_THREADS);
-        tail_st = bnd[M_all];
-        const int W = a.budget > 0 ? a.budget : 0;
-        const int C = count_c ? a.count_limit : 0x7fffffff;
-        LC_LSTAMP0(15);
-        // ---- lengths; what is past the count or pinned is no candidate (key 0), pinned chunks are selected
-        int cln[EC];
-        uint32_t kmin1 = 0xffffffffu, kmax = 0u;                    // (lowest candidate key) - 1, highest
-#pragma unroll
-        for (int e = 0; e < EC; ++e) {
-            const bool valid = j0 + 64 * e < M;
-            cln[e] = valid ? max(0, cend[e] - cst[e]) : 0;
-            const bool pinned = valid && cst[e] < a.sink;
-            const int len_p = cln[e];
-            stok[e] = pinned ? len_p : 0;
-            ck[e] = (valid && !pinned) ? ck[e] : 0u;
-            kmin1 = min(kmin1, ck[e] - 1u);                         // key 0 wraps to the largest value: ignored
-            kmax = max(kmax, ck[e]);
-        }
-        {
-            const uint32_t wmin = lc_wave_min_uniform(kmin1), wmax = lc_wave_max_uniform(kmax);
-            if (lane == 0) { fs.kmin[wave] = wmin; fs.kmax[wave] = wmax; }
-        }
-        lc_barrier_lds();
-        kmin1 = fs.kmin[0];
-        kmax = fs.kmax[0];
-#pragma unroll
-        for (int w = 1; w < LC_DEC_THREADS / 64; ++w) { kmin1 = min(kmin1, fs.kmin[w]); kmax = max(kmax, fs.kmax[w]); }
-        LC_LSTAMP0(18);
-        if (kmax != 0u) {                                           // (uniform) there are candidates
-            const uint32_t kmin = kmin1 + 1u;
-            const uint32_t span = kmax - kmin;
-            const int bits = span ? 32 - __clz(span) : 0;
-            const int shift = bits > BITS ? bits - BITS : 0;        // (span >> shift) < BINS
-            // bin of every chunk: -1 = no candidate (those add their length to a slot nobody reads)
-            int cbin[EC];
-#pragma unroll
-            for (int e = 0; e < EC; ++e) {
-                const int bin = (int)((ck[e] - kmin) >> shift);
-                cbin[e] = ck[e] != 0u ? bin : -1;
-                const int slot = (int)min((uint32_t)cbin[e], (uint32_t)BINS);
-                atomicAdd(&fs.hw[slot], cln[e]);
-                if (count_c) atomicAdd(&fs.hc[slot], 1);
-            }
-            lc_barrier_lds();
-            LC_LSTAMP0(19);
-            // ---- every wavefront scans all bins from the top: lane l holds bins BINS - 1 - PER l - i, i < PER
-            constexpr int PER = BINS / 64;
-            int fb = -1, remW = W, remC = C;                        // cutoff bin (-1: every candidate fits), what is left for it
-            {
-                int pw[PER];                                        // inclusive prefix sums within the lane, bins descending
-                const int4* hw4 = reinterpret_cast<const int4*>(fs.hw + BINS - PER * (lane + 1));
-#pragma unroll
-                for (int v = 0; v < PER / 4; ++v) {
-                    const int4 x = hw4[PER / 4 - 1 - v];
-                    pw[4 * v + 0] = x.w; pw[4 * v + 1] = x.z; pw[4 * v + 2] = x.y; pw[4 * v + 3] = x.x;
-                }
-#pragma unroll
-                for (int i = 1; i < PER; ++i) pw[i] += pw[i - 1];
-                const int cw = lc_wave_scan_incl(pw[PER - 1]) - pw[PER - 1];      // length of all higher lanes' bins
-                // bins of this lane that still fit (prefix sums grow, so they are the first `fit` ones) and their total
-                int fit = 0, fitw = 0, cc = 0, fitc = 0;
-                if (!count_c) {
-#pragma unroll
-                    for (int i = 0; i < PER; ++i) {
-                        const bool ok = cw + pw[i] <= W;
-                        fit += ok ? 1 : 0;
-                        fitw = ok ? pw[i] : fitw;
-                    }
-                } else {
-                    int pc[PER];
-                    const int4* hc4 = reinterpret_cast<const int4*>(fs.hc + BINS - PER * (lane + 1));
-#pragma unroll
-                    for (int v = 0; v < PER / 4; ++v) {
-                        const int4 y = hc4[PER / 4 - 1 - v];
-                        pc[4 * v + 0] = y.w; pc[4 * v + 1] = y.z; pc[4 * v + 2] = y.y; pc[4 * v + 3] = y.x;
-                    }
-#pragma unroll
-                    for (int i = 1; i < PER; ++i) pc[i] += pc[i - 1];
-                    cc = lc_wave_scan_incl(pc[PER - 1]) - pc[PER - 1];
-#pragma unroll
-                    for (int i = 0; i < PER; ++i) {
-                        const bool ok = cw + pw[i] <= W && cc + pc[i] <= C;
-                        fit += ok ? 1 : 0;
-                        fitw = ok ? pw[i] : fitw;
-                        fitc = ok ? pc[i] : fitc;
-                    }
-                }
-                const unsigned long long bal = __ballot(fit < PER); // the prefix ends in the first bin that no longer fits
-                if (bal != 0ull) {
-                    const int fl = __ffsll((long long)bal) - 1;     // lowest lane = highest bins
-                    fb = BINS - 1 - (PER * fl + lc_readlane(fit, fl));
-                    remW = W - (lc_readlane(cw, fl) + lc_readlane(fitw, fl));
-                    if (count_c) remC = C - (lc_readlane(cc, fl) + lc_readlane(fitc, fl));
-                }
-            }
-            // ---- chunks above the cutoff bin are in; those in it go to the short list
-            unsigned long long cutm[EC];
-            unsigned long long anycut = 0ull;
-#pragma unroll
-            for (int e = 0; e < EC; ++e) {
-                const int len_e = cln[e], old_e = stok[e];          // (values first: a select of two array slots keeps both arrays in memory)
-                stok[e] = cbin[e] > fb ? len_e : old_e;
-                cutm[e] = __ballot(fb >= 0 && cbin[e] == fb);
-                anycut |= cutm[e];
-            }
-            int cpos[EC];
-            if (anycut != 0ull) {                                   // (uniform per wavefront)
-                int n_mine = 0;
-#pragma unroll
-                for (int e = 0; e < EC; ++e) {
-                    cpos[e] = n_mine + lc_mbcnt(cutm[e]);
-                    n_mine += __popcll(cutm[e]);
-                }
-                int base = 0;
-                if (lane == 0) base = atomicAdd(&fs.n_cand, n_mine);
-                base = lc_readlane(base, 0);
-#pragma unroll
-                for (int e = 0; e < EC; ++e) {
-                    cpos[e] += base;
-                    if (((cutm[e] >> lane) & 1ull) && cpos[e] < LC_DEC_CAND)
-                        fs.cand[cpos[e]] = make_int4((int)ck[e], cln[e], j0 + 64 * e, 0);
-                }
-            }
-            lc_barrier_lds();
-            LC_LSTAMP0(11);
-            const int nc = fs.n_cand;
-            if (nc <= LC_DEC_CAND) {
-                // ---- each owner ranks its chunk against the list: length and number of the chunks before it
-                // (the list is padded with key 0 entries, which come before nothing)
-                if (anycut != 0ull) {
-#pragma unroll
-                    for (int e = 0; e < EC; ++e) {
-                        if (cutm[e] != 0ull) {                      // (uniform per wavefront)
-                            const uint32_t km = ck[e];
-                            const int im = j0 + 64 * e;
-                            int wb = 0, cb = 0;
-                            for (int t = 0; t < nc; t += 4) {
-#pragma unroll
-                                for (int u = 0; u < 4; ++u) {
-                                    const int4 o = fs.cand[t + u];
-                                    const bool before = (uint32_t)o.x > km || ((uint32_t)o.x == km && o.z < im);
-                                    wb += before ? o.y : 0;
-                                    cb += before ? 1 : 0;
-                                }
-                            }
-                            const int len_e = cln[e], old_e = stok[e];
-                            const bool in = ((cutm[e] >> lane) & 1ull) && wb + len_e <= remW && cb + 1 <= remC;
-                            stok[e] = in ? len_e : old_e;
-                        }
-                    }
-                }
-            } else {
-                // ---- a crowded or tied cutoff bin: the general select routine on its chunks alone
-                uint32_t* skey = reinterpret_cast<uint32_t*>(lds_dyn);
-                int* slen = lds_dyn + EC * LC_DEC_THREADS;
-                lc_leaf_select_prepare<LC_DEC_THREADS>(sel_sh);
-                lc_barrier_lds();
-                uint32_t bmin = 0xffffffffu, bmax = 0u;
-#pragma unroll
-                for (int e = 0; e < EC; ++e) {
-                    const int j = j0 + 64 * e;
-                    const bool cnd = (cutm[e] >> lane) & 1ull;
-                    const uint32_t k = cnd ? (ck[e] == 0xffffffffu ? 0xfffffffeu : ck[e]) : 0u;     // the mark is reserved
-                    skey[j] = k;
-                    slen[j] = cln[e];
-                    if (cnd) { bmin = min(bmin, k); bmax = max(bmax, k); }
-                }
-                lc_leaf_select_range(bmin, bmax, sel_sh);
-                lc_barrier_lds();
-                const uint32_t thr = lc_leaf_select<LC_DEC_THREADS>(M, skey, slen, (long long)remW,
-                                                                    count_c ? (long long)remC : 0x7fffffffLL, sel_sh);
-                __syncthreads();
-#pragma unroll
-                for (int e = 0; e < EC; ++e) {
-                    const int len_e = cln[e], old_e = stok[e];
-                    const bool in = ((cutm[e] >> lane) & 1ull) && skey[j0 + 64 * e] > thr;
-                    stok[e] = in ? len_e : old_e;
-                }
-            }
-        }
-        LC_LSTAMP0(12);
-        // ---- token offsets in id order: EC independent wavefront scans, their totals chained, then
-        // the four wavefront totals
-        {
-            int inc[EC], tot[EC];
-#pragma unroll
-            for (int e = 0; e < EC; ++e) inc[e] = lc_wave_scan_incl(stok[e]);
-#pragma unroll
-            for (int e = 0; e < EC; ++e) tot[e] = lc_readlane(inc[e], 63);
-            int run = 0;
-#pragma unroll
-            for (int e = 0; e < EC; ++e) {
-                coff[e] = run + inc[e] - stok[e];
-                run += tot[e];
-            }
-            if (lane == 0) fs.wtok[wave] = run;
-        }
-        const bool want_ids = a.ids_out != nullptr && s == 0;
-        int crank[EC];
-        if (want_ids) {                                             // (uniform) the same for the chunk counts
-            int inc[EC], tot[EC];
-#pragma unroll
-            for (int e = 0; e < EC; ++e) inc[e] = lc_wave_scan_incl(stok[e] > 0 ? 1 : 0);
-#pragma unroll
-            for (int e = 0; e < EC; ++e) tot[e] = lc_readlane(inc[e], 63);
-            int run = 0;
-#pragma unroll
-            for (int e = 0; e < EC; ++e) {
-                crank[e] = run + inc[e] - (stok[e] > 0 ? 1 : 0);
-                run += tot[e];
-            }
-            if (lane == 0) fs.wcnt[wave] = run;
-        }
-        lc_barrier_lds();
-#pragma unroll
-        for (int w = 0; w < LC_DEC_THREADS / 64; ++w) {
-            const int wt = fs.wtok[w];
-            if (w < wave) base_tok += wt;
-            n_sel_tok += wt;
-        }
-        tail_ln = max(0, T - tail_st);
-        n_tok = n_sel_tok + tail_ln;
-        if (want_ids) {                                             // the chunk list, for callers that want it
-            int base_cnt = 0;
-#pragma unroll
-            for (int w = 0; w < LC_DEC_THREADS / 64; ++w) {
-                const int wc = fs.wcnt[w];
-                if (w < wave) base_cnt += wc;
-                n_sel += wc;
-            }
-            int32_t* io = a.ids_out + (size_t)bh * a.cap;
-#pragma unroll
-            for (int e = 0; e < EC; ++e) {
-                const int r = base_cnt + crank[e];
-                if (stok[e] > 0 && r < a.cap) io[r] = j0 + 64 * e;
-            }
-            if (tid == 0 && a.counts_out != nullptr) a.counts_out[bh] = min(n_sel, a.cap);
-        }
-        n_runs = n_sel + 1;
+        lc_select_chunks<LC_DEC_THREADS, EC>(ix, b, bh, a.keys, a.budget, a.sink, s == 0 ? a.ids_out : nullptr,
+                                             a.counts_out, a.cap, sel_store, fused_store, lds_dyn, cs);
+        T = cs.T;
+        M = cs.M;
+        n_tok = cs.n_tok;
+        n_runs = cs.n_sel + 1;
     }
     LC_LSTAMP0(1);
     int S_eff = (n_tok + LC_DEC_MIN_TOKENS_PER_SPLIT - 1) / LC_DEC_MIN_TOKENS_PER_SPLIT;
@@ -619,16 +301,16 @@ lc_decode_kernel(const LcDecodeArgs a) {
                 };
 #pragma unroll
                 for (int e = 0; e < EC; ++e) {
-                    const int off = base_tok + coff[e];
-                    unsigned long long mask = __ballot(stok[e] > 0 && off < tile0 + tl && tile0 < off + stok[e]);
+                    const int off = cs.base_tok + cs.coff[e];
+                    unsigned long long mask = __ballot(cs.stok[e] > 0 && off < tile0 + tl && tile0 < off + cs.stok[e]);
                     while (mask != 0ull) {
                         const int l = __ffsll((long long)mask) - 1;
                         mask &= mask - 1ull;
-                        fill(lc_readlane(off, l), lc_readlane(cst[e], l), lc_readlane(stok[e], l));
+                        fill(lc_readlane(off, l), lc_readlane(cs.cst[e], l), lc_readlane(cs.stok[e], l));
                     }
                 }
-                if (wave == 0 && tail_ln > 0 && n_sel_tok < tile0 + tl && tile0 < n_sel_tok + tail_ln)
-                    fill(n_sel_tok, tail_st, tail_ln);
+                if (wave == 0 && cs.tail_ln > 0 && cs.n_sel_tok < tile0 + tl && tile0 < cs.n_sel_tok + cs.tail_ln)
+                    fill(cs.n_sel_tok, cs.tail_st, cs.tail_ln);
                 LC_LSTAMP0(17);
                 lc_barrier_lds();
             } else {
@@ -869,7 +551,6 @@ static void fill_common(LcDecodeArgs& a, const lc_index* idx, const LcWs& ws, co
     a.counts_out = nullptr;
     a.budget = 0;
     a.sink = 0;
-    a.count_limit = 0;
     a.ew = 0;
     a.max_tokens = idx->cfg.max_tokens;
 }
@@ -932,7 +613,6 @@ int lc_launch_decode_fused(const lc_index* idx, const LcWs& ws, const void* q, c
     a.cap = cap;
     a.budget = budget;
     a.sink = idx->cfg.sink_tokens;
-    a.count_limit = (idx->cfg.policy == LC_POLICY_BEAM && idx->cfg.beam[0] > 0) ? idx->cfg.beam[0] : 0;
     a.ew = ((max_M > 0 ? max_M : 1) + LC_DEC_THREADS - 1) / LC_DEC_THREADS;
     if (a.ew > LC_DEC_EC_MAX) return LC_ERR_CAPACITY;
     switch (G) {

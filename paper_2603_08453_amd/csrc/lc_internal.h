@@ -82,6 +82,10 @@ extern "C" int lc_decode_step_impl(const lc_index* idx, const void* q, const voi
                                    int32_t* chunk_ids, int32_t* counts, int cap, void* ws, size_t ws_bytes,
                                    void* stream, bool second_kernel_only);
 
+// Limits of the two level walks (pure host functions).
+int lc_walk_max_internal_nodes();   // exact walk: internal nodes of one (sequence, head), all levels together
+int lc_beam_max_level_nodes();      // top-k per level: nodes of one internal level of one (sequence, head)
+
 // Launchers (each enqueues on `stream` and returns LC_OK or LC_ERR_HIP).
 int lc_launch_build(const lc_index* idx, const LcWs& ws, const void* K, const int64_t ks[3],
                     int max_M, hipStream_t stream);

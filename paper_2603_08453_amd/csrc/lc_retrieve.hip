@@ -20,10 +20,12 @@
 #include "lc_internal.h"
 
 #define LC_TAU_SLACK 1e-3f
+#define LC_WALK_LDS_LIMIT (150 * 1024)   // dynamic LDS a walking workgroup may take
 #define LC_COUNT_SELECT_MAX 1024         // up to this many candidates the O(n^2 / threads) rank is used
 
 LC_STAMP_DECL(lc_dbg_upper)
 LC_STAMP_DECL(lc_dbg_leaf)
+LC_STAMP_DECL(lc_dbg_beam)
 #ifdef LC_DBG_TIMES
 extern "C" int lc_dbg_sel_read(unsigned long long* host) {
     return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(lc_dbg_sel), sizeof(lc_dbg_sel));
@@ -191,111 +193,6 @@ lc_upper_kernel(const LcRetrieveArgs a) {
         while (l + 1 < L && u >= off_sh[l + 1]) ++l;
         return l;
     };
-    if (a.policy == LC_POLICY_BEAM) {
-        // ---- top-k per level (Algorithm 1): only the children of the kept nodes are ever scored.
-        // Candidates of a level sit in a compact list in ascending node order (so that equal scores
-        // fall to the lower id); per level: score the list, rank it, flag the kept nodes, gather
-        // their children.
-        uint8_t* want_b = a.want + (size_t)bh * ix.cap[0];
-        const int o1b = off_sh[1];
-        const int n_1b = off_sh[2 < L ? 2 : L] - o1b;
-        if (a.budget <= 0) {
-            for (int i = tid; i < n_1b; i += LC_UP_THREADS) want_b[i] = 0;
-            return;
-        }
-        for (int u = tid; u < NU; u += LC_UP_THREADS) {
-            const int l = level_of(u);
-            upar[u] = ix.parent[l][(size_t)bh * ix.cap[l] + (u - off_sh[l])];
-            kp[u] = 0;
-        }
-        int* cid = reinterpret_cast<int*>(ekB);              // candidate node ids (within their level)
-        int* cid_next = ewB;
-        uint8_t* cflag = reinterpret_cast<uint8_t*>(untok);  // kept flag per list position
-        int n_c = off_sh[L] - off_sh[L - 1];
-        for (int i = tid; i < n_c; i += LC_UP_THREADS) cid[i] = i;
-        __syncthreads();
-        for (int l = L - 1; l >= 1; --l) {
-            const int o = off_sh[l];
-            if (n_c <= LC_UP_GROUPS) {            // a short list: one node per group, nothing to batch
-                if (grp < n_c) {
-                    const size_t n = (size_t)bh * ix.cap[l] + cid[grp];
-                    const LcNodeFrag f = lc_load_node(ix.center[l] + n * LC_D, sub);
-                    const float R = ix.radius[l][n];
-                    const int nc = ix.nchunk[l][n];
-                    float sc = score_node(f, R);
-                    if (nc <= 0) sc = LC_NEG_INF;
-                    if (sub == 0) { ekA[grp] = lc_score_key(sc); ewA[grp] = 0; }
-                }
-            } else {
-                for (int i0 = grp; i0 < n_c; i0 += NB * LC_UP_GROUPS) {
-                    LcNodeFrag f[NB];
-                    float R[NB];
-                    int nc[NB];
-#pragma unroll
-                    for (int k = 0; k < NB; ++k) {
-                        const size_t n = (size_t)bh * ix.cap[l] + cid[min(i0 + k * LC_UP_GROUPS, n_c - 1)];
-                        f[k] = lc_load_node(ix.center[l] + n * LC_D, sub);
-                        R[k] = ix.radius[l][n];
-                        nc[k] = ix.nchunk[l][n];
-                    }
-#pragma unroll
-                    for (int k = 0; k < NB; ++k) {
-                        const int i = i0 + k * LC_UP_GROUPS;
-                        float sc = score_node(f[k], R[k]);
-                        if (nc[k] <= 0) sc = LC_NEG_INF;
-                        if (sub == 0 && i < n_c) { ekA[i] = lc_score_key(sc); ewA[i] = 0; }
-                    }
-                }
-            }
-            if (tid < 4 && n_c + tid < ((n_c + 3) & ~3)) { ekA[n_c + tid] = 0u; ewA[n_c + tid] = 0; }
-            __syncthreads();
-            LC_STAMP0(lc_dbg_upper, 8 + 3 * (L - 1 - l));
-            const long long C = a.beam[l] > 0 ? a.beam[l] : 0x7fffffffLL;
-            if (n_c <= LC_COUNT_SELECT_MAX) {
-                uint32_t mk;
-                int reached;
-                lc_small_select<LC_UP_THREADS, false>(n_c, 0, 0x7fffffffffffLL, C, ekA, ewA, cflag, sel_sh, &mk, &reached);
-            } else {
-                auto keyf = [&](int i) -> uint32_t { return ekA[i]; };
-                auto wf = [&](int) -> int { return 0; };
-                const LcSel r = lc_block_select<LC_UP_THREADS>(n_c, 0x7fffffffffffLL, C, keyf, wf, sel_sh);
-                int tie_c = 0;
-                for (int t0 = 0; t0 < n_c; t0 += LC_UP_THREADS) {
-                    const int i = t0 + tid;
-                    const uint32_t k = (i < n_c) ? ekA[i] : 0u;
-                    const int eq = (!r.all && k != 0u && k == r.kstar) ? 1 : 0;
-                    int tot;
-                    const int ex = lc_block_scan<LC_UP_THREADS>(eq, sel_sh, &tot);
-                    if (i < n_c) cflag[i] = (k != 0u && (k > r.kstar || (eq && tie_c + ex + 1 <= r.remC))) ? 1 : 0;
-                    tie_c += tot;
-                }
-            }
-            __syncthreads();
-            for (int i = tid; i < n_c; i += LC_UP_THREADS)
-                if (cflag[i]) kp[o + cid[i]] = 1;
-            __syncthreads();
-            LC_STAMP0(lc_dbg_upper, 9 + 3 * (L - 1 - l));
-            if (l >= 2) {                     // the kept nodes' children, in ascending order
-                const int ob = off_sh[l - 1], n_b = off_sh[l] - ob;
-                int n_new = 0;
-                for (int base = 0; base < n_b; base += LC_UP_THREADS) {
-                    const int i = base + tid;
-                    const int in = (i < n_b && kp[o + upar[ob + i]]) ? 1 : 0;
-                    int tot;
-                    const int ex = lc_block_scan<LC_UP_THREADS>(in, sel_sh, &tot);
-                    if (in) cid_next[n_new + ex] = i;
-                    n_new += tot;
-                }
-                __syncthreads();
-                int* t = cid; cid = cid_next; cid_next = t;
-                n_c = n_new;
-                if (n_c == 0) break;          // nothing below the kept nodes: no chunk is wanted
-            }
-        }
-        for (int i = tid; i < n_1b; i += LC_UP_THREADS) want_b[i] = kp[o1b + i];
-        LC_STAMP0(lc_dbg_upper, 7);
-        return;
-    }
     for (int u = tid; u < NU; u += LC_UP_THREADS) {
         const int l = level_of(u);
         const size_t n = (size_t)bh * ix.cap[l] + (u - off_sh[l]);
@@ -347,7 +244,7 @@ lc_upper_kernel(const LcRetrieveArgs a) {
     int* ew = ewA;
     uint32_t* ek_next = ekB;
     int* ew_next = ewB;
-    const bool with_tokens = a.policy == LC_POLICY_EXACT;
+    const bool with_tokens = true;
     {
         const int o = off_sh[L - 1], n_l = off_sh[L] - o;
         for (int i = tid; i < ((n_l + 3) & ~3); i += LC_UP_THREADS) {
@@ -360,26 +257,7 @@ lc_upper_kernel(const LcRetrieveArgs a) {
         const int o = off_sh[l], n_l = off_sh[l + 1] - o;
         uint32_t mk;
         int reached;
-        if (a.policy == LC_POLICY_BEAM) {
-            const long long C = a.beam[l] > 0 ? a.beam[l] : 0x7fffffffLL;
-            if (n_l <= LC_COUNT_SELECT_MAX) {
-                lc_small_select<LC_UP_THREADS, false>(n_l, 0, 0x7fffffffffffLL, C, ek, ew, kp + o, sel_sh, &mk, &reached);
-            } else {
-                auto keyf = [&](int i) -> uint32_t { return ek[i]; };
-                auto wf = [&](int) -> int { return 0; };
-                const LcSel r = lc_block_select<LC_UP_THREADS>(n_l, 0x7fffffffffffLL, C, keyf, wf, sel_sh);
-                int tie_c = 0;
-                for (int t0 = 0; t0 < n_l; t0 += LC_UP_THREADS) {
-                    const int i = t0 + tid;
-                    const uint32_t k = (i < n_l) ? ek[i] : 0u;
-                    const int eq = (!r.all && k != 0u && k == r.kstar) ? 1 : 0;
-                    int tot;
-                    const int ex = lc_block_scan<LC_UP_THREADS>(eq, sel_sh, &tot);
-                    if (i < n_l) kp[o + i] = (k != 0u && (k > r.kstar || (eq && tie_c + ex + 1 <= r.remC))) ? 1 : 0;
-                    tie_c += tot;
-                }
-            }
-        } else {
+        {
             // EXACT, probe pass: keep the best frontier nodes until their subtree token counts reach the budget
             if (n_l <= LC_COUNT_SELECT_MAX) {
                 lc_small_select<LC_UP_THREADS, false>(n_l, 1, (long long)a.budget, 0x7fffffffLL, ek, ew, kp + o, sel_sh, &mk, &reached);
@@ -406,10 +284,6 @@ lc_upper_kernel(const LcRetrieveArgs a) {
             int* tw = ew; ew = ew_next; ew_next = tw;
         }
         LC_STAMP0(lc_dbg_upper, 10 + 3 * (L - 1 - l));
-    }
-    if (a.policy == LC_POLICY_BEAM) {
-        write_want();
-        return;
     }
     LC_STAMP0(lc_dbg_upper, 3);
     // ---- compact the probe's chunks (children of the kept level-1 nodes, not pinned) into LDS.
@@ -510,6 +384,324 @@ lc_upper_kernel(const LcRetrieveArgs a) {
     }
     write_want();
     LC_STAMP0(lc_dbg_upper, 7);
+}
+
+
+// ---------------------------------------------------------------------------------
+// top-k per level (Algorithm 1): the whole retrieval in one workgroup per (sequence, head)
+// ---------------------------------------------------------------------------------
+// Only the children of the kept nodes are ever scored, so the work follows the beam sizes, not the
+// size of the index: per level, score the candidate list (ascending node order, so that equal
+// scores fall to the lower id), rank it, mark the kept nodes in a bitmap, gather their children.
+// The chunks under the kept level-1 nodes are scored the same way, cut by the token budget (and the
+// chunk-count limit beam[0]) and written out in ascending order behind the pinned chunks.
+// The lists live in LDS while a level's candidates number at most `chunk_cap`; a longer list goes
+// to the workspace (same code through generic pointers, slower).
+#define LC_BM_THREADS 1024
+#define LC_BM_GROUPS (LC_BM_THREADS / 16)
+#define LC_BM_KEPT_WORDS 2048             // kept bitmap: up to 65536 nodes per internal level
+#define LC_BM_MAX_LEVEL_NODES (LC_BM_KEPT_WORDS * 32)
+#define LC_BM_PF 4                       // chunks per thread whose parent and boundary are fetched at kernel start
+#define LC_BM_RANK_MAX 128               // chunk lists up to this length are ranked directly, longer ones by histogram
+
+__host__ __device__ inline size_t lc_beam_lds_bytes(int cap_l) { return (size_t)cap_l * 17; }
+
+template <int G>
+__global__ void __launch_bounds__(LC_BM_THREADS)
+lc_beam_kernel(const LcRetrieveArgs a) {
+    extern __shared__ int lds_dyn[];
+    __shared__ LcLeafSelSh leaf_sh;
+    __shared__ int sel_sh[LC_SEL_SH];
+    __shared__ uint32_t kept[LC_BM_KEPT_WORDS];
+    constexpr int NB = G <= 6 ? 2 : 1;            // nodes in flight per group (the lists are short; 128 registers per lane)
+
+    LC_STAMP0(lc_dbg_beam, 0);
+    const LcDev& ix = a.ix;
+    const int h = blockIdx.x, b = blockIdx.y;
+    const int bh = b * ix.H + h;
+    const int tid = threadIdx.x;
+    const int sub = tid & 15, grp = tid >> 4;
+    const int L = ix.L;
+    const int cap0 = ix.cap[0];
+    const int M = min(ix.state[bh * 4 + 1], cap0);
+    const int* bnd = ix.bounds + (size_t)b * (cap0 + 1);
+
+    // candidate lists: ids of the current level, ids of the next, keys, weights, kept flags
+    const int CL = a.chunk_cap;
+    int* const l_cid = lds_dyn;
+    int* const l_nxt = lds_dyn + CL;
+    uint32_t* const l_key = reinterpret_cast<uint32_t*>(lds_dyn + 2 * CL);
+    int* const l_wgt = lds_dyn + 3 * CL;
+    uint8_t* const l_flg = reinterpret_cast<uint8_t*>(lds_dyn + 4 * CL);
+    int* const gs = a.scratch + (size_t)bh * 4 * cap0;
+    int* const g_cid = gs;
+    int* const g_nxt = gs + cap0;
+    uint32_t* const g_key = reinterpret_cast<uint32_t*>(gs + 2 * cap0);
+    int* const g_wgt = gs + 3 * cap0;
+    uint8_t* const g_flg = a.want + (size_t)bh * cap0;
+
+    constexpr bool QP = G > 2;                   // (see lc_upper_kernel; this kernel waits for memory, not for the ALU)
+    float qf[QP ? 1 : G][8], qn[G];
+    uint32_t qp[QP ? G : 1][4];
+    if constexpr (QP) lc_load_query_packed<G>(a.q + (size_t)b * ix.H * G * LC_D, h, sub, qp, qn);
+    else lc_load_query_frags<G>(a.q + (size_t)b * ix.H * G * LC_D, h, sub, qf, qn);
+    auto score_node = [&](const LcNodeFrag& f, float R) -> float {
+        if constexpr (QP) return lc_score_frag_packed<G>(f, R, qp, qn);
+        else return lc_score_frag<G>(f, R, qf, qn);
+    };
+
+    // What the chunk stage will need much later -- parents and boundaries of this thread's first
+    // LC_BM_PF chunks (thread t looks at the chunks [t E, t E + E), E = ceil(M / threads)) -- is
+    // fetched now: the arrays are cap0 long, so only the count has to arrive first.
+    const int* par0 = ix.parent[0] + (size_t)bh * cap0;
+    const int EM = (M + LC_BM_THREADS - 1) / LC_BM_THREADS;
+    const int j_lo = min(M, tid * EM), j_hi = min(M, j_lo + EM);
+    int pf_p[LC_BM_PF], pf_s[LC_BM_PF];
+#pragma unroll
+    for (int k = 0; k < LC_BM_PF; ++k) {
+        const int j = min(j_lo + k, cap0 - 1);
+        pf_p[k] = L > 1 ? par0[j] : 0;
+        pf_s[k] = bnd[j];
+    }
+
+    // optional score output: everything that is never scored reads -inf
+    float* scores = a.scores ? a.scores + (size_t)bh * cap0 : nullptr;
+    if (scores)
+        for (int j = tid; j < M; j += LC_BM_THREADS) scores[j] = LC_NEG_INF;
+
+    // ---- top level: every node is a candidate
+    int n_c = L > 1 ? ix.nlev[b * LC_MAX_LEVELS + (L - 1)] : 0;
+    bool in_lds = n_c <= CL;
+    int* cid = in_lds ? l_cid : g_cid;
+    for (int i = tid; i < n_c; i += LC_BM_THREADS) cid[i] = i;
+    __syncthreads();
+
+    LC_STAMP0(lc_dbg_beam, 1);
+    for (int l = L - 1; l >= 1; --l) {
+        uint32_t* key = in_lds ? l_key : g_key;
+        int* wgt = in_lds ? l_wgt : g_wgt;
+        uint8_t* flg = in_lds ? l_flg : g_flg;
+        // ---- score the candidates of this level
+        for (int i0 = grp; i0 < n_c; i0 += NB * LC_BM_GROUPS) {
+            LcNodeFrag f[NB];
+            float R[NB];
+            int nc[NB];
+#pragma unroll
+            for (int k = 0; k < NB; ++k) {
+                const size_t n = (size_t)bh * ix.cap[l] + cid[min(i0 + k * LC_BM_GROUPS, n_c - 1)];
+                f[k] = lc_load_node(ix.center[l] + n * LC_D, sub);
+                R[k] = ix.radius[l][n];
+                nc[k] = ix.nchunk[l][n];
+            }
+#pragma unroll
+            for (int k = 0; k < NB; ++k) {
+                const int i = i0 + k * LC_BM_GROUPS;
+                float sc = score_node(f[k], R[k]);
+                if (nc[k] <= 0) sc = LC_NEG_INF;
+                if (sub == 0 && i < n_c) { key[i] = lc_score_key(sc); wgt[i] = 0; }
+            }
+        }
+        if (in_lds && tid < 4 && n_c + tid < ((n_c + 3) & ~3)) { key[n_c + tid] = 0u; wgt[n_c + tid] = 0; }
+        __syncthreads();
+        LC_STAMP0(lc_dbg_beam, 2 + 4 * (L - 1 - l));
+        // ---- keep the beam[l] best
+        const long long C = a.beam[l] > 0 ? a.beam[l] : 0x7fffffffLL;
+        if (in_lds && n_c <= LC_COUNT_SELECT_MAX) {
+            uint32_t mk;
+            int reached;
+            lc_small_select<LC_BM_THREADS, false>(n_c, 0, 0x7fffffffffffLL, C, key, wgt, flg, sel_sh, &mk, &reached);
+        } else {
+            auto keyf = [&](int i) -> uint32_t { return key[i]; };
+            auto wf = [&](int) -> int { return 0; };
+            const LcSel r = lc_block_select<LC_BM_THREADS>(n_c, 0x7fffffffffffLL, C, keyf, wf, sel_sh);
+            int tie_c = 0;
+            for (int t0 = 0; t0 < n_c; t0 += LC_BM_THREADS) {
+                const int i = t0 + tid;
+                const uint32_t k = (i < n_c) ? key[i] : 0u;
+                const int eq = (!r.all && k != 0u && k == r.kstar) ? 1 : 0;
+                int tot;
+                const int ex = lc_block_scan<LC_BM_THREADS>(eq, sel_sh, &tot);
+                if (i < n_c) flg[i] = (k != 0u && (k > r.kstar || (eq && tie_c + ex + 1 <= r.remC))) ? 1 : 0;
+                tie_c += tot;
+            }
+        }
+        LC_STAMP0(lc_dbg_beam, 3 + 4 * (L - 1 - l));
+        // ---- bitmap of the kept nodes
+        const int n_l = ix.nlev[b * LC_MAX_LEVELS + l];
+        for (int i = tid; i < (n_l + 31) / 32; i += LC_BM_THREADS) kept[i] = 0u;
+        __syncthreads();
+        for (int i = tid; i < n_c; i += LC_BM_THREADS)
+            if (flg[i]) atomicOr(&kept[cid[i] >> 5], 1u << (cid[i] & 31));
+        __syncthreads();
+        LC_STAMP0(lc_dbg_beam, 4 + 4 * (L - 1 - l));
+        if (l == 1) break;
+        // ---- the kept nodes' children, in ascending order: count them, pick where the list goes, write it
+        const int n_b = ix.nlev[b * LC_MAX_LEVELS + (l - 1)];
+        const int* par = ix.parent[l - 1] + (size_t)bh * ix.cap[l - 1];
+        auto is_child = [&](int i) -> int {
+            if (i >= n_b) return 0;
+            const int p = par[i];
+            return (p >= 0 && p < n_l && ((kept[p >> 5] >> (p & 31)) & 1u)) ? 1 : 0;
+        };
+        // (thread t looks at the nodes [t E, t E + E): one count, one scan, one write pass)
+        const int E = (n_b + LC_BM_THREADS - 1) / LC_BM_THREADS;
+        const int i_lo = min(n_b, tid * E), i_hi = min(n_b, i_lo + E);
+        int n_new = 0, mine = 0;
+#pragma unroll 2
+        for (int i = i_lo; i < i_hi; ++i) mine += is_child(i);
+        int pos = lc_block_scan<LC_BM_THREADS>(mine, sel_sh, &n_new);
+        const bool nxt_lds = n_new <= CL;
+        int* nxt = nxt_lds ? (cid == l_cid ? l_nxt : l_cid) : (cid == g_cid ? g_nxt : g_cid);
+        if (mine > 0) {
+#pragma unroll 2
+            for (int i = i_lo; i < i_hi; ++i)
+                if (is_child(i)) nxt[pos++] = i;
+        }
+        __syncthreads();
+        LC_STAMP0(lc_dbg_beam, 5 + 4 * (L - 1 - l));
+        cid = nxt;
+        in_lds = nxt_lds;
+        n_c = n_new;
+    }
+
+    // ---- chunks: children of the kept level-1 nodes (every chunk if the index has no level above
+    // them), without the pinned ones; the pinned chunks are the leading ones and are counted here
+    const int W = a.budget > 0 ? a.budget : 0;
+    const int n_1 = L > 1 ? ix.nlev[b * LC_MAX_LEVELS + 1] : 0;
+    auto chunk_state_of = [&](int j, int start, int p) -> int {        // 0 = not a candidate, 1 = candidate, 2 = pinned
+        if (j >= M) return 0;
+        if (start < a.sink) return 2;
+        if (W <= 0) return 0;
+        if (L == 1) return 1;
+        return (p >= 0 && p < n_1 && ((kept[p >> 5] >> (p & 31)) & 1u)) ? 1 : 0;
+    };
+    auto chunk_state = [&](int j) -> int { return j < M ? chunk_state_of(j, bnd[j], L > 1 ? par0[j] : 0) : 0; };
+    LC_STAMP0(lc_dbg_beam, 20);
+    int n_pin = 0;
+    n_c = 0;
+    {
+        // (the verdicts of the prefetched chunks stay in a register mask; longer runs read memory)
+        unsigned pf_cand = 0u;
+        int mine = 0, pins = 0;
+#pragma unroll
+        for (int k = 0; k < LC_BM_PF; ++k) {
+            const int st = j_lo + k < j_hi ? chunk_state_of(j_lo + k, pf_s[k], pf_p[k]) : 0;
+            if (st == 1) pf_cand |= 1u << k;
+            mine += st == 1 ? 1 : 0;
+            pins += st == 2 ? 1 : 0;
+        }
+#pragma unroll 2
+        for (int j = j_lo + LC_BM_PF; j < j_hi; ++j) {
+            const int st = chunk_state(j);
+            mine += st == 1 ? 1 : 0;
+            pins += st == 2 ? 1 : 0;
+        }
+        int pos, e1;
+        lc_block_scan2<LC_BM_THREADS>(mine, pins, sel_sh, &pos, &e1, &n_c, &n_pin);
+        in_lds = n_c <= CL;
+        int* nxt = in_lds ? (cid == l_cid ? l_nxt : l_cid) : (cid == g_cid ? g_nxt : g_cid);
+        if (mine > 0) {
+#pragma unroll
+            for (int k = 0; k < LC_BM_PF; ++k)
+                if ((pf_cand >> k) & 1u) nxt[pos++] = j_lo + k;
+#pragma unroll 2
+            for (int j = j_lo + LC_BM_PF; j < j_hi; ++j)
+                if (chunk_state(j) == 1) nxt[pos++] = j;
+        }
+        cid = nxt;
+    }
+    lc_leaf_select_prepare<LC_BM_THREADS>(leaf_sh);
+    __syncthreads();
+    LC_STAMP0(lc_dbg_beam, 21);
+    uint32_t* key = in_lds ? l_key : g_key;
+    int* wgt = in_lds ? l_wgt : g_wgt;
+    // ---- score them: key and length per candidate
+    {
+        const size_t cb = (size_t)bh * cap0;
+        const bool c0b = ix.c0_bf16 != 0;
+        uint32_t kmin = 0xffffffffu, kmax = 0u;
+        constexpr int NBC = G <= 2 ? 4 : (G <= 4 ? 3 : NB);     // (little else is live here)
+        for (int i0 = grp; i0 < n_c; i0 += NBC * LC_BM_GROUPS) {
+            LcNodeFrag f[NBC];
+            float R[NBC];
+            int s0[NBC], s1[NBC], jj[NBC];
+#pragma unroll
+            for (int k = 0; k < NBC; ++k) {
+                const int j = cid[min(i0 + k * LC_BM_GROUPS, n_c - 1)];
+                jj[k] = j;
+                f[k] = lc_load_chunk_node(ix.center[0], c0b, cb + j, sub);
+                R[k] = ix.radius[0][cb + j];
+                s0[k] = bnd[j];
+                s1[k] = bnd[j + 1];
+            }
+#pragma unroll
+            for (int k = 0; k < NBC; ++k) {
+                const int i = i0 + k * LC_BM_GROUPS;
+                const float sc = score_node(c0b ? lc_widen_chunk_frag(f[k]) : f[k], R[k]);
+                uint32_t kk = lc_score_key(sc);
+                if (kk == 0xffffffffu) kk = 0xfffffffeu;           // the select routine's mark is reserved
+                if (sub == 0 && i < n_c) {
+                    key[i] = kk;
+                    wgt[i] = max(0, s1[k] - s0[k]);
+                    if (scores) scores[jj[k]] = sc;
+                }
+                if (i < n_c && kk != 0u) { kmin = min(kmin, kk); kmax = max(kmax, kk); }
+            }
+        }
+        lc_leaf_select_range(kmin, kmax, leaf_sh);
+    }
+    if (in_lds && tid < 4 && n_c + tid < ((n_c + 3) & ~3)) { key[n_c + tid] = 0u; wgt[n_c + tid] = 0; }
+    __syncthreads();
+    LC_STAMP0(lc_dbg_beam, 22);
+    const long long C0 = a.beam[0] > 0 ? a.beam[0] : 0x7fffffffLL;
+    uint8_t* flg = in_lds ? l_flg : g_flg;
+    if (in_lds && n_c <= LC_BM_RANK_MAX) {
+        // a short list: every chunk is ranked against the others directly
+        uint32_t mk;
+        int reached;
+        lc_small_select<LC_BM_THREADS, false>(n_c, 0, (long long)W, C0, key, wgt, flg, sel_sh, &mk, &reached);
+    } else {
+        const uint32_t thr = lc_leaf_select<LC_BM_THREADS>(n_c, key, wgt, (long long)W, C0, leaf_sh);
+        __syncthreads();
+        for (int i = tid; i < n_c; i += LC_BM_THREADS) flg[i] = key[i] > thr ? 1 : 0;
+    }
+    __syncthreads();
+    LC_STAMP0(lc_dbg_beam, 23);
+    // ---- the chunk list: pinned chunks (ids 0 .. n_pin - 1), then the selected candidates in ascending order
+    int32_t* ids = a.ids + (size_t)bh * a.cap;
+    for (int j = tid; j < min(n_pin, a.cap); j += LC_BM_THREADS) ids[j] = j;
+    int n_sel = 0;
+    {
+        const int E = (n_c + LC_BM_THREADS - 1) / LC_BM_THREADS;
+        const int i_lo = min(n_c, tid * E), i_hi = min(n_c, i_lo + E);
+        int mine = 0;
+        for (int i = i_lo; i < i_hi; ++i) mine += flg[i] ? 1 : 0;
+        int pos = n_pin + lc_block_scan<LC_BM_THREADS>(mine, sel_sh, &n_sel);
+        for (int i = i_lo; i < i_hi; ++i) {
+            if (flg[i]) {
+                if (pos < a.cap) ids[pos] = cid[i];
+                ++pos;
+            }
+        }
+    }
+    const int pos0 = n_pin + n_sel;
+    LC_STAMP0(lc_dbg_beam, 24);
+    if (tid == 0) a.counts[bh] = min(pos0, a.cap);
+}
+
+template <int G>
+static int launch_beam_g(LcRetrieveArgs& a, int max_nodes, hipStream_t stream) {
+    // LDS lists for up to 4096 candidates per level (more go to the workspace)
+    int cl = ((max_nodes > 0 ? max_nodes : 1) + 63) / 64 * 64;
+    if (cl > 4096) cl = 4096;
+    a.chunk_cap = cl;
+    const size_t lds = lc_beam_lds_bytes(cl);
+    if (lds + sizeof(LcLeafSelSh) + LC_SEL_SH * 4 + LC_BM_KEPT_WORDS * 4 + 256 > 48 * 1024)
+        LC_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&lc_beam_kernel<G>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(lc_beam_kernel<G>, dim3(a.ix.H, a.ix.B), dim3(LC_BM_THREADS), lds, stream, a);
+    LC_HIP_CHECK(hipGetLastError());
+    return LC_OK;
 }
 
 // Kernel 2 runs 1024 threads = 64 groups: one chunk per group while scoring; the last workgroup
@@ -736,6 +928,7 @@ lc_score_kernel(const LcRetrieveArgs a) {
     }
 }
 
+
 template <int G, int R>
 static int launch_score(const LcRetrieveArgs& a, int max_M, hipStream_t stream) {
     const int per = R * (LC_SC_THREADS / 16);
@@ -768,7 +961,8 @@ template <int G>
 static int launch_retrieve_g(LcRetrieveArgs& a, int max_M, hipStream_t stream) {
     const LcDev& ix = a.ix;
     const int mc = ((max_M + 63) / 64) * 64;
-    const size_t lds_limit = 150 * 1024;
+    const size_t lds_limit = LC_WALK_LDS_LIMIT;
+    if (a.policy == LC_POLICY_BEAM) return launch_beam_g<G>(a, a.upper_cap > max_M ? a.upper_cap : max_M, stream);
     if (a.walk) {
         // as long a probe list as LDS holds next to the internal-node slots
         const int uc = a.upper_cap;
@@ -805,6 +999,14 @@ static int launch_retrieve_g(LcRetrieveArgs& a, int max_M, hipStream_t stream) {
     if (r == 4) return launch_leaf<G, 4>(a, max_M, lds2, stream);
     return launch_leaf<G, 8>(a, max_M, lds2, stream);
 }
+
+// Most internal nodes of one (sequence, head) that the exact level walk holds in LDS (with the shortest probe list).
+int lc_walk_max_internal_nodes() {
+    int uc = 64;
+    while (lc_upper_lds_bytes(uc + 64, 64) <= (size_t)LC_WALK_LDS_LIMIT) uc += 64;
+    return uc;
+}
+int lc_beam_max_level_nodes() { return LC_BM_MAX_LEVEL_NODES; }
 
 int lc_launch_retrieve(const lc_index* idx, const LcWs& ws, const void* q, int G, int budget,
                        int32_t* ids, int32_t* counts, float* scores, int cap,
