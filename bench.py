@@ -45,10 +45,149 @@ def parse():
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--stream-steps", type=int, default=0, help="streaming workload: decode steps (0 = the workload's own)")
     ap.add_argument("--pmc-mode", action="store_true",
                     help="for rocprofv3 --pmc runs: eager steps only, then a plain device copy of known size "
                          "(2 x 256 MiB) that calibrates the byte counters")
     return ap.parse_args()
+
+
+
+def bench_stream(args, w):
+    """The streaming configuration: a prefill, then `w.stream_steps` real decode steps, each of them
+    lc_append (one new token; the open chunk closes at the drawn lengths and is grafted lazily)
+    followed by lc_decode_step on the grown sequence.  Four passes, each on an index of its own:
+    append + decode and append alone, launched eagerly and replayed from one HIP graph that holds
+    every step of the stream as its own nodes (the close decisions are by-value kernel arguments, so
+    each step keeps its own).  One (K, V, index) per pass, 143 MB: the rows stay in the last-level cache
+    between steps, as they would in a real stream."""
+    import torch
+    from paper_2603_08453_amd import binding as lc
+    lc.lib()
+    dev = torch.device("cuda:0")
+    G, steps = w.G, (w.stream_steps if args.stream_steps <= 0 else args.stream_steps)
+    s0 = wl.make_sequence(w, 0, w.T)
+    st = wl.make_stream(w, 0, steps)
+    M0 = len(s0.bounds) - 1
+    n_close = int(st.close.sum())
+    cfg = lc.lc_config_default(levels=w.levels, fanout=w.fanout, max_chunks=M0 + n_close + 8,
+                               max_tokens=w.T + steps + 8, decode_splits=args.splits)
+    to_t = lambda bits: torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(torch.bfloat16)
+    k_dev, v_dev, q_dev = to_t(st.k).to(dev), to_t(st.v).to(dev), to_t(st.q).to(dev)
+    K0 = torch.zeros((1, w.H_kv, cfg.max_tokens, w.d), dtype=torch.bfloat16, device=dev)
+    V0 = torch.zeros_like(K0)
+    K0[0, :, : s0.T] = to_t(s0.K).to(dev)
+    V0[0, :, : s0.T] = to_t(s0.V).to(dev)
+    out = torch.zeros((1, w.H_q, w.d), dtype=torch.float32, device=dev)
+
+    def fresh():
+        K, V = K0.clone(), V0.clone()
+        ib = torch.zeros(lc.lc_index_bytes(cfg, 1, w.H_kv), dtype=torch.uint8, device=dev)
+        ws = torch.zeros(lc.lc_workspace_bytes(cfg, 1, w.H_q, w.H_kv), dtype=torch.uint8, device=dev)
+        idx = lc.lc_build_index(cfg, K, [s0.T], [s0.bounds], ib, ws)
+        torch.cuda.synchronize()
+        return dict(K=K, V=V, ib=ib, ws=ws, idx=idx)
+
+    def run(rp, with_decode, lo, hi):
+        for t in range(lo, hi):
+            lc.lc_append(rp["idx"], rp["K"], rp["V"], k_dev[t:t + 1], v_dev[t:t + 1], [int(st.close[t])], rp["ws"])
+            if with_decode:
+                lc.lc_decode_step(rp["idx"], q_dev[t:t + 1], rp["K"], rp["V"], w.budget, out, rp["ws"])
+
+    def eager(with_decode):
+        rp = fresh()
+        run(rp, with_decode, 0, args.warmup)              # warm-up steps are part of the stream, untimed
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        run(rp, with_decode, args.warmup, steps)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) / (steps - args.warmup) * 1e6, rp
+
+    def graphed(with_decode):
+        rp = fresh()
+        side = torch.cuda.Stream()
+        run(rp, with_decode, 0, args.warmup)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(g, stream=side):
+                run(rp, with_decode, args.warmup, steps)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        g.replay()                                        # once: a second replay would append the stream again
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / (steps - args.warmup), rp
+
+    step_eager, rp_e = eager(True)
+    app_eager, _ = eager(False)
+    step_graph = app_graph = None
+    rp_g = None
+    if not args.no_graph:
+        step_graph, rp_g = graphed(True)
+        app_graph, _ = graphed(False)
+    # both full passes must end in the same state and give the same last output
+    T_e, M_e, _ = rp_e["idx"].info(0)
+    assert (T_e, M_e) == (w.T + steps, M0 + n_close), (T_e, M_e)
+    if rp_g is not None:
+        assert rp_g["idx"].info(0)[:2] == (T_e, M_e)
+        a = lc.unpack_blob(lc.lc_index_export(rp_e["idx"]))["seqs"][0]
+        b = lc.unpack_blob(lc.lc_index_export(rp_g["idx"]))["seqs"][0]
+        assert all(np.array_equal(a["heads"][h][l]["center"], b["heads"][h][l]["center"])
+                   for h in range(w.H_kv) for l in range(w.levels)), "graph replay and eager stream diverged"
+
+    # the dominant kernel (selection + attention of lc_decode_step) alone, on the final state
+    rp = rp_e
+    q_last = q_dev[steps - 1:steps]
+    ids = torch.zeros((1, w.H_kv, w.budget + 8), dtype=torch.int32, device=dev)
+    counts = torch.zeros((1, w.H_kv), dtype=torch.int32, device=dev)
+    lc.lc_decode_step(rp["idx"], q_last, rp["K"], rp["V"], w.budget, out, rp["ws"], chunk_ids=ids, counts=counts)
+    torch.cuda.synchronize()
+    blob = lc.unpack_blob(lc.lc_index_export(rp["idx"]))["seqs"][0]
+    lens = np.diff(blob["bounds"].astype(np.int64))
+    ih, ch = ids.cpu().numpy(), counts.cpu().numpy()
+    tok = sum(int(lens[ih[0, h, : ch[0, h]]].sum()) + (T_e - int(blob["bounds"][-1])) for h in range(w.H_kv))
+    dom_bytes = tok * 4 * w.d + w.H_q * w.d * 6 + M_e * w.H_kv * 12
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        lc.lc_bench_select_attend(rp["idx"], q_last, rp["K"], rp["V"], w.budget, out, rp["ws"])
+        side.synchronize()
+        with torch.cuda.graph(g, stream=side):
+            for _ in range(200):
+                lc.lc_bench_select_attend(rp["idx"], q_last, rp["K"], rp["V"], w.budget, out, rp["ws"])
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    g.replay()
+    torch.cuda.synchronize()
+    e0.record()
+    g.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    dom_us = e0.elapsed_time(e1) * 1e3 / 200
+    best = min(x for x in (step_eager, step_graph) if x is not None)
+    res = {
+        "metric": "us per decode step per layer (append + retrieve + attend), streaming",
+        "value": round(best, 2), "unit": "us/step", "n_gpus": 1, "steps": steps - args.warmup, "warmup": args.warmup,
+        "ms_per_step": round(best * 1e-3, 5), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 in, f32 accumulate", "data": "synthetic (seeded; clustered keys, drifting stream)",
+        "config": {"workload": w.name, "batch": 1, "q_heads": w.H_q, "kv_heads": w.H_kv, "head_dim": w.d,
+                   "prefill": w.T, "stream_steps": steps, "chunks_at_start": M0, "chunks_closed": n_close,
+                   "levels": w.levels, "fanout": w.fanout, "budget": w.budget,
+                   "launch": "hip-graph" if best == step_graph else "eager"},
+        "roofline": {"bound": "hbm", "achieved": round(dom_bytes / (dom_us * 1e-6) / 1e9, 1), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(dom_bytes / (dom_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4), "traffic": None,
+                     "kernel": f"lc_decode_kernel<{G}, true, ...>", "bytes_per_launch": round(dom_bytes),
+                     "us_per_launch": round(dom_us, 2),
+                     "note": "one replica, rows resident in the last-level cache: bytes served, not HBM bytes"},
+        "cpu_baseline": None,
+        "extra": {"step_us_eager": round(step_eager, 2), "step_us_graph": None if step_graph is None else round(step_graph, 2),
+                  "append_us_eager": round(app_eager, 2), "append_us_graph": None if app_graph is None else round(app_graph, 2),
+                  "append_share_of_step_graph": None if step_graph is None else round(app_graph / step_graph, 3),
+                  "tokens_attended_last_step": tok},
+    }
+    print(json.dumps(res), flush=True)
 
 
 def main():
@@ -64,6 +203,9 @@ def main():
     dev = torch.device("cuda:0")
     w = wl.WORKLOADS[args.workload]
     G = w.G
+    if w.stream_steps > 0:
+        bench_stream(args, w)
+        return
 
     # ------------------------------------------------------------- inputs
     t0 = time.time()

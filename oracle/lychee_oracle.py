@@ -139,6 +139,9 @@ class Index:
     ntok: List[np.ndarray]
     nchunk: List[np.ndarray]
     center_dtype: int = CENTER_F32
+    min_margin: float = float("inf")   # build only: smallest best-vs-second-best similarity gap the
+                                       # clustering passed through (how near it came to a tie); not
+                                       # part of the stored index
 
     @property
     def M(self) -> int:
@@ -193,7 +196,7 @@ def direction_of(center: np.ndarray) -> np.ndarray:
 
 
 def spherical_kmeans(X: np.ndarray, k: int, iters: int,
-                     trace: Optional[list] = None) -> Tuple[np.ndarray, np.ndarray]:
+                     trace: Optional[list] = None, margins: Optional[list] = None) -> Tuple[np.ndarray, np.ndarray]:
     """Spherical k-means on unit rows X [N, d] (Section 4.3; Appendix A: 10 iterations).
 
     Similarity is the inner product.  Initial centroid c is the point with
@@ -203,7 +206,9 @@ def spherical_kmeans(X: np.ndarray, k: int, iters: int,
     (or a zero sum) keeps its previous centroid.  Returns (labels, centroids)
     where labels come from the last assignment and centroids from the last
     update.  `trace`, if given, receives the objective sum_i <x_i, m_label(i)>
-    measured right after each assignment.
+    measured right after each assignment; `margins`, if given, receives per
+    iteration the smallest gap between a point's best and second-best similarity
+    (how close the assignment came to a tie; instrumentation only).
     """
     N = X.shape[0]
     m = np.stack([X[(c * N) // k] for c in range(k)]).astype(np.float64)
@@ -213,6 +218,9 @@ def spherical_kmeans(X: np.ndarray, k: int, iters: int,
         labels = np.argmax(sim, axis=1)                 # first maximum = lowest id
         if trace is not None:
             trace.append(float(sim[np.arange(N), labels].sum()))
+        if margins is not None and k >= 2 and N > 0:
+            top2 = np.partition(sim, k - 2, axis=1)[:, k - 2:]
+            margins.append(float((top2[:, 1] - top2[:, 0]).min()))
         for c in range(k):
             members = X[labels == c]
             if len(members) == 0:
@@ -266,7 +274,10 @@ def build_index(K: np.ndarray, bounds: Sequence[int], T: int, L: int, F,
         k = max(1, -(-N // level_fanout(F, level)))
         X = np.stack([direction_of(c) for c in below]) if N else np.zeros((0, d))
         if N:
-            labels, m = spherical_kmeans(X, k, iters)
+            gaps: list = []
+            labels, m = spherical_kmeans(X, k, iters, margins=gaps)
+            if gaps:
+                idx.min_margin = min(idx.min_margin, min(gaps))
         else:
             labels, m = np.zeros(0, dtype=np.int64), np.tile(unit(np.zeros(d)), (k, 1))
         idx.parent[level - 1] = labels.astype(np.int64)

@@ -118,3 +118,21 @@ def dense_attention_library(q: np.ndarray, K: np.ndarray, V: np.ndarray):
     from scipy.special import logsumexp, softmax
     x = (np.asarray(q, np.float64) @ np.asarray(K, np.float64).T) / math.sqrt(q.shape[1])
     return softmax(x, axis=1) @ np.asarray(V, np.float64), logsumexp(x, axis=1)
+
+
+TOPOLOGY_TIE = 2e-5     # a float32 dot product of two unit vectors of 128 entries is off by up to about 1e-5
+
+
+def same_topology_or_near_tie(gi, oi, levels, where, tally):
+    """The GPU-built tree `gi` must have the oracle's parents at every level below `levels` unless the
+    oracle's own clustering of this tree passed through a near-tie (oi.min_margin <= TOPOLOGY_TIE), in
+    which case a float32 assignment may legitimately fall the other way; such trees are counted in
+    tally["near_tie"], matching ones in tally["same"].  Returns whether the topology matches."""
+    same = all(np.array_equal(gi.parent[l], oi.parent[l]) for l in range(levels))
+    if same:
+        tally["same"] = tally.get("same", 0) + 1
+    else:
+        assert oi.min_margin <= TOPOLOGY_TIE, \
+            f"{where}: topology differs from the oracle's although its clustering never came closer to a tie than {oi.min_margin:.3g}"
+        tally["near_tie"] = tally.get("near_tie", 0) + 1
+    return same

@@ -31,7 +31,7 @@ def _say(msg):
     print(f"[case] {msg}", flush=True)
 
 
-def _check_step(G, case, qb, budget, heads=None, seqs=None, tag=""):
+def _check_step(G, case, qb, budget, heads=None, seqs=None, tag="", quiet=False):
     """One decode step on the GPU (own ids) against the oracle, for the listed (sequence, head)s."""
     w = case.w
     ids, scores, _ = G.gpu_retrieve(case, qb, budget, want_scores=False)
@@ -58,8 +58,9 @@ def _check_step(G, case, qb, budget, heads=None, seqs=None, tag=""):
             worst = (max(worst[0], mx), max(worst[1], rel))
             assert mx <= ATTN_MAX_ABS and rel <= ATTN_REL_L2, (tag, b, h, mx, rel)
             assert np.all(np.abs(lse[b, h * w.G:(h + 1) * w.G] - ref_lse) <= 1e-3)
-    _say(f"{tag}: worst attention max|err| {worst[0]:.2e}, rel L2 {worst[1]:.2e}; "
-         f"{n_band} (seq, head) sets differ from the oracle inside the tie band")
+    if not quiet:
+        _say(f"{tag}: worst attention max|err| {worst[0]:.2e}, rel L2 {worst[1]:.2e}; "
+             f"{n_band} (seq, head) sets differ from the oracle inside the tie band")
     return ids
 
 
@@ -115,8 +116,10 @@ def test_c3_index_build_on_gpu(G):
     case = G.make_case(w, build_on="gpu", cap=w.budget + 8)
     blob = lc.unpack_blob(lc.lc_index_export(case.idx))
     s = blob["seqs"][0]
-    same = 0
-    for h in (0, 5):
+    tally = {}
+    qb = np.stack([sq.Q[0] for sq in case.seqs])
+    ids, _, _ = G.gpu_retrieve(case, qb, w.budget, want_scores=False)
+    for h in range(w.H_kv):
         oi = case.oidx[0][h]
         gi = G.levels_to_oracle_index(s["heads"][h], s["bounds"], s["T"], w.fanout, orc.TOKEN_BALL)
         assert [gi.n(l) for l in range(w.levels)] == [oi.n(l) for l in range(w.levels)]
@@ -124,12 +127,11 @@ def test_c3_index_build_on_gpu(G):
         assert np.all(gi.radius[0] >= oi.radius[0] * (1 - 1e-6)) and np.all(gi.radius[0] <= oi.radius[0] * (1 + 2e-5))
         H.check_counts(gi)
         H.check_covering_invariant(gi, case.Kf(0, h), slack=1e-6)
-        same += int(all(np.array_equal(gi.parent[l], oi.parent[l]) for l in range(w.levels - 1)))
-        qb = np.stack([sq.Q[0] for sq in case.seqs])
-        ids, _, _ = G.gpu_retrieve(case, qb, w.budget, want_scores=False)
+        H.same_topology_or_near_tie(gi, oi, w.levels - 1, f"C3 build h{h}", tally)
         q = wl.bf16_bits_to_f64(qb[0, h * 4:(h + 1) * 4])
         H.accept_ids(ids[0][h], orc.node_scores(gi, 0, q), gi.lens(), w.budget)
-    _say(f"C3 GPU build: {same}/2 checked heads reproduce the oracle's k-means topology exactly")
+    _say(f"C3 GPU build: {tally.get('same', 0)}/{w.H_kv} heads reproduce the oracle's k-means topology exactly, "
+         f"{tally.get('near_tie', 0)} differ behind a near-tie of the oracle's clustering")
 
 
 def test_c2_batch4_32k(G):
@@ -137,13 +139,11 @@ def test_c2_batch4_32k(G):
     w = wl.C2
     _say("building C2 (4 x 32768 tokens, L=3, F=16, budget 2048, 64 queries)")
     case = G.make_case(w, prune=lc.LC_PRUNE_AUTO, cap=w.budget + 8)
-    for qi in (0, 17, 63):
-        qb = np.stack([s.Q[qi] for s in case.seqs])
-        _check_step(G, case, qb, w.budget, heads=(0, 3, 7), tag=f"C2 query {qi}")
-    # all 64 queries: properties that hold without the oracle (budget respected, ids valid and ascending)
+    # all 64 queries x 4 sequences x 8 heads against the oracle, and the properties that hold without it
+    # (budget respected, ids valid and ascending)
     for qi in range(w.n_queries):
         qb = np.stack([s.Q[qi] for s in case.seqs])
-        ids, _, _ = G.gpu_retrieve(case, qb, w.budget, want_scores=False)
+        ids = _check_step(G, case, qb, w.budget, tag=f"C2 query {qi}", quiet=qi % 16 != 0)
         for b in range(w.B):
             lens = case.oidx[b][0].lens()
             for h in range(w.H_kv):
@@ -161,9 +161,9 @@ def test_c5_ragged_batch16_gqa7(G):
     qb = np.stack([s.Q[0] for s in case.seqs])
     Ts = [s.T for s in case.seqs]
     _say(f"C5 sequence lengths: {Ts}")
-    _check_step(G, case, qb, w.budget, seqs=(0, int(np.argmin(Ts)), int(np.argmax(Ts)), 9), tag="C5")
+    _check_step(G, case, qb, w.budget, tag="C5")                      # all 16 sequences x 4 heads
     lc.lc_set_prune(case.idx, lc.LC_PRUNE_ALWAYS)
-    _check_step(G, case, qb, w.budget, seqs=(3, 15), heads=(1,), tag="C5 level walk")
+    _check_step(G, case, qb, w.budget, tag="C5 level walk")
 
 
 def test_c4_streaming_2048_steps(G):

@@ -411,7 +411,7 @@ def test_build_index_matches_oracle(G, geometry):
     w = wl.tiny("build", B=2, levels=3, fanout=4, T=0, T_range=(800, 1600), chunk_lo=3, chunk_hi=30)
     case = G.make_case(w, tails=[4, 0], geometry=geometry, build_on="gpu")
     blob = lc.unpack_blob(lc.lc_index_export(case.idx))
-    same_topology = 0
+    tally = {}
     for b in range(w.B):
         s = blob["seqs"][b]
         assert s["T"] == case.seqs[b].T and np.array_equal(s["bounds"], case.seqs[b].bounds)
@@ -426,15 +426,14 @@ def test_build_index_matches_oracle(G, geometry):
             # invariants of the GPU-built index, by brute force
             H.check_covering_invariant(gi, case.Kf(b, h), slack=1e-6)
             H.check_counts(gi)
-            if all(np.array_equal(gi.parent[l], oi.parent[l]) for l in range(w.levels - 1)):
-                same_topology += 1
+            if H.same_topology_or_near_tie(gi, oi, w.levels - 1, f"build b{b} h{h}", tally):
                 for l in range(1, w.levels):
                     live = oi.nchunk[l] > 0
                     assert np.allclose(gi.center[l][live], oi.center[l][live], rtol=1e-5, atol=1e-5)
                     assert np.all(gi.radius[l][live] >= oi.radius[l][live] * (1 - 1e-6))
                     assert np.all(gi.radius[l][live] <= oi.radius[l][live] * (1 + 5e-5) + 1e-6)
-    _say(f"build geometry={geometry}: {same_topology}/{w.B * w.H_kv} (seq, head) trees have the oracle's topology")
-    assert same_topology >= (w.B * w.H_kv) // 2
+    _say(f"build geometry={geometry}: {tally.get('same', 0)}/{w.B * w.H_kv} (seq, head) trees have the oracle's topology, "
+         f"{tally.get('near_tie', 0)} differ behind a near-tie of the oracle's clustering")
     # retrieval on the GPU-built index is exact with respect to its own stored values
     qb = _q_batch(case, 0)
     ids, scores, _ = G.gpu_retrieve(case, qb, w.budget)
@@ -499,7 +498,8 @@ def test_bf16_chunk_centers_built_on_gpu(G, geometry):
     w = wl.tiny("halfbuild", B=2, levels=3, fanout=4, T=0, T_range=(800, 1600), chunk_lo=3, chunk_hi=30)
     case = G.make_case(w, tails=[4, 0], geometry=geometry, build_on="gpu", center_dtype=lc.LC_CENTER_BF16)
     blob = lc.unpack_blob(lc.lc_index_export(case.idx))
-    n_el = n_diff = same_topology = 0
+    n_el = n_diff = 0
+    tally = {}
     for b in range(w.B):
         s = blob["seqs"][b]
         for h in range(w.H_kv):
@@ -516,11 +516,10 @@ def test_bf16_chunk_centers_built_on_gpu(G, geometry):
             assert np.all(gi.radius[0][exact_rows] <= oi.radius[0][exact_rows] * (1 + 2e-5) + 1e-7)
             H.check_covering_invariant(gi, case.Kf(b, h), slack=1e-6)
             H.check_counts(gi)
-            same_topology += int(all(np.array_equal(gi.parent[l], oi.parent[l]) for l in range(w.levels - 1)))
+            H.same_topology_or_near_tie(gi, oi, w.levels - 1, f"bf16 build b{b} h{h}", tally)
     _say(f"bf16 build geometry={geometry}: {n_diff} of {n_el} chunk-center elements one bfloat16 step from the "
-         f"oracle's; {same_topology}/{w.B * w.H_kv} trees have the oracle's topology")
+         f"oracle's; {tally.get('same', 0)}/{w.B * w.H_kv} trees have the oracle's topology, {tally.get('near_tie', 0)} differ behind a near-tie")
     assert n_diff <= 0.002 * n_el
-    assert same_topology >= (w.B * w.H_kv) // 2
     qb = _q_batch(case, 0)
     ids, scores, _ = G.gpu_retrieve(case, qb, w.budget)
     ids_f, out_f, _ = G.gpu_step(case, qb, w.budget)
@@ -609,7 +608,7 @@ def test_per_level_fanouts_built_on_gpu(G):
     case = G.make_case(w, tails=[5, 0], build_on="gpu", fanouts=fan)
     blob = lc.unpack_blob(lc.lc_index_export(case.idx))
     assert blob["fanouts"][:3] == fan
-    same_topology = 0
+    tally = {}
     for b in range(w.B):
         s = blob["seqs"][b]
         T, M, n_lev = case.idx.info(b)
@@ -620,9 +619,8 @@ def test_per_level_fanouts_built_on_gpu(G):
             assert [gi.n(l) for l in range(3)] == [oi.n(l) for l in range(3)]
             H.check_covering_invariant(gi, case.Kf(b, h), slack=1e-6)
             H.check_counts(gi)
-            same_topology += int(all(np.array_equal(gi.parent[l], oi.parent[l]) for l in range(2)))
-    _say(f"tiers: {same_topology}/{w.B * w.H_kv} trees have the oracle's topology")
-    assert same_topology >= (w.B * w.H_kv) // 2
+            H.same_topology_or_near_tie(gi, oi, 2, f"tiers b{b} h{h}", tally)
+    _say(f"tiers: {tally.get('same', 0)}/{w.B * w.H_kv} trees have the oracle's topology, {tally.get('near_tie', 0)} differ behind a near-tie")
     # a blob of this index is refused by a configuration with other fan-outs
     import torch
     other = lc.lc_config_default(levels=3, fanout=16, fanouts=[0, 2, 8], max_chunks=case.cfg.max_chunks,
@@ -744,7 +742,7 @@ def test_recluster_after_a_stream_equals_a_fresh_build(G):
     lc.lc_recluster(case.idx, case.ws)
     torch.cuda.synchronize()
     after = lc.unpack_blob(lc.lc_index_export(case.idx))
-    same_topology = 0
+    tally = {}
     for b in range(w.B):
         sb, sa = before["seqs"][b], after["seqs"][b]
         assert sa["T"] == sb["T"] and np.array_equal(sa["bounds"], sb["bounds"])
@@ -761,8 +759,7 @@ def test_recluster_after_a_stream_equals_a_fresh_build(G):
             assert np.array_equal(gi.center[0], gb.center[0]) and np.array_equal(gi.radius[0], gb.radius[0])
             H.check_covering_invariant(gi, Kf[b][h], slack=1e-6)
             H.check_counts(gi)
-            if all(np.array_equal(gi.parent[l], fresh.parent[l]) for l in range(L - 1)):
-                same_topology += 1
+            if H.same_topology_or_near_tie(gi, fresh, L - 1, f"recluster b{b} h{h}", tally):
                 for l in range(1, L):
                     live = fresh.nchunk[l] > 0
                     assert np.allclose(gi.center[l][live], fresh.center[l][live], rtol=1e-5, atol=1e-5)
@@ -771,8 +768,8 @@ def test_recluster_after_a_stream_equals_a_fresh_build(G):
             if b == 0 and h == 0:
                 _say(f"drift: mean level-1 radius {gb.radius[1][gb.nchunk[1] > 0].mean():.3f} over {gb.n(1)} nodes "
                      f"before, {gi.radius[1].mean():.3f} over {gi.n(1)} nodes after re-clustering")
-    _say(f"recluster: {same_topology}/{w.B * w.H_kv} (seq, head) trees have the topology of the oracle's fresh build")
-    assert same_topology >= (w.B * w.H_kv) // 2
+    _say(f"recluster: {tally.get('same', 0)}/{w.B * w.H_kv} (seq, head) trees have the topology of the oracle's fresh build, "
+         f"{tally.get('near_tie', 0)} differ behind a near-tie")
     # retrieval and attention on the re-clustered index (level walk on) agree with the oracle on it
     qb = np.stack([st.q[steps - 1] for st in streams])
     ids, _, _ = G.gpu_retrieve(case, qb, 150)

@@ -111,7 +111,7 @@ def test_append_without_shift_term_is_caught(monkeypatch):
 def test_kmeans_argmin_is_caught(monkeypatch):
     real_argmax = np.argmax
 
-    def bad_kmeans(X, k, iters, trace=None):
+    def bad_kmeans(X, k, iters, trace=None, margins=None):
         N = X.shape[0]
         m = np.stack([X[(c * N) // k] for c in range(k)]).astype(np.float64)
         labels = np.argmin(X @ m.T, axis=1)
