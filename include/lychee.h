@@ -276,6 +276,15 @@ int lc_append(lc_index* idx, void* K, void* V, const int64_t kv_strides[3],
               const void* k_new, const void* v_new, const uint8_t* close_chunk,
               void* ws /* unused, may be NULL */, size_t ws_bytes, void* stream);
 
+/* Sizes the two level walks are limited to (pure host function; either pointer may be NULL).
+ *   exact_walk_internal_nodes   EXACT with the level walk on: internal nodes (all levels above the
+ *                               chunks together) of one (sequence, head); the walk keeps them in LDS.
+ *                               Beyond it LC_PRUNE_ALWAYS gives LC_ERR_CAPACITY and LC_PRUNE_AUTO
+ *                               scans flat (same selection).  A flat scan has no such limit.
+ *   beam_level_nodes            BEAM: nodes of one internal level of one (sequence, head); beyond it
+ *                               lc_retrieve / lc_decode_step give LC_ERR_CAPACITY. */
+void lc_walk_limits(int32_t* exact_walk_internal_nodes, int32_t* beam_level_nodes);
+
 /* Host-side view of the index state: tokens, closed chunks and level sizes of
  * sequence b (n_per_level: host int32[LC_MAX_LEVELS], may be NULL). */
 int lc_index_info(const lc_index* idx, int b, int32_t* T, int32_t* M, int32_t* n_per_level);

@@ -139,6 +139,8 @@ class Index:
     ntok: List[np.ndarray]
     nchunk: List[np.ndarray]
     center_dtype: int = CENTER_F32
+    radius_build: Optional[List[np.ndarray]] = None   # radii as the last (re)build left them: the baseline of
+                                                      # radius_drift(); the lazy update never touches it
     min_margin: float = float("inf")   # build only: smallest best-vs-second-best similarity gap the
                                        # clustering passed through (how near it came to a tie); not
                                        # part of the stored index
@@ -305,7 +307,24 @@ def build_index(K: np.ndarray, bounds: Sequence[int], T: int, L: int, F,
         idx.parent.append(np.full(k, -1, dtype=np.int64))
         idx.ntok.append(ntok)
         idx.nchunk.append(nchunk)
+    idx.radius_build = [r.copy() for r in idx.radius]
     return idx
+
+
+def radius_drift(idx: Index, level: int) -> Tuple[float, float, float, int]:
+    """How far the lazy update has inflated the radii of `level` (>= 1) since the last (re)build:
+    (sum of the radii at build, sum of the radii now, largest growth of one node, nodes counted),
+    over the nodes that held chunks at build time (finite radius then).  Radii only grow under the
+    lazy update (Section 4.4), so sum now >= sum at build; the paper's limitations paragraph
+    proposes re-clustering once they have inflated: a caller re-clusters when
+    sum now > (1 + tau) * sum at build."""
+    assert idx.radius_build is not None and level >= 1
+    base = idx.radius_build[level]
+    live = np.isfinite(base)
+    now = idx.radius[level][: len(base)]
+    if not live.any():
+        return 0.0, 0.0, 0.0, 0
+    return float(base[live].sum()), float(now[live].sum()), float((now[live] - base[live]).max()), int(live.sum())
 
 
 # --------------------------------------------------------------------------

@@ -326,6 +326,11 @@ int lc_set_prune(lc_index* idx, int prune) {
     return LC_OK;
 }
 
+void lc_walk_limits(int32_t* exact_walk_internal_nodes, int32_t* beam_level_nodes) {
+    if (exact_walk_internal_nodes) *exact_walk_internal_nodes = lc_walk_max_internal_nodes();
+    if (beam_level_nodes) *beam_level_nodes = lc_beam_max_level_nodes();
+}
+
 int lc_index_info(const lc_index* idx, int b, int32_t* T, int32_t* M, int32_t* n_per_level) {
     if (!idx || b < 0 || b >= idx->B) return LC_ERR_INVALID_ARG;
     if (T) *T = idx->T[b];

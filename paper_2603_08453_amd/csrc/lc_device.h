@@ -125,6 +125,20 @@ __device__ __forceinline__ void lc_store_agent4(__amdgpu_buffer_rsrc_t r, int by
     v.z = __float_as_int(f.z); v.w = __float_as_int(f.w);
     __builtin_amdgcn_raw_buffer_store_b128(v, r, byte_offset, 0, 16);
 }
+// 4-byte and 1-byte reads and 4-byte writes through a range-checked buffer resource: an index outside
+// [0, extent) reads 0 / writes nothing instead of touching memory that is not the array's.
+__device__ __forceinline__ int lc_buf_load_i32(__amdgpu_buffer_rsrc_t r, int index) {
+    return __builtin_amdgcn_raw_buffer_load_b32(r, index * 4, 0, 0);
+}
+__device__ __forceinline__ float lc_buf_load_f32(__amdgpu_buffer_rsrc_t r, int index) {
+    return __int_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, index * 4, 0, 0));
+}
+__device__ __forceinline__ int lc_buf_load_u8(__amdgpu_buffer_rsrc_t r, int index) {
+    return (int)(unsigned char)__builtin_amdgcn_raw_buffer_load_b8(r, index, 0, 0);
+}
+__device__ __forceinline__ void lc_buf_store_u32(__amdgpu_buffer_rsrc_t r, int index, uint32_t v) {
+    __builtin_amdgcn_raw_buffer_store_b32((int)v, r, index * 4, 0, 0);
+}
 // Returns true in every thread of the last workgroup to arrive at `counter` (of `expected`).
 __device__ __forceinline__ bool lc_arrive_last(int* counter, int expected, int* flag_sh) {
     // Wait until this thread's hand-off stores have been acknowledged (they are write-through, so

@@ -18,9 +18,9 @@
 // and nothing reads global memory element by element inside a dependent loop.
 #include "lc_device.h"
 #include "lc_internal.h"
+#include "lc_walk_layout.h"
 
 #define LC_TAU_SLACK 1e-3f
-#define LC_WALK_LDS_LIMIT (150 * 1024)   // dynamic LDS a walking workgroup may take
 #define LC_COUNT_SELECT_MAX 1024         // up to this many candidates the O(n^2 / threads) rank is used
 
 LC_STAMP_DECL(lc_dbg_upper)
@@ -104,15 +104,7 @@ __device__ __forceinline__ void lc_small_select(int n, int mode, long long W, lo
 // ---------------------------------------------------------------------------------
 // kernel 1: internal levels
 // ---------------------------------------------------------------------------------
-// LDS bytes of the upper kernel: 13 per internal-node slot (key, token count, parent, kept flag),
-// 16 per select-scratch slot (two key/weight buffers), 12 per probe-list slot.
-__host__ __device__ inline int lc_upper_scratch_entries(int UC, int PC) {
-    const int q = ((PC / 4 + 63) / 64) * 64;            // the tau step parks PC flag bytes there
-    return UC > q ? UC : q;
-}
-__host__ __device__ inline size_t lc_upper_lds_bytes(int UC, int PC) {
-    return (size_t)UC * 13 + (size_t)lc_upper_scratch_entries(UC, PC) * 16 + (size_t)PC * 12;
-}
+// (LDS layout: lc_walk_layout.h: 13 bytes per internal-node slot, 16 per select-scratch slot, 12 per probe-list slot)
 
 // One workgroup of 1024 threads (64 groups of 16 lanes) per (sequence, head).  All
 // global loads of a phase are issued before any of them is used: at batch 1 the
@@ -146,19 +138,20 @@ lc_upper_kernel(const LcRetrieveArgs a) {
     }
     // LDS carve-up: internal nodes (UC entries each), select scratch, probe list (PC entries each)
     const int UC = a.upper_cap, PC = a.chunk_cap;
-    const int SC = lc_upper_scratch_entries(UC, PC);
-    uint32_t* ukey = reinterpret_cast<uint32_t*>(lds_dyn);
-    int* untok = lds_dyn + UC;
-    int* upar = lds_dyn + 2 * UC;
-    uint8_t* kp = reinterpret_cast<uint8_t*>(lds_dyn + 3 * UC);
+    const LcUpperLayout ly = lc_upper_layout(UC, PC);
+    char* const lds_b = reinterpret_cast<char*>(lds_dyn);
+    uint32_t* ukey = reinterpret_cast<uint32_t*>(lds_b + ly.ukey);
+    int* untok = reinterpret_cast<int*>(lds_b + ly.untok);
+    int* upar = reinterpret_cast<int*>(lds_b + ly.upar);
+    uint8_t* kp = reinterpret_cast<uint8_t*>(lds_b + ly.kp);
     // two (key, weight) staging buffers for the per-level selects, used alternately
-    uint32_t* ekA = reinterpret_cast<uint32_t*>(lds_dyn + 3 * UC + UC / 4);     // UC, PC multiples of 64
-    int* ewA = reinterpret_cast<int*>(ekA) + SC;
-    uint32_t* ekB = reinterpret_cast<uint32_t*>(ewA + SC);
-    int* ewB = reinterpret_cast<int*>(ekB) + SC;
-    int* plist = ewB + SC;
-    int* plen = plist + PC;
-    uint32_t* pkey = reinterpret_cast<uint32_t*>(plen + PC);
+    uint32_t* ekA = reinterpret_cast<uint32_t*>(lds_b + ly.ekA);
+    int* ewA = reinterpret_cast<int*>(lds_b + ly.ewA);
+    uint32_t* ekB = reinterpret_cast<uint32_t*>(lds_b + ly.ekB);
+    int* ewB = reinterpret_cast<int*>(lds_b + ly.ewB);
+    int* plist = reinterpret_cast<int*>(lds_b + ly.plist);
+    int* plen = reinterpret_cast<int*>(lds_b + ly.plen);
+    uint32_t* pkey = reinterpret_cast<uint32_t*>(lds_b + ly.pkey);
 
     // Query fragments: widened once for small groups; for large ones kept as packed bfloat16 words
     // and widened per node, which keeps this 1024-thread kernel within its 128 registers per lane.
@@ -404,7 +397,6 @@ lc_upper_kernel(const LcRetrieveArgs a) {
 #define LC_BM_PF 4                       // chunks per thread whose parent and boundary are fetched at kernel start
 #define LC_BM_RANK_MAX 128               // chunk lists up to this length are ranked directly, longer ones by histogram
 
-__host__ __device__ inline size_t lc_beam_lds_bytes(int cap_l) { return (size_t)cap_l * 17; }
 
 template <int G>
 __global__ void __launch_bounds__(LC_BM_THREADS)
@@ -428,11 +420,13 @@ lc_beam_kernel(const LcRetrieveArgs a) {
 
     // candidate lists: ids of the current level, ids of the next, keys, weights, kept flags
     const int CL = a.chunk_cap;
-    int* const l_cid = lds_dyn;
-    int* const l_nxt = lds_dyn + CL;
-    uint32_t* const l_key = reinterpret_cast<uint32_t*>(lds_dyn + 2 * CL);
-    int* const l_wgt = lds_dyn + 3 * CL;
-    uint8_t* const l_flg = reinterpret_cast<uint8_t*>(lds_dyn + 4 * CL);
+    const LcBeamLayout ly = lc_beam_layout(CL);
+    char* const lds_b = reinterpret_cast<char*>(lds_dyn);
+    int* const l_cid = reinterpret_cast<int*>(lds_b + ly.cid);
+    int* const l_nxt = reinterpret_cast<int*>(lds_b + ly.nxt);
+    uint32_t* const l_key = reinterpret_cast<uint32_t*>(lds_b + ly.key);
+    int* const l_wgt = reinterpret_cast<int*>(lds_b + ly.wgt);
+    uint8_t* const l_flg = reinterpret_cast<uint8_t*>(lds_b + ly.flg);
     int* const gs = a.scratch + (size_t)bh * 4 * cap0;
     int* const g_cid = gs;
     int* const g_nxt = gs + cap0;
@@ -691,11 +685,10 @@ lc_beam_kernel(const LcRetrieveArgs a) {
 
 template <int G>
 static int launch_beam_g(LcRetrieveArgs& a, int max_nodes, hipStream_t stream) {
-    // LDS lists for up to 4096 candidates per level (more go to the workspace)
-    int cl = ((max_nodes > 0 ? max_nodes : 1) + 63) / 64 * 64;
-    if (cl > 4096) cl = 4096;
+    // LDS lists for up to LC_BEAM_LIST_MAX candidates per level (more go to the workspace)
+    const int cl = lc_beam_list_slots(max_nodes);
     a.chunk_cap = cl;
-    const size_t lds = lc_beam_lds_bytes(cl);
+    const size_t lds = (size_t)lc_beam_layout(cl).total;
     if (lds + sizeof(LcLeafSelSh) + LC_SEL_SH * 4 + LC_BM_KEPT_WORDS * 4 + 256 > 48 * 1024)
         LC_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&lc_beam_kernel<G>),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
@@ -728,11 +721,16 @@ lc_leaf_kernel(const LcRetrieveArgs a) {
     const int sub = tid & 15, grp = tid >> 4;
     const size_t cb = (size_t)bh * ix.cap[0];
     constexpr bool c0b = BF16;
-    const int* bnd = ix.bounds + (size_t)b * (ix.cap[0] + 1);
+    const int cap0 = ix.cap[0];
+    const int* bnd = ix.bounds + (size_t)b * (cap0 + 1);
     uint32_t* keys = a.keys + cb;
     float* scores = a.scores ? a.scores + cb : nullptr;
-    const uint8_t* want = a.want + cb;
-    const int* par0 = ix.parent[0] + cb;
+    // the per-chunk arrays of the scoring part through range-checked buffer resources (an index
+    // derived from stored values -- a parent pointer -- cannot reach memory outside its array)
+    const __amdgpu_buffer_rsrc_t bnd_r = lc_buffer(bnd, (cap0 + 1) * 4);
+    const __amdgpu_buffer_rsrc_t want_r = lc_buffer(a.want + cb, cap0);
+    const __amdgpu_buffer_rsrc_t par_r = lc_buffer(ix.parent[0] + cb, cap0 * 4);
+    const __amdgpu_buffer_rsrc_t rad_r = lc_buffer(ix.radius[0] + cb, cap0 * 4);
     const bool have_want = a.walk != 0;
 
     LC_STAMP0(lc_dbg_leaf, 0);
@@ -743,11 +741,11 @@ lc_leaf_kernel(const LcRetrieveArgs a) {
     float rv[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-        const int j = min(j_lo + r * LC_LF_GROUPS + grp, ix.cap[0] - 1);
+        const int j = min(j_lo + r * LC_LF_GROUPS + grp, cap0 - 1);
         jj[r] = j;
-        // (rows past the chunk count hold whatever the buffer held: the parent is clamped, the result unused)
-        wv[r] = (bnd[j] >= a.sink ? 1 : 0) & (have_want ? (int)want[min(max(par0[j], 0), ix.cap[0] - 1)] : 1);
-        rv[r] = ix.radius[0][cb + j];
+        // (rows past the chunk count hold whatever the buffer held: the result is unused)
+        wv[r] = (lc_buf_load_i32(bnd_r, j) >= a.sink ? 1 : 0) & (have_want ? lc_buf_load_u8(want_r, lc_buf_load_i32(par_r, j)) : 1);
+        rv[r] = lc_buf_load_f32(rad_r, j);
     }
     // Without a level walk every chunk below M is scored, so its center can be fetched right away
     // instead of one memory round trip later (with a walk the centers of pruned chunks are the
@@ -892,20 +890,25 @@ lc_score_kernel(const LcRetrieveArgs a) {
     const int sub = tid & 15, grp = tid >> 4;
     const size_t cb = (size_t)bh * ix.cap[0];
     constexpr bool c0b = BF16;
-    const int* bnd = ix.bounds + (size_t)b * (ix.cap[0] + 1);
-    uint32_t* keys = a.keys + cb;
-    const uint8_t* want = a.want + cb;
-    const int* par0 = ix.parent[0] + cb;
+    const int cap0 = ix.cap[0];
+    // the per-chunk arrays through range-checked buffer resources (an index derived from stored
+    // values -- a parent pointer -- cannot reach memory outside its array)
+    const __amdgpu_buffer_rsrc_t bnd_r = lc_buffer(ix.bounds + (size_t)b * (cap0 + 1), (cap0 + 1) * 4);
+    const __amdgpu_buffer_rsrc_t keys_r = lc_buffer(a.keys + cb, cap0 * 4);
+    const __amdgpu_buffer_rsrc_t want_r = lc_buffer(a.want + cb, cap0);
+    const __amdgpu_buffer_rsrc_t par_r = lc_buffer(ix.parent[0] + cb, cap0 * 4);
+    const __amdgpu_buffer_rsrc_t rad_r = lc_buffer(ix.radius[0] + cb, cap0 * 4);
     const bool have_want = a.walk != 0;
     const int j_lo = blockIdx.x * (R * GROUPS);
     int jj[R], wv[R];
     float rv[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-        const int j = min(j_lo + r * GROUPS + grp, ix.cap[0] - 1);
+        const int j = min(j_lo + r * GROUPS + grp, cap0 - 1);
         jj[r] = j;
-        wv[r] = (bnd[j] >= a.sink ? 1 : 0) & (have_want ? (int)want[min(max(par0[j], 0), ix.cap[0] - 1)] : 1);
-        rv[r] = ix.radius[0][cb + j];
+        // (rows past the chunk count hold whatever the buffer held: the result is unused)
+        wv[r] = (lc_buf_load_i32(bnd_r, j) >= a.sink ? 1 : 0) & (have_want ? lc_buf_load_u8(want_r, lc_buf_load_i32(par_r, j)) : 1);
+        rv[r] = lc_buf_load_f32(rad_r, j);
     }
     LcNodeFrag pre[R];
     if (!have_want) {
@@ -924,7 +927,7 @@ lc_score_kernel(const LcRetrieveArgs a) {
             if (!have_want) sv = lc_score_chunk_frag<G>(pre[r], c0b, rv[r], qf, qn);
             else sv = lc_score_chunk_frag<G>(lc_load_chunk_node(ix.center[0], c0b, cb + jj[r], sub), c0b, rv[r], qf, qn);
         }
-        if (j < M && sub == 0) keys[j] = lc_score_key(sv);
+        if (j < M && sub == 0) lc_buf_store_u32(keys_r, j, lc_score_key(sv));
     }
 }
 
@@ -964,10 +967,10 @@ static int launch_retrieve_g(LcRetrieveArgs& a, int max_M, hipStream_t stream) {
     const size_t lds_limit = LC_WALK_LDS_LIMIT;
     if (a.policy == LC_POLICY_BEAM) return launch_beam_g<G>(a, a.upper_cap > max_M ? a.upper_cap : max_M, stream);
     if (a.walk) {
-        // as long a probe list as LDS holds next to the internal-node slots
-        const int uc = a.upper_cap;
-        int pc = mc;
-        while (pc > 64 && lc_upper_lds_bytes(uc, pc) > lds_limit) pc -= 64;
+        // as long a probe list as LDS holds next to the internal-node slots (the host has checked that one fits)
+        int uc, pc;
+        if (!lc_upper_launch_shape(a.upper_cap, max_M, &uc, &pc)) return LC_ERR_CAPACITY;
+        a.upper_cap = uc;
         a.chunk_cap = pc;
         const size_t lds = lc_upper_lds_bytes(uc, pc);
         if (lds > 48 * 1024)
@@ -1001,11 +1004,7 @@ static int launch_retrieve_g(LcRetrieveArgs& a, int max_M, hipStream_t stream) {
 }
 
 // Most internal nodes of one (sequence, head) that the exact level walk holds in LDS (with the shortest probe list).
-int lc_walk_max_internal_nodes() {
-    int uc = 64;
-    while (lc_upper_lds_bytes(uc + 64, 64) <= (size_t)LC_WALK_LDS_LIMIT) uc += 64;
-    return uc;
-}
+int lc_walk_max_internal_nodes() { return lc_upper_max_internal_nodes(); }
 int lc_beam_max_level_nodes() { return LC_BM_MAX_LEVEL_NODES; }
 
 int lc_launch_retrieve(const lc_index* idx, const LcWs& ws, const void* q, int G, int budget,

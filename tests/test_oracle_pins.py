@@ -451,6 +451,9 @@ def test_append_keeps_invariants(geometry, L):
     import lc_workloads as wl
     K = wl.bf16_bits_to_f64(wl.f32_to_bf16_bits(K.astype(np.float32)))
     idx = orc.build_index(K, c["bounds"], c["T"], L, 3, geometry=geometry)
+    for level in range(1, L):                               # nothing has drifted right after a build
+        sb, sn, mg, n = orc.radius_drift(idx, level)
+        assert sb == sn and mg == 0.0 and n == int(np.isfinite(idx.radius[level]).sum())
     prev_r = [x.copy() for x in idx.radius]
     open_len = idx.T - int(idx.bounds[-1])
     for step in range(extra):
@@ -465,6 +468,11 @@ def test_append_keeps_invariants(geometry, L):
             H.check_counts(idx)
             for level in range(1, L):                       # radii never shrink
                 assert np.all(idx.radius[level] >= prev_r[level])
+                # ... so the drift figures are the plain differences to the radii at build
+                sb, sn, mg, n = orc.radius_drift(idx, level)
+                live = np.isfinite(idx.radius_build[level])
+                assert sn >= sb and mg >= 0.0
+                assert mg == pytest.approx(float((idx.radius[level][live] - idx.radius_build[level][live]).max()))
             prev_r = [x.copy() for x in idx.radius]
             if L > 1:
                 # moving average == batch mean of descendant chunk centers (TOKEN_BALL)
@@ -492,6 +500,8 @@ def test_append_picks_nearest_direction_and_first_on_tie():
     assert np.allclose(idx.center[1][1], (e[1] + e[1] + 2 * e[1]) / 3, atol=1e-7)
     # radius: max(old + shift, |mu_x - mu'| + r_x) = max(0 + 1/3, 2/3 + 0)
     assert abs(idx.radius[1][1] - 2 / 3) < 1e-6
+    # drift since the build: both clusters had radius 0; cluster 1 grew to 2/3, cluster 0 did not move
+    assert orc.radius_drift(idx, 1) == pytest.approx((0.0, 2 / 3, 2 / 3, 2), abs=1e-6)
     # a chunk equidistant (in direction) from both clusters goes to the lower id
     K2 = np.vstack([K, np.tile(e[2], (2, 1))])
     idx.T = 12
