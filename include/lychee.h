@@ -165,6 +165,23 @@ int lc_build_index(lc_index** out, const lc_config* cfg,
  */
 int lc_recluster(lc_index* idx, void* ws, size_t ws_bytes, void* stream);
 
+/*
+ * lc_index_drift -- how far the lazy update has inflated the radii of one internal level since the
+ * index was built, imported or last re-clustered (the paper's limitations section: re-cluster
+ * "when radii inflate").  Per (sequence, head), over the nodes that held chunks at that time:
+ *   drift[(b * H_kv + h) * 4 + 0]   sum of those nodes' radii then
+ *   drift[... + 1]                  sum of their radii now (never smaller: radii only grow)
+ *   drift[... + 2]                  largest growth of a single node
+ *   drift[... + 3]                  number of nodes counted
+ * A caller triggers lc_recluster when sum now > (1 + tau) * sum then (tau 0.25 is a reasonable
+ * start: the Eq. 2 bounds of that level have then loosened by a quarter on average).
+ *   level   1 <= level < cfg.levels
+ *   drift   host float[B * H_kv * 4]
+ *   ws      device workspace of at least B * H_kv * 16 bytes (any lc_workspace_bytes() buffer does)
+ * Synchronises the stream (the result is copied to the host).
+ */
+int lc_index_drift(const lc_index* idx, int level, float* drift /* host */, void* ws, size_t ws_bytes, void* stream);
+
 /* Change the retrieval policy of an existing index (host state only). */
 int lc_set_policy(lc_index* idx, int policy, const int32_t* beam /* host, LC_MAX_LEVELS, may be NULL */,
                   int sink_tokens);

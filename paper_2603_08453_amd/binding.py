@@ -110,6 +110,10 @@ def lib() -> ctypes.CDLL:
     L.lc_decode_workspace_bytes.restype = ctypes.c_size_t
     L.lc_static_workspace_bytes.argtypes = []
     L.lc_static_workspace_bytes.restype = ctypes.c_size_t
+    L.lc_index_drift.argtypes = [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_float), vp, ctypes.c_size_t, vp]
+    L.lc_index_drift.restype = ctypes.c_int
+    L.lc_walk_limits.argtypes = [i32p, i32p]
+    L.lc_walk_limits.restype = None
     L.lc_recluster.argtypes = [vp, vp, ctypes.c_size_t, vp]
     L.lc_recluster.restype = ctypes.c_int
     # measurement aids (lychee_bench.h)
@@ -261,6 +265,21 @@ def lc_sparse_decode(idx: Index, q, K, V, chunk_ids, counts, out, ws, lse=None, 
                                 cap, H_q, _ptr(out), _ptr(lse), _ptr(ws), ws.numel() * ws.element_size(),
                                 _stream(stream))
     _check(rc, "lc_sparse_decode")
+
+
+def lc_index_drift(idx: Index, level: int, ws, stream=None) -> np.ndarray:
+    """[B][H_kv][4] floats: sum of the level's radii at build, sum now, largest growth, nodes counted."""
+    out = (ctypes.c_float * (idx.B * idx.H_kv * 4))()
+    _check(lib().lc_index_drift(idx.handle, int(level), out, _ptr(ws), ws.numel() * ws.element_size(),
+                                _stream(stream)), "lc_index_drift")
+    return np.frombuffer(out, dtype=np.float32).reshape(idx.B, idx.H_kv, 4).copy()
+
+
+def lc_walk_limits():
+    """(internal nodes the exact walk holds, nodes of one level under top-k per level)."""
+    a, b = ctypes.c_int32(), ctypes.c_int32()
+    lib().lc_walk_limits(ctypes.byref(a), ctypes.byref(b))
+    return int(a.value), int(b.value)
 
 
 def lc_recluster(idx: Index, ws, stream=None) -> None:

@@ -81,6 +81,7 @@ size_t lc_layout_index(const lc_config* cfg, int B, int H, int d, void* base, Lc
         D->parent[l] = c.take<int>(n);
         D->ntok[l] = c.take<int>(n);
         D->nchunk[l] = c.take<int>(n);
+        D->rbuild[l] = l >= 1 ? c.take<float>(n) : nullptr;
     }
     return align_up(c.off);
 }
@@ -323,6 +324,19 @@ int lc_set_prune(lc_index* idx, int prune) {
     if (!idx) return LC_ERR_INVALID_ARG;
     if (prune != LC_PRUNE_AUTO && prune != LC_PRUNE_ALWAYS && prune != LC_PRUNE_NEVER) return LC_ERR_INVALID_ARG;
     idx->cfg.prune = prune;
+    return LC_OK;
+}
+
+int lc_index_drift(const lc_index* idx, int level, float* drift, void* ws, size_t ws_bytes, void* stream) {
+    if (!idx || !drift || !ws || (reinterpret_cast<uintptr_t>(ws) & 255u)) return LC_ERR_INVALID_ARG;
+    if (level < 1 || level >= idx->cfg.levels) return LC_ERR_INVALID_ARG;
+    const size_t n = (size_t)idx->B * idx->H_kv * 4;
+    if (ws_bytes < n * sizeof(float)) return LC_ERR_WORKSPACE_TOO_SMALL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int rc = lc_launch_drift(idx, level, static_cast<float*>(ws), s);
+    if (rc) return rc;
+    LC_HIP_CHECK(hipMemcpyAsync(drift, ws, n * sizeof(float), hipMemcpyDeviceToHost, s));
+    LC_HIP_CHECK(hipStreamSynchronize(s));
     return LC_OK;
 }
 
@@ -772,6 +786,7 @@ int lc_index_import(lc_index** out, const lc_config* cfg, const void* blob, size
                     }
                     p += nl * d * 4;
                     if (e == hipSuccess) e = hipMemcpy(D.radius[l] + base, p, nl * 4, hipMemcpyHostToDevice);
+                    if (e == hipSuccess && l >= 1) e = hipMemcpy(D.rbuild[l] + base, p, nl * 4, hipMemcpyHostToDevice);
                     p += nl * 4;
                     if (e == hipSuccess) e = hipMemcpy(D.parent[l] + base, p, nl * 4, hipMemcpyHostToDevice);
                     p += nl * 4;

@@ -373,7 +373,9 @@ lc_node_kernel(LcDev ix, int l, const int* anc, const float* cent, int cent_cap,
         lc_unit_frag(mu, sub, d);
         lc_store8(next_pts + ((size_t)bh * next_cap + u) * LC_D + 8 * sub, d);
         if (sub == 0) {
-            ix.radius[l + 1][n] = nch > 0 ? lc_pad_radius(R) : LC_NEG_INF;
+            const float R_st = nch > 0 ? lc_pad_radius(R) : LC_NEG_INF;
+            ix.radius[l + 1][n] = R_st;
+            ix.rbuild[l + 1][n] = R_st;          // the baseline that lc_index_drift measures growth against
             ix.parent[l + 1][n] = -1;
             ix.ntok[l + 1][n] = ntk;
             ix.nchunk[l + 1][n] = nch;
@@ -430,6 +432,50 @@ int lc_launch_build(const lc_index* idx, const LcWs& ws, const void* Kp, const i
         float* t = pts; pts = other; other = t;
         const int tc = pts_cap; pts_cap = other_cap; other_cap = tc;
     }
+    return LC_OK;
+}
+
+// ---------------------------------------------------------------------------------
+// drift of one level's radii since the last (re)build
+// ---------------------------------------------------------------------------------
+// One workgroup per (sequence, head): over the nodes with a finite radius at build time, the sum of
+// those radii, the sum of the radii now, the largest growth and the count (fixed reduction order).
+__global__ void __launch_bounds__(LC_BT)
+lc_drift_kernel(LcDev ix, int level, float* out) {
+    __shared__ float sh[4][LC_BT / 64];
+    const int h = blockIdx.x, b = blockIdx.y;
+    const int bh = b * ix.H + h;
+    const int n_l = min(ix.nlev[b * LC_MAX_LEVELS + level], ix.cap[level]);
+    const size_t base = (size_t)bh * ix.cap[level];
+    float s_then = 0.f, s_now = 0.f, grow = 0.f, cnt = 0.f;
+    for (int n = threadIdx.x; n < n_l; n += LC_BT) {
+        const float r0 = ix.rbuild[level][base + n], r1 = ix.radius[level][base + n];
+        if (r0 > LC_NEG_INF) {
+            s_then += r0;
+            s_now += r1;
+            grow = fmaxf(grow, r1 - r0);
+            cnt += 1.f;
+        }
+    }
+    s_then = lc_sum64(s_then);
+    s_now = lc_sum64(s_now);
+    grow = lc_max64(grow);
+    cnt = lc_sum64(cnt);
+    if ((threadIdx.x & 63) == 0) {
+        const int w = threadIdx.x >> 6;
+        sh[0][w] = s_then; sh[1][w] = s_now; sh[2][w] = grow; sh[3][w] = cnt;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float a = 0.f, c = 0.f, g = 0.f, k = 0.f;
+        for (int w = 0; w < LC_BT / 64; ++w) { a += sh[0][w]; c += sh[1][w]; g = fmaxf(g, sh[2][w]); k += sh[3][w]; }
+        out[bh * 4 + 0] = a; out[bh * 4 + 1] = c; out[bh * 4 + 2] = g; out[bh * 4 + 3] = k;
+    }
+}
+
+int lc_launch_drift(const lc_index* idx, int level, float* out, hipStream_t stream) {
+    hipLaunchKernelGGL(lc_drift_kernel, dim3(idx->dev.H, idx->dev.B), dim3(LC_BT), 0, stream, idx->dev, level, out);
+    LC_HIP_CHECK(hipGetLastError());
     return LC_OK;
 }
 

@@ -25,6 +25,7 @@ struct LcDev {
     int* parent[LC_MAX_LEVELS];
     int* ntok[LC_MAX_LEVELS];
     int* nchunk[LC_MAX_LEVELS];
+    float* rbuild[LC_MAX_LEVELS];   // levels >= 1: the radius as the last (re)build left it (baseline of lc_index_drift)
 };
 
 struct lc_index {
@@ -101,6 +102,8 @@ bool lc_decode_fused_fits(int G, int max_M);
 int lc_launch_decode_fused(const lc_index* idx, const LcWs& ws, const void* q, const void* K, const void* V,
                            const int64_t ks[3], int G, int splits, int budget, int32_t* ids_out,
                            int32_t* counts_out, int cap, int max_M, float* out, float* lse, hipStream_t stream);
+// out (device): [B][H][4] floats: sum of radii at build, sum now, largest growth, nodes counted
+int lc_launch_drift(const lc_index* idx, int level, float* out, hipStream_t stream);
 int lc_launch_append(const lc_index* idx, void* K, void* V, const int64_t ks[3],
                      const void* k_new, const void* v_new, const uint8_t* close_dev_flags_or_null,
                      uint32_t close_mask_lo, hipStream_t stream);

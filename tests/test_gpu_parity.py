@@ -739,8 +739,34 @@ def test_recluster_after_a_stream_equals_a_fresh_build(G):
                     orc.close_chunk(oi, Kf[b][h])
     torch.cuda.synchronize()
     before = lc.unpack_blob(lc.lc_index_export(case.idx))
+    # how far the radii have drifted since the build, against the oracle's definition on its own
+    # lazily updated tree (same parent choices on both sides, so the same nodes grew)
+    triggered = 0
+    for level in range(1, L):
+        drift = lc.lc_index_drift(case.idx, level, case.ws)
+        for b in range(w.B):
+            for h in range(w.H_kv):
+                oi = case.oidx[b][h]
+                gb = G.levels_to_oracle_index(before["seqs"][b]["heads"][h], before["seqs"][b]["bounds"],
+                                              before["seqs"][b]["T"], F, orc.TOKEN_BALL)
+                then, now, grow, n = orc.radius_drift(oi, level)
+                got = drift[b, h]
+                assert got[3] == n and got[1] >= got[0] and got[2] >= 0.0, (level, b, h, got)
+                if np.array_equal(gb.parent[0], oi.parent[0]):
+                    # (the GPU inflates every updated radius by a few 1e-6 to stay on the safe side of its
+                    # float32 rounding; over some thirty updates of a node that adds up to a few 1e-4)
+                    assert np.allclose(got[:3], [then, now, grow], rtol=1e-3, atol=1e-4), (level, b, h, got, then, now, grow)
+                    assert got[1] >= now * (1 - 1e-6) and got[2] >= grow * (1 - 1e-6) - 1e-6
+                triggered += int(level == 1 and got[1] > 1.02 * got[0])
+        if level == 1:
+            _say(f"drift of level 1 before re-clustering: sum of radii now / at build = "
+                 f"{drift[..., 1].sum() / drift[..., 0].sum():.4f}, largest growth of one node {drift[..., 2].max():.3f}")
+    assert triggered > 0                     # 400 streamed tokens did inflate some tree's fine clusters
     lc.lc_recluster(case.idx, case.ws)
     torch.cuda.synchronize()
+    for level in range(1, L):                # a re-clustered index starts from a fresh baseline
+        drift = lc.lc_index_drift(case.idx, level, case.ws)
+        assert np.array_equal(drift[..., 0], drift[..., 1]) and np.all(drift[..., 2] == 0.0)
     after = lc.unpack_blob(lc.lc_index_export(case.idx))
     tally = {}
     for b in range(w.B):

@@ -104,6 +104,8 @@ def test_argument_errors_before_any_gpu_work(L):
     assert L.lc_decode_step(None, fake, fake, fake, strides, 32, 10, fake, None, None, None, 0, fake, 1 << 20,
                             None) == lc.LC_ERR_INVALID_ARG
     assert L.lc_recluster(None, fake, 1 << 20, None) == lc.LC_ERR_INVALID_ARG
+    four = (ctypes.c_float * 4)()
+    assert L.lc_index_drift(None, 1, four, fake, 1 << 20, None) == lc.LC_ERR_INVALID_ARG
     assert L.lc_bench_select_attend(None, fake, fake, fake, strides, 8, 16, fake, None, fake, 1 << 20, None) == lc.LC_ERR_INVALID_ARG
     assert L.lc_bench_read_sweep(None, 1 << 20, fake, 2048, None) == lc.LC_ERR_INVALID_ARG
     assert L.lc_bench_read_sweep(fake, 100, fake, 2048, None) == lc.LC_ERR_INVALID_ARG          # not a multiple of 16
