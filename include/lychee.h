@@ -147,6 +147,9 @@ size_t lc_workspace_bytes(const lc_config* cfg /* host */, int B, int H_q, int H
  *   index_buf     device buffer of >= lc_index_bytes() bytes, 256-byte aligned,
  *                 owned by the caller, must outlive the handle
  *   ws            device workspace of >= lc_workspace_bytes() bytes
+ *
+ * Asynchronous: the host arrays are copied (into pinned staging memory the library keeps per
+ * device for the life of the process) before the call returns, the stream is not waited for.
  */
 int lc_build_index(lc_index** out, const lc_config* cfg,
                    const void* K, const int64_t k_strides[3],
@@ -160,8 +163,8 @@ int lc_build_index(lc_index** out, const lc_config* cfg,
  * nodes and lets radii grow).  Keeps the chunk nodes (level 0) as they are and rebuilds every
  * level above them exactly as lc_build_index does -- ceil(N/F) clusters per level for the
  * current chunk counts, the same k-means -- so the result equals lc_build_index on the whole
- * sequence as it now stands.  K and V are not read.  Synchronises the stream once (a small host
- * to device copy of the level sizes).  Same workspace size as lc_build_index.
+ * sequence as it now stands.  K and V are not read.  Asynchronous like lc_build_index.  Same
+ * workspace size as lc_build_index.
  */
 int lc_recluster(lc_index* idx, void* ws, size_t ws_bytes, void* stream);
 

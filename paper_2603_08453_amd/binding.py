@@ -163,9 +163,12 @@ def _strides3(t) -> "ctypes.Array":
     return (ctypes.c_int64 * 3)(t.stride(0), t.stride(1), t.stride(2))
 
 
-def _i32(a) -> "ctypes.Array":
-    a = [int(x) for x in a]
-    return (ctypes.c_int32 * len(a))(*a)
+def _i32(a):
+    """Host int32 array for a C `const int32_t*` argument (the numpy array owns the memory for the call)."""
+    arr = np.array(a, dtype=np.int32).reshape(-1)          # a private, writable, contiguous copy
+    if arr.size == 0:
+        arr = np.zeros(1, dtype=np.int32)
+    return (ctypes.c_int32 * arr.size).from_buffer(arr)    # keeps `arr` alive
 
 
 def lc_config_default(**overrides) -> LcConfig:
@@ -226,7 +229,7 @@ def lc_build_index(cfg: LcConfig, K, seq_lens: Sequence[int], chunk_bounds: Sequ
     """K: torch bf16 [B][H_kv][tokens][d] on the GPU; chunk_bounds: per sequence, host ints."""
     B, H_kv, _, d = K.shape
     counts = [len(b) - 1 for b in chunk_bounds]
-    flat = [int(x) for b in chunk_bounds for x in b]
+    flat = np.concatenate([np.asarray(b, dtype=np.int32).reshape(-1) for b in chunk_bounds])
     out = ctypes.c_void_p()
     rc = lib().lc_build_index(ctypes.byref(out), ctypes.byref(cfg), _ptr(K), _strides3(K), _i32(seq_lens),
                               _i32(flat), _i32(counts), B, H_kv, d, _ptr(index_buf),

@@ -209,30 +209,77 @@ void fill_level_counts(lc_index* h) {
     }
 }
 
-// state, nlev, bounds, sync -> device (synchronous small copies from host staging vectors)
-int upload_state(lc_index* h, const int32_t* bounds_concat, hipStream_t stream) {
+// Host side of the small uploads (counts, chunk boundaries): one pinned buffer per device, kept for
+// the life of the process and grown on demand, so that an upload is one asynchronous copy and no
+// wait for the stream.  The event marks the last copy that read the buffer; it is waited for before
+// the buffer is written again (long done, normally).
+struct LcStage {
+    int32_t* host = nullptr;
+    size_t ints = 0;
+    hipEvent_t read = nullptr;
+};
+constexpr int LC_STAGE_DEVICES = 64;
+LcStage g_stage[LC_STAGE_DEVICES];
+std::mutex g_stage_mutex;
+
+// Returns the current device's buffer with room for `ints` values (the lock must be held).
+int stage_reserve(size_t ints, LcStage** out) {
+    int dev = 0;
+    LC_HIP_CHECK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= LC_STAGE_DEVICES) return LC_ERR_INVALID_ARG;
+    LcStage& st = g_stage[dev];
+    if (!st.read) LC_HIP_CHECK(hipEventCreateWithFlags(&st.read, hipEventDisableTiming));
+    else LC_HIP_CHECK(hipEventSynchronize(st.read));
+    if (st.ints < ints) {
+        if (st.host) LC_HIP_CHECK(hipHostFree(st.host));
+        st.host = nullptr;
+        st.ints = 0;
+        const size_t want = ints < 16384 ? 16384 : ints + ints / 2;
+        LC_HIP_CHECK(hipHostMalloc(reinterpret_cast<void**>(&st.host), want * sizeof(int32_t), hipHostMallocDefault));
+        st.ints = want;
+    }
+    *out = &st;
+    return LC_OK;
+}
+
+// state, nlev, zeroed arrival counters and chunk boundaries -> device: staged as
+// [state | nlev | boundaries of all sequences], copied once into `dev_stage` (workspace memory the
+// build overwrites later) and put in place by one kernel.
+int upload_state(lc_index* h, const int32_t* bounds_concat, void* dev_stage, hipStream_t stream) {
     const int B = h->B, H = h->H_kv;
-    std::vector<int> state((size_t)B * H * 4, 0), nlev((size_t)B * LC_MAX_LEVELS, 0);
+    const size_t n_state = (size_t)B * H * 4, n_nlev = (size_t)B * LC_MAX_LEVELS;
+    size_t n_bounds = 0;
+    for (int b = 0; b < B; ++b) n_bounds += (size_t)h->M[b] + 1;
+    const size_t total = n_state + n_nlev + n_bounds;
+    std::lock_guard<std::mutex> lock(g_stage_mutex);
+    LcStage* st = nullptr;
+    const int rc = stage_reserve(total, &st);
+    if (rc != LC_OK) return rc;
+    int32_t* p = st->host;
+    memset(p, 0, n_state * sizeof(int32_t));
     for (int b = 0; b < B; ++b) {
         for (int hh = 0; hh < H; ++hh) {
-            state[((size_t)b * H + hh) * 4 + 0] = h->T[b];
-            state[((size_t)b * H + hh) * 4 + 1] = h->M[b];
+            p[((size_t)b * H + hh) * 4 + 0] = h->T[b];
+            p[((size_t)b * H + hh) * 4 + 1] = h->M[b];
         }
-        for (int l = 0; l < LC_MAX_LEVELS; ++l) nlev[(size_t)b * LC_MAX_LEVELS + l] = h->N[(size_t)b * LC_MAX_LEVELS + l];
     }
-    LC_HIP_CHECK(hipMemcpyAsync(h->dev.state, state.data(), state.size() * sizeof(int), hipMemcpyHostToDevice, stream));
-    LC_HIP_CHECK(hipMemcpyAsync(h->dev.nlev, nlev.data(), nlev.size() * sizeof(int), hipMemcpyHostToDevice, stream));
-    std::vector<int> zeros((size_t)B * H * 4, 0);
-    LC_HIP_CHECK(hipMemcpyAsync(h->dev.sync, zeros.data(), zeros.size() * sizeof(int), hipMemcpyHostToDevice, stream));
-    size_t off = 0;
-    for (int b = 0; b < B; ++b) {
-        const size_t n = (size_t)h->M[b] + 1;
-        LC_HIP_CHECK(hipMemcpyAsync(h->dev.bounds + (size_t)b * (h->dev.cap[0] + 1), bounds_concat + off,
-                                    n * sizeof(int), hipMemcpyHostToDevice, stream));
-        off += n;
-    }
-    // the staging vectors die at return: make sure the copies are done
-    LC_HIP_CHECK(hipStreamSynchronize(stream));
+    for (size_t i = 0; i < n_nlev; ++i) p[n_state + i] = h->N[i];
+    memcpy(p + n_state + n_nlev, bounds_concat, n_bounds * sizeof(int32_t));
+    LC_HIP_CHECK(hipMemcpyAsync(dev_stage, p, total * sizeof(int32_t), hipMemcpyHostToDevice, stream));
+    LC_HIP_CHECK(hipEventRecord(st->read, stream));
+    return lc_launch_place_state(h, static_cast<const int32_t*>(dev_stage), stream);
+}
+
+// nodes per level -> device (lc_recluster)
+int upload_level_counts(lc_index* h, hipStream_t stream) {
+    const size_t n_nlev = (size_t)h->B * LC_MAX_LEVELS;
+    std::lock_guard<std::mutex> lock(g_stage_mutex);
+    LcStage* st = nullptr;
+    const int rc = stage_reserve(n_nlev, &st);
+    if (rc != LC_OK) return rc;
+    for (size_t i = 0; i < n_nlev; ++i) st->host[i] = h->N[i];
+    LC_HIP_CHECK(hipMemcpyAsync(h->dev.nlev, st->host, n_nlev * sizeof(int32_t), hipMemcpyHostToDevice, stream));
+    LC_HIP_CHECK(hipEventRecord(st->read, stream));
     return LC_OK;
 }
 
@@ -281,7 +328,7 @@ int lc_build_index(lc_index** out, const lc_config* cfg, const void* K, const in
     }
     fill_level_counts(h);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    rc = upload_state(h, chunk_bounds, s);
+    rc = upload_state(h, chunk_bounds, w.dirs, s);
     if (rc == LC_OK) rc = lc_launch_build(h, w, K, k_strides, max_M, s);
     if (rc != LC_OK) {
         delete h;
@@ -299,10 +346,8 @@ int lc_recluster(lc_index* idx, void* ws, size_t ws_bytes, void* stream) {
     lc_layout_ws(&idx->cfg, idx->B, idx->H_kv, idx->H_kv, idx->d, 1, ws, &w);
     hipStream_t s = static_cast<hipStream_t>(stream);
     fill_level_counts(idx);                       // nodes per level follow the current chunk counts
-    std::vector<int> nlev((size_t)idx->B * LC_MAX_LEVELS, 0);
-    for (size_t i = 0; i < nlev.size(); ++i) nlev[i] = idx->N[i];
-    LC_HIP_CHECK(hipMemcpyAsync(idx->dev.nlev, nlev.data(), nlev.size() * sizeof(int), hipMemcpyHostToDevice, s));
-    LC_HIP_CHECK(hipStreamSynchronize(s));        // the staging vector dies at return
+    const int rc = upload_level_counts(idx, s);
+    if (rc != LC_OK) return rc;
     int max_M = 0;
     for (int b = 0; b < idx->B; ++b)
         if (idx->M[b] > max_M) max_M = idx->M[b];
@@ -761,7 +806,9 @@ int lc_index_import(lc_index** out, const lc_config* cfg, const void* blob, size
                 }
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (rc == LC_OK) rc = upload_state(h, bounds_concat.data(), s);
+    // staged through the chunk centers' memory, which the copies below overwrite once the stream has drained
+    if (rc == LC_OK) rc = upload_state(h, bounds_concat.data(), h->dev.center[0], s);
+    if (rc == LC_OK && hipStreamSynchronize(s) != hipSuccess) rc = LC_ERR_HIP;
     if (rc == LC_OK) {
         const LcDev& D = h->dev;
         for (int b = 0; b < B && rc == LC_OK; ++b)

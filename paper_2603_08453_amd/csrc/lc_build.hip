@@ -27,13 +27,28 @@ __device__ __forceinline__ float lc_pad_radius(float r) { return r > 0.f ? r * (
 // covers the tokens around the value that is stored), and all threads hold the stored radius.
 // sh: LC_BG * 128 + LC_BG floats.
 // ---------------------------------------------------------------------------------
+#define LC_POOL_KEEP 8            // rows per 16-lane group that stay in registers between the two passes (chunks up to 128 tokens are read once)
 __device__ __forceinline__ void lc_pool_rows(const uint16_t* __restrict__ Kbh, long long ks_tok, int lo, int hi,
                                              int geometry, bool round_bf16, float* sh, float (&mu)[8], float* radius) {
     const int tid = threadIdx.x, sub = tid & 15, grp = tid >> 4;
     float sum[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) sum[i] = 0.f;
-    for (int r = lo + grp; r < hi; r += LC_BG) {
+    uint4 keep[LC_POOL_KEEP];
+#pragma unroll
+    for (int k = 0; k < LC_POOL_KEEP; ++k) {
+        const int r = lo + grp + k * LC_BG;
+        keep[k] = make_uint4(0u, 0u, 0u, 0u);
+        if (r < hi) keep[k] = *reinterpret_cast<const uint4*>(Kbh + (long long)r * ks_tok + 8 * sub);
+    }
+#pragma unroll
+    for (int k = 0; k < LC_POOL_KEEP; ++k) {          // (rows past the chunk hold zeros: they add nothing)
+        float f[8];
+        lc_unpack8(keep[k], f);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) sum[i] += f[i];
+    }
+    for (int r = lo + grp + LC_POOL_KEEP * LC_BG; r < hi; r += LC_BG) {
         const uint4 v = *reinterpret_cast<const uint4*>(Kbh + (long long)r * ks_tok + 8 * sub);
         float f[8];
         lc_unpack8(v, f);
@@ -77,8 +92,7 @@ __device__ __forceinline__ void lc_pool_rows(const uint16_t* __restrict__ Kbh, l
         for (int i = 0; i < 8; ++i) mu[i] = lc_round_bf16(mu[i]);
     }
     float far2 = 0.f;
-    for (int r = lo + grp; r < hi; r += LC_BG) {
-        const uint4 v = *reinterpret_cast<const uint4*>(Kbh + (long long)r * ks_tok + 8 * sub);
+    auto reach = [&](const uint4& v) {
         float f[8];
         lc_unpack8(v, f);
         float d2 = 0.f;
@@ -86,7 +100,12 @@ __device__ __forceinline__ void lc_pool_rows(const uint16_t* __restrict__ Kbh, l
         for (int i = 0; i < 8; ++i) { const float t = f[i] - mu[i]; d2 = fmaf(t, t, d2); }
         d2 = lc_sum16(d2);
         far2 = fmaxf(far2, d2);
-    }
+    };
+#pragma unroll
+    for (int k = 0; k < LC_POOL_KEEP; ++k)
+        if (lo + grp + k * LC_BG < hi) reach(keep[k]);
+    for (int r = lo + grp + LC_POOL_KEEP * LC_BG; r < hi; r += LC_BG)
+        reach(*reinterpret_cast<const uint4*>(Kbh + (long long)r * ks_tok + 8 * sub));
     __syncthreads();
     if (sub == 0) sh[grp] = far2;
     __syncthreads();
@@ -147,23 +166,93 @@ __device__ __forceinline__ void lc_c0_load8(const LcDev& ix, size_t n, int sub, 
 }
 
 // ---------------------------------------------------------------------------------
-// level 0: one block per chunk
+// level 0: one wavefront per chunk
 // ---------------------------------------------------------------------------------
+// The four 16-lane groups of a wavefront take the chunk's rows in turn (lane `sub` of a group holds
+// columns [8 sub, 8 sub + 8) of a row); the first LC_POOLW_KEEP rows of every group stay in registers
+// between the mean pass and the radius pass, so chunks of up to 4 * LC_POOLW_KEEP tokens are read
+// once (longer ones find their other rows in the L2 cache the second time).
+// No workgroup barrier: the groups' partial sums meet through wavefront shuffles.
+#define LC_POOLW_KEEP 8
+__device__ __forceinline__ float lc_sum_groups4(float v) { v += __shfl_xor(v, 16); v += __shfl_xor(v, 32); return v; }
 __global__ void __launch_bounds__(LC_BT)
 lc_pool_kernel(LcDev ix, const uint16_t* K, long long ks_seq, long long ks_head, long long ks_tok,
                int geometry, float* dirs) {
-    __shared__ float sh[LC_BG * LC_D + LC_BG];
-    const int j = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int h = blockIdx.y, b = blockIdx.z;
     const int bh = b * ix.H + h;
+    const int lane = threadIdx.x & 63, sub = lane & 15, g4 = lane >> 4;
+    const int j = blockIdx.x * (LC_BT / 64) + (threadIdx.x >> 6);
     const int M = ix.state[bh * 4 + 1];
-    if (j >= M) return;
+    if (j >= M) return;                                            // (whole wavefronts leave: nothing below waits across them)
     const int* bnd = ix.bounds + (size_t)b * (ix.cap[0] + 1);
     const int lo = bnd[j], hi = bnd[j + 1];
-    const int sub = threadIdx.x & 15;
-    float mu[8], radius;
-    lc_pool_rows(K + b * ks_seq + h * ks_head, ks_tok, lo, hi, geometry, ix.c0_bf16 != 0, sh, mu, &radius);
+    const uint16_t* Kbh = K + b * ks_seq + h * ks_head;
+    const bool round_bf16 = ix.c0_bf16 != 0;
+    uint4 keep[LC_POOLW_KEEP];
+#pragma unroll
+    for (int k = 0; k < LC_POOLW_KEEP; ++k) {
+        const int r = lo + g4 + 4 * k;
+        keep[k] = make_uint4(0u, 0u, 0u, 0u);
+        if (r < hi) keep[k] = *reinterpret_cast<const uint4*>(Kbh + (long long)r * ks_tok + 8 * sub);
+    }
+    float sum[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) sum[i] = 0.f;
+#pragma unroll
+    for (int k = 0; k < LC_POOLW_KEEP; ++k) {                       // (rows past the chunk hold zeros: they add nothing)
+        float f[8];
+        lc_unpack8(keep[k], f);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) sum[i] += f[i];
+    }
+    for (int r = lo + g4 + 4 * LC_POOLW_KEEP; r < hi; r += 4) {
+        float f[8];
+        lc_unpack8(*reinterpret_cast<const uint4*>(Kbh + (long long)r * ks_tok + 8 * sub), f);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) sum[i] += f[i];
+    }
+    // The rows stay packed (four registers each) across the two passes: an empty statement that
+    // claims to rewrite them keeps the compiler from holding their unpacked copies as well, which
+    // would double the registers per row and halve the resident wavefronts.
+#pragma unroll
+    for (int k = 0; k < LC_POOLW_KEEP; ++k)
+        asm volatile("" : "+v"(keep[k].x), "+v"(keep[k].y), "+v"(keep[k].z), "+v"(keep[k].w));
+    float mu[8];
+    const float inv_n = 1.0f / (float)(hi - lo);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) mu[i] = lc_sum_groups4(sum[i]) * inv_n;
+    float radius = 0.f;
+    if (geometry == LC_GEOMETRY_PAPER_UNIT) {
+        float un[8];
+        lc_unit_frag(mu, sub, un);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) mu[i] = round_bf16 ? lc_round_bf16(un[i]) : un[i];
+    } else {
+        if (round_bf16) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) mu[i] = lc_round_bf16(mu[i]);
+        }
+        float far2 = 0.f;
+        auto reach = [&](const uint4& v) {
+            float f[8];
+            lc_unpack8(v, f);
+            float d2 = 0.f;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) { const float t = f[i] - mu[i]; d2 = fmaf(t, t, d2); }
+            d2 = lc_sum16(d2);
+            far2 = fmaxf(far2, d2);
+        };
+#pragma unroll
+        for (int k = 0; k < LC_POOLW_KEEP; ++k)
+            if (lo + g4 + 4 * k < hi) reach(keep[k]);
+        for (int r = lo + g4 + 4 * LC_POOLW_KEEP; r < hi; r += 4)
+            reach(*reinterpret_cast<const uint4*>(Kbh + (long long)r * ks_tok + 8 * sub));
+        far2 = fmaxf(far2, __shfl_xor(far2, 16));
+        far2 = fmaxf(far2, __shfl_xor(far2, 32));
+        radius = lc_pad_radius(sqrtf(far2));
+    }
     const size_t n = (size_t)bh * ix.cap[0] + j;
-    if (threadIdx.x < 16) {
+    if (g4 == 0) {
         lc_c0_store8(ix, n, sub, mu);
         float u[8];
         lc_unit_frag(mu, sub, u);
@@ -218,37 +307,156 @@ lc_kmeans_init_kernel(LcDev ix, int l, const float* pts, int pts_cap, float* cen
     cent[((size_t)bh * cent_cap + c) * LC_D + threadIdx.x] = v;
 }
 
-// label(i) = argmax_c <x_i, m_c>, ties to the lower c.  One 16-lane group per point.
+// label(i) = argmax_c <x_i, m_c>, ties to the lower c: the one dense contraction of the build
+// (N x k x 128 per iteration), on the matrix cores in float32 (v_mfma_f32_16x16x4_f32).
+// A wavefront takes 16 points (the A operand, in registers for the whole kernel), the workgroup's
+// four wavefronts share centroid tiles staged in LDS (the B operand).  Both operands walk the 128
+// dimensions in the same permuted order -- step (t, u) pairs dimension 16 t + 4 kk + u of a point
+// with the same dimension of a centroid, kk = lane / 16 being the instruction's K index -- so that
+// each lane fetches its share of a row as eight 16-byte pieces.  The result tile leaves lane (q, j)
+// with the similarities of points 4 q + r (r < 4) to centroid j of the block; every lane keeps the
+// best of its column per point, and the 16 lanes of a row merge (value, then lower id) at the end.
+#define LC_AS_PTS 64              // points per workgroup
+#define LC_AS_TILE 64             // centroids per LDS tile
+#define LC_AS_ROW (LC_D + 4)      // floats per staged centroid row (the pad spreads the 16 rows of a block over the banks)
+typedef float lc_f32x4_b __attribute__((ext_vector_type(4)));
+// One 16 x 16 block of similarities: the wavefront's 16 points (xa, the A operand) against the 16
+// centroid rows of which `brow` is this lane's (already offset by 4 * kk); lane j's centroid has id c.
+__device__ __forceinline__ void lc_assign_block(const float4 (&xa)[8], const float* brow, int c, int k,
+                                                float (&best)[4], int (&arg)[4]) {
+    lc_f32x4_b d = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        const float4 mb = *reinterpret_cast<const float4*>(brow + 16 * t);
+        d = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[t].x, mb.x, d, 0, 0, 0);
+        d = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[t].y, mb.y, d, 0, 0, 0);
+        d = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[t].z, mb.z, d, 0, 0, 0);
+        d = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[t].w, mb.w, d, 0, 0, 0);
+    }
+    if (c < k) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            if (d[r] > best[r]) { best[r] = d[r]; arg[r] = c; }
+    }
+}
+// merge the 16 columns of a row: larger similarity wins, equal ones go to the lower centroid id
+__device__ __forceinline__ int lc_assign_merge(float bv, int ba) {
+    auto merge = [&](float ov, int oa) {
+        if (ov > bv || (ov == bv && oa < ba)) { bv = ov; ba = oa; }
+    };
+    merge(lc_dpp<0xB1>(bv), __builtin_amdgcn_update_dpp(0, ba, 0xB1, 0xF, 0xF, true));
+    merge(lc_dpp<0x4E>(bv), __builtin_amdgcn_update_dpp(0, ba, 0x4E, 0xF, 0xF, true));
+    merge(lc_dpp<0x141>(bv), __builtin_amdgcn_update_dpp(0, ba, 0x141, 0xF, 0xF, true));
+    merge(lc_dpp<0x140>(bv), __builtin_amdgcn_update_dpp(0, ba, 0x140, 0xF, 0xF, true));
+    return ba;
+}
 __global__ void __launch_bounds__(LC_BT)
 lc_kmeans_assign_kernel(LcDev ix, int l, const float* pts, int pts_cap, const float* cent, int cent_cap) {
+    __shared__ __attribute__((aligned(16))) float tile[LC_AS_TILE * LC_AS_ROW];
     const int h = blockIdx.y, b = blockIdx.z;
     const int bh = b * ix.H + h;
-    const int sub = threadIdx.x & 15, grp = threadIdx.x >> 4;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int j = lane & 15, kk = lane >> 4;
     const int N = lc_level_count(ix, b, bh, l);
     const int k = ix.nlev[b * LC_MAX_LEVELS + l + 1];
-    const int i = blockIdx.x * LC_BG + grp;
-    if (i >= N) return;
-    float x[8];
-    lc_load8(pts + ((size_t)bh * pts_cap + i) * LC_D + 8 * sub, x);
-    const float* cb = cent + (size_t)bh * cent_cap * LC_D;
-    float best = LC_NEG_INF;
-    int arg = 0;
-    for (int c = 0; c < k; ++c) {
-        float m[8];
-        lc_load8(cb + (size_t)c * LC_D + 8 * sub, m);
-        float p = 0.f;
+    const int i0 = blockIdx.x * LC_AS_PTS + wave * 16;             // this wavefront's first point
+    if ((int)blockIdx.x * LC_AS_PTS >= N) return;
+    // A operand: point i0 + j, dimensions 16 t + 4 kk + (0..3)
+    float4 xa[8];
+    {
+        const float* row = pts + ((size_t)bh * pts_cap + min(i0 + j, N - 1)) * LC_D + 4 * kk;
 #pragma unroll
-        for (int t = 0; t < 8; ++t) p = fmaf(x[t], m[t], p);
-        p = lc_sum16(p);
-        if (p > best) { best = p; arg = c; }
+        for (int t = 0; t < 8; ++t) xa[t] = *reinterpret_cast<const float4*>(row + 16 * t);
     }
-    if (sub == 0) ix.parent[l][(size_t)bh * ix.cap[l] + i] = arg;
+    const float* cb = cent + (size_t)bh * cent_cap * LC_D;
+    float best[4];
+    int arg[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) { best[r] = LC_NEG_INF; arg[r] = 0x7fffffff; }
+    // a tile's rows travel global memory -> registers -> LDS; the next tile's loads are issued
+    // before the current tile's products, so their latency is covered by the matrix work
+    constexpr int PF = LC_AS_TILE * (LC_D / 4) / LC_BT;             // float4 pieces per thread and tile
+    float4 pf[PF];
+    auto fetch = [&](int c0) {
+        const int nc = min(LC_AS_TILE, k - c0);
+#pragma unroll
+        for (int e = 0; e < PF; ++e) {
+            const int v = tid + e * LC_BT;
+            const int c = v / (LC_D / 4), q = v % (LC_D / 4);
+            pf[e] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (c < nc) pf[e] = *reinterpret_cast<const float4*>(cb + (size_t)(c0 + c) * LC_D + 4 * q);
+        }
+    };
+    fetch(0);
+    for (int c0 = 0; c0 < k; c0 += LC_AS_TILE) {
+        const int nc = min(LC_AS_TILE, k - c0);
+        __syncthreads();                                            // the previous tile has been used
+#pragma unroll
+        for (int e = 0; e < PF; ++e) {
+            const int v = tid + e * LC_BT;
+            *reinterpret_cast<float4*>(tile + (v / (LC_D / 4)) * LC_AS_ROW + 4 * (v % (LC_D / 4))) = pf[e];
+        }
+        if (c0 + LC_AS_TILE < k) fetch(c0 + LC_AS_TILE);
+        __syncthreads();
+        for (int cj = 0; cj < nc; cj += 16)
+            lc_assign_block(xa, tile + (cj + j) * LC_AS_ROW + 4 * kk, c0 + cj + j, k, best, arg);
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int ba = lc_assign_merge(best[r], arg[r]);
+        const int i = i0 + 4 * kk + r;
+        if (j == 0 && i < N) ix.parent[l][(size_t)bh * ix.cap[l] + i] = ba;
+    }
+}
+
+// Ascending list, in LDS, of the i in [base, base + LC_MEM_WIN) below n with lab[i] == c; returns its
+// length in every thread.  Every label is loaded once, coalesced, all loads in flight together;
+// positions come from wavefront ballots and one scan of the 64 (row, wavefront) counts, so the order
+// is fixed.  cnt: 2 * 64 + 1 ints of LDS; mem: LC_MEM_WIN ints.  All LC_BT threads must call.
+#define LC_MEM_WIN 4096
+__device__ __forceinline__ int lc_collect_members(const int* __restrict__ lab, int n, int base, int c, int* mem, int* cnt) {
+    constexpr int E = LC_MEM_WIN / LC_BT;
+    constexpr int W = LC_BT / 64;
+    static_assert(E * W == 64, "one wavefront scans the (row, wavefront) counts");
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int lv[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+        const int i = base + e * LC_BT + tid;
+        lv[e] = i < n ? lab[i] : -1;
+    }
+    unsigned long long m[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+        m[e] = __ballot(lv[e] == c);
+        if (lane == 0) cnt[e * W + wave] = __popcll(m[e]);
+    }
+    __syncthreads();
+    if (wave == 0) {
+        const int v = cnt[lane];
+        const int inc = lc_wave_scan_incl(v);
+        cnt[64 + lane] = inc - v;
+        if (lane == 63) cnt[128] = inc;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+        if (lv[e] == c) {
+            const unsigned long long below = m[e] & ((1ull << lane) - 1ull);
+            mem[cnt[64 + e * W + wave] + __popcll(below)] = base + e * LC_BT + tid;
+        }
+    }
+    __syncthreads();
+    return cnt[128];
 }
 
 // m_c = normalise(sum of members); a cluster without members (or with a zero sum) keeps m_c.
+// One workgroup per cluster: it lists its members (above), then the 16 groups add them up in turn.
 __global__ void __launch_bounds__(LC_BT)
 lc_kmeans_update_kernel(LcDev ix, int l, const float* pts, int pts_cap, float* cent, int cent_cap) {
     __shared__ float sh[LC_BG * LC_D];
+    __shared__ int mem[LC_MEM_WIN];
+    __shared__ int cnt[2 * 64 + 1];
     const int c = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int bh = b * ix.H + h;
     const int sub = threadIdx.x & 15, grp = threadIdx.x >> 4;
@@ -259,13 +467,16 @@ lc_kmeans_update_kernel(LcDev ix, int l, const float* pts, int pts_cap, float* c
     float sum[8];
 #pragma unroll
     for (int t = 0; t < 8; ++t) sum[t] = 0.f;
-    for (int i = grp; i < N; i += LC_BG) {
-        if (lab[i] == c) {
+    for (int base = 0; base < N; base += LC_MEM_WIN) {
+        const int nm = lc_collect_members(lab, N, base, c, mem, cnt);
+#pragma unroll 4
+        for (int t0 = grp; t0 < nm; t0 += LC_BG) {
             float x[8];
-            lc_load8(pts + ((size_t)bh * pts_cap + i) * LC_D + 8 * sub, x);
+            lc_load8(pts + ((size_t)bh * pts_cap + mem[t0]) * LC_D + 8 * sub, x);
 #pragma unroll
             for (int t = 0; t < 8; ++t) sum[t] += x[t];
         }
+        __syncthreads();                                            // the list is rewritten by the next window
     }
 #pragma unroll
     for (int t = 0; t < 8; ++t) sh[grp * LC_D + 8 * sub + t] = sum[t];
@@ -291,6 +502,125 @@ lc_kmeans_update_kernel(LcDev ix, int l, const float* pts, int pts_cap, float* c
     }
 }
 
+// The whole clustering of a small level (up to LC_KS_MAX_N points into up to LC_KS_MAX_K clusters)
+// in one kernel, one workgroup per (sequence, head): centroids and labels live in LDS, the
+// iterations are separated by workgroup barriers instead of kernel boundaries.  Same steps as the
+// three kernels above: strided start, assign (ties to the lower id), normalised member sums (members
+// added in ascending order; a cluster without members or with a zero sum keeps its centroid).
+#define LC_KS_MAX_N 224
+#define LC_KS_MAX_K 64
+static inline size_t lc_kmeans_small_lds(int N, int k) {
+    return (size_t)((N > 0 ? N : 1) + ((k + 15) & ~15)) * LC_AS_ROW * sizeof(float);
+}
+__global__ void __launch_bounds__(LC_BT)
+lc_kmeans_small_kernel(LcDev ix, int l, const float* pts, int pts_cap, float* cent, int cent_cap, int iters,
+                       int x_rows) {
+    extern __shared__ __attribute__((aligned(16))) float ks_dyn[];   // x_rows point rows, then the centroid rows
+    __shared__ int lab[LC_KS_MAX_N];
+    __shared__ int moff[LC_KS_MAX_K + 1];
+    __shared__ unsigned short mem[LC_KS_MAX_N];
+    const int h = blockIdx.x, b = blockIdx.y;
+    const int bh = b * ix.H + h;
+    const int tid = threadIdx.x, sub = tid & 15, grp = tid >> 4, lane = tid & 63, wave = tid >> 6;
+    const int j = lane & 15, kk = lane >> 4;
+    const int N = min(min(lc_level_count(ix, b, bh, l), LC_KS_MAX_N), x_rows);
+    const int k = min(ix.nlev[b * LC_MAX_LEVELS + l + 1], LC_KS_MAX_K);
+    const int k16 = (k + 15) & ~15;
+    const int rounds = (N + 63) >> 6;
+    const float* P = pts + (size_t)bh * pts_cap * LC_D;
+    float* X = ks_dyn;
+    float* cs = ks_dyn + (size_t)x_rows * LC_AS_ROW;
+    for (int v = tid; v < N * (LC_D / 4); v += LC_BT) {
+        const int i = v / (LC_D / 4), q = v % (LC_D / 4);
+        *reinterpret_cast<float4*>(X + i * LC_AS_ROW + 4 * q) = *reinterpret_cast<const float4*>(P + (size_t)i * LC_D + 4 * q);
+    }
+    for (int i = tid; i < N; i += LC_BT) lab[i] = 0;
+    __syncthreads();
+    for (int v = tid; v < k16 * LC_D; v += LC_BT) {
+        const int c = v / LC_D, t = v % LC_D;
+        float m = 0.f;
+        if (c < k) m = N > 0 ? X[(int)(((long long)c * N) / k) * LC_AS_ROW + t] : (t == 0 ? 1.f : 0.f);
+        cs[c * LC_AS_ROW + t] = m;
+    }
+    __syncthreads();
+    for (int it = 0; it < iters; ++it) {
+        for (int i0 = 16 * wave; i0 < N; i0 += 16 * (LC_BT / 64)) {
+            float4 xa[8];
+            const float* row = X + min(i0 + j, N - 1) * LC_AS_ROW + 4 * kk;
+#pragma unroll
+            for (int t = 0; t < 8; ++t) xa[t] = *reinterpret_cast<const float4*>(row + 16 * t);
+            float best[4];
+            int arg[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) { best[r] = LC_NEG_INF; arg[r] = 0x7fffffff; }
+            for (int cj = 0; cj < k; cj += 16)
+                lc_assign_block(xa, cs + (cj + j) * LC_AS_ROW + 4 * kk, cj + j, k, best, arg);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int ba = lc_assign_merge(best[r], arg[r]);
+                const int i = i0 + 4 * kk + r;
+                if (j == 0 && i < N) lab[i] = ba;
+            }
+        }
+        __syncthreads();
+        // members of every cluster, ascending, as one list ordered by cluster: counts, offsets, ids
+        for (int c = wave; c < k; c += LC_BT / 64) {
+            int n = 0;
+            for (int r = 0; r < rounds; ++r) {
+                const int i = lane + 64 * r;
+                n += __popcll(__ballot(i < N && lab[i] == c));
+            }
+            if (lane == 0) moff[c + 1] = n;
+        }
+        if (tid == 0) moff[0] = 0;
+        __syncthreads();
+        if (wave == 0) {
+            int v = lane < k ? moff[lane + 1] : 0;
+            v = lc_wave_scan_incl(v);
+            if (lane < k) moff[lane + 1] = v;
+        }
+        __syncthreads();
+        for (int c = wave; c < k; c += LC_BT / 64) {
+            int at = moff[c];
+            for (int r = 0; r < rounds; ++r) {
+                const int i = lane + 64 * r;
+                const bool in = i < N && lab[i] == c;
+                const unsigned long long m = __ballot(in);
+                if (in) mem[at + __popcll(m & ((1ull << lane) - 1ull))] = (unsigned short)i;
+                at += __popcll(m);
+            }
+        }
+        __syncthreads();
+        for (int c = grp; c < k; c += LC_BG) {
+            float sum[8];
+#pragma unroll
+            for (int t = 0; t < 8; ++t) sum[t] = 0.f;
+            const int j1 = moff[c + 1];
+#pragma unroll 4
+            for (int jm = moff[c]; jm < j1; ++jm) {
+                float x[8];
+                lc_load8(X + (int)mem[jm] * LC_AS_ROW + 8 * sub, x);
+#pragma unroll
+                for (int t = 0; t < 8; ++t) sum[t] += x[t];
+            }
+            float n2 = 0.f;
+#pragma unroll
+            for (int t = 0; t < 8; ++t) n2 = fmaf(sum[t], sum[t], n2);
+            n2 = lc_sum16(n2);
+            if (n2 > 0.f) {
+                const float inv = 1.0f / sqrtf(n2);
+#pragma unroll
+                for (int t = 0; t < 8; ++t) sum[t] *= inv;
+                lc_store8(cs + c * LC_AS_ROW + 8 * sub, sum);
+            }
+        }
+        __syncthreads();
+    }
+    for (int i = tid; i < N; i += LC_BT) ix.parent[l][(size_t)bh * ix.cap[l] + i] = lab[i];
+    for (int v = tid; v < k * LC_D; v += LC_BT)
+        cent[(size_t)bh * cent_cap * LC_D + v] = cs[(v / LC_D) * LC_AS_ROW + (v % LC_D)];
+}
+
 // anc[j] <- label of anc[j] at the level just clustered (anc starts as identity)
 __global__ void lc_anc_kernel(LcDev ix, int l, int* anc) {
     const int h = blockIdx.y, b = blockIdx.z;
@@ -304,11 +634,14 @@ __global__ void lc_anc_kernel(LcDev ix, int l, int* anc) {
 }
 
 // node u of level l+1: center, radius over all descendant chunks, counts, direction
+#define LC_NODE_BATCH 8
 __global__ void __launch_bounds__(LC_BT)
 lc_node_kernel(LcDev ix, int l, const int* anc, const float* cent, int cent_cap, int geometry,
                float* next_pts, int next_cap) {
     __shared__ float sh[LC_BG * LC_D + LC_BG];
     __shared__ int shi[2 * LC_BG];
+    __shared__ int mem[LC_MEM_WIN];
+    __shared__ int mcnt[2 * 64 + 1];
     const int u = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int bh = b * ix.H + h;
     const int sub = threadIdx.x & 15, grp = threadIdx.x >> 4;
@@ -317,19 +650,39 @@ lc_node_kernel(LcDev ix, int l, const int* anc, const float* cent, int cent_cap,
     const int M = ix.state[bh * 4 + 1];
     const int* a = anc + (size_t)bh * ix.cap[0];
     const size_t cb = (size_t)bh * ix.cap[0];
+    // the node's chunks are listed window by window (lc_collect_members); the 16 groups take them in turn
     float sum[8];
 #pragma unroll
     for (int t = 0; t < 8; ++t) sum[t] = 0.f;
     int cnt = 0, tok = 0;
-    for (int j = grp; j < M; j += LC_BG) {
-        if (a[j] == u) {
-            float c[8];
-            lc_c0_load8(ix, cb + j, sub, c);
+    int nm = 0;
+    for (int base = 0; base < M; base += LC_MEM_WIN) {
+        nm = lc_collect_members(a, M, base, u, mem, mcnt);
+        for (int t0 = grp; t0 < nm; t0 += LC_NODE_BATCH * LC_BG) {  // a batch of rows in flight per group
+            float c[LC_NODE_BATCH][8];
+            int nt[LC_NODE_BATCH];
 #pragma unroll
-            for (int t = 0; t < 8; ++t) sum[t] += c[t];
-            cnt += 1;
-            tok += ix.ntok[0][cb + j];
+            for (int q = 0; q < LC_NODE_BATCH; ++q) {
+                const int t1 = t0 + q * LC_BG;
+                const bool in = t1 < nm;
+                nt[q] = -1;
+                if (in) {
+                    const int j = mem[t1];
+                    lc_c0_load8(ix, cb + j, sub, c[q]);
+                    nt[q] = ix.ntok[0][cb + j];
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < LC_NODE_BATCH; ++q) {
+                if (nt[q] >= 0) {
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) sum[t] += c[q][t];
+                    cnt += 1;
+                    tok += nt[q];
+                }
+            }
         }
+        if (base + LC_MEM_WIN < M) __syncthreads();                 // the list is rewritten by the next window
     }
 #pragma unroll
     for (int t = 0; t < 8; ++t) sh[grp * LC_D + 8 * sub + t] = sum[t];
@@ -351,16 +704,34 @@ lc_node_kernel(LcDev ix, int l, const int* anc, const float* cent, int cent_cap,
     }
     __syncthreads();
     float far = LC_NEG_INF;
-    for (int j = grp; j < M; j += LC_BG) {
-        if (a[j] == u) {
-            float c[8];
-            lc_c0_load8(ix, cb + j, sub, c);
-            float d2 = 0.f;
+    for (int base = 0; base < M; base += LC_MEM_WIN) {
+        if (M > LC_MEM_WIN) nm = lc_collect_members(a, M, base, u, mem, mcnt);    // (a single window still holds its list)
+        for (int t0 = grp; t0 < nm; t0 += LC_NODE_BATCH * LC_BG) {
+            float c[LC_NODE_BATCH][8];
+            float r0[LC_NODE_BATCH];
 #pragma unroll
-            for (int t = 0; t < 8; ++t) { const float e = c[t] - mu[t]; d2 = fmaf(e, e, d2); }
-            d2 = lc_sum16(d2);
-            far = fmaxf(far, lc_pad_radius(sqrtf(d2)) + ix.radius[0][cb + j]);
+            for (int q = 0; q < LC_NODE_BATCH; ++q) {
+                const int t1 = t0 + q * LC_BG;
+                const bool in = t1 < nm;
+#pragma unroll
+                for (int t = 0; t < 8; ++t) c[q][t] = mu[t];
+                r0[q] = LC_NEG_INF;                                 // (a slot past the list reaches nothing)
+                if (in) {
+                    const int j = mem[t1];
+                    lc_c0_load8(ix, cb + j, sub, c[q]);
+                    r0[q] = ix.radius[0][cb + j];
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < LC_NODE_BATCH; ++q) {
+                float d2 = 0.f;
+#pragma unroll
+                for (int t = 0; t < 8; ++t) { const float e = c[q][t] - mu[t]; d2 = fmaf(e, e, d2); }
+                d2 = lc_sum16(d2);
+                far = fmaxf(far, lc_pad_radius(sqrtf(d2)) + r0[q]);
+            }
         }
+        if (base + LC_MEM_WIN < M) __syncthreads();
     }
     if (sub == 0) sh[grp] = far;
     __syncthreads();
@@ -391,7 +762,7 @@ int lc_launch_build(const lc_index* idx, const LcWs& ws, const void* Kp, const i
     const int geometry = idx->cfg.geometry;
     const int B = ix.B, H = ix.H, L = ix.L;
     if (max_M > 0 && K != nullptr) {
-        hipLaunchKernelGGL(lc_pool_kernel, dim3(max_M, H, B), dim3(LC_BT), 0, stream, ix, K,
+        hipLaunchKernelGGL(lc_pool_kernel, dim3((max_M + LC_BT / 64 - 1) / (LC_BT / 64), H, B), dim3(LC_BT), 0, stream, ix, K,
                            (long long)ks[0], (long long)ks[1], (long long)ks[2], geometry, ws.dirs);
         LC_HIP_CHECK(hipGetLastError());
     } else if (max_M > 0) {
@@ -410,12 +781,22 @@ int lc_launch_build(const lc_index* idx, const LcWs& ws, const void* Kp, const i
             maxK = idx->N[b * LC_MAX_LEVELS + l + 1] > maxK ? idx->N[b * LC_MAX_LEVELS + l + 1] : maxK;
         }
         const int cent_cap = ix.cap[1];
-        hipLaunchKernelGGL(lc_kmeans_init_kernel, dim3(maxK, H, B), dim3(LC_D), 0, stream, ix, l,
-                           (const float*)pts, pts_cap, ws.cent_a, cent_cap);
+        const bool small = maxN <= LC_KS_MAX_N && maxK <= LC_KS_MAX_K;      // the whole clustering in one kernel
+        if (small) {
+            const int x_rows = maxN > 0 ? maxN : 1;
+            const size_t lds = lc_kmeans_small_lds(x_rows, maxK);
+            LC_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&lc_kmeans_small_kernel),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+            hipLaunchKernelGGL(lc_kmeans_small_kernel, dim3(H, B), dim3(LC_BT), lds, stream, ix, l, (const float*)pts,
+                               pts_cap, ws.cent_a, cent_cap, idx->cfg.kmeans_iters, x_rows);
+        } else {
+            hipLaunchKernelGGL(lc_kmeans_init_kernel, dim3(maxK, H, B), dim3(LC_D), 0, stream, ix, l,
+                               (const float*)pts, pts_cap, ws.cent_a, cent_cap);
+        }
         LC_HIP_CHECK(hipGetLastError());
         if (maxN > 0) {
-            for (int it = 0; it < idx->cfg.kmeans_iters; ++it) {
-                hipLaunchKernelGGL(lc_kmeans_assign_kernel, dim3((maxN + LC_BG - 1) / LC_BG, H, B), dim3(LC_BT), 0,
+            for (int it = 0; it < (small ? 0 : idx->cfg.kmeans_iters); ++it) {
+                hipLaunchKernelGGL(lc_kmeans_assign_kernel, dim3((maxN + LC_AS_PTS - 1) / LC_AS_PTS, H, B), dim3(LC_BT), 0,
                                    stream, ix, l, (const float*)pts, pts_cap, (const float*)ws.cent_a, cent_cap);
                 hipLaunchKernelGGL(lc_kmeans_update_kernel, dim3(maxK, H, B), dim3(LC_BT), 0, stream, ix, l,
                                    (const float*)pts, pts_cap, ws.cent_a, cent_cap);
@@ -471,6 +852,30 @@ lc_drift_kernel(LcDev ix, int level, float* out) {
         for (int w = 0; w < LC_BT / 64; ++w) { a += sh[0][w]; c += sh[1][w]; g = fmaxf(g, sh[2][w]); k += sh[3][w]; }
         out[bh * 4 + 0] = a; out[bh * 4 + 1] = c; out[bh * 4 + 2] = g; out[bh * 4 + 3] = k;
     }
+}
+
+// staged = [state: B*H*4 | nlev: B*LC_MAX_LEVELS | boundaries: M_0 + 1, M_1 + 1, ...]; block b < B
+// moves sequence b's boundaries, block B the counts (and clears the arrival counters).
+__global__ void __launch_bounds__(LC_BT)
+lc_place_state_kernel(LcDev ix, const int32_t* staged, int B) {
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const int n_state = B * ix.H * 4, n_nlev = B * LC_MAX_LEVELS;
+    if (b == B) {
+        for (int i = tid; i < n_state; i += LC_BT) { ix.state[i] = staged[i]; ix.sync[i] = 0; }
+        for (int i = tid; i < n_nlev; i += LC_BT) ix.nlev[i] = staged[n_state + i];
+        return;
+    }
+    int off = n_state + n_nlev;
+    for (int s = 0; s < b; ++s) off += staged[s * ix.H * 4 + 1] + 1;
+    const int n = staged[b * ix.H * 4 + 1] + 1;
+    int* dst = ix.bounds + (size_t)b * (ix.cap[0] + 1);
+    for (int i = tid; i < n; i += LC_BT) dst[i] = staged[off + i];
+}
+
+int lc_launch_place_state(const lc_index* idx, const int32_t* staged, hipStream_t stream) {
+    hipLaunchKernelGGL(lc_place_state_kernel, dim3(idx->B + 1), dim3(LC_BT), 0, stream, idx->dev, staged, idx->B);
+    LC_HIP_CHECK(hipGetLastError());
+    return LC_OK;
 }
 
 int lc_launch_drift(const lc_index* idx, int level, float* out, hipStream_t stream) {

@@ -104,6 +104,9 @@ int lc_launch_decode_fused(const lc_index* idx, const LcWs& ws, const void* q, c
                            int32_t* counts_out, int cap, int max_M, float* out, float* lse, hipStream_t stream);
 // out (device): [B][H][4] floats: sum of radii at build, sum now, largest growth, nodes counted
 int lc_launch_drift(const lc_index* idx, int level, float* out, hipStream_t stream);
+// Puts a staged [state | nlev | chunk boundaries of all sequences] block (device memory) in place
+// and zeroes the arrival counters.
+int lc_launch_place_state(const lc_index* idx, const int32_t* staged, hipStream_t stream);
 int lc_launch_append(const lc_index* idx, void* K, void* V, const int64_t ks[3],
                      const void* k_new, const void* v_new, const uint8_t* close_dev_flags_or_null,
                      uint32_t close_mask_lo, hipStream_t stream);
