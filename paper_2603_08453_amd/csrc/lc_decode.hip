@@ -13,8 +13,6 @@
 //   V row (one 16-byte load), four rows make a full 1 KiB wavefront load.
 #include <type_traits>
 
-#define LC_SEL_STAMP_X false          // (the selection's own stamps are for the chunk kernel)
-#define LC_SEL_LSTAMP(i) LC_LSTAMP0(20 + (i))
 #include "lc_device.h"
 #include "lc_internal.h"
 #include "lc_select.h"
@@ -34,12 +32,6 @@
 typedef __bf16 lc_bf16x8 __attribute__((ext_vector_type(8)));
 typedef float lc_f32x4 __attribute__((ext_vector_type(4)));
 
-LC_STAMP_DECL(lc_dbg_decode)
-#ifdef LC_DBG_TIMES
-extern "C" int lc_dbg_sel2_read(unsigned long long* host) {
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(lc_dbg_sel), sizeof(lc_dbg_sel));
-}
-#endif
 
 struct LcDecodeArgs {
     LcDev ix;
@@ -122,8 +114,6 @@ lc_decode_kernel(const LcDecodeArgs a) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int sub = tid & 15, grp = tid >> 4, q4 = lane >> 4;
 
-    LC_LSTAMP_INIT();
-    LC_LSTAMP0(0);
     const int* bnd = ix.bounds + (size_t)b * (ix.cap[0] + 1);
     // the query block in MFMA B layout (lane (q4, n): head n, columns 8 q4 + 32 j + [0, 8))
     uint4 qb[4];
@@ -190,7 +180,6 @@ lc_decode_kernel(const LcDecodeArgs a) {
         n_tok = cs.n_tok;
         n_runs = cs.n_sel + 1;
     }
-    LC_LSTAMP0(1);
     int S_eff = (n_tok + LC_DEC_MIN_TOKENS_PER_SPLIT - 1) / LC_DEC_MIN_TOKENS_PER_SPLIT;
     S_eff = max(1, min(S, S_eff));
 
@@ -286,7 +275,6 @@ lc_decode_kernel(const LcDecodeArgs a) {
             }
         };
 
-        LC_LSTAMP0(8);
         // The split's tokens are handled in tiles; for each tile the workgroup first writes the cache
         // row of every token into LDS, then every group streams a contiguous slice of the tile.
         for (int tile0 = lo; tile0 < hi; tile0 += LC_DEC_TILE) {
@@ -311,7 +299,6 @@ lc_decode_kernel(const LcDecodeArgs a) {
                 }
                 if (wave == 0 && cs.tail_ln > 0 && cs.n_sel_tok < tile0 + tl && tile0 < cs.n_sel_tok + cs.tail_ln)
                     fill(cs.n_sel_tok, cs.tail_st, cs.tail_ln);
-                LC_LSTAMP0(17);
                 lc_barrier_lds();
             } else {
                 // The few entries that overlap the tile go into a window at slot (entry index mod window
@@ -319,7 +306,6 @@ lc_decode_kernel(const LcDecodeArgs a) {
                 // entries that hold the tile's first and last token leave their indices; then one small
                 // binary search per token, in parallel.
                 __syncthreads();
-                LC_LSTAMP0(16);
                 {
                     auto entry = [&](int i, int off, int st, int ln) {
                         if (ln > 0 && off < tile0 + tl && tile0 < off + ln) {
@@ -345,9 +331,7 @@ lc_decode_kernel(const LcDecodeArgs a) {
                         carry += tot;
                     }
                 }
-                LC_LSTAMP0(17);
                 __syncthreads();
-                LC_LSTAMP0(13);
                 {
                     const int w_first = win_hd[0], w_last = win_hd[1];
                     for (int i = tid; i < tl; i += LC_DEC_THREADS) {
@@ -363,7 +347,6 @@ lc_decode_kernel(const LcDecodeArgs a) {
                 }
                 __syncthreads();
             }
-            LC_LSTAMP0(9);
             const int per = (tl + LC_DEC_GROUPS - 1) / LC_DEC_GROUPS;
             const int n_it = (per + U - 1) / U;            // the same for every wavefront: the MFMA needs all lanes
             tv = min(tl, grp * per);
@@ -375,14 +358,12 @@ lc_decode_kernel(const LcDecodeArgs a) {
             for (int it = 0; it < n_it; it += 2) {
                 if (it + 1 < n_it) issue(it + 1, kB, vB);
                 consume(it, kA, vA);
-                LC_LSTAMP0(10);
                 if (it + 1 >= n_it) break;
                 if (it + 2 < n_it) issue(it + 2, kA, vA);
                 consume(it + 1, kB, vB);
             }
         }
 
-        LC_LSTAMP0(2);
         // ---- combine the 4 groups of a wave (xor 16, 32), then the waves through LDS
 #pragma unroll
         for (int off = 16; off < 64; off <<= 1) {
@@ -413,7 +394,6 @@ lc_decode_kernel(const LcDecodeArgs a) {
             }
         }
         __syncthreads();
-        LC_LSTAMP0(14);
         // one float4 slot of the split's partial per thread, stored at agent scope
         float* pml = a.part_ml + ((size_t)bh * S + s) * G * 2;
         const __amdgpu_buffer_rsrc_t pacc_w = lc_buffer(a.part_acc + ((size_t)bh * S + s) * G * LC_D);
@@ -438,14 +418,9 @@ lc_decode_kernel(const LcDecodeArgs a) {
         }
     }
 
-    LC_LSTAMP0(3);
     // ---- the last split to arrive merges (log-sum-exp merge of the partial results)
-    if (!lc_arrive_last(&ix.sync[bh * 4 + 1], S, &last_sh)) {
-        LC_LSTAMP_FLUSH(lc_dbg_decode);
-        return;
-    }
+    if (!lc_arrive_last(&ix.sync[bh * 4 + 1], S, &last_sh)) return;
 
-    LC_LSTAMP(4);
     // The accumulator partials do not depend on the scales, so their loads go out first and fly
     // while the (m, l) pairs are fetched and turned into per-split scales.
     const __amdgpu_buffer_rsrc_t pacc_r = lc_buffer(a.part_acc + (size_t)bh * S * G * LC_D);
@@ -486,7 +461,6 @@ lc_decode_kernel(const LcDecodeArgs a) {
         if (lane == 0) { mrg_hd[2 * gg] = mx; mrg_hd[2 * gg + 1] = den; }
     }
     __syncthreads();
-    LC_LSTAMP(5);
     float4 acc4 = make_float4(0.f, 0.f, 0.f, 0.f);
     if (wy < WAYS) {
         for (int sp0 = wy; sp0 < n_part; sp0 += MR * WAYS) {
@@ -504,7 +478,6 @@ lc_decode_kernel(const LcDecodeArgs a) {
         if (WAYS > 1 && wy > 0) mrg_red[(wy - 1) * NV + v] = acc4;
     }
     __syncthreads();
-    LC_LSTAMP(6);
     if (wy == 0) {
 #pragma unroll
         for (int k = 1; k < WAYS; ++k) {
@@ -518,8 +491,6 @@ lc_decode_kernel(const LcDecodeArgs a) {
             make_float4(acc4.x * inv, acc4.y * inv, acc4.z * inv, acc4.w * inv);
         if (a.lse && c4 == 0) a.lse[o] = den > 0.f ? (mx + log2f(den)) * LC_LN2 : LC_NEG_INF;
     }
-    LC_LSTAMP(7);
-    LC_LSTAMP_FLUSH(lc_dbg_decode);
     if (tid == 0) ix.sync[bh * 4 + 1] = 0;
 }
 

@@ -6,42 +6,6 @@
 
 #define LC_D 128                  // head dimension the kernels are written for
 
-// Development aid (off in the product build): phase time stamps of one workgroup.
-#ifdef LC_DBG_TIMES
-#define LC_STAMP_DECL(name) __device__ unsigned long long name[32]; \
-    extern "C" int name##_read(unsigned long long* host) { \
-        return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(name), sizeof(name)); }
-#define LC_STAMP0(name, i) do { if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) \
-    name[i] = wall_clock64(); } while (0)
-#define LC_STAMP(name, i) do { if (blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) name[i] = wall_clock64(); } while (0)
-static __device__ unsigned long long lc_dbg_sel[32];
-#ifndef LC_SEL_STAMP_X
-#define LC_SEL_STAMP_X true
-#endif
-#define LC_SEL_STAMP(i) do { if ((LC_SEL_STAMP_X) && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) lc_dbg_sel[i] = wall_clock64(); } while (0)
-// The same, parked in LDS and written out when the workgroup leaves: a global store at the stamp
-// would be waited for by the next barrier (a barrier drains the vector memory counter) and so
-// lengthen the very phase it is meant to time.
-static __shared__ unsigned long long lc_stamp_lds[32];
-#define LC_LSTAMP_INIT() do { if (threadIdx.x == 0) for (int i_ = 0; i_ < 32; ++i_) lc_stamp_lds[i_] = 0ull; } while (0)
-#define LC_LSTAMP0(i) do { if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) \
-    lc_stamp_lds[i] = wall_clock64(); } while (0)
-#define LC_LSTAMP(i) do { if (blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) lc_stamp_lds[i] = wall_clock64(); } while (0)
-#define LC_LSTAMP_FLUSH(name) do { if (blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) \
-    for (int i_ = 0; i_ < 32; ++i_) if (lc_stamp_lds[i_] != 0ull) name[i_] = lc_stamp_lds[i_]; } while (0)
-#else
-#define LC_SEL_STAMP(i)
-#define LC_STAMP_DECL(name)
-#define LC_STAMP0(name, i)
-#define LC_STAMP(name, i)
-#define LC_LSTAMP_INIT()
-#define LC_LSTAMP0(i)
-#define LC_LSTAMP(i)
-#define LC_LSTAMP_FLUSH(name)
-#endif
-#ifndef LC_SEL_LSTAMP
-#define LC_SEL_LSTAMP(i)
-#endif
 #define LC_NEG_INF (-__builtin_huge_valf())
 
 // ---------------------------------------------------------------- bf16 unpacking
@@ -402,7 +366,6 @@ __device__ __forceinline__ LcSel lc_block_select(int n, long long W, long long C
     out.kstar = 0u;
     out.remW = 0;
     out.remC = 0;
-    LC_SEL_STAMP(0); LC_SEL_LSTAMP(0);
     // ---- range of the candidate keys
     if (!have_range) {
         for (int i = threadIdx.x; i < n; i += NT) {
@@ -416,7 +379,6 @@ __device__ __forceinline__ LcSel lc_block_select(int n, long long W, long long C
     __syncthreads();
 #pragma unroll
     for (int w = 0; w < NT / 64; ++w) { kmin = min(kmin, (uint32_t)mm[w]); kmax = max(kmax, (uint32_t)mm[32 + w]); }
-    LC_SEL_STAMP(1); LC_SEL_LSTAMP(1);
     if (kmax == 0u) { out.all = 1; __syncthreads(); return out; }            // no candidate at all
     const uint32_t diff = kmin ^ kmax;
     int top = diff ? 32 - __clz(diff) : 0;                   // bits [0, top) may differ
@@ -430,7 +392,6 @@ __device__ __forceinline__ LcSel lc_block_select(int n, long long W, long long C
     while (top > 0) {
         const int width = top >= 8 ? 8 : top;
         const int shift = top - width;
-        LC_SEL_STAMP(2 + 3 * npass); LC_SEL_LSTAMP(2 + 3 * npass);
         for (int i = threadIdx.x; i < 256; i += NT) { hw[i] = 0; hc[i] = 0; }
         __syncthreads();
         for (int i = threadIdx.x; i < n; i += NT) {
@@ -442,7 +403,6 @@ __device__ __forceinline__ LcSel lc_block_select(int n, long long W, long long C
             }
         }
         __syncthreads();
-        LC_SEL_STAMP(3 + 3 * npass); LC_SEL_LSTAMP(3 + 3 * npass);
         if (threadIdx.x < 64) {
             const int l = threadIdx.x;
             int w[4], c[4];
@@ -471,7 +431,6 @@ __device__ __forceinline__ LcSel lc_block_select(int n, long long W, long long C
             }
         }
         __syncthreads();
-        LC_SEL_STAMP(4 + 3 * npass); LC_SEL_LSTAMP(4 + 3 * npass);
         ++npass;
         const int found = res[0];
         if (found < 0) {            // everything in scope fits: only possible in the first pass
@@ -602,7 +561,6 @@ template <int NT>
 __device__ __forceinline__ uint32_t lc_leaf_select(int n, uint32_t* skey, const int* slen, long long W, long long C,
                                                    LcLeafSelSh& sh) {
     const int tid = threadIdx.x;
-    LC_SEL_STAMP(0); LC_SEL_LSTAMP(0);
     const uint32_t kmin = (uint32_t)sh.mm[0], kmax = (uint32_t)sh.mm[1];
     if (kmax == 0u) return 0u;                                   // no candidate at all
     int remW = (int)(W > 0x7fffffffLL ? 0x7fffffffLL : (W < 0 ? 0 : W));
@@ -611,7 +569,6 @@ __device__ __forceinline__ uint32_t lc_leaf_select(int n, uint32_t* skey, const 
     uint32_t lo = kmin, hi = kmax;
     int pass = 0;
     for (;;) {
-        LC_SEL_STAMP(1 + 4 * pass); LC_SEL_LSTAMP(1 + 4 * pass);
         const uint32_t span = hi - lo;
         const int bits = span ? 32 - __clz(span) : 0;
         const int shift = bits > LC_LS_BITS ? bits - LC_LS_BITS : 0;     // (span >> shift) < LC_LS_BINS
@@ -630,7 +587,6 @@ __device__ __forceinline__ uint32_t lc_leaf_select(int n, uint32_t* skey, const 
             }
         }
         __syncthreads();
-        LC_SEL_STAMP(2 + 4 * pass); LC_SEL_LSTAMP(2 + 4 * pass);
         // descending scan: thread t looks at bin 1023 - t (at PER consecutive bins with fewer threads)
         constexpr int PER = LC_LS_BINS / NT;
         int w[PER], c[PER], sw = 0, sc = 0;
@@ -661,7 +617,6 @@ __device__ __forceinline__ uint32_t lc_leaf_select(int n, uint32_t* skey, const 
             cc += c[j];
         }
         __syncthreads();
-        LC_SEL_STAMP(3 + 4 * pass); LC_SEL_LSTAMP(3 + 4 * pass);
         const int fb = sh.res[0];
         if (fb < 0) return lo - 1u;                               // every candidate in scope fits
         remW -= sh.res[1];
@@ -679,7 +634,6 @@ __device__ __forceinline__ uint32_t lc_leaf_select(int n, uint32_t* skey, const 
             }
         }
         __syncthreads();
-        LC_SEL_STAMP(4 + 4 * pass); LC_SEL_LSTAMP(4 + 4 * pass);
         const int nc = sh.ncand;
         if (nc <= LC_LS_CAND) {
             // ---- ranked directly

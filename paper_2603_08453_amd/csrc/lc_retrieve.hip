@@ -23,14 +23,6 @@
 #define LC_TAU_SLACK 1e-3f
 #define LC_COUNT_SELECT_MAX 1024         // up to this many candidates the O(n^2 / threads) rank is used
 
-LC_STAMP_DECL(lc_dbg_upper)
-LC_STAMP_DECL(lc_dbg_leaf)
-LC_STAMP_DECL(lc_dbg_beam)
-#ifdef LC_DBG_TIMES
-extern "C" int lc_dbg_sel_read(unsigned long long* host) {
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(lc_dbg_sel), sizeof(lc_dbg_sel));
-}
-#endif
 
 struct LcRetrieveArgs {
     LcDev ix;
@@ -121,7 +113,6 @@ lc_upper_kernel(const LcRetrieveArgs a) {
     __shared__ int off_sh[LC_MAX_LEVELS + 1];
     constexpr int NB = (G <= 4) ? 4 : 2;          // nodes in flight per group
 
-    LC_STAMP0(lc_dbg_upper, 0);
     const LcDev& ix = a.ix;
     const int h = blockIdx.x, b = blockIdx.y;
     const int bh = b * ix.H + h;
@@ -178,7 +169,6 @@ lc_upper_kernel(const LcRetrieveArgs a) {
     }
     __syncthreads();
     const int NU = off_sh[L];
-    LC_STAMP0(lc_dbg_upper, 1);
 
     // ---- internal nodes, all levels as one list: parents, token counts, scores
     auto level_of = [&](int u) -> int {
@@ -214,7 +204,6 @@ lc_upper_kernel(const LcRetrieveArgs a) {
         }
     }
     __syncthreads();
-    LC_STAMP0(lc_dbg_upper, 2);
 
     uint8_t* want = a.want + (size_t)bh * ix.cap[0];
     const int* bnd = ix.bounds + (size_t)b * (ix.cap[0] + 1);
@@ -262,9 +251,7 @@ lc_upper_kernel(const LcRetrieveArgs a) {
                     kp[o + i] = (ek[i] != 0u && (r.all || ek[i] >= r.kstar)) ? 1 : 0;      // whole tie group
             }
         }
-        LC_STAMP0(lc_dbg_upper, 8 + 3 * (L - 1 - l));
         __syncthreads();
-        LC_STAMP0(lc_dbg_upper, 9 + 3 * (L - 1 - l));
         if (l >= 2) {                 // stage the children of the kept nodes as the next level's candidates
             const int ob = off_sh[l - 1], n_b = off_sh[l] - ob;
             for (int n = tid; n < ((n_b + 3) & ~3); n += LC_UP_THREADS) {
@@ -276,9 +263,7 @@ lc_upper_kernel(const LcRetrieveArgs a) {
             uint32_t* tk = ek; ek = ek_next; ek_next = tk;
             int* tw = ew; ew = ew_next; ew_next = tw;
         }
-        LC_STAMP0(lc_dbg_upper, 10 + 3 * (L - 1 - l));
     }
-    LC_STAMP0(lc_dbg_upper, 3);
     // ---- compact the probe's chunks (children of the kept level-1 nodes, not pinned) into LDS.
     // The list holds at most PC chunks; dropping the rest only weakens tau0, never the result.
     int n_probe = 0;
@@ -315,7 +300,6 @@ lc_upper_kernel(const LcRetrieveArgs a) {
     }
     n_probe = min(n_probe, PC);
     __syncthreads();
-    LC_STAMP0(lc_dbg_upper, 4);
     // ---- score them
     {
         const size_t cb = (size_t)bh * ix.cap[0];
@@ -340,7 +324,6 @@ lc_upper_kernel(const LcRetrieveArgs a) {
         if (tid < 4 && n_probe + tid < ((n_probe + 3) & ~3)) { pkey[n_probe + tid] = 0u; plen[n_probe + tid] = 0; }
     }
     __syncthreads();
-    LC_STAMP0(lc_dbg_upper, 5);
     // ---- tau0: the score at which the probe chunks' cumulative length reaches the budget
     uint32_t tau_key = 1u;                  // keep everything unless the probe proves a cutoff
     {
@@ -362,7 +345,6 @@ lc_upper_kernel(const LcRetrieveArgs a) {
             if (tau_key == 0u) tau_key = 1u;
         }
     }
-    LC_STAMP0(lc_dbg_upper, 6);
     // ---- verify pass: keep every node whose bound reaches tau0 and whose parent was kept
     {
         const int o = off_sh[L - 1], n_l = off_sh[L] - o;
@@ -376,7 +358,6 @@ lc_upper_kernel(const LcRetrieveArgs a) {
         __syncthreads();
     }
     write_want();
-    LC_STAMP0(lc_dbg_upper, 7);
 }
 
 
@@ -407,7 +388,6 @@ lc_beam_kernel(const LcRetrieveArgs a) {
     __shared__ uint32_t kept[LC_BM_KEPT_WORDS];
     constexpr int NB = G <= 6 ? 2 : 1;            // nodes in flight per group (the lists are short; 128 registers per lane)
 
-    LC_STAMP0(lc_dbg_beam, 0);
     const LcDev& ix = a.ix;
     const int h = blockIdx.x, b = blockIdx.y;
     const int bh = b * ix.H + h;
@@ -470,7 +450,6 @@ lc_beam_kernel(const LcRetrieveArgs a) {
     for (int i = tid; i < n_c; i += LC_BM_THREADS) cid[i] = i;
     __syncthreads();
 
-    LC_STAMP0(lc_dbg_beam, 1);
     for (int l = L - 1; l >= 1; --l) {
         uint32_t* key = in_lds ? l_key : g_key;
         int* wgt = in_lds ? l_wgt : g_wgt;
@@ -497,7 +476,6 @@ lc_beam_kernel(const LcRetrieveArgs a) {
         }
         if (in_lds && tid < 4 && n_c + tid < ((n_c + 3) & ~3)) { key[n_c + tid] = 0u; wgt[n_c + tid] = 0; }
         __syncthreads();
-        LC_STAMP0(lc_dbg_beam, 2 + 4 * (L - 1 - l));
         // ---- keep the beam[l] best
         const long long C = a.beam[l] > 0 ? a.beam[l] : 0x7fffffffLL;
         if (in_lds && n_c <= LC_COUNT_SELECT_MAX) {
@@ -519,7 +497,6 @@ lc_beam_kernel(const LcRetrieveArgs a) {
                 tie_c += tot;
             }
         }
-        LC_STAMP0(lc_dbg_beam, 3 + 4 * (L - 1 - l));
         // ---- bitmap of the kept nodes
         const int n_l = ix.nlev[b * LC_MAX_LEVELS + l];
         for (int i = tid; i < (n_l + 31) / 32; i += LC_BM_THREADS) kept[i] = 0u;
@@ -527,7 +504,6 @@ lc_beam_kernel(const LcRetrieveArgs a) {
         for (int i = tid; i < n_c; i += LC_BM_THREADS)
             if (flg[i]) atomicOr(&kept[cid[i] >> 5], 1u << (cid[i] & 31));
         __syncthreads();
-        LC_STAMP0(lc_dbg_beam, 4 + 4 * (L - 1 - l));
         if (l == 1) break;
         // ---- the kept nodes' children, in ascending order: count them, pick where the list goes, write it
         const int n_b = ix.nlev[b * LC_MAX_LEVELS + (l - 1)];
@@ -552,7 +528,6 @@ lc_beam_kernel(const LcRetrieveArgs a) {
                 if (is_child(i)) nxt[pos++] = i;
         }
         __syncthreads();
-        LC_STAMP0(lc_dbg_beam, 5 + 4 * (L - 1 - l));
         cid = nxt;
         in_lds = nxt_lds;
         n_c = n_new;
@@ -570,7 +545,6 @@ lc_beam_kernel(const LcRetrieveArgs a) {
         return (p >= 0 && p < n_1 && ((kept[p >> 5] >> (p & 31)) & 1u)) ? 1 : 0;
     };
     auto chunk_state = [&](int j) -> int { return j < M ? chunk_state_of(j, bnd[j], L > 1 ? par0[j] : 0) : 0; };
-    LC_STAMP0(lc_dbg_beam, 20);
     int n_pin = 0;
     n_c = 0;
     {
@@ -606,7 +580,6 @@ lc_beam_kernel(const LcRetrieveArgs a) {
     }
     lc_leaf_select_prepare<LC_BM_THREADS>(leaf_sh);
     __syncthreads();
-    LC_STAMP0(lc_dbg_beam, 21);
     uint32_t* key = in_lds ? l_key : g_key;
     int* wgt = in_lds ? l_wgt : g_wgt;
     // ---- score them: key and length per candidate
@@ -646,7 +619,6 @@ lc_beam_kernel(const LcRetrieveArgs a) {
     }
     if (in_lds && tid < 4 && n_c + tid < ((n_c + 3) & ~3)) { key[n_c + tid] = 0u; wgt[n_c + tid] = 0; }
     __syncthreads();
-    LC_STAMP0(lc_dbg_beam, 22);
     const long long C0 = a.beam[0] > 0 ? a.beam[0] : 0x7fffffffLL;
     uint8_t* flg = in_lds ? l_flg : g_flg;
     if (in_lds && n_c <= LC_BM_RANK_MAX) {
@@ -660,7 +632,6 @@ lc_beam_kernel(const LcRetrieveArgs a) {
         for (int i = tid; i < n_c; i += LC_BM_THREADS) flg[i] = key[i] > thr ? 1 : 0;
     }
     __syncthreads();
-    LC_STAMP0(lc_dbg_beam, 23);
     // ---- the chunk list: pinned chunks (ids 0 .. n_pin - 1), then the selected candidates in ascending order
     int32_t* ids = a.ids + (size_t)bh * a.cap;
     for (int j = tid; j < min(n_pin, a.cap); j += LC_BM_THREADS) ids[j] = j;
@@ -679,7 +650,6 @@ lc_beam_kernel(const LcRetrieveArgs a) {
         }
     }
     const int pos0 = n_pin + n_sel;
-    LC_STAMP0(lc_dbg_beam, 24);
     if (tid == 0) a.counts[bh] = min(pos0, a.cap);
 }
 
@@ -733,7 +703,6 @@ lc_leaf_kernel(const LcRetrieveArgs a) {
     const __amdgpu_buffer_rsrc_t rad_r = lc_buffer(ix.radius[0] + cb, cap0 * 4);
     const bool have_want = a.walk != 0;
 
-    LC_STAMP0(lc_dbg_leaf, 0);
     // loads that do not depend on M are issued together with it (the arrays are cap0 long)
     const int j_lo = blockIdx.x * (R * LC_LF_GROUPS);
     int jj[R];
@@ -768,7 +737,6 @@ lc_leaf_kernel(const LcRetrieveArgs a) {
     };
     const int M = ix.state[bh * 4 + 1];
 
-    LC_STAMP0(lc_dbg_leaf, 1);
     if (j_lo < M) {
         if (a.budget > 0) {
             float sv[R];
@@ -797,14 +765,12 @@ lc_leaf_kernel(const LcRetrieveArgs a) {
         }
     }
 
-    LC_STAMP0(lc_dbg_leaf, 2);
     // ---- last workgroup of this (sequence, head) selects
     // (every workgroup empties its select histogram on the way: whichever turns out to be the last
     // finds it ready behind the barriers of the arrival)
     lc_leaf_select_prepare<LC_LF_THREADS>(sel_sh);
     if (!lc_arrive_last(&ix.sync[bh * 4 + 0], (int)gridDim.x, &last_sh)) return;
 
-    LC_STAMP(lc_dbg_leaf, 3);
     // stage keys and lengths (pinned chunks get length -1) in LDS, or fall back to global scratch
     uint32_t* skey;
     int* slen;
@@ -817,23 +783,36 @@ lc_leaf_kernel(const LcRetrieveArgs a) {
         slen = g + ix.cap[0];
     }
     uint32_t kmin = 0xffffffffu, kmax = 0u;
-#pragma unroll 4
-    for (int j = tid; j < M; j += LC_LF_THREADS) {
-        const int s0 = bnd[j], s1 = bnd[j + 1];
-        const uint32_t k = lc_load_agent(&keys[j]);
-        skey[j] = k;
-        slen[j] = (s0 < a.sink) ? -1 : (s1 - s0);
-        if (k != 0u) { kmin = min(kmin, k); kmax = max(kmax, k); }
+    // (batches of eight chunks per thread, all their loads in flight together: a memory round trip
+    // per batch instead of one per chunk)
+    constexpr int SB = 8;
+    for (int j0 = tid; j0 < M; j0 += SB * LC_LF_THREADS) {
+        int s0[SB], s1[SB];
+        uint32_t kv[SB];
+#pragma unroll
+        for (int e = 0; e < SB; ++e) {
+            const int j = min(j0 + e * LC_LF_THREADS, M - 1);
+            s0[e] = bnd[j];
+            s1[e] = bnd[j + 1];
+            kv[e] = lc_load_agent(&keys[j]);
+        }
+#pragma unroll
+        for (int e = 0; e < SB; ++e) {
+            const int j = j0 + e * LC_LF_THREADS;
+            if (j < M) {
+                skey[j] = kv[e];
+                slen[j] = (s0[e] < a.sink) ? -1 : (s1[e] - s0[e]);
+                if (kv[e] != 0u) { kmin = min(kmin, kv[e]); kmax = max(kmax, kv[e]); }
+            }
+        }
     }
     lc_leaf_select_range(kmin, kmax, sel_sh);
     __syncthreads();
 
-    LC_STAMP(lc_dbg_leaf, 4);
     const long long C = (a.policy == LC_POLICY_BEAM && a.beam[0] > 0) ? a.beam[0] : 0x7fffffffLL;
     const uint32_t thr = lc_leaf_select<LC_LF_THREADS>(M, skey, slen, a.budget > 0 ? (long long)a.budget : 0LL, C,
                                                        sel_sh);
 
-    LC_STAMP(lc_dbg_leaf, 5);
     // each thread owns a contiguous run of chunks, so the ids come out ascending: count, scan, write
     int E = (M + LC_LF_THREADS - 1) / LC_LF_THREADS;
     E |= 1;                                             // odd stride: no LDS bank conflicts
@@ -861,7 +840,6 @@ lc_leaf_kernel(const LcRetrieveArgs a) {
             ++pos;
         }
     }
-    LC_STAMP(lc_dbg_leaf, 6);
     if (tid == 0) {
         a.counts[bh] = min(tot_s, a.cap);
         ix.sync[bh * 4 + 0] = 0;                 // ready for the next call

@@ -119,7 +119,6 @@ __device__ __forceinline__ void lc_select_chunks(const LcDev& ix, int b, int bh,
     o.M = min(M_all, EC * NT);
     o.tail_st = bnd[M_all];
     const int W = budget > 0 ? budget : 0;
-    LC_LSTAMP0(15);
     // ---- lengths; what is past the count or pinned is no candidate (key 0), pinned chunks are selected
     int cln[EC];
     uint32_t kmin1 = 0xffffffffu, kmax = 0u;                    // (lowest candidate key) - 1, highest
@@ -143,7 +142,6 @@ __device__ __forceinline__ void lc_select_chunks(const LcDev& ix, int b, int bh,
     kmax = fs.kmax[0];
 #pragma unroll
     for (int w = 1; w < NT / 64; ++w) { kmin1 = min(kmin1, fs.kmin[w]); kmax = max(kmax, fs.kmax[w]); }
-    LC_LSTAMP0(18);
     if (kmax != 0u) {                                           // (uniform) there are candidates
         const uint32_t kmin = kmin1 + 1u;
         const uint32_t span = kmax - kmin;
@@ -159,7 +157,6 @@ __device__ __forceinline__ void lc_select_chunks(const LcDev& ix, int b, int bh,
             atomicAdd(&fs.hw[slot], cln[e]);
         }
         lc_barrier_lds();
-        LC_LSTAMP0(19);
         // ---- every wavefront scans all bins from the top: lane l holds bins BINS - 1 - PER l - i, i < PER
         constexpr int PER = BINS / 64;
         int fb = -1, remW = W;                                  // cutoff bin (-1: every candidate fits), budget left for it
@@ -218,7 +215,6 @@ __device__ __forceinline__ void lc_select_chunks(const LcDev& ix, int b, int bh,
             }
         }
         lc_barrier_lds();
-        LC_LSTAMP0(11);
         const int nc = fs.n_cand;
         if (nc <= LC_SEL_CAND) {
             // ---- each owner ranks its chunk against the list: length and number of the chunks before it
@@ -272,7 +268,6 @@ __device__ __forceinline__ void lc_select_chunks(const LcDev& ix, int b, int bh,
             }
         }
     }
-    LC_LSTAMP0(12);
     // ---- token offsets in id order: EC independent wavefront scans, their totals chained, then
     // the four wavefront totals
     {
