@@ -188,28 +188,36 @@ lc_pool_kernel(LcDev ix, const uint16_t* K, long long ks_seq, long long ks_head,
     const int lo = bnd[j], hi = bnd[j + 1];
     const uint16_t* Kbh = K + b * ks_seq + h * ks_head;
     const bool round_bf16 = ix.c0_bf16 != 0;
-    uint4 keep[LC_POOLW_KEEP];
+    // a batch = LC_POOLW_KEEP rows per group, all loads in flight together (rows past the chunk read as zeros)
+    auto load_batch = [&](int base, uint4 (&buf)[LC_POOLW_KEEP]) {
 #pragma unroll
-    for (int k = 0; k < LC_POOLW_KEEP; ++k) {
-        const int r = lo + g4 + 4 * k;
-        keep[k] = make_uint4(0u, 0u, 0u, 0u);
-        if (r < hi) keep[k] = *reinterpret_cast<const uint4*>(Kbh + (long long)r * ks_tok + 8 * sub);
-    }
+        for (int k = 0; k < LC_POOLW_KEEP; ++k) {
+            // (no branch around the load -- the compiler would wait for one load before issuing the
+            // next; a row past the chunk re-reads the chunk's last row and is zeroed afterwards)
+            const int r = base + g4 + 4 * k;
+            const uint4 v = *reinterpret_cast<const uint4*>(Kbh + (long long)max(min(r, hi - 1), lo) * ks_tok + 8 * sub);
+            buf[k] = r < hi ? v : make_uint4(0u, 0u, 0u, 0u);
+        }
+    };
+    uint4 keep[LC_POOLW_KEEP];
+    load_batch(lo, keep);
     float sum[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) sum[i] = 0.f;
+    auto add_batch = [&](const uint4 (&buf)[LC_POOLW_KEEP]) {
 #pragma unroll
-    for (int k = 0; k < LC_POOLW_KEEP; ++k) {                       // (rows past the chunk hold zeros: they add nothing)
-        float f[8];
-        lc_unpack8(keep[k], f);
+        for (int k = 0; k < LC_POOLW_KEEP; ++k) {                   // (zero rows add nothing)
+            float f[8];
+            lc_unpack8(buf[k], f);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) sum[i] += f[i];
-    }
-    for (int r = lo + g4 + 4 * LC_POOLW_KEEP; r < hi; r += 4) {
-        float f[8];
-        lc_unpack8(*reinterpret_cast<const uint4*>(Kbh + (long long)r * ks_tok + 8 * sub), f);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) sum[i] += f[i];
+            for (int i = 0; i < 8; ++i) sum[i] += f[i];
+        }
+    };
+    add_batch(keep);
+    for (int base = lo + 4 * LC_POOLW_KEEP; base < hi; base += 4 * LC_POOLW_KEEP) {
+        uint4 more[LC_POOLW_KEEP];
+        load_batch(base, more);
+        add_batch(more);
     }
     // The rows stay packed (four registers each) across the two passes: an empty statement that
     // claims to rewrite them keeps the compiler from holding their unpacked copies as well, which
@@ -245,8 +253,13 @@ lc_pool_kernel(LcDev ix, const uint16_t* K, long long ks_seq, long long ks_head,
 #pragma unroll
         for (int k = 0; k < LC_POOLW_KEEP; ++k)
             if (lo + g4 + 4 * k < hi) reach(keep[k]);
-        for (int r = lo + g4 + 4 * LC_POOLW_KEEP; r < hi; r += 4)
-            reach(*reinterpret_cast<const uint4*>(Kbh + (long long)r * ks_tok + 8 * sub));
+        for (int base = lo + 4 * LC_POOLW_KEEP; base < hi; base += 4 * LC_POOLW_KEEP) {
+            uint4 more[LC_POOLW_KEEP];
+            load_batch(base, more);
+#pragma unroll
+            for (int k = 0; k < LC_POOLW_KEEP; ++k)
+                if (base + g4 + 4 * k < hi) reach(more[k]);
+        }
         far2 = fmaxf(far2, __shfl_xor(far2, 16));
         far2 = fmaxf(far2, __shfl_xor(far2, 32));
         radius = lc_pad_radius(sqrtf(far2));
