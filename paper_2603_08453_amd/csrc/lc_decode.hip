@@ -207,24 +207,28 @@ lc_decode_kernel(const LcDecodeArgs a) {
         // MFMA A operand -- and V for the tokens of its own group.
         const int gk = (wave << 2) + (sub >> 2), uk = sub & 3;
         int tv = 0, tv_end = 0, tk = 0, tk_end = 0;
+        // Branch-free: a branch around a load would put each row lookup (an LDS read) and its load in a
+        // basic block of its own, waited for one after the other.  All row lookups go out together
+        // (slot 0 stands in where there is no token) and a load without a token gets an offset past
+        // the resource's end, which the range check answers with zeros.
         auto issue = [&](int it, lc_v4i (&kv)[4], lc_v4i (&vv)[U]) {
             const int k_tok = tk + it * U + uk;
-            if (uk < U && k_tok < tk_end) {
-                const int ko = rows[k_tok] * row_bytes + 16 * q4;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) kv[j] = __builtin_amdgcn_raw_buffer_load_b128(Kr, ko + 64 * j, 0, 0);
-            } else {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) kv[j] = lc_v4i{0, 0, 0, 0};
-            }
+            const bool k_in = uk < U && k_tok < tk_end;
+            const int k_row = rows[k_in ? k_tok : 0];
+            int v_row[U];
+            bool v_in[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int v_tok = tv + it * U + u;
-                if (v_tok < tv_end)
-                    vv[u] = __builtin_amdgcn_raw_buffer_load_b128(Vr, rows[v_tok] * row_bytes + 16 * sub, 0, 0);
-                else
-                    vv[u] = lc_v4i{0, 0, 0, 0};
+                v_in[u] = v_tok < tv_end;
+                v_row[u] = rows[v_in[u] ? v_tok : 0];
             }
+            const int ko = k_in ? k_row * row_bytes + 16 * q4 : slab_bytes;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) kv[j] = __builtin_amdgcn_raw_buffer_load_b128(Kr, ko + 64 * j, 0, 0);
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                vv[u] = __builtin_amdgcn_raw_buffer_load_b128(Vr, v_in[u] ? v_row[u] * row_bytes + 16 * sub : slab_bytes, 0, 0);
         };
         // logits of the wavefront's 16 tokens for all heads (MFMA), one online-softmax update of
         // this lane's head, then P.V for every head with the broadcast probabilities
