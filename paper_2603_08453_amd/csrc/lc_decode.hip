@@ -564,6 +564,9 @@ template <int G, int EC>
 static int launch_fused_ge(const LcDecodeArgs& a, int splits, hipStream_t stream) {
     // key and length of every chunk, touched only when the cutoff bin overflows its short list
     const size_t lds = (size_t)EC * LC_DEC_THREADS * 8;
+    if (lds > 16 * 1024)        // static + dynamic may pass the default per-workgroup allowance
+        LC_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&lc_decode_kernel<G, true, EC>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     hipLaunchKernelGGL((lc_decode_kernel<G, true, EC>), dim3(splits, a.ix.H, a.ix.B), dim3(LC_DEC_THREADS), lds, stream, a);
     LC_HIP_CHECK(hipGetLastError());
     return LC_OK;

@@ -239,6 +239,24 @@ def test_fused_step_falls_back_with_many_chunks(G):
     _check_decode(G, case, qb, ids, tag="many-chunks")
 
 
+@pytest.mark.parametrize("T,Hq", [(1100, 4), (2200, 4), (3000, 8), (4600, 4), (7200, 4), (7200, 8)])
+def test_fused_step_at_every_selection_width(G, T, Hq):
+    """Chunk counts on both sides of each width of the in-register selection (2, 4, 6, 10 and 16
+    chunks per lane of a 256-thread workgroup), up to just below the 4096 chunks where the step
+    changes to the separate kernels; the ragged last wavefront is partly empty in each."""
+    w = wl.tiny(f"width-{T}", levels=2, fanout=16, T=T, chunk_lo=1, chunk_hi=3, H_q=Hq, H_kv=1, budget=300)
+    case = G.make_case(w)
+    _say(f"{w.name}: {case.oidx[0][0].M} chunks, G = {Hq}")
+    assert case.oidx[0][0].M <= 4096
+    qb = _q_batch(case, 0)
+    ids = _check_retrieve(G, case, qb, 300, tag=w.name)                    # the separate calls against the oracle,
+    _check_decode(G, case, qb, ids, tag=w.name)                            # then the step against the separate calls
+    for budget in (0, 300, 10 ** 6):
+        _check_step(G, case, qb, budget, tag=w.name)
+    _check_step(G, case, qb, 64, sink=7, tag=w.name + " sink")
+    _check_step(G, case, np.zeros_like(qb), 200, tag=w.name + " q=0")      # one tie group: the overflow path
+
+
 def test_more_chunks_than_the_select_can_stage_in_lds(G):
     """About twenty thousand chunks: the scoring kernel's last workgroup stages keys and lengths in
     global scratch instead of LDS, and the fused step falls back to the separate kernels."""
