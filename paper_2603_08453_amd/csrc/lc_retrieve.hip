@@ -513,18 +513,37 @@ lc_beam_kernel(const LcRetrieveArgs a) {
             const int p = par[i];
             return (p >= 0 && p < n_l && ((kept[p >> 5] >> (p & 31)) & 1u)) ? 1 : 0;
         };
-        // (thread t looks at the nodes [t E, t E + E): one count, one scan, one write pass)
+        // (thread t looks at the nodes [t E, t E + E): one count, one scan, one write pass.  The parent
+        // pointers are fetched in batches of eight with no branch around the loads -- a memory round
+        // trip per batch, not per node -- and the verdicts of the first 32 nodes stay in a register mask.)
         const int E = (n_b + LC_BM_THREADS - 1) / LC_BM_THREADS;
         const int i_lo = min(n_b, tid * E), i_hi = min(n_b, i_lo + E);
-        int n_new = 0, mine = 0;
-#pragma unroll 2
-        for (int i = i_lo; i < i_hi; ++i) mine += is_child(i);
+        const int i_last = max(n_b - 1, 0);
+        unsigned vmask = 0u;
+        const int E_b = E > 4 ? min(E, 32) : 0;                   // short runs: node by node below
+        for (int k0 = 0; k0 < E_b; k0 += 8) {
+            int pv[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) pv[k] = par[min(i_lo + k0 + k, i_last)];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int pp = pv[k];
+                const bool in = i_lo + k0 + k < i_hi && pp >= 0 && pp < n_l;
+                const uint32_t w = kept[in ? pp >> 5 : 0];
+                vmask |= (in && ((w >> (pp & 31)) & 1u)) ? 1u << (k0 + k) : 0u;
+            }
+        }
+        int n_new = 0, mine = __popc(vmask);
+        for (int i = i_lo + E_b; i < i_hi; ++i) mine += is_child(i);
         int pos = lc_block_scan<LC_BM_THREADS>(mine, sel_sh, &n_new);
         const bool nxt_lds = n_new <= CL;
         int* nxt = nxt_lds ? (cid == l_cid ? l_nxt : l_cid) : (cid == g_cid ? g_nxt : g_cid);
         if (mine > 0) {
-#pragma unroll 2
-            for (int i = i_lo; i < i_hi; ++i)
+            while (vmask != 0u) {
+                nxt[pos++] = i_lo + __ffs((int)vmask) - 1;
+                vmask &= vmask - 1u;
+            }
+            for (int i = i_lo + E_b; i < i_hi; ++i)
                 if (is_child(i)) nxt[pos++] = i;
         }
         __syncthreads();
@@ -548,18 +567,35 @@ lc_beam_kernel(const LcRetrieveArgs a) {
     int n_pin = 0;
     n_c = 0;
     {
-        // (the verdicts of the prefetched chunks stay in a register mask; longer runs read memory)
-        unsigned pf_cand = 0u;
-        int mine = 0, pins = 0;
+        // (the verdicts of a thread's first 32 chunks stay in a register mask: those of the prefetched
+        // chunks, then batches of eight whose parents and boundaries are fetched together with no
+        // branch around the loads; longer runs read memory chunk by chunk)
+        unsigned cand = 0u;
+        int pins = 0;
 #pragma unroll
         for (int k = 0; k < LC_BM_PF; ++k) {
             const int st = j_lo + k < j_hi ? chunk_state_of(j_lo + k, pf_s[k], pf_p[k]) : 0;
-            if (st == 1) pf_cand |= 1u << k;
-            mine += st == 1 ? 1 : 0;
+            cand |= st == 1 ? 1u << k : 0u;
             pins += st == 2 ? 1 : 0;
         }
-#pragma unroll 2
-        for (int j = j_lo + LC_BM_PF; j < j_hi; ++j) {
+        const int j_last = max(M - 1, 0);
+        for (int k0 = LC_BM_PF; k0 < min(EM, 32); k0 += 8) {
+            int pv[8], sv[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int j = min(j_lo + k0 + k, j_last);
+                pv[k] = L > 1 ? par0[j] : 0;
+                sv[k] = bnd[j];
+            }
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int st = (k0 + k < 32 && j_lo + k0 + k < j_hi) ? chunk_state_of(j_lo + k0 + k, sv[k], pv[k]) : 0;
+                cand |= st == 1 ? 1u << (k0 + k) : 0u;
+                pins += st == 2 ? 1 : 0;
+            }
+        }
+        int mine = __popc(cand);
+        for (int j = j_lo + 32; j < j_hi; ++j) {
             const int st = chunk_state(j);
             mine += st == 1 ? 1 : 0;
             pins += st == 2 ? 1 : 0;
@@ -569,11 +605,11 @@ lc_beam_kernel(const LcRetrieveArgs a) {
         in_lds = n_c <= CL;
         int* nxt = in_lds ? (cid == l_cid ? l_nxt : l_cid) : (cid == g_cid ? g_nxt : g_cid);
         if (mine > 0) {
-#pragma unroll
-            for (int k = 0; k < LC_BM_PF; ++k)
-                if ((pf_cand >> k) & 1u) nxt[pos++] = j_lo + k;
-#pragma unroll 2
-            for (int j = j_lo + LC_BM_PF; j < j_hi; ++j)
+            while (cand != 0u) {
+                nxt[pos++] = j_lo + __ffs((int)cand) - 1;
+                cand &= cand - 1u;
+            }
+            for (int j = j_lo + 32; j < j_hi; ++j)
                 if (chunk_state(j) == 1) nxt[pos++] = j;
         }
         cid = nxt;
