@@ -239,7 +239,8 @@ int lc_sparse_decode(const lc_index* idx, const void* q, const void* K, const vo
  * head) from them, so no chunk list travels through memory on the critical path.
  * When a sequence has more than 4096 chunks, the chunks no longer fit the registers of
  * the selecting workgroups and the call runs the kernels of the two separate entry
- * points instead (through a chunk list in the workspace); the results are the same.
+ * points instead (through a chunk list in the workspace); so it does under the BEAM
+ * policy, whose selection needs the kept set of every level.  The results are the same.
  *
  *   chunk_ids, counts  optional outputs as in lc_retrieve (both or neither); cap
  *                      is checked only when they are given
@@ -319,8 +320,9 @@ int lc_index_info(const lc_index* idx, int b, int32_t* T, int32_t* M, int32_t* n
  *                      int32 parent[N_l], int32 ntok[N_l], int32 nchunk[N_l]
  * Centers are float32 in the blob whatever center_dtype says (bfloat16 values widened); import
  * requires the blob's L, fan-outs, geometry and center_dtype to equal the configuration's.
- * lc_index_export synchronises the stream.  With blob == NULL it only stores the
- * required size in *bytes.
+ * lc_index_export and lc_index_import synchronise the stream (import copies with blocking
+ * copies; it is a test and checkpoint path, not a hot one).  With blob == NULL export only
+ * stores the required size in *bytes.
  */
 int lc_index_export(const lc_index* idx, void* blob /* host */, size_t* bytes /* host, in/out */, void* stream);
 int lc_index_import(lc_index** out, const lc_config* cfg, const void* blob /* host */, size_t blob_bytes,
