@@ -423,11 +423,24 @@ def test_split_count_does_not_change_the_result(G):
 
 # ----------------------------------------------------------------- index build on the GPU
 
+# shapes of the build: levels small enough to be clustered whole in one workgroup; a batch whose
+# chunk level straddles that kernel's limit (224 points, 64 clusters) so that the level takes the
+# tiled kernels and the one above it the small one; chunks of 1..200 tokens, i.e. pooling with
+# one, several and partly filled batches of rows
+BUILD_SHAPES = {
+    "small-levels": dict(B=2, levels=3, fanout=4, T=0, T_range=(800, 1600), chunk_lo=3, chunk_hi=30),
+    "straddle": dict(B=2, levels=3, fanout=3, T=0, T_range=(2900, 4600), chunk_lo=4, chunk_hi=24),
+    "long-chunks": dict(B=1, levels=3, fanout=4, T=9000, chunk_lo=1, chunk_hi=200),
+}
+
+
+@pytest.mark.parametrize("shape", list(BUILD_SHAPES))
 @pytest.mark.parametrize("geometry", [orc.TOKEN_BALL, orc.PAPER_UNIT])
-def test_build_index_matches_oracle(G, geometry):
+def test_build_index_matches_oracle(G, geometry, shape):
     from paper_2603_08453_amd import binding as lc
-    w = wl.tiny("build", B=2, levels=3, fanout=4, T=0, T_range=(800, 1600), chunk_lo=3, chunk_hi=30)
-    case = G.make_case(w, tails=[4, 0], geometry=geometry, build_on="gpu")
+    w = wl.tiny("build-" + shape, **BUILD_SHAPES[shape])
+    case = G.make_case(w, tails=[4, 0][:w.B], geometry=geometry, build_on="gpu")
+    _say(f"build {shape}: chunks per sequence {[case.oidx[b][0].M for b in range(w.B)]}")
     blob = lc.unpack_blob(lc.lc_index_export(case.idx))
     tally = {}
     for b in range(w.B):
