@@ -1,18 +1,22 @@
 // Retrieval kernels: Eq. 2 node scoring, level-by-level pruning, budget selection.
 //
-// Kernel 1 (lc_upper_kernel): one workgroup per (sequence, KV head).  It stages the
-// internal nodes' small arrays (parents, subtree token counts) in LDS with a few
-// batched loads, scores every internal node (levels >= 1), and walks the levels
-// top-down with the frontier held in LDS:
-//   EXACT  probe pass  -> a lower bound tau0 of the selection cutoff,
-//          verify pass -> every node whose bound reaches tau0 stays;
-//   BEAM   keep the beam[l] best frontier nodes per level (Algorithm 1).
-// It leaves one byte per chunk: score it or not.
+// lc_upper_kernel (EXACT policy with the level walk on): one workgroup per (sequence, KV head).
+// It stages the internal nodes' small arrays (parents, subtree token counts) in LDS with a few
+// batched loads, scores every internal node (levels >= 1), and walks the levels top-down with
+// the frontier held in LDS: a probe pass gives a lower bound tau0 of the selection cutoff, the
+// verify pass keeps every node whose bound reaches tau0.  It leaves one byte per level-1 node:
+// score the chunks below it or not.
 //
-// Kernel 2 (lc_leaf_kernel): many workgroups per (sequence, KV head) score the
-// wanted chunks; the last workgroup to finish for a (sequence, head) pulls the keys
-// into LDS, runs the weighted radix select (weights = chunk lengths) and emits the
-// ids in ascending order.
+// lc_beam_kernel (BEAM policy, Algorithm 1): one workgroup per (sequence, KV head) does the whole
+// retrieval -- per level score the candidates, keep the beam[l] best, gather their children; at
+// the chunk level cut by the token budget and write the ids.
+//
+// lc_leaf_kernel (lc_retrieve, and the decode step beyond what its selecting workgroups hold):
+// many workgroups per (sequence, KV head) score the wanted chunks; the last workgroup to finish
+// for a (sequence, head) pulls the keys into LDS, runs the weighted histogram select (weights =
+// chunk lengths) and emits the ids in ascending order.
+//
+// lc_score_kernel (first kernel of a decode step): the scoring half of lc_leaf_kernel alone.
 //
 // The kernels are latency-bound at batch 1, so global loads are issued in batches
 // and nothing reads global memory element by element inside a dependent loop.
@@ -94,7 +98,7 @@ __device__ __forceinline__ void lc_small_select(int n, int mode, long long W, lo
 }
 
 // ---------------------------------------------------------------------------------
-// kernel 1: internal levels
+// lc_upper_kernel: internal levels (EXACT walk)
 // ---------------------------------------------------------------------------------
 // (LDS layout: lc_walk_layout.h: 13 bytes per internal-node slot, 16 per select-scratch slot, 12 per probe-list slot)
 
@@ -703,14 +707,14 @@ static int launch_beam_g(LcRetrieveArgs& a, int max_nodes, hipStream_t stream) {
     return LC_OK;
 }
 
-// Kernel 2 runs 1024 threads = 64 groups: one chunk per group while scoring; the last workgroup
+// lc_leaf_kernel runs 1024 threads = 64 groups: one chunk per group while scoring; the last workgroup
 // has enough threads to hold a few keys each during the select.
 #define LC_LF_THREADS 1024
 #define LC_LF_THREADS_MAX LC_LF_THREADS
 #define LC_LF_GROUPS (LC_LF_THREADS / 16)
 
 // ---------------------------------------------------------------------------------
-// kernel 2: chunk scoring + budget selection by the last workgroup
+// lc_leaf_kernel: chunk scoring + budget selection by the last workgroup
 // ---------------------------------------------------------------------------------
 // BF16: how the chunk-level centers are stored (a compile-time copy of the index's flag).
 template <int G, int R, bool BF16>
@@ -886,7 +890,7 @@ lc_leaf_kernel(const LcRetrieveArgs a) {
 // launcher
 // ---------------------------------------------------------------------------------
 // ---------------------------------------------------------------------------------
-// kernel 2': chunk scoring only (the fused decode step selects by itself)
+// lc_score_kernel: chunk scoring only (the decode step's second kernel selects by itself)
 // ---------------------------------------------------------------------------------
 // The same scoring as lc_leaf_kernel without the selection behind it, so without its LDS and its
 // 1024-thread workgroups: NT threads = NT/16 groups, R chunks per group.
