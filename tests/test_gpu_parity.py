@@ -476,6 +476,47 @@ def test_build_index_matches_oracle(G, geometry, shape):
             H.accept_ids(ids[b][h], orc.node_scores(gi, 0, q), gi.lens(), w.budget)
 
 
+@pytest.mark.parametrize("seed", list(range(int(__import__("os").environ.get("LC_RANDOM_BUILDS", "8")))))
+def test_random_builds(G, seed):
+    """Seeded random shapes built on the GPU: level 0 against the oracle directly, the levels above
+    wherever the oracle's clustering has no near-tie, the covering invariant by brute force."""
+    from paper_2603_08453_amd import binding as lc
+    r = np.random.default_rng(5000 + seed)
+    h_kv = int(r.integers(1, 4))
+    B = int(r.integers(1, 4))
+    levels = int(r.integers(2, 5))
+    fanout = int(r.integers(2, 12))
+    lo = int(r.integers(1, 12))
+    hi = lo + int(r.integers(0, 90))
+    t_lo = int(r.integers(200, 5000))
+    geometry = orc.TOKEN_BALL if r.random() < 0.7 else orc.PAPER_UNIT
+    w = wl.tiny(f"rbuild{seed}", cfg_id=5000 + seed, B=B, H_q=h_kv, H_kv=h_kv, levels=levels, fanout=fanout, T=0,
+                T_range=(t_lo, t_lo + int(r.integers(1, 3000))), chunk_lo=lo, chunk_hi=hi)
+    # (float32 chunk centers: with bfloat16 ones a mean next to a rounding boundary may round the other
+    # way in float32 than in float64, which the dedicated bfloat16 build test allows for)
+    case = G.make_case(w, tails=[int(x) for x in r.integers(0, 20, size=B)], geometry=geometry, build_on="gpu")
+    _say(f"build seed {seed}: B={B} H_kv={h_kv} L={levels} F={fanout} chunks {lo}..{hi} "
+         f"M={[case.oidx[b][0].M for b in range(B)]} geometry {geometry}")
+    blob = lc.unpack_blob(lc.lc_index_export(case.idx))
+    tally = {}
+    for b in range(B):
+        sq = blob["seqs"][b]
+        for h in range(h_kv):
+            oi = case.oidx[b][h]
+            gi = G.levels_to_oracle_index(sq["heads"][h], sq["bounds"], sq["T"], w.fanout, geometry)
+            assert [gi.n(l) for l in range(levels)] == [oi.n(l) for l in range(levels)]
+            assert np.allclose(gi.center[0], oi.center[0], rtol=2e-6, atol=2e-6)
+            assert np.all(gi.radius[0] >= oi.radius[0] * (1 - 1e-6))
+            H.check_covering_invariant(gi, case.Kf(b, h), slack=1e-6)
+            H.check_counts(gi)
+            if H.same_topology_or_near_tie(gi, oi, levels - 1, f"rbuild{seed} b{b} h{h}", tally):
+                for l in range(1, levels):
+                    live = oi.nchunk[l] > 0
+                    assert np.allclose(gi.center[l][live], oi.center[l][live], rtol=1e-5, atol=1e-5)
+                    assert np.all(gi.radius[l][live] >= oi.radius[l][live] * (1 - 1e-6))
+    _say(f"  {tally.get('same', 0)} trees with the oracle's topology, {tally.get('near_tie', 0)} behind a near-tie")
+
+
 def _bf16_ulp(x):
     """Spacing of bfloat16 values at |x| (8 significant bits)."""
     _, e = np.frexp(np.abs(x))
