@@ -150,6 +150,8 @@ size_t lc_workspace_bytes(const lc_config* cfg /* host */, int B, int H_q, int H
  *
  * Asynchronous: the host arrays are copied (into pinned staging memory the library keeps per
  * device for the life of the process) before the call returns, the stream is not waited for.
+ * Not meant for stream capture: the host arrays are read when the call is made, not when a
+ * captured graph is replayed.
  */
 int lc_build_index(lc_index** out, const lc_config* cfg,
                    const void* K, const int64_t k_strides[3],
