@@ -352,6 +352,36 @@ __device__ __forceinline__ void lc_assign_block(const float4 (&xa)[8], const flo
             if (d[r] > best[r]) { best[r] = d[r]; arg[r] = c; }
     }
 }
+// Two blocks at once: the two accumulators are independent chains, so the matrix pipe is not left
+// waiting for one instruction's result before the next can start (a wavefront is alone on its
+// SIMD here).  Each block's own sum runs in the same order as in lc_assign_block: same bits.
+__device__ __forceinline__ void lc_assign_block2(const float4 (&xa)[8], const float* brow0, const float* brow1,
+                                                 int c0, int c1, int k, float (&best)[4], int (&arg)[4]) {
+    lc_f32x4_b d0 = {0.f, 0.f, 0.f, 0.f}, d1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        const float4 m0 = *reinterpret_cast<const float4*>(brow0 + 16 * t);
+        const float4 m1 = *reinterpret_cast<const float4*>(brow1 + 16 * t);
+        d0 = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[t].x, m0.x, d0, 0, 0, 0);
+        d1 = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[t].x, m1.x, d1, 0, 0, 0);
+        d0 = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[t].y, m0.y, d0, 0, 0, 0);
+        d1 = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[t].y, m1.y, d1, 0, 0, 0);
+        d0 = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[t].z, m0.z, d0, 0, 0, 0);
+        d1 = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[t].z, m1.z, d1, 0, 0, 0);
+        d0 = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[t].w, m0.w, d0, 0, 0, 0);
+        d1 = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[t].w, m1.w, d1, 0, 0, 0);
+    }
+    if (c0 < k) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            if (d0[r] > best[r]) { best[r] = d0[r]; arg[r] = c0; }
+    }
+    if (c1 < k) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            if (d1[r] > best[r]) { best[r] = d1[r]; arg[r] = c1; }
+    }
+}
 // merge the 16 columns of a row: larger similarity wins, equal ones go to the lower centroid id
 __device__ __forceinline__ int lc_assign_merge(float bv, int ba) {
     auto merge = [&](float ov, int oa) {
@@ -411,8 +441,11 @@ lc_kmeans_assign_kernel(LcDev ix, int l, const float* pts, int pts_cap, const fl
         }
         if (c0 + LC_AS_TILE < k) fetch(c0 + LC_AS_TILE);
         __syncthreads();
-        for (int cj = 0; cj < nc; cj += 16)
-            lc_assign_block(xa, tile + (cj + j) * LC_AS_ROW + 4 * kk, c0 + cj + j, k, best, arg);
+        int cj = 0;
+        for (; cj + 16 < nc; cj += 32)
+            lc_assign_block2(xa, tile + (cj + j) * LC_AS_ROW + 4 * kk, tile + (cj + 16 + j) * LC_AS_ROW + 4 * kk,
+                             c0 + cj + j, c0 + cj + 16 + j, k, best, arg);
+        if (cj < nc) lc_assign_block(xa, tile + (cj + j) * LC_AS_ROW + 4 * kk, c0 + cj + j, k, best, arg);
     }
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
@@ -566,8 +599,11 @@ lc_kmeans_small_kernel(LcDev ix, int l, const float* pts, int pts_cap, float* ce
             int arg[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r) { best[r] = LC_NEG_INF; arg[r] = 0x7fffffff; }
-            for (int cj = 0; cj < k; cj += 16)
-                lc_assign_block(xa, cs + (cj + j) * LC_AS_ROW + 4 * kk, cj + j, k, best, arg);
+            int cj = 0;
+            for (; cj + 16 < k; cj += 32)
+                lc_assign_block2(xa, cs + (cj + j) * LC_AS_ROW + 4 * kk, cs + (cj + 16 + j) * LC_AS_ROW + 4 * kk,
+                                 cj + j, cj + 16 + j, k, best, arg);
+            if (cj < k) lc_assign_block(xa, cs + (cj + j) * LC_AS_ROW + 4 * kk, cj + j, k, best, arg);
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int ba = lc_assign_merge(best[r], arg[r]);
