@@ -114,11 +114,13 @@ size_t lc_layout_ws(const lc_config* cfg, int B, int H_q, int H, int d, int spli
     W->part_ml = c.take<float>((size_t)B * H_q * splits * 2);
     W->dirs = W->cent_a = W->cent_b = nullptr;
     W->anc = nullptr;
+    W->kflags = nullptr;
     if (with_build) {
         W->dirs = c.take<float>(BH * cap[0] * d);
         W->cent_a = c.take<float>(BH * cap1 * d);
         W->cent_b = c.take<float>(BH * cap1 * d);
         W->anc = c.take<int>(BH * cap[0]);
+        W->kflags = c.take<int>(BH * LC_KM_FLAGS);
     }
     W->total = align_up(c.off);
     return W->total;

@@ -306,9 +306,10 @@ __device__ __forceinline__ int lc_level_count(const LcDev& ix, int b, int bh, in
 
 // centroid c starts at point floor(c * N / k)
 __global__ void __launch_bounds__(LC_D)
-lc_kmeans_init_kernel(LcDev ix, int l, const float* pts, int pts_cap, float* cent, int cent_cap) {
+lc_kmeans_init_kernel(LcDev ix, int l, const float* pts, int pts_cap, float* cent, int cent_cap, int* flags) {
     const int c = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int bh = b * ix.H + h;
+    if (c == 0 && flags && threadIdx.x < LC_KM_FLAGS) flags[bh * LC_KM_FLAGS + threadIdx.x] = 0;
     const int N = lc_level_count(ix, b, bh, l);
     const int k = ix.nlev[b * LC_MAX_LEVELS + l + 1];
     if (c >= k) return;
@@ -393,11 +394,18 @@ __device__ __forceinline__ int lc_assign_merge(float bv, int ba) {
     merge(lc_dpp<0x140>(bv), __builtin_amdgcn_update_dpp(0, ba, 0x140, 0xF, 0xF, true));
     return ba;
 }
+// `flags` (may be null): flags[bh][t] = iteration t moved a point.  An iteration that moves none is a
+// fixed point -- the update would rebuild the same centroids from the same members and every later
+// iteration would repeat it -- so from then on the kernels of this (sequence, head) return at once:
+// iteration `it` assigns only if it <= 1 or iteration it - 1 moved a point, and leaves its own flag
+// at zero otherwise, which passes the verdict on.
 __global__ void __launch_bounds__(LC_BT)
-lc_kmeans_assign_kernel(LcDev ix, int l, const float* pts, int pts_cap, const float* cent, int cent_cap) {
+lc_kmeans_assign_kernel(LcDev ix, int l, const float* pts, int pts_cap, const float* cent, int cent_cap, int it,
+                        int* flags) {
     __shared__ __attribute__((aligned(16))) float tile[LC_AS_TILE * LC_AS_ROW];
     const int h = blockIdx.y, b = blockIdx.z;
     const int bh = b * ix.H + h;
+    if (flags && it >= 2 && flags[bh * LC_KM_FLAGS + it - 1] == 0) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int j = lane & 15, kk = lane >> 4;
     const int N = lc_level_count(ix, b, bh, l);
@@ -451,7 +459,11 @@ lc_kmeans_assign_kernel(LcDev ix, int l, const float* pts, int pts_cap, const fl
     for (int r = 0; r < 4; ++r) {
         const int ba = lc_assign_merge(best[r], arg[r]);
         const int i = i0 + 4 * kk + r;
-        if (j == 0 && i < N) ix.parent[l][(size_t)bh * ix.cap[l] + i] = ba;
+        if (j == 0 && i < N) {
+            int* lab = ix.parent[l] + (size_t)bh * ix.cap[l] + i;
+            if (flags && *lab != ba) flags[bh * LC_KM_FLAGS + it] = 1;     // (every writer stores the same value)
+            *lab = ba;
+        }
     }
 }
 
@@ -499,12 +511,14 @@ __device__ __forceinline__ int lc_collect_members(const int* __restrict__ lab, i
 // m_c = normalise(sum of members); a cluster without members (or with a zero sum) keeps m_c.
 // One workgroup per cluster: it lists its members (above), then the 16 groups add them up in turn.
 __global__ void __launch_bounds__(LC_BT)
-lc_kmeans_update_kernel(LcDev ix, int l, const float* pts, int pts_cap, float* cent, int cent_cap) {
+lc_kmeans_update_kernel(LcDev ix, int l, const float* pts, int pts_cap, float* cent, int cent_cap, int it,
+                        const int* flags) {
     __shared__ float sh[LC_BG * LC_D];
     __shared__ int mem[LC_MEM_WIN];
     __shared__ int cnt[2 * 64 + 1];
     const int c = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int bh = b * ix.H + h;
+    if (flags && it >= 1 && flags[bh * LC_KM_FLAGS + it] == 0) return;      // no point moved: the centroids stand
     const int sub = threadIdx.x & 15, grp = threadIdx.x >> 4;
     const int N = lc_level_count(ix, b, bh, l);
     const int k = ix.nlev[b * LC_MAX_LEVELS + l + 1];
@@ -565,6 +579,7 @@ lc_kmeans_small_kernel(LcDev ix, int l, const float* pts, int pts_cap, float* ce
     __shared__ int lab[LC_KS_MAX_N];
     __shared__ int moff[LC_KS_MAX_K + 1];
     __shared__ unsigned short mem[LC_KS_MAX_N];
+    __shared__ int changed[2];                    // labels changed in this iteration (one flag per parity of `it`)
     const int h = blockIdx.x, b = blockIdx.y;
     const int bh = b * ix.H + h;
     const int tid = threadIdx.x, sub = tid & 15, grp = tid >> 4, lane = tid & 63, wave = tid >> 6;
@@ -581,6 +596,7 @@ lc_kmeans_small_kernel(LcDev ix, int l, const float* pts, int pts_cap, float* ce
         *reinterpret_cast<float4*>(X + i * LC_AS_ROW + 4 * q) = *reinterpret_cast<const float4*>(P + (size_t)i * LC_D + 4 * q);
     }
     for (int i = tid; i < N; i += LC_BT) lab[i] = 0;
+    if (tid < 2) changed[tid] = 0;
     __syncthreads();
     for (int v = tid; v < k16 * LC_D; v += LC_BT) {
         const int c = v / LC_D, t = v % LC_D;
@@ -608,10 +624,18 @@ lc_kmeans_small_kernel(LcDev ix, int l, const float* pts, int pts_cap, float* ce
             for (int r = 0; r < 4; ++r) {
                 const int ba = lc_assign_merge(best[r], arg[r]);
                 const int i = i0 + 4 * kk + r;
-                if (j == 0 && i < N) lab[i] = ba;
+                if (j == 0 && i < N) {
+                    if (lab[i] != ba) changed[it & 1] = 1;
+                    lab[i] = ba;
+                }
             }
         }
+        if (tid == 0) changed[(it + 1) & 1] = 0;                    // (last read before the previous barrier)
         __syncthreads();
+        // An iteration that moves no point is a fixed point: the update would rebuild the same
+        // centroids from the same members and every later iteration would repeat it, so the
+        // remaining iterations are skipped (the first iteration always runs its update).
+        if (it > 0 && changed[it & 1] == 0) break;
         // members of every cluster, ascending, as one list ordered by cluster: counts, offsets, ids
         for (int c = wave; c < k; c += LC_BT / 64) {
             int n = 0;
@@ -810,6 +834,7 @@ int lc_launch_build(const lc_index* idx, const LcWs& ws, const void* Kp, const i
     const uint16_t* K = static_cast<const uint16_t*>(Kp);
     const int geometry = idx->cfg.geometry;
     const int B = ix.B, H = ix.H, L = ix.L;
+    int* const kflags = idx->cfg.kmeans_iters < LC_KM_FLAGS ? ws.kflags : nullptr;   // (more iterations: no early exit)
     if (max_M > 0 && K != nullptr) {
         hipLaunchKernelGGL(lc_pool_kernel, dim3((max_M + LC_BT / 64 - 1) / (LC_BT / 64), H, B), dim3(LC_BT), 0, stream, ix, K,
                            (long long)ks[0], (long long)ks[1], (long long)ks[2], geometry, ws.dirs);
@@ -840,15 +865,15 @@ int lc_launch_build(const lc_index* idx, const LcWs& ws, const void* Kp, const i
                                pts_cap, ws.cent_a, cent_cap, idx->cfg.kmeans_iters, x_rows);
         } else {
             hipLaunchKernelGGL(lc_kmeans_init_kernel, dim3(maxK, H, B), dim3(LC_D), 0, stream, ix, l,
-                               (const float*)pts, pts_cap, ws.cent_a, cent_cap);
+                               (const float*)pts, pts_cap, ws.cent_a, cent_cap, kflags);
         }
         LC_HIP_CHECK(hipGetLastError());
         if (maxN > 0) {
             for (int it = 0; it < (small ? 0 : idx->cfg.kmeans_iters); ++it) {
                 hipLaunchKernelGGL(lc_kmeans_assign_kernel, dim3((maxN + LC_AS_PTS - 1) / LC_AS_PTS, H, B), dim3(LC_BT), 0,
-                                   stream, ix, l, (const float*)pts, pts_cap, (const float*)ws.cent_a, cent_cap);
+                                   stream, ix, l, (const float*)pts, pts_cap, (const float*)ws.cent_a, cent_cap, it, kflags);
                 hipLaunchKernelGGL(lc_kmeans_update_kernel, dim3(maxK, H, B), dim3(LC_BT), 0, stream, ix, l,
-                                   (const float*)pts, pts_cap, ws.cent_a, cent_cap);
+                                   (const float*)pts, pts_cap, ws.cent_a, cent_cap, it, (const int*)kflags);
             }
             LC_HIP_CHECK(hipGetLastError());
             if (max_M > 0) {

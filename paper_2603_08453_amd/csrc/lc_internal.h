@@ -44,6 +44,7 @@ struct lc_index {
 size_t lc_layout_index(const lc_config* cfg, int B, int H, int d, void* base, LcDev* dev);
 
 // Workspace carve-up (all offsets 256-byte aligned).
+#define LC_KM_FLAGS 64       // k-means iterations whose progress flags the workspace holds
 struct LcWs {
     // retrieval
     uint32_t* keys;      // [B][H][cap0] order-preserving score keys of the chunks (0 = not a candidate)
@@ -59,6 +60,7 @@ struct LcWs {
     float* cent_a;       // [B][H][cap1][d] centroids (ping)
     float* cent_b;       // [B][H][cap1][d] centroids (pong)
     int* anc;            // [B][H][cap0] chunk -> ancestor at the level being built
+    int* kflags;         // [B][H][LC_KM_FLAGS] "iteration t of the k-means moved a point" (tiled kernels only)
     size_t total;
 };
 // with_build = false leaves out the build scratch (dirs, centroids, ancestors): what a decode step needs.
